@@ -1,0 +1,238 @@
+/*
+ * twilight.h - C ABI of the MI355X (gfx950) Twilight decode hot path.
+ *
+ * One decode step of one attention layer (paper: Figure 5, Section 4.1):
+ *
+ *   twilight_kquant_append   new K/V rows -> paged bf16 pools, INT4 K copy
+ *                            (Section 4.2; Appendix B.1), per-page key bounds
+ *   twilight_select_pages    token selector: top pages by a per-page upper
+ *                            bound of q.k (Section 4, challenge C1; Sec. 4.1)
+ *   twilight_topp_prune      Twilight pruner: INT4 scores, softmax, top-p
+ *                            threshold, per-group union (Sec. 4.2, Alg. 1,
+ *                            Definition 3.3, Appendix B.2)
+ *   twilight_sparse_decode   attention over the kept tokens (Definition 3.1,
+ *                            Appendix B.2), split along the list with a
+ *                            log-sum-exp combine
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *     `stream` is a hipStream_t passed as void* (NULL = default stream).
+ *   - The caller owns every buffer.  The library allocates nothing, frees
+ *     nothing, copies nothing between host and device and never synchronises;
+ *     all work is enqueued on `stream`.
+ *   - head_dim must be 128, page_size 16, quant_group 32,
+ *     num_q_heads / num_kv_heads one of 1, 2, 4, 8.
+ *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
+ *   - Token indices are logical positions in their sequence (0 .. len-1);
+ *     page ids are logical page numbers (token / 16); both ascending in every
+ *     list.  Pool addresses are resolved through page_table in the kernels.
+ *     A page_table entry outside [0, num_pool_pages) is skipped (its tokens
+ *     score -inf / are not written) - no out-of-bounds access is made.
+ *   - Return value: TW_OK (0) or a negative TW_E* code for problems the host
+ *     can see (NULL pointer, unsupported shape, workspace too small, launch
+ *     failure).  Data-dependent conditions set bits in the device `status`
+ *     word where an entry point has one.
+ */
+#ifndef TWILIGHT_H
+#define TWILIGHT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TW_ABI_VERSION 1
+
+#define TW_OK 0
+#define TW_EINVAL (-1)     /* NULL pointer, unsupported shape or parameter */
+#define TW_EWORKSPACE (-2) /* workspace smaller than twilight_workspace_bytes */
+#define TW_ELAUNCH (-3)    /* HIP reported an error at launch */
+
+/* status bits (device word) */
+#define TW_STATUS_UNION_TRUNCATED 1u /* a group's union exceeded union_stride */
+#define TW_STATUS_KEPT_TRUNCATED 2u  /* a head's kept list exceeded kept_stride */
+
+/*
+ * Paged KV cache of one layer.  Layouts (all row-major, page = 16 tokens):
+ *   k_pool, v_pool  bf16 [num_pool_pages][num_kv_heads][16][128]
+ *   kq_pool         u8   [num_pool_pages][num_kv_heads][16][64]
+ *                   INT4 codes 0..15 of K.  Dims 8w..8w+7 of a token form the
+ *                   32-bit little-endian word w (w = 0..15); its byte k
+ *                   (k = 0..3) holds code[8w+k] in the low nibble and
+ *                   code[8w+k+4] in the high nibble.
+ *   kq_meta         fp16 [num_pool_pages][num_kv_heads][16][4][2]
+ *                   (scale, zero) of each group of 32 dims:
+ *                   K ~ code * scale + zero           (Appendix B.1)
+ *   page_minmax     bf16 [num_pool_pages][num_kv_heads][2][128]
+ *                   element-wise (min, max) of K over the page's valid tokens
+ *   page_table      i32  [batch][max_pages_per_seq]  logical page -> pool page
+ *   seq_lens        i32  [batch]  tokens valid in the cache
+ */
+typedef struct twilight_kv {
+  int32_t batch;
+  int32_t num_q_heads;
+  int32_t num_kv_heads;
+  int32_t head_dim;          /* 128 */
+  int32_t page_size;         /* 16  */
+  int32_t quant_group;       /* 32  */
+  int32_t max_pages_per_seq; /* row length of page_table */
+  int32_t reserved;          /* 0 */
+  int64_t num_pool_pages;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  void* k_pool;
+  void* v_pool;
+  void* kq_pool;
+  void* kq_meta;
+  void* page_minmax;
+} twilight_kv_t;
+
+/*
+ * Append new tokens (stage 4; Section 4.2 "extra INT4 asymmetrically
+ * quantized K cache", Appendix B.1 "dynamic" quantisation with fp16 scale
+ * and zero).  For sequence b the n_new[b] rows starting at row
+ * new_offsets[b] of k_new / v_new become tokens start_pos[b] ..
+ * start_pos[b]+n_new[b]-1.  Written: k_pool, v_pool (bf16 copies), kq_pool,
+ * kq_meta, page_minmax of every page touched.  A page that already holds
+ * tokens below start_pos[b] keeps their contribution to page_minmax (which
+ * must be valid); otherwise its bounds are rebuilt from the new tokens.
+ * seq_lens is NOT read or written (the caller advances it).
+ *
+ * Quantisation, per token, KV head and group of 32 dims, fp32 arithmetic,
+ * every operation rounded on its own:
+ *   scale = fp16((max - min) * (1/15)),  zero = fp16(min),
+ *   code  = clamp(rint((x - zero) * (1 / scale)), 0, 15)   (0 if scale == 0).
+ * Inputs must be finite with |x| < 3e4 (fp16 range of scale and zero).
+ *
+ *   k_new, v_new   bf16 [total_new][num_kv_heads][128]; v_new may be NULL
+ *                  (V pool untouched).  kv->k_pool may be NULL (no bf16 copy).
+ *   start_pos, n_new, new_offsets   i32 [batch]
+ *   max_new        host: upper bound of n_new[] (sizes the launch)
+ */
+int twilight_kquant_append(const twilight_kv_t* kv, const void* k_new, const void* v_new,
+                           const int32_t* start_pos, const int32_t* n_new, const int32_t* new_offsets,
+                           int32_t max_new, void* stream);
+
+/*
+ * Token selector (stage 1; Section 4.1 "Token Selector ... conservative
+ * budget", Section 4 C1: per-page pooling, 16 tokens per page).  For every
+ * (sequence, query head): U[P] = sum_d max(q_d*min[P,d], q_d*max[P,d]) in
+ * fp32 - 16 partial sums of 8 consecutive dims each, left to right, then a
+ * pairwise tree over the partials - and the Kp = min(ceil(budget/16), pages)
+ * pages with the largest U are kept; equal U: lower page id first.
+ *
+ *   q              bf16 [batch][num_q_heads][128]
+ *   budget_tokens  i32  [batch]
+ *   sel_pages      i32  [batch][num_q_heads][max_sel]  out, ascending ids
+ *   sel_count      i32  [batch][num_q_heads]           out, min(Kp, max_sel)
+ *   ws             >= twilight_workspace_bytes(TW_WS_SELECT, ...)
+ */
+int twilight_select_pages(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
+                          int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Estimated scores alone (first half of stage 2; Section 4.2 "SpGEMV",
+ * Appendix B.1).  q is quantised per head to int8 (sq = max|q| * (1/127),
+ * qi = clamp(rint(q / sq), -127, 127)); per token and group j of 32 dims
+ * I_j = sum qi_d * code_d (int32), Qs_j = sum qi_d;
+ *   s_hat = ((T0 + T1) + (T2 + T3)) * (sq * (1/sqrt(128))),
+ *   T_j   = fl(scale_j * float(I_j)) + fl(zero_j * float(Qs_j))   (fp32).
+ * Candidate slot c of head (b, h) is token sel_pages[b][h][c / 16] * 16 +
+ * c % 16; slots at or beyond seq_lens[b] score -inf.
+ *
+ *   sel_pages      NULL = every page of the sequence (then max_sel is
+ *                  ignored and the row length is max_pages_per_seq * 16)
+ *   scores         fp32 [batch][num_q_heads][max_sel * 16]            out
+ *   dots           i32  [batch][num_q_heads][max_sel * 16][4] or NULL out
+ */
+int twilight_int4_score(const twilight_kv_t* kv, const void* q, const int32_t* sel_pages,
+                        const int32_t* sel_count, int32_t max_sel, float* scores, int32_t* dots,
+                        void* stream);
+
+/*
+ * Twilight pruner (stage 2; Section 4.2, Algorithm 1, Definition 3.3,
+ * Appendix B.2).  Per (sequence, query head): s_hat as above over the
+ * candidates, W = softmax(s_hat) over the candidates, tau* = the largest
+ * weight value whose upper set {W >= tau*} has mass >= p, kept = that upper
+ * set (all ties at the cut).  The threshold is searched on the bit pattern
+ * of s_hat, 8 bits per step, with masses accumulated in 64-bit fixed point.
+ * p >= 1 keeps every candidate.  Per (sequence, KV head): union = sorted
+ * unique union of the kept sets of its query heads.
+ *
+ *   sel_pages/sel_count/max_sel   as in twilight_int4_score (NULL = all)
+ *   p              host, in (0, 1]
+ *   kept_count     i32 [batch][num_q_heads]               out
+ *   kept_idx       i32 [batch][num_q_heads][kept_stride]  out or NULL
+ *   union_count    i32 [batch * num_kv_heads]             out
+ *   union_idx      i32 [batch * num_kv_heads][union_stride] out, ascending
+ *   status         u32 device word, OR-ed with TW_STATUS_* bits; lists are
+ *                  then cut after their first stride entries (counts too)
+ *   ws             >= twilight_workspace_bytes(TW_WS_PRUNE, ...)
+ */
+int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const int32_t* sel_pages,
+                        const int32_t* sel_count, int32_t max_sel, float p,
+                        int32_t* kept_count, int32_t* kept_idx, int32_t kept_stride,
+                        int32_t* union_count, int32_t* union_idx, int32_t union_stride,
+                        uint32_t* status, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Sparse decode attention (stage 3; Definition 3.1 with the weights
+ * renormalised over the attended set, Appendix B.2 group-wise varlen).
+ * Every query head of KV head g attends over union_idx[b*Hkv+g][0..count):
+ *   out = sum_t softmax_t(q.K_t / sqrt(128)) V_t      bf16 in, fp32 math.
+ * The list is split into chunks handled by different workgroups; partial
+ * (max, sum, accumulator) triples are merged by log-sum-exp.
+ *
+ *   union_idx      NULL = dense attention over all seq_lens[b] tokens
+ *                  (union_count and union_stride are then ignored)
+ *   out            bf16 [batch][num_q_heads][128]
+ *   lse            fp32 [batch][num_q_heads] or NULL: natural-log
+ *                  log-sum-exp of the scaled logits (-inf for an empty set,
+ *                  whose output row is 0)
+ *   ws             >= twilight_workspace_bytes(TW_WS_DECODE, ...)
+ */
+int twilight_sparse_decode(const twilight_kv_t* kv, const void* q, const int32_t* union_count,
+                           const int32_t* union_idx, int32_t union_stride, void* out, float* lse,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* Workspace sizes (host-only query; no GPU needed). */
+#define TW_WS_SELECT 0
+#define TW_WS_PRUNE 1
+#define TW_WS_DECODE 2
+/*  max_sel: as passed to the call (0 with sel_pages == NULL);
+ *  union_stride: as passed to sparse_decode (0 for dense). */
+size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, int32_t max_sel, int32_t union_stride);
+
+const char* twilight_strerror(int code);
+int twilight_abi_version(void);
+
+/*
+ * Per-kernel timing with HIP events recorded on the launch stream, for
+ * benchmarks.  mode 0 = off (default), 1 = bracket every kernel.  While on,
+ * each launch adds one record {kernel id, start event, stop event} (at most
+ * TW_PROF_MAX_RECORDS between two collects; further launches are not timed).
+ * twilight_prof_collect synchronises the events, writes up to `cap` records
+ * (kernel id, milliseconds) to the HOST arrays and clears the list; returns
+ * the number written.  Not thread-safe; one stream at a time.
+ */
+#define TW_PROF_MAX_RECORDS 4096
+#define TW_K_KQUANT_APPEND 0
+#define TW_K_PAGE_SCORE 1
+#define TW_K_PAGE_SELECT 2
+#define TW_K_INT4_SCORE 3
+#define TW_K_TOPP 4
+#define TW_K_UNION 5
+#define TW_K_DECODE 6
+#define TW_K_COMBINE 7
+#define TW_K_COUNT 8
+int twilight_prof_enable(int mode);
+int twilight_prof_collect(int32_t* kernel_ids /*host*/, float* ms /*host*/, int32_t cap);
+const char* twilight_kernel_name(int kernel_id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TWILIGHT_H */

@@ -1,0 +1,140 @@
+"""ctypes binding of libtwilight.so - argument marshalling only.
+
+Every function has the name and argument order of its C entry point
+(include/twilight.h).  Tensors are torch CUDA tensors used purely as device
+memory; the current torch stream is passed as the HIP stream.  There is no
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtwilight.so")
+
+TW_WS_SELECT, TW_WS_PRUNE, TW_WS_DECODE = 0, 1, 2
+TW_STATUS_UNION_TRUNCATED, TW_STATUS_KEPT_TRUNCATED = 1, 2
+KERNEL_NAMES = ["kquant_append", "page_score", "page_select", "int4_score", "topp", "union",
+                "sparse_decode", "combine"]
+
+_vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+
+
+class twilight_kv_t(ctypes.Structure):
+    _fields_ = [("batch", _i32), ("num_q_heads", _i32), ("num_kv_heads", _i32), ("head_dim", _i32),
+                ("page_size", _i32), ("quant_group", _i32), ("max_pages_per_seq", _i32), ("reserved", _i32),
+                ("num_pool_pages", _i64), ("page_table", _vp), ("seq_lens", _vp), ("k_pool", _vp),
+                ("v_pool", _vp), ("kq_pool", _vp), ("kq_meta", _vp), ("page_minmax", _vp)]
+
+
+class TwilightError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    """Load libtwilight.so (built by paper_2502_02770_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise TwilightError("libtwilight.so not found at %s - run `python -m paper_2502_02770_amd.build`" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    kvp = ctypes.POINTER(twilight_kv_t)
+    L.twilight_kquant_append.argtypes = [kvp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]
+    L.twilight_select_pages.argtypes = [kvp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
+    L.twilight_int4_score.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
+    L.twilight_topp_prune.argtypes = [kvp, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
+    L.twilight_sparse_decode.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
+    L.twilight_workspace_bytes.argtypes = [ctypes.c_int, kvp, _i32, _i32]
+    L.twilight_workspace_bytes.restype = _sz
+    L.twilight_strerror.argtypes = [ctypes.c_int]
+    L.twilight_strerror.restype = ctypes.c_char_p
+    L.twilight_abi_version.restype = ctypes.c_int
+    L.twilight_prof_enable.argtypes = [ctypes.c_int]
+    L.twilight_prof_collect.argtypes = [_vp, _vp, _i32]
+    L.twilight_kernel_name.argtypes = [ctypes.c_int]
+    L.twilight_kernel_name.restype = ctypes.c_char_p
+    for f in ("twilight_kquant_append", "twilight_select_pages", "twilight_int4_score", "twilight_topp_prune",
+              "twilight_sparse_decode", "twilight_prof_enable", "twilight_prof_collect"):
+        getattr(L, f).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor required"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(code):
+    if code != 0:
+        raise TwilightError("twilight call failed (%d): %s" % (code, lib().twilight_strerror(code).decode()))
+
+
+def make_kv(batch, num_q_heads, num_kv_heads, max_pages_per_seq, num_pool_pages, page_table, seq_lens,
+            k_pool=None, v_pool=None, kq_pool=None, kq_meta=None, page_minmax=None):
+    """Fill a twilight_kv_t from torch tensors (which the caller keeps alive)."""
+    kv = twilight_kv_t()
+    kv.batch, kv.num_q_heads, kv.num_kv_heads = batch, num_q_heads, num_kv_heads
+    kv.head_dim, kv.page_size, kv.quant_group = 128, 16, 32
+    kv.max_pages_per_seq, kv.reserved, kv.num_pool_pages = max_pages_per_seq, 0, num_pool_pages
+    for name, t in (("page_table", page_table), ("seq_lens", seq_lens), ("k_pool", k_pool), ("v_pool", v_pool),
+                    ("kq_pool", kq_pool), ("kq_meta", kq_meta), ("page_minmax", page_minmax)):
+        setattr(kv, name, None if t is None else t.data_ptr())
+    return kv
+
+
+def twilight_workspace_bytes(which, kv, max_sel=0, union_stride=0):
+    return int(lib().twilight_workspace_bytes(which, ctypes.byref(kv), max_sel, union_stride))
+
+
+def twilight_kquant_append(kv, k_new, v_new, start_pos, n_new, new_offsets, max_new):
+    _check(lib().twilight_kquant_append(ctypes.byref(kv), _ptr(k_new), _ptr(v_new), _ptr(start_pos), _ptr(n_new),
+                                        _ptr(new_offsets), int(max_new), _stream()))
+
+
+def twilight_select_pages(kv, q, budget_tokens, sel_pages, sel_count, max_sel, ws):
+    _check(lib().twilight_select_pages(ctypes.byref(kv), _ptr(q), _ptr(budget_tokens), _ptr(sel_pages),
+                                       _ptr(sel_count), int(max_sel), _ptr(ws), ws.numel() * ws.element_size(),
+                                       _stream()))
+
+
+def twilight_int4_score(kv, q, sel_pages, sel_count, max_sel, scores, dots=None):
+    _check(lib().twilight_int4_score(ctypes.byref(kv), _ptr(q), _ptr(sel_pages), _ptr(sel_count), int(max_sel),
+                                     _ptr(scores), _ptr(dots), _stream()))
+
+
+def twilight_topp_prune(kv, q, sel_pages, sel_count, max_sel, p, kept_count, kept_idx, kept_stride,
+                        union_count, union_idx, union_stride, status, ws):
+    _check(lib().twilight_topp_prune(ctypes.byref(kv), _ptr(q), _ptr(sel_pages), _ptr(sel_count), int(max_sel),
+                                     float(p), _ptr(kept_count), _ptr(kept_idx), int(kept_stride),
+                                     _ptr(union_count), _ptr(union_idx), int(union_stride), _ptr(status),
+                                     _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def twilight_sparse_decode(kv, q, union_count, union_idx, union_stride, out, lse, ws):
+    _check(lib().twilight_sparse_decode(ctypes.byref(kv), _ptr(q), _ptr(union_count), _ptr(union_idx),
+                                        int(union_stride), _ptr(out), _ptr(lse), _ptr(ws),
+                                        ws.numel() * ws.element_size(), _stream()))
+
+
+def twilight_prof_enable(mode):
+    _check(lib().twilight_prof_enable(int(mode)))
+
+
+def twilight_prof_collect(cap=4096):
+    """-> list of (kernel name, milliseconds) since the last collect."""
+    ids = (ctypes.c_int32 * cap)()
+    ms = (ctypes.c_float * cap)()
+    n = lib().twilight_prof_collect(ids, ms, cap)
+    return [(KERNEL_NAMES[ids[i]], float(ms[i])) for i in range(n)]

@@ -1,0 +1,199 @@
+// Stage 1: Quest-style page selector (paper: Section 4.1 "Token Selector",
+// Section 4 challenge C1: pooling per 16-token page).
+//
+// page_score:  U[h,P] = sum_d max(q_d*min[P,d], q_d*max[P,d]).  16 lanes per
+//              page, each lane one 16-byte load of min and of max (8 dims);
+//              the G query heads of the KV head share the loaded bounds.
+//              fp32 order: 8 dims left to right per lane, then a pairwise
+//              DPP tree over the 16 lanes (bit-reproducible).
+// page_select: per (sequence, query head) the Kp largest bounds, ties to the
+//              lower page id, by a 4 x 8-bit radix select on the order-
+//              preserving key, then an ordered compaction (ascending ids).
+#include "tw_common.h"
+
+namespace {
+
+constexpr int PS_PAGES_PER_WG = 64;   // 4 waves x 4 pages x 4 iterations
+
+struct ScoreArgs {
+  const uint32_t* q;          // bf16 pairs [b][Hq][64]
+  const uint4* page_minmax;   // [page][Hkv][2][16]
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  float* scores;              // [b][Hq][max_pages]
+  int Hq, Hkv, max_pages;
+  long long pool_pages;
+};
+
+template <int G>
+__global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
+  const int b = blockIdx.z, g = blockIdx.y;
+  const int tid = threadIdx.x, seg = tid & 15, grp = tid >> 4;   // grp: 0..15 page slot in the WG
+  const int n = a.seq_lens[b];
+  int P = (n + TW_PAGE - 1) / TW_PAGE;
+  if (P > a.max_pages) P = a.max_pages;
+  const int base = blockIdx.x * PS_PAGES_PER_WG;
+  if (base >= P) return;
+
+  // q of the G heads, the 8 dims of this lane; the sign decides which corner
+  // of the [min,max] box maximises q_d * k_d.
+  float q[G][8];
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    const uint4 r = *(const uint4*)(a.q + ((long long)(b * a.Hq + g * G + h)) * 64 + seg * 4);
+    tw_unpack8(r, q[h]);
+  }
+
+#pragma unroll 2
+  for (int it = 0; it < PS_PAGES_PER_WG / 16; ++it) {
+    const int lp = base + it * 16 + grp;
+    const bool live = lp < P;
+    long long pool = live ? (long long)a.page_table[(long long)b * a.max_pages + lp] : -1;
+    const bool ok = pool >= 0 && pool < a.pool_pages;
+    float mn[8], mx[8];
+    if (ok) {
+      const uint4* pm = a.page_minmax + (pool * a.Hkv + g) * 32;
+      const uint4 rmn = pm[seg], rmx = pm[16 + seg];
+      tw_unpack8(rmn, mn);
+      tw_unpack8(rmx, mx);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { mn[i] = 0.f; mx[i] = 0.f; }
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        // the product of two bf16 values is exact in fp32, so this fused
+        // multiply-add rounds exactly like "acc + q*v"
+        const float v = q[h][i] > 0.f ? mx[i] : mn[i];
+        acc = __builtin_fmaf(q[h][i], v, acc);
+      }
+      acc = tw_row16_sum(acc);
+      if (seg == 0 && live)
+        a.scores[((long long)(b * a.Hq + g * G + h)) * a.max_pages + lp] =
+            ok ? __fadd_rn(acc, 0.0f) : -__builtin_inff();
+    }
+  }
+}
+
+struct SelectArgs {
+  const float* scores;        // [b][Hq][max_pages]
+  const int32_t* seq_lens;
+  const int32_t* budget;
+  int32_t* sel_pages;         // [b][Hq][max_sel]
+  int32_t* sel_count;
+  int Hq, max_pages, max_sel;
+};
+
+__global__ __launch_bounds__(256) void page_select_kernel(SelectArgs a) {
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  const int B = a.budget[b];
+  long long kp = B > 0 ? ((long long)B + TW_PAGE - 1) / TW_PAGE : 0;
+  if (kp > P) kp = P;
+  if (kp > a.max_sel) kp = a.max_sel;
+  const int Kp = (int)kp;
+  const float* sc = a.scores + ((long long)(b * a.Hq + h)) * a.max_pages;
+  int32_t* out = a.sel_pages + ((long long)(b * a.Hq + h)) * a.max_sel;
+  if (tid == 0) a.sel_count[b * a.Hq + h] = Kp;
+  if (Kp == 0) return;
+  if (Kp == P) {                         // budget covers the sequence: every page
+    for (int i = tid; i < P; i += 256) out[i] = i;
+    return;
+  }
+
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t wsum[17];
+  __shared__ uint32_t sh_prefix, sh_remaining;
+  uint32_t prefix = 0, remaining = (uint32_t)Kp;
+  // radix select of the Kp-th largest key, 8 bits per pass from the top
+#pragma unroll 1
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    hist[tid] = 0;
+    __syncthreads();
+    const uint32_t himask = shift == 24 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    for (int i = tid; i < P; i += 256) {
+      const uint32_t key = tw_float_key(sc[i]);
+      if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    // thread t looks at digit 255-t: inclusive count of keys with digit >= its own
+    const uint32_t mine = hist[255 - tid];
+    uint32_t total;
+    const uint32_t incl = tw_block_scan_u32(mine, wsum, &total);
+    if (incl >= remaining && incl - mine < remaining) {
+      sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+      sh_remaining = remaining - (incl - mine);
+    }
+    __syncthreads();
+    prefix = sh_prefix;
+    remaining = sh_remaining;
+    __syncthreads();
+  }
+  // prefix = key of the Kp-th largest bound; `remaining` pages with exactly
+  // that key are taken, lowest ids first.
+  const uint32_t T = prefix, need_eq = remaining;
+  uint32_t run_gt = 0, run_eq = 0;
+#pragma unroll 1
+  for (int base = 0; base < P; base += 256) {
+    const int i = base + tid;
+    uint32_t key = 0;
+    const bool in = i < P;
+    if (in) key = tw_float_key(sc[i]);
+    const uint32_t fgt = (in && key > T) ? 1u : 0u;
+    const uint32_t feq = (in && key == T) ? 1u : 0u;
+    uint32_t total;
+    const uint32_t incl = tw_block_scan_u32(fgt | (feq << 16), wsum, &total);
+    const uint32_t gt_before = run_gt + (incl & 0xFFFFu) - fgt;
+    const uint32_t eq_before = run_eq + (incl >> 16) - feq;
+    if (fgt || (feq && eq_before < need_eq)) {
+      const uint32_t pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
+      if (pos < (uint32_t)a.max_sel) out[pos] = i;
+    }
+    run_gt += total & 0xFFFFu;
+    run_eq += total >> 16;
+  }
+}
+
+template <int G>
+void launch_score(const ScoreArgs& a, dim3 grid, hipStream_t s) {
+  hipLaunchKernelGGL(page_score_kernel<G>, grid, dim3(256), 0, s, a);
+}
+
+}  // namespace
+
+extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
+                                     int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
+                                     void* ws, size_t ws_bytes, void* stream) {
+  TwDims d;
+  if (int e = tw_check_kv(kv, &d)) return e;
+  if (!q || !budget_tokens || !sel_pages || !sel_count || max_sel <= 0 || !kv->page_minmax) return TW_EINVAL;
+  if (!ws || ws_bytes < twilight_workspace_bytes(TW_WS_SELECT, kv, max_sel, 0)) return TW_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+
+  ScoreArgs a;
+  a.q = (const uint32_t*)q; a.page_minmax = (const uint4*)kv->page_minmax;
+  a.page_table = kv->page_table; a.seq_lens = kv->seq_lens; a.scores = (float*)ws;
+  a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.pool_pages = d.pool_pages;
+  dim3 grid((d.max_pages + PS_PAGES_PER_WG - 1) / PS_PAGES_PER_WG, d.Hkv, d.batch);
+  tw_prof_before(TW_K_PAGE_SCORE, s);
+  switch (d.G) {
+    case 1: launch_score<1>(a, grid, s); break;
+    case 2: launch_score<2>(a, grid, s); break;
+    case 4: launch_score<4>(a, grid, s); break;
+    default: launch_score<8>(a, grid, s); break;
+  }
+  if (int e = tw_prof_after(s)) return e;
+
+  SelectArgs sa;
+  sa.scores = (const float*)ws; sa.seq_lens = kv->seq_lens; sa.budget = budget_tokens;
+  sa.sel_pages = sel_pages; sa.sel_count = sel_count;
+  sa.Hq = d.Hq; sa.max_pages = d.max_pages; sa.max_sel = max_sel;
+  tw_prof_before(TW_K_PAGE_SELECT, s);
+  hipLaunchKernelGGL(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+  return tw_prof_after(s);
+}

@@ -1,0 +1,564 @@
+// Stage 2: the Twilight pruner (paper: Section 4.2, Algorithm 1,
+// Definition 3.3, Appendix B.1 and B.2).
+//
+// int4_score  estimated logits from the INT4 K copy.  One wave = one page per
+//             step: 64 lanes x 16 B = the page's 1 KiB of codes, lane =
+//             (token, group of 32 dims); 8 integer dot4 per lane and head,
+//             scale/zero applied per group, quad DPP sum over the 4 groups.
+// topp        per (sequence, query head): max, then a radix bisection of the
+//             threshold on the fixed-point distance to the max logit (11 bits
+//             per pass, masses in 64-bit fixed point so that sums do not
+//             depend on the order of the atomics), finished by an exact
+//             resolve on the score's own bit pattern inside one wave.
+// union       per (sequence, KV head): bitmap in LDS, ordered emit.
+#include "tw_common.h"
+
+namespace {
+
+constexpr float kInv127 = 0x1.020408p-7f;    // fp32(1/127)
+constexpr float kRsqrtD = 0x1.6a09e6p-4f;    // fp32(1/sqrt(128))
+constexpr uint32_t kKeyNegInf = 0x007FFFFFu;  // tw_float_key(-inf)
+
+// ------------------------------------------------------------------ int4_score
+struct ScoreArgs {
+  const uint16_t* q;          // bf16 [b][Hq][128]
+  const int32_t* sel_pages;   // [b][Hq][max_sel] or nullptr (all pages)
+  const int32_t* sel_count;
+  const int32_t* page_table;
+  const int32_t* seq_lens;
+  const uint4* kq_pool;       // 64 uint4 per (page, head)
+  const uint32_t* kq_meta;    // 64 words per (page, head)
+  float* scores;              // [b][Hq][cand_stride]
+  int32_t* dots;              // [b][Hq][cand_stride][4] or nullptr
+  int Hq, Hkv, max_pages, max_sel, cand_stride, pw;   // pw: pages per wave (<= 64)
+  long long pool_pages;
+};
+
+// NH = heads scored per loaded page: 1 with per-head page lists, G when every
+// page is a candidate (the G heads of a KV head then share each load).
+template <int NH, bool FULL, bool DOTS>
+__global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int b, g, h0;
+  if (FULL) { b = blockIdx.y / a.Hkv; g = blockIdx.y % a.Hkv; h0 = g * NH; }
+  else      { b = blockIdx.y / a.Hq;  h0 = blockIdx.y % a.Hq; g = h0 / (a.Hq / a.Hkv); }
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  int count = P;
+  if (!FULL) { count = a.sel_count[b * a.Hq + h0]; if (count > a.max_sel) count = a.max_sel; }
+  const int wg_first = blockIdx.x * 4 * a.pw;
+  if (wg_first >= count) return;
+
+  // ---- quantise q of the NH heads to int8 (symmetric, per head)
+  __shared__ int qi_s[NH][32];
+  __shared__ float red[4];
+  __shared__ float c_s[NH];
+#pragma unroll 1
+  for (int h = 0; h < NH; ++h) {
+    float v = 0.f;
+    if (tid < 128) v = __uint_as_float((uint32_t)a.q[((long long)(b * a.Hq + h0 + h)) * 128 + tid] << 16);
+    float av = fabsf(v);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) av = fmaxf(av, __shfl_xor(av, o, 64));
+    if (lane == 0) red[wave] = av;
+    __syncthreads();
+    const float amax = fmaxf(red[0], red[1]);
+    const float sq = __fmul_rn(amax, kInv127);
+    if (tid < 128) {
+      int qi = 0;
+      if (sq > 0.f) {
+        float t = rintf(__fdiv_rn(v, sq));
+        t = fminf(fmaxf(t, -127.f), 127.f);
+        qi = (int)t;
+      }
+      ((int8_t*)qi_s[h])[tid] = (int8_t)qi;
+    }
+    if (tid == 0) c_s[h] = __fmul_rn(sq, kRsqrtD);
+    __syncthreads();
+  }
+  const int j = lane & 3;                       // this lane's group of 32 dims
+  int qw[NH][8];
+  float qsf[NH], cc[NH];
+#pragma unroll
+  for (int h = 0; h < NH; ++h) {
+    int qs = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      qw[h][k] = qi_s[h][8 * j + k];
+      qs = __builtin_amdgcn_sdot4(qw[h][k], 0x01010101, qs, false);
+    }
+    qsf[h] = (float)qs;
+    cc[h] = c_s[h];
+  }
+
+  // ---- this wave's pages: lane k holds the k-th one (logical id, pool id)
+  const int first = wg_first + wave * a.pw;
+  int my_lp = -1, my_pool = -1;
+  if (lane < a.pw && first + lane < count) {
+    my_lp = FULL ? first + lane : a.sel_pages[((long long)(b * a.Hq + h0)) * a.max_sel + first + lane];
+    if (my_lp >= 0 && my_lp < P) {
+      const int pp = a.page_table[(long long)b * a.max_pages + my_lp];
+      if (pp >= 0 && pp < a.pool_pages) my_pool = pp;
+    }
+  }
+  int npages = count - first;
+  if (npages > a.pw) npages = a.pw;
+
+#pragma unroll 1
+  for (int k0 = 0; k0 < npages; k0 += 4) {
+#pragma unroll
+   for (int kk = 0; kk < 4; ++kk) {
+    const int k = k0 + kk;                     // wave-uniform; pages past the end act as invalid
+    const int lp = __builtin_amdgcn_readlane(my_lp, k & 63);
+    const int pool = k < npages ? __builtin_amdgcn_readlane(my_pool, k & 63) : -1;
+    uint4 nib = make_uint4(0, 0, 0, 0);
+    uint32_t meta = 0;
+    if (pool >= 0) {
+      const long long blk = ((long long)pool * a.Hkv + g) * 64;
+      nib = a.kq_pool[blk + lane];
+      meta = a.kq_meta[blk + lane];
+    }
+    const int u0 = nib.x & 0x0F0F0F0F, u1 = (nib.x >> 4) & 0x0F0F0F0F;
+    const int u2 = nib.y & 0x0F0F0F0F, u3 = (nib.y >> 4) & 0x0F0F0F0F;
+    const int u4 = nib.z & 0x0F0F0F0F, u5 = (nib.z >> 4) & 0x0F0F0F0F;
+    const int u6 = nib.w & 0x0F0F0F0F, u7 = (nib.w >> 4) & 0x0F0F0F0F;
+    const float sc = __half2float(__ushort_as_half((unsigned short)(meta & 0xFFFFu)));
+    const float ze = __half2float(__ushort_as_half((unsigned short)(meta >> 16)));
+    const int tok = lp * TW_PAGE + (lane >> 2);
+    const bool valid = pool >= 0 && tok < n;
+    const long long slot = (long long)(first + k) * TW_PAGE + (lane >> 2);
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      int I = __builtin_amdgcn_sdot4(qw[h][0], u0, 0, false);
+      I = __builtin_amdgcn_sdot4(qw[h][1], u1, I, false);
+      I = __builtin_amdgcn_sdot4(qw[h][2], u2, I, false);
+      I = __builtin_amdgcn_sdot4(qw[h][3], u3, I, false);
+      I = __builtin_amdgcn_sdot4(qw[h][4], u4, I, false);
+      I = __builtin_amdgcn_sdot4(qw[h][5], u5, I, false);
+      I = __builtin_amdgcn_sdot4(qw[h][6], u6, I, false);
+      I = __builtin_amdgcn_sdot4(qw[h][7], u7, I, false);
+      float T = __fadd_rn(__fmul_rn(sc, (float)I), __fmul_rn(ze, qsf[h]));
+      T = tw_quad_sum(T);
+      const float s = valid ? __fmul_rn(T, cc[h]) : -__builtin_inff();
+      const long long row = ((long long)(b * a.Hq + h0 + h)) * a.cand_stride;
+      if (k < npages) {
+        if (j == 0) a.scores[row + slot] = s;
+        if (DOTS) a.dots[(row + slot) * 4 + j] = valid ? I : 0;
+      }
+    }
+   }
+  }
+}
+
+// ------------------------------------------------------------------ top-p
+__device__ __forceinline__ unsigned long long tw_wave_sum_u64(unsigned long long v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Inclusive scan of one u64 per thread over a 1024-thread block.
+__device__ __forceinline__ unsigned long long tw_block_scan_u64(unsigned long long v, unsigned long long* wsum,
+                                                                unsigned long long* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  unsigned long long x = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    unsigned long long y = __shfl_up(x, o, 64);
+    if (lane >= o) x += y;
+  }
+  if (lane == 63) wsum[wave] = x;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned long long run = 0;
+    for (int w = 0; w < nw; ++w) { unsigned long long t = wsum[w]; wsum[w] = run; run += t; }
+    wsum[16] = run;
+  }
+  __syncthreads();
+  x += wsum[wave];
+  *total = wsum[16];
+  __syncthreads();
+  return x;
+}
+
+struct ToppArgs {
+  const float* scores;        // [b][Hq][cand_stride]
+  const int32_t* sel_pages;   // or nullptr
+  const int32_t* sel_count;
+  const int32_t* seq_lens;
+  int32_t* kept_count;
+  int32_t* kept_idx;          // or nullptr
+  uint32_t* thr_key;          // [b][Hq] out: kept <=> key(score) >= thr_key
+  uint32_t* status;
+  int Hq, max_pages, max_sel, cand_stride, kept_stride;
+  float p;
+};
+
+constexpr int TP_THREADS = 1024;
+constexpr int TP_NB = 2048;        // buckets per radix pass
+constexpr int TP_EPT = 8;          // register-cached elements per thread
+
+// distance to the max logit in 2^-26 units, saturating at 64
+__device__ __forceinline__ uint32_t tp_rank(float m, float s) {
+  const float d = __fsub_rn(m, s);
+  return d >= 64.f ? 0xFFFFFFFFu : (uint32_t)(d * 67108864.f);
+}
+// softmax numerator in 2^-40 fixed point
+__device__ __forceinline__ unsigned long long tp_mass(float m, float s) {
+  return (unsigned long long)(__expf(__fsub_rn(s, m)) * 1099511627776.f);
+}
+
+template <bool CACHED>
+__global__ __launch_bounds__(TP_THREADS) void topp_kernel(ToppArgs a) {
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int bh = b * a.Hq + h;
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  int count = P;
+  if (a.sel_pages) { count = a.sel_count[bh]; if (count > a.max_sel) count = a.max_sel; if (count < 0) count = 0; }
+  const int N = count * TW_PAGE;
+  const float* row = a.scores + (long long)bh * a.cand_stride;
+  const int iters = CACHED ? TP_EPT : (N + TP_THREADS - 1) / TP_THREADS;
+
+  __shared__ unsigned long long histM[TP_NB];
+  __shared__ uint32_t histC[TP_NB];
+  __shared__ unsigned long long wsum64[17];
+  __shared__ uint32_t wsum32[17];
+  __shared__ float redf[16];
+  __shared__ uint32_t sh_bkt, sh_pop, sh_T, sh_n;
+  __shared__ unsigned long long sh_A;
+  __shared__ uint32_t cand_key[64];
+  __shared__ unsigned long long cand_mass[64];
+
+  float sreg[CACHED ? TP_EPT : 1];
+  if (CACHED) {
+#pragma unroll
+    for (int e = 0; e < TP_EPT; ++e) {
+      const int i = e * TP_THREADS + tid;
+      sreg[e] = i < N ? row[i] : -__builtin_inff();
+    }
+  }
+#define TP_LOAD(e) (CACHED ? sreg[CACHED ? (e) : 0] : ((e) * TP_THREADS + tid < N ? row[(e) * TP_THREADS + tid] : -__builtin_inff()))
+
+  // ---- pass 1: max
+  float m = -__builtin_inff();
+#pragma unroll
+  for (int e = 0; e < iters; ++e) m = fmaxf(m, TP_LOAD(e));
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+  if (lane == 0) redf[wave] = m;
+  __syncthreads();
+  m = redf[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) m = fmaxf(m, redf[w]);
+
+  uint32_t T;
+  if (!(m > -__builtin_inff())) {
+    T = 0xFFFFFFFFu;                          // no valid candidate: keep nothing
+  } else if (a.p >= 1.0f) {
+    T = kKeyNegInf + 1u;                      // keep every finite score
+  } else {
+    // ---- radix bisection on rank = (m - s) * 2^26: 11 + 11 + 10 bits
+    uint32_t prefix = 0, pop = 0;
+    unsigned long long A = 0, target = 0;
+    int shift = 21, nbits = 11, level = 0;
+#pragma unroll 1
+    for (;;) {
+      for (int i = tid; i < TP_NB; i += TP_THREADS) { histM[i] = 0; histC[i] = 0; }
+      __syncthreads();
+      const uint32_t himask = level == 0 ? 0u : (0xFFFFFFFFu << (shift + nbits));
+#pragma unroll
+      for (int e = 0; e < iters; ++e) {
+        const float s = TP_LOAD(e);
+        if (s > -__builtin_inff()) {
+          const uint32_t r = tp_rank(m, s);
+          if ((r & himask) == prefix) {
+            const uint32_t bk = (r >> shift) & ((1u << nbits) - 1u);
+            atomicAdd(&histM[bk], tp_mass(m, s));
+            atomicAdd(&histC[bk], 1u);
+          }
+        }
+      }
+      __syncthreads();
+      // thread t owns buckets 2t, 2t+1 (ascending rank = descending score)
+      const unsigned long long m0 = histM[2 * tid], m1 = histM[2 * tid + 1];
+      unsigned long long total;
+      const unsigned long long incl = tw_block_scan_u64(m0 + m1, wsum64, &total);
+      if (level == 0) {                       // total = Z; mass needed = p * Z
+        const double t = ceil((double)a.p * (double)total);
+        target = t < 1.0 ? 1ull : (unsigned long long)t;
+        if (target > total) target = total;
+      }
+      const unsigned long long before = A + incl - (m0 + m1);
+      if (before < target && before + m0 >= target) {
+        sh_bkt = 2 * tid; sh_A = before; sh_pop = histC[2 * tid];
+      } else if (before + m0 < target && before + m0 + m1 >= target) {
+        sh_bkt = 2 * tid + 1; sh_A = before + m0; sh_pop = histC[2 * tid + 1];
+      }
+      __syncthreads();
+      prefix |= sh_bkt << shift;
+      A = sh_A;
+      pop = sh_pop;
+      __syncthreads();
+      if (pop <= 64 || level == 2) break;
+      ++level;
+      if (level == 1) { shift = 10; nbits = 11; } else { shift = 0; nbits = 10; }
+    }
+    // ---- the threshold lies among the `pop` scores whose rank matches
+    // `prefix` down to bit `shift`; mass A lies strictly above them.
+    const uint32_t fmask = shift == 0 ? 0xFFFFFFFFu : (0xFFFFFFFFu << shift);
+    if (pop <= 64) {
+      if (tid == 0) sh_n = 0;
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < iters; ++e) {
+        const float s = TP_LOAD(e);
+        if (s > -__builtin_inff() && (tp_rank(m, s) & fmask) == prefix) {
+          const uint32_t at = atomicAdd(&sh_n, 1u);
+          if (at < 64) { cand_key[at] = tw_float_key(s); cand_mass[at] = tp_mass(m, s); }
+        }
+      }
+      __syncthreads();
+      if (wave == 0) {
+        const uint32_t cn = sh_n < 64 ? sh_n : 64;
+        const uint32_t kx = lane < cn ? cand_key[lane] : 0u;
+        unsigned long long S = 0;
+        for (uint32_t jx = 0; jx < cn; ++jx)
+          if (cand_key[jx] >= kx) S += cand_mass[jx];
+        uint32_t best = (lane < cn && A + S >= target) ? kx : 0u;
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) { const uint32_t y = __shfl_xor(best, o, 64); best = y > best ? y : best; }
+        if (lane == 0) sh_T = best;
+      }
+      __syncthreads();
+      T = sh_T;
+    } else {
+      // more than 64 scores within 2^-26 of each other: keep all of them
+      uint32_t kmin = 0xFFFFFFFFu;
+#pragma unroll
+      for (int e = 0; e < iters; ++e) {
+        const float s = TP_LOAD(e);
+        if (s > -__builtin_inff() && (tp_rank(m, s) & fmask) == prefix) {
+          const uint32_t k = tw_float_key(s);
+          kmin = k < kmin ? k : kmin;
+        }
+      }
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) { const uint32_t y = __shfl_xor(kmin, o, 64); kmin = y < kmin ? y : kmin; }
+      if (lane == 0) wsum32[wave] = kmin;
+      __syncthreads();
+      kmin = wsum32[0];
+      for (int w = 1; w < 16; ++w) kmin = wsum32[w] < kmin ? wsum32[w] : kmin;
+      __syncthreads();
+      T = kmin;
+    }
+  }
+
+  // ---- emit: count and (optionally) the ascending token list
+  if (tid == 0) a.thr_key[bh] = T;
+  uint32_t run = 0;
+  int32_t* out = a.kept_idx ? a.kept_idx + (long long)bh * a.kept_stride : nullptr;
+#pragma unroll
+  for (int e = 0; e < iters; ++e) {
+    const int i = e * TP_THREADS + tid;
+    const float s = TP_LOAD(e);
+    const uint32_t f = (i < N && tw_float_key(s) >= T) ? 1u : 0u;
+    uint32_t total;
+    const uint32_t incl = tw_block_scan_u32(f, wsum32, &total);
+    if (f && out) {
+      const uint32_t pos = run + incl - 1;
+      if (pos < (uint32_t)a.kept_stride) {
+        const int pg = a.sel_pages ? a.sel_pages[(long long)bh * a.max_sel + (i >> 4)] : (i >> 4);
+        out[pos] = pg * TW_PAGE + (i & 15);
+      }
+    }
+    run += total;
+  }
+  if (tid == 0) {
+    if (out && run > (uint32_t)a.kept_stride) {
+      atomicOr(a.status, TW_STATUS_KEPT_TRUNCATED);
+      run = a.kept_stride;
+    }
+    a.kept_count[bh] = (int32_t)run;
+  }
+#undef TP_LOAD
+}
+
+// ------------------------------------------------------------------ union
+struct UnionArgs {
+  const float* scores;
+  const uint32_t* thr_key;
+  const int32_t* sel_pages;   // or nullptr
+  const int32_t* sel_count;
+  const int32_t* seq_lens;
+  int32_t* union_count;
+  int32_t* union_idx;
+  uint32_t* status;
+  int Hq, Hkv, G, max_pages, max_sel, cand_stride, union_stride;
+};
+
+constexpr int UN_THREADS = 1024;
+constexpr int UN_SEG = 1 << 18;               // tokens per bitmap segment (32 KiB of LDS)
+
+__global__ __launch_bounds__(UN_THREADS) void union_kernel(UnionArgs a) {
+  const int b = blockIdx.x / a.Hkv, g = blockIdx.x % a.Hkv, tid = threadIdx.x;
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
+  __shared__ uint32_t bitmap[UN_SEG / 32];
+  __shared__ uint32_t wsum[17];
+  int32_t* out = a.union_idx + (long long)blockIdx.x * a.union_stride;
+  uint32_t run = 0;
+#pragma unroll 1
+  for (int seg0 = 0; seg0 < ntok; seg0 += UN_SEG) {
+    const int seg1 = seg0 + UN_SEG < ntok ? seg0 + UN_SEG : ntok;
+    for (int i = tid; i < UN_SEG / 32; i += UN_THREADS) bitmap[i] = 0;
+    __syncthreads();
+#pragma unroll 1
+    for (int hh = 0; hh < a.G; ++hh) {
+      const int bh = b * a.Hq + g * a.G + hh;
+      const uint32_t T = a.thr_key[bh];
+      const float* row = a.scores + (long long)bh * a.cand_stride;
+      if (a.sel_pages) {
+        int count = a.sel_count[bh];
+        if (count > a.max_sel) count = a.max_sel;
+        const int32_t* pages = a.sel_pages + (long long)bh * a.max_sel;
+        // page slots [s0, s1) whose tokens fall in [seg0, seg1): the list is ascending
+        int lo = 0, hi = count;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (pages[mid] * TW_PAGE + TW_PAGE <= seg0) lo = mid + 1; else hi = mid; }
+        const int s0 = lo;
+        hi = count;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (pages[mid] * TW_PAGE < seg1) lo = mid + 1; else hi = mid; }
+        const int s1 = lo;
+        for (int c = s0 * TW_PAGE + tid; c < s1 * TW_PAGE; c += UN_THREADS) {
+          if (tw_float_key(row[c]) >= T) {
+            const int t = pages[c >> 4] * TW_PAGE + (c & 15) - seg0;
+            if (t >= 0 && t < UN_SEG) atomicOr(&bitmap[t >> 5], 1u << (t & 31));
+          }
+        }
+      } else {
+        for (int c = seg0 + tid; c < seg1; c += UN_THREADS)
+          if (tw_float_key(row[c]) >= T) { const int t = c - seg0; atomicOr(&bitmap[t >> 5], 1u << (t & 31)); }
+      }
+    }
+    __syncthreads();
+    const int words = (seg1 - seg0 + 31) >> 5;
+#pragma unroll 1
+    for (int wb = 0; wb < words; wb += UN_THREADS) {
+      uint32_t w = wb + tid < words ? bitmap[wb + tid] : 0u;
+      uint32_t total;
+      const uint32_t incl = tw_block_scan_u32(__popc(w), wsum, &total);
+      uint32_t pos = run + incl - __popc(w);
+      while (w) {
+        const int bit = __ffs(w) - 1;
+        w &= w - 1;
+        if (pos < (uint32_t)a.union_stride) out[pos] = seg0 + (wb + tid) * 32 + bit;
+        ++pos;
+      }
+      run += total;
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    if (run > (uint32_t)a.union_stride) { atomicOr(a.status, TW_STATUS_UNION_TRUNCATED); run = a.union_stride; }
+    a.union_count[blockIdx.x] = (int32_t)run;
+  }
+}
+
+// ------------------------------------------------------------------ launches
+int pages_per_wave(long long total_pages_all_rows, int count_bound) {
+  // aim for >= ~2048 waves in flight chip-wide, 4..64 pages per wave
+  int pw = 64;
+  while (pw > 4 && total_pages_all_rows / pw < 4096) pw >>= 1;
+  while (pw > 4 && pw / 2 >= count_bound) pw >>= 1;
+  return pw;
+}
+
+template <int NH, bool FULL>
+void launch_score(const ScoreArgs& a, dim3 grid, bool dots, hipStream_t s) {
+  if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true>), grid, dim3(256), 0, s, a);
+  else      hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false>), grid, dim3(256), 0, s, a);
+}
+
+int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int32_t* sel_pages,
+              const int32_t* sel_count, int32_t max_sel, float* scores, int32_t* dots, hipStream_t s) {
+  ScoreArgs a;
+  a.q = (const uint16_t*)q; a.sel_pages = sel_pages; a.sel_count = sel_count;
+  a.page_table = kv->page_table; a.seq_lens = kv->seq_lens;
+  a.kq_pool = (const uint4*)kv->kq_pool; a.kq_meta = (const uint32_t*)kv->kq_meta;
+  a.scores = scores; a.dots = dots;
+  a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.max_sel = max_sel;
+  a.pool_pages = d.pool_pages;
+  const bool full = sel_pages == nullptr;
+  const int bound = full ? d.max_pages : max_sel;
+  a.cand_stride = bound * TW_PAGE;
+  a.pw = pages_per_wave((long long)bound * d.batch * (full ? d.Hkv : d.Hq), bound);
+  dim3 grid((bound + 4 * a.pw - 1) / (4 * a.pw), d.batch * (full ? d.Hkv : d.Hq));
+  tw_prof_before(TW_K_INT4_SCORE, s);
+  if (!full) launch_score<1, false>(a, grid, dots != nullptr, s);
+  else switch (d.G) {
+    case 1: launch_score<1, true>(a, grid, dots != nullptr, s); break;
+    case 2: launch_score<2, true>(a, grid, dots != nullptr, s); break;
+    case 4: launch_score<4, true>(a, grid, dots != nullptr, s); break;
+    default: launch_score<8, true>(a, grid, dots != nullptr, s); break;
+  }
+  return tw_prof_after(s);
+}
+
+}  // namespace
+
+extern "C" int twilight_int4_score(const twilight_kv_t* kv, const void* q, const int32_t* sel_pages,
+                                   const int32_t* sel_count, int32_t max_sel, float* scores, int32_t* dots,
+                                   void* stream) {
+  TwDims d;
+  if (int e = tw_check_kv(kv, &d)) return e;
+  if (!q || !scores || !kv->kq_pool || !kv->kq_meta) return TW_EINVAL;
+  if (sel_pages && (!sel_count || max_sel <= 0)) return TW_EINVAL;
+  return run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, dots, (hipStream_t)stream);
+}
+
+extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const int32_t* sel_pages,
+                                   const int32_t* sel_count, int32_t max_sel, float p,
+                                   int32_t* kept_count, int32_t* kept_idx, int32_t kept_stride,
+                                   int32_t* union_count, int32_t* union_idx, int32_t union_stride,
+                                   uint32_t* status, void* ws, size_t ws_bytes, void* stream) {
+  TwDims d;
+  if (int e = tw_check_kv(kv, &d)) return e;
+  if (!q || !kept_count || !union_count || !union_idx || !status || !kv->kq_pool || !kv->kq_meta) return TW_EINVAL;
+  if (sel_pages && (!sel_count || max_sel <= 0)) return TW_EINVAL;
+  if (!(p > 0.f) || p > 1.f || union_stride <= 0 || (kept_idx && kept_stride <= 0)) return TW_EINVAL;
+  const bool full = sel_pages == nullptr;
+  const int bound = full ? d.max_pages : max_sel;
+  if ((long long)bound * TW_PAGE > (1ll << 22)) return TW_EINVAL;   // fixed-point mass headroom
+  if (!ws || ws_bytes < twilight_workspace_bytes(TW_WS_PRUNE, kv, full ? 0 : max_sel, 0)) return TW_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const int cand_stride = bound * TW_PAGE;
+  float* scores = (float*)ws;
+  uint32_t* thr = (uint32_t*)((char*)ws + (((size_t)d.batch * d.Hq * cand_stride * 4 + 255) & ~(size_t)255));
+
+  if (int e = run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, nullptr, s)) return e;
+
+  ToppArgs t;
+  t.scores = scores; t.sel_pages = sel_pages; t.sel_count = sel_count; t.seq_lens = kv->seq_lens;
+  t.kept_count = kept_count; t.kept_idx = kept_idx; t.thr_key = thr; t.status = status;
+  t.Hq = d.Hq; t.max_pages = d.max_pages; t.max_sel = max_sel; t.cand_stride = cand_stride;
+  t.kept_stride = kept_stride; t.p = p;
+  tw_prof_before(TW_K_TOPP, s);
+  if (cand_stride <= TP_THREADS * TP_EPT)
+    hipLaunchKernelGGL(topp_kernel<true>, dim3(d.Hq, d.batch), dim3(TP_THREADS), 0, s, t);
+  else
+    hipLaunchKernelGGL(topp_kernel<false>, dim3(d.Hq, d.batch), dim3(TP_THREADS), 0, s, t);
+  if (int e = tw_prof_after(s)) return e;
+
+  UnionArgs u;
+  u.scores = scores; u.thr_key = thr; u.sel_pages = sel_pages; u.sel_count = sel_count;
+  u.seq_lens = kv->seq_lens; u.union_count = union_count; u.union_idx = union_idx; u.status = status;
+  u.Hq = d.Hq; u.Hkv = d.Hkv; u.G = d.G; u.max_pages = d.max_pages; u.max_sel = max_sel;
+  u.cand_stride = cand_stride; u.union_stride = union_stride;
+  tw_prof_before(TW_K_UNION, s);
+  hipLaunchKernelGGL(union_kernel, dim3(d.batch * d.Hkv), dim3(UN_THREADS), 0, s, u);
+  return tw_prof_after(s);
+}

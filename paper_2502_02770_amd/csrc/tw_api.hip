@@ -1,0 +1,131 @@
+// Host-side pieces shared by the entry points: argument checks, workspace
+// sizes, error strings, and the optional per-kernel event timing.
+#include "tw_common.h"
+
+int tw_decode_chunk(bool dense);
+long long tw_decode_max_items(const TwDims& d, bool dense, int union_stride);
+
+int tw_check_kv(const twilight_kv_t* kv, TwDims* d) {
+  if (!kv) return TW_EINVAL;
+  if (kv->head_dim != TW_HEAD_DIM || kv->page_size != TW_PAGE || kv->quant_group != TW_QGROUP) return TW_EINVAL;
+  if (kv->batch <= 0 || kv->num_q_heads <= 0 || kv->num_kv_heads <= 0) return TW_EINVAL;
+  if (kv->num_q_heads % kv->num_kv_heads) return TW_EINVAL;
+  const int G = kv->num_q_heads / kv->num_kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return TW_EINVAL;
+  if (kv->max_pages_per_seq <= 0 || kv->max_pages_per_seq > (1 << 27)) return TW_EINVAL;
+  if (kv->num_pool_pages <= 0 || kv->num_pool_pages * kv->num_kv_heads * TW_PAGE > 0x7FFFFFFFll) return TW_EINVAL;
+  if ((long long)kv->batch * kv->num_q_heads > 65535ll) return TW_EINVAL;   // grid.y limit
+  if (!kv->page_table || !kv->seq_lens) return TW_EINVAL;
+  d->batch = kv->batch; d->Hq = kv->num_q_heads; d->Hkv = kv->num_kv_heads; d->G = G;
+  d->max_pages = kv->max_pages_per_seq; d->pool_pages = kv->num_pool_pages;
+  return TW_OK;
+}
+
+int tw_num_cus() {
+  static int cus[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cus[dev] = n;
+  }
+  return cus[dev];
+}
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+extern "C" size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, int32_t max_sel, int32_t union_stride) {
+  TwDims d;
+  // the pointers are not needed for sizing: check the shape fields only
+  twilight_kv_t tmp;
+  if (!kv) return 0;
+  tmp = *kv;
+  int dummy = 0;
+  tmp.page_table = &dummy; tmp.seq_lens = &dummy;
+  if (tw_check_kv(&tmp, &d)) return 0;
+  const size_t bh = (size_t)d.batch * d.Hq;
+  switch (which) {
+    case TW_WS_SELECT:
+      return align256(bh * d.max_pages * 4);
+    case TW_WS_PRUNE: {
+      const size_t bound = max_sel > 0 ? (size_t)max_sel : (size_t)d.max_pages;
+      return align256(bh * bound * TW_PAGE * 4) + align256(bh * 4);
+    }
+    case TW_WS_DECODE: {
+      const bool dense = union_stride <= 0;
+      const size_t items = (size_t)tw_decode_max_items(d, dense, union_stride);
+      return align256((size_t)(d.batch * d.Hkv + 1) * 4) + align256(items * d.G * 8) + align256(items * d.G * 128 * 4);
+    }
+    default:
+      return 0;
+  }
+}
+
+extern "C" const char* twilight_strerror(int code) {
+  switch (code) {
+    case TW_OK: return "ok";
+    case TW_EINVAL: return "invalid argument (NULL pointer, unsupported shape or parameter)";
+    case TW_EWORKSPACE: return "workspace missing or smaller than twilight_workspace_bytes";
+    case TW_ELAUNCH: return "HIP reported an error at kernel launch";
+    default: return "unknown error code";
+  }
+}
+
+extern "C" int twilight_abi_version(void) { return TW_ABI_VERSION; }
+
+extern "C" const char* twilight_kernel_name(int id) {
+  static const char* names[TW_K_COUNT] = {"kquant_append", "page_score", "page_select", "int4_score",
+                                          "topp", "union", "sparse_decode", "combine"};
+  return (id >= 0 && id < TW_K_COUNT) ? names[id] : "?";
+}
+
+// ---------------------------------------------------------------- profiling
+namespace {
+struct ProfRec { int id; hipEvent_t e0, e1; };
+int g_mode = 0;
+int g_n = 0;
+bool g_open = false;
+ProfRec g_rec[TW_PROF_MAX_RECORDS];
+int g_created = 0;   // events exist for records [0, g_created)
+}  // namespace
+
+extern "C" int twilight_prof_enable(int mode) {
+  g_mode = mode ? 1 : 0;
+  g_n = 0;
+  g_open = false;
+  return TW_OK;
+}
+
+void tw_prof_before(int kernel_id, hipStream_t s) {
+  g_open = false;
+  if (!g_mode || g_n >= TW_PROF_MAX_RECORDS) return;
+  if (g_n >= g_created) {
+    if (hipEventCreate(&g_rec[g_n].e0) != hipSuccess) return;
+    if (hipEventCreate(&g_rec[g_n].e1) != hipSuccess) return;
+    g_created = g_n + 1;
+  }
+  g_rec[g_n].id = kernel_id;
+  if (hipEventRecord(g_rec[g_n].e0, s) == hipSuccess) g_open = true;
+}
+
+int tw_prof_after(hipStream_t s) {
+  if (g_open) {
+    hipEventRecord(g_rec[g_n].e1, s);
+    ++g_n;
+    g_open = false;
+  }
+  return hipGetLastError() == hipSuccess ? TW_OK : TW_ELAUNCH;
+}
+
+extern "C" int twilight_prof_collect(int32_t* kernel_ids, float* ms, int32_t cap) {
+  int w = 0;
+  for (int i = 0; i < g_n; ++i) {
+    if (hipEventSynchronize(g_rec[i].e1) != hipSuccess) break;
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, g_rec[i].e0, g_rec[i].e1) != hipSuccess) break;
+    if (w < cap && kernel_ids && ms) { kernel_ids[w] = g_rec[i].id; ms[w] = t; ++w; }
+  }
+  g_n = 0;
+  return w;
+}

@@ -1,0 +1,66 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, sizes workspaces and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_2502_02770_amd as T
+    if not os.path.exists(T.binding.LIB_PATH):
+        from paper_2502_02770_amd.build import build
+        build(verbose=False)
+    return T
+
+
+def test_exports_every_declared_symbol(T):
+    hdr = open(os.path.join(ROOT, "include", "twilight.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(twilight_[a-z0-9_]+)\s*\(", hdr))
+    assert {"twilight_kquant_append", "twilight_select_pages", "twilight_topp_prune",
+            "twilight_sparse_decode"} <= names
+    L = T.binding.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert L.twilight_abi_version() == 1
+    assert L.twilight_strerror(0) == b"ok" and b"workspace" in L.twilight_strerror(-2)
+    assert L.twilight_kernel_name(3) == b"int4_score"
+
+
+def test_workspace_sizes(T):
+    kv = T.make_kv(8, 32, 8, 2048, 16384, None, None)
+    assert T.twilight_workspace_bytes(0, kv, 256, 0) == 8 * 32 * 2048 * 4
+    assert T.twilight_workspace_bytes(1, kv, 256, 0) >= 8 * 32 * 256 * 16 * 4 + 8 * 32 * 4
+    assert T.twilight_workspace_bytes(1, kv, 0, 0) >= 8 * 32 * 2048 * 16 * 4
+    sparse = T.twilight_workspace_bytes(2, kv, 0, 16384)
+    assert sparse >= 64 * (16384 // 64) * 4 * 130 * 4
+    assert T.twilight_workspace_bytes(2, kv, 0, 0) > 0
+    bad = T.make_kv(8, 32, 5, 2048, 16384, None, None)           # 32 q heads over 5 kv heads
+    assert T.twilight_workspace_bytes(0, bad, 256, 0) == 0
+
+
+def test_bad_arguments_are_rejected_on_the_host(T):
+    L = T.binding.lib()
+    one = ctypes.c_void_p(4096)                                    # never dereferenced: checks fail first
+    kv = T.make_kv(1, 32, 8, 16, 16, None, None)
+    assert L.twilight_kquant_append(ctypes.byref(kv), one, None, one, one, one, 4, None) == -1   # NULL tables
+    kv.page_table, kv.seq_lens = 4096, 4096
+    kv.head_dim = 64
+    assert L.twilight_select_pages(ctypes.byref(kv), one, one, one, one, 4, one, 1 << 20, None) == -1
+    kv.head_dim = 128
+    kv.kq_pool, kv.kq_meta, kv.page_minmax, kv.k_pool, kv.v_pool = 4096, 4096, 4096, 4096, 4096
+    assert L.twilight_select_pages(ctypes.byref(kv), one, one, one, one, 4, one, 16, None) == -2  # workspace
+    assert L.twilight_topp_prune(ctypes.byref(kv), one, one, one, 4, ctypes.c_float(1.5), one, None, 0, one, one,
+                                 64, one, one, 1 << 20, None) == -1                                # p > 1
+    assert L.twilight_topp_prune(ctypes.byref(kv), one, one, one, 4, ctypes.c_float(0.0), one, None, 0, one, one,
+                                 64, one, one, 1 << 20, None) == -1                                # p = 0
+    assert L.twilight_sparse_decode(ctypes.byref(kv), one, None, one, 64, one, None, one, 1 << 20, None) == -1
+    assert L.twilight_sparse_decode(ctypes.byref(kv), one, one, one, 64, one, None, one, 8, None) == -2
+    assert L.twilight_int4_score(ctypes.byref(kv), one, one, None, 4, one, None, None) == -1
+    with pytest.raises(T.TwilightError):
+        T.binding._check(-3)

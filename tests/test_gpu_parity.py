@@ -1,0 +1,333 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle
+on the same seeded inputs.  Integer / index results bit-exact; top-p sets
+equal outside a 1e-6 band around the threshold weight; attention outputs
+within max-abs 2e-2 and rel-L2 1e-3 of the bf16-rounded oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import twilight_oracle as O
+from workloads import synth
+from tests.gpu_util import build_cache, gather_logical, unpack_codes, u16, oracle_seq
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2 = 2e-2, 1e-3
+
+
+def _T():
+    import paper_2502_02770_amd as T
+    return T
+
+
+def small_workloads():
+    """Sizes the oracle finishes in seconds, spanning several tiles and ragged tails."""
+    yield synth.config(0, scale=0.25, seed=0)                                           # 1 x 1024, identity table
+    yield synth.make_workload("ragged", [1000, 37, 16, 2049, 513], budget=lambda n: max(16, n // 4), p=0.9,
+                              heavy_frac=0.02, alpha_range=(0.0, 3.0), shuffle_pool=True, extra_pool_pages=7, seed=5)
+    yield synth.make_workload("mha", [700, 300], num_q_heads=4, num_kv_heads=4, budget=256, p=0.8,
+                              shuffle_pool=True, seed=6)
+    yield synth.make_workload("gqa8", [1500], num_q_heads=16, num_kv_heads=2, budget=512, p=0.95,
+                              alpha_cycle=[0.0, 0.5, 2.0, 6.0], seed=7)
+
+
+def check_cache(w, cache):
+    kq = cache.kq_pool.cpu(); meta = cache.kq_meta.cpu(); mm = cache.page_minmax.cpu()
+    kp = cache.k_pool.cpu(); vp = cache.v_pool.cpu() if cache.v_pool is not None else None
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        row = w.page_table[b]
+        codes = unpack_codes(gather_logical(kq, row, n).numpy())          # [n, Hkv, 128]
+        mt = gather_logical(meta, row, n)                                  # [n, Hkv, 4, 2] fp16
+        kl = gather_logical(kp, row, n)
+        assert torch.equal(kl.view(torch.int16), w.seq_k(b).view(torch.int16))
+        if vp is not None:
+            assert torch.equal(gather_logical(vp, row, n).view(torch.int16), w.seq_v(b).view(torch.int16))
+        P = (n + 15) // 16
+        for g in range(w.num_kv_heads):
+            kb = synth.bits(w.seq_k(b)[:, g])
+            u, s, z = O.quantize_k(kb)
+            assert np.array_equal(codes[:, g], u), (w.name, b, g)
+            assert np.array_equal(u16(mt[:, g, :, 0]), s.view(np.uint16))
+            assert np.array_equal(u16(mt[:, g, :, 1]), z.view(np.uint16))
+            mn, mx = O.page_minmax(kb)
+            pm = mm[row[:P].long(), g]                                     # [P, 2, 128]
+            assert np.array_equal(u16(pm[:, 0]), mn) and np.array_equal(u16(pm[:, 1]), mx)
+
+
+@pytest.mark.parametrize("w", list(small_workloads()), ids=lambda w: w.name)
+def test_kquant_append_bit_exact(w):
+    cache = build_cache(w)
+    check_cache(w, cache)
+
+
+def test_kquant_incremental_append_equals_bulk():
+    T = _T()
+    w = synth.make_workload("incr", [100, 45], budget=64, shuffle_pool=True, seed=11)
+    dev = "cuda"
+    cache = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev)
+    k, v = w.k.to(dev), w.v.to(dev)
+    # prefix in bulk, then ragged steps that start mid-page and cross page boundaries
+    done = [0, 0]
+    for step in ([60, 20], [1, 1], [7, 0], [30, 24], [2, 0]):
+        start = torch.tensor(done, dtype=torch.int32, device=dev)
+        nn = torch.tensor(step, dtype=torch.int32, device=dev)
+        offs = torch.tensor([w.seq_offsets[b] + done[b] for b in range(2)], dtype=torch.int32, device=dev)
+        cache.append(k, v, start, nn, offs, max(step))
+        done = [done[b] + step[b] for b in range(2)]
+    torch.cuda.synchronize()
+    assert done == [100, 45]
+    check_cache(w, cache)
+
+
+def run_pipeline(w, cache, with_kept=True):
+    T = _T()
+    dev = cache.k_pool.device
+    max_sel = None if w.full_selector else int(max(-(-int(b) // 16) for b in w.budget))
+    if max_sel is not None:
+        max_sel = min(max_sel, cache.max_pages)
+    st = T.DecodeStep(cache, max_sel=max_sel, with_kept_idx=with_kept)
+    q = w.q.to(dev)
+    st.run(q, w.budget.to(dev), w.p)
+    torch.cuda.synchronize()
+    return st, q
+
+
+def check_topp(kept_gpu, s_hat, cand, p):
+    """GPU kept set vs the oracle's, tolerant inside the 1e-6 band around tau*."""
+    mask, tau = O.topp_set(s_hat, p)
+    W = O.softmax_weights(s_hat)
+    gm = np.isin(cand, kept_gpu)
+    assert set(kept_gpu) <= set(cand.tolist())
+    diff = gm != mask
+    assert np.all(np.abs(W[diff] - tau) <= 1e-6), "kept set differs outside the tolerance band"
+    assert W[gm].sum() >= p - 1e-6
+    if gm.any():
+        low = W[gm].min()
+        assert W[gm & (W > low)].sum() < p + 1e-6
+        assert W[gm].min() >= W[~gm].max() - 1e-12 if (~gm).any() else True
+    return not diff.any()
+
+
+@pytest.mark.parametrize("w", list(small_workloads()), ids=lambda w: w.name)
+def test_pipeline_against_oracle(w):
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache)
+    assert int(st.status.item()) == 0
+    G = w.num_q_heads // w.num_kv_heads
+    scores = st.ws_prune.cpu().numpy().view(np.float32)
+    cand_stride = st.max_sel * 16
+    out = st.out.cpu(); lse = st.lse.cpu().numpy()
+    pscores = st.ws_select.cpu().numpy().view(np.float32)
+    for b in range(w.batch):
+        r = oracle_seq(w, b)
+        n = int(w.seq_lens[b])
+        P = (n + 15) // 16
+        for h in range(w.num_q_heads):
+            bh = b * w.num_q_heads + h
+            # stage 1: page bounds and page sets, bit-exact
+            assert np.array_equal(pscores[bh * cache.max_pages: bh * cache.max_pages + P], r["U"][h]), (b, h)
+            cnt = int(st.sel_count[b, h])
+            assert st.sel_pages[b, h, :cnt].cpu().numpy().tolist() == r["pages"][h].tolist(), (b, h)
+            # stage 2a: fp32 scores bit-exact (candidate slots of valid tokens)
+            sl = scores[bh * cand_stride: bh * cand_stride + cnt * 16]
+            slot_tok = (r["pages"][h][:, None].astype(np.int64) * 16 + np.arange(16)[None]).reshape(-1)
+            assert np.array_equal(sl[slot_tok < n], r["s_hat"][h]), (b, h)
+            assert np.all(np.isneginf(sl[slot_tok >= n]))
+            # stage 2b/c: kept sets
+            kc = int(st.kept_count[b, h])
+            kept = st.kept_idx[b, h, :kc].cpu().numpy()
+            assert np.all(np.diff(kept) > 0)
+            check_topp(kept, r["s_hat"][h], r["cand"][h], w.p)
+        for g in range(w.num_kv_heads):
+            gi = b * w.num_kv_heads + g
+            uc = int(st.union_count[gi])
+            un = st.union_idx[gi, :uc].cpu().numpy()
+            mine = np.unique(np.concatenate([st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+                                             for h in range(g * G, g * G + G)]))
+            assert un.tolist() == mine.tolist()
+            # stage 3 with the GPU's own sets, against the oracle's attention over the same set
+            for h in range(g * G, g * G + G):
+                ref, rl = O.attention(synth.bits(w.q[b, h]), synth.bits(w.seq_k(b)[:, g]), synth.bits(w.seq_v(b)[:, g]), un)
+                ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
+                got = out[b, h].float().numpy().astype(np.float64)
+                assert np.abs(got - ref).max() <= MAX_ABS
+                assert np.linalg.norm(got - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6, (b, h, np.linalg.norm(got - ref) / np.linalg.norm(ref))
+                assert abs(lse[b, h] - rl) <= 1e-3 * max(1.0, abs(rl))
+
+
+@pytest.mark.parametrize("w", list(small_workloads())[:2], ids=lambda w: w.name)
+def test_int4_dots_bit_exact_list_and_full(w):
+    T = _T()
+    cache = build_cache(w)
+    dev = cache.k_pool.device
+    q = w.q.to(dev)
+    # full mode: every page is a candidate, the G heads of a KV head share the loads
+    stride = cache.max_pages * 16
+    sc = torch.zeros(w.batch, w.num_q_heads, stride, dtype=torch.float32, device=dev)
+    dots = torch.zeros(w.batch, w.num_q_heads, stride, 4, dtype=torch.int32, device=dev)
+    T.twilight_int4_score(cache.kv, q, None, None, 0, sc, dots)
+    torch.cuda.synchronize()
+    sc, dots = sc.cpu().numpy(), dots.cpu().numpy()
+    G = w.num_q_heads // w.num_kv_heads
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        for h in range(w.num_q_heads):
+            kb = synth.bits(w.seq_k(b)[:, h // G])
+            u, s, z = O.quantize_k(kb)
+            qi, sq = O.quantize_q(synth.bits(w.q[b, h]))
+            I, Qs = O.int4_dots(qi, u)
+            assert np.array_equal(dots[b, h, :n], I)
+            assert np.array_equal(sc[b, h, :n], O.int4_scores(qi, sq, u, s, z))
+            assert np.all(np.isneginf(sc[b, h, n:((n + 15) // 16) * 16]))
+    # list mode with an arbitrary (reversed-then-sorted subset) page list
+    max_sel = 9
+    sel = torch.zeros(w.batch, w.num_q_heads, max_sel, dtype=torch.int32)
+    cnt = torch.zeros(w.batch, w.num_q_heads, dtype=torch.int32)
+    rng = np.random.default_rng(0)
+    for b in range(w.batch):
+        P = (int(w.seq_lens[b]) + 15) // 16
+        for h in range(w.num_q_heads):
+            c = int(min(P, rng.integers(0, max_sel + 1)))
+            sel[b, h, :c] = torch.from_numpy(np.sort(rng.choice(P, c, replace=False)).astype(np.int32))
+            cnt[b, h] = c
+    sc2 = torch.full((w.batch, w.num_q_heads, max_sel * 16), 7.0, dtype=torch.float32, device=dev)
+    d2 = torch.zeros(w.batch, w.num_q_heads, max_sel * 16, 4, dtype=torch.int32, device=dev)
+    T.twilight_int4_score(cache.kv, q, sel.to(dev), cnt.to(dev), max_sel, sc2, d2)
+    torch.cuda.synchronize()
+    sc2, d2 = sc2.cpu().numpy(), d2.cpu().numpy()
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        for h in range(w.num_q_heads):
+            c = int(cnt[b, h])
+            tok = (sel[b, h, :c].numpy()[:, None].astype(np.int64) * 16 + np.arange(16)[None]).reshape(-1)
+            ok = tok < n
+            assert np.array_equal(sc2[b, h, :c * 16][ok], sc[b, h][tok[ok]])
+            assert np.array_equal(d2[b, h, :c * 16][ok], dots[b, h][tok[ok]])
+            assert np.all(np.isneginf(sc2[b, h, :c * 16][~ok]))
+
+
+def test_full_selector_pruner_and_long_rows():
+    """Every token a candidate (the 'Full' selector): group-shared scoring, the streaming
+    top-p path (more candidates than the register-cached path holds) and entropy per head."""
+    w = synth.make_workload("full", [9000, 300], num_q_heads=16, num_kv_heads=2, p=0.95, heavy_frac=0.005,
+                            alpha_cycle=[0.0, 0.5, 2.0, 6.0], full_selector=True, shuffle_pool=True, seed=9)
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache)
+    assert int(st.status.item()) == 0
+    exact = 0
+    for b in range(w.batch):
+        r = oracle_seq(w, b)
+        for h in range(w.num_q_heads):
+            kept = st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+            exact += check_topp(kept, r["s_hat"][h], r["cand"][h], w.p)
+        G = w.num_q_heads // w.num_kv_heads
+        for g in range(w.num_kv_heads):
+            gi = b * w.num_kv_heads + g
+            mine = np.unique(np.concatenate([st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+                                             for h in range(g * G, g * G + G)]))
+            assert st.union_idx[gi, :int(st.union_count[gi])].cpu().numpy().tolist() == mine.tolist()
+    assert exact >= w.batch * w.num_q_heads - 2      # sets identical to the oracle's, bar band cases
+
+
+def test_attention_with_oracle_sets_and_dense():
+    """Stage 3 alone: the oracle's union sets uploaded as the index lists; and the dense mode."""
+    T = _T()
+    w = synth.make_workload("attn", [1300, 70, 640], budget=lambda n: n // 2, p=0.9, shuffle_pool=True, seed=13)
+    cache = build_cache(w)
+    dev = cache.k_pool.device
+    q = w.q.to(dev)
+    G = w.num_q_heads // w.num_kv_heads
+    rs = [oracle_seq(w, b) for b in range(w.batch)]
+    stride = max(len(u) for r in rs for u in r["union"]) + 3
+    uidx = torch.zeros(w.batch * w.num_kv_heads, stride, dtype=torch.int32)
+    ucnt = torch.zeros(w.batch * w.num_kv_heads, dtype=torch.int32)
+    for b, r in enumerate(rs):
+        for g, u in enumerate(r["union"]):
+            uidx[b * w.num_kv_heads + g, :len(u)] = torch.from_numpy(u)
+            ucnt[b * w.num_kv_heads + g] = len(u)
+    ucnt[1] = 0                                                        # an empty list -> zero row, lse -inf
+    out = torch.zeros(w.batch, w.num_q_heads, 128, dtype=torch.bfloat16, device=dev)
+    lse = torch.zeros(w.batch, w.num_q_heads, dtype=torch.float32, device=dev)
+    ws = torch.empty(T.twilight_workspace_bytes(T.binding.TW_WS_DECODE, cache.kv, 0, stride), dtype=torch.uint8, device=dev)
+    T.twilight_sparse_decode(cache.kv, q, ucnt.to(dev), uidx.to(dev), stride, out, lse, ws)
+    torch.cuda.synchronize()
+    o, l = out.cpu().float().numpy().astype(np.float64), lse.cpu().numpy()
+    for b, r in enumerate(rs):
+        for h in range(w.num_q_heads):
+            if b == 0 and h // G == 1:
+                assert not o[b, h].any() and np.isneginf(l[b, h])
+                continue
+            ref = O.bf16_to_f32(r["out_bf16"][h]).astype(np.float64)
+            assert np.abs(o[b, h] - ref).max() <= MAX_ABS
+            assert np.linalg.norm(o[b, h] - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
+            assert abs(l[b, h] - r["lse"][h]) <= 1e-3 * max(1.0, abs(r["lse"][h]))
+    # dense
+    st = T.DecodeStep(cache, max_sel=4)
+    d = st.dense(q, lse=lse).cpu().float().numpy().astype(np.float64)
+    torch.cuda.synchronize()
+    l = lse.cpu().numpy()
+    for b in range(w.batch):
+        ref, rl = O.dense_decode(synth.bits(w.q[b]), synth.bits(w.seq_k(b)), synth.bits(w.seq_v(b)))
+        ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
+        assert np.abs(d[b] - ref).max() <= MAX_ABS
+        assert np.linalg.norm(d[b] - ref) <= REL_L2 * np.linalg.norm(ref)
+        assert np.allclose(l[b], rl, rtol=1e-3, atol=1e-3)
+
+
+def test_p1_full_budget_reproduces_dense_attention():
+    T = _T()
+    w = synth.make_workload("p1", [530, 99], budget=10 ** 6, p=1.0, shuffle_pool=True, seed=17)
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache)
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        assert all(int(c) == n for c in st.kept_count[b])
+        for g in range(w.num_kv_heads):
+            gi = b * w.num_kv_heads + g
+            assert st.union_idx[gi, :int(st.union_count[gi])].cpu().numpy().tolist() == list(range(n))
+        ref, _ = O.dense_decode(synth.bits(w.q[b]), synth.bits(w.seq_k(b)), synth.bits(w.seq_v(b)))
+        ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
+        got = st.out[b].cpu().float().numpy().astype(np.float64)
+        assert np.abs(got - ref).max() <= MAX_ABS and np.linalg.norm(got - ref) <= REL_L2 * np.linalg.norm(ref)
+
+
+def test_degenerate_inputs():
+    """Length-1 sequence, single-token union, all-equal scores (every candidate ties at the cut),
+    zero query (all scores 0), truncated union."""
+    T = _T()
+    w = synth.make_workload("degen", [1, 40, 64], budget=32, p=0.5, heavy_frac=0.0, alpha_range=(0, 0), seed=19)
+    w.q[2] = 0                                                         # zero query: uniform weights
+    w.k[w.seq_offsets[1]:w.seq_offsets[2]] = w.k[w.seq_offsets[1]]     # identical keys: ties
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache)
+    assert int(st.status.item()) == 0
+    assert all(int(c) == 1 for c in st.kept_count[0])
+    for h in range(w.num_q_heads):
+        g = h // 4
+        assert torch.equal(st.out[0, h].cpu().view(torch.int16), w.seq_v(0)[0, g].view(torch.int16))
+        for b in (1, 2):   # ties: the whole candidate set (budget 32 -> 2 pages) is kept
+            r = oracle_seq(w, b)
+            kc = int(st.kept_count[b, h])
+            assert st.kept_idx[b, h, :kc].cpu().numpy().tolist() == r["kept"][h].tolist()
+            assert kc == len(r["cand"][h])
+    # union capacity overflow is reported and truncated deterministically
+    st2 = T.DecodeStep(cache, max_sel=2, union_stride=5, with_kept_idx=True)
+    st2.run(q, w.budget.to(q.device), w.p)
+    torch.cuda.synchronize()
+    assert int(st2.status.item()) & T.binding.TW_STATUS_UNION_TRUNCATED
+    assert int(st2.union_count[w.num_kv_heads * 1]) == 5
+    assert st2.union_idx[w.num_kv_heads * 1, :5].cpu().tolist() == st.union_idx[w.num_kv_heads * 1, :5].cpu().tolist()
+
+
+def test_results_are_deterministic_run_to_run():
+    w = synth.config(0, scale=0.25, seed=3)
+    cache = build_cache(w)
+    a, q = run_pipeline(w, cache)
+    b, _ = run_pipeline(w, cache)
+    for name in ("sel_pages", "sel_count", "kept_count", "kept_idx", "union_count", "out"):
+        x, y = getattr(a, name), getattr(b, name)
+        assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
+                           y.view(torch.int16) if y.dtype == torch.bfloat16 else y), name
