@@ -218,7 +218,7 @@ int twilight_abi_version(void);
  * (kernel id, milliseconds) to the HOST arrays and clears the list; returns
  * the number written.  Not thread-safe; one stream at a time.
  */
-#define TW_PROF_MAX_RECORDS 4096
+#define TW_PROF_MAX_RECORDS 65536
 #define TW_K_KQUANT_APPEND 0
 #define TW_K_PAGE_SCORE 1
 #define TW_K_PAGE_SELECT 2

@@ -132,7 +132,7 @@ def twilight_prof_enable(mode):
     _check(lib().twilight_prof_enable(int(mode)))
 
 
-def twilight_prof_collect(cap=4096):
+def twilight_prof_collect(cap=65536):
     """-> list of (kernel name, milliseconds) since the last collect."""
     ids = (ctypes.c_int32 * cap)()
     ms = (ctypes.c_float * cap)()
