@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
       acc = tw_row16_sum(acc);
       if (seg == 0 && live)
         a.scores[((long long)(b * a.Hq + g * G + h)) * a.max_pages + lp] =
-            ok ? __fadd_rn(acc, 0.0f) : -__builtin_inff();
+            ok ? __fadd_rn(acc, 0.0f) : -3.402823466e38f;   // unmapped page: ranks last
     }
   }
 }
@@ -159,6 +159,163 @@ __global__ __launch_bounds__(256) void page_select_kernel(SelectArgs a) {
   }
 }
 
+
+// ---- page_select for sequences of up to 8192 pages: bounds staged in LDS.
+// The Kp-th largest bound is located by bucketing the live key interval
+// linearly into 2048 buckets (one pass when the bounds are spread out),
+// narrowing to the bucket that holds it, and finishing with an exact rank
+// computation once at most 256 candidates remain.
+constexpr int SEL_LDS_PAGES = 8192;
+constexpr int SEL_NB = 2048;
+constexpr int SEL_CAP = 256;
+
+__device__ __forceinline__ float tw_key_float(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+}
+
+__global__ __launch_bounds__(256) void page_select_lds_kernel(SelectArgs a) {
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  const int B = a.budget[b];
+  long long kp = B > 0 ? ((long long)B + TW_PAGE - 1) / TW_PAGE : 0;
+  if (kp > P) kp = P;
+  if (kp > a.max_sel) kp = a.max_sel;
+  const int Kp = (int)kp;
+  const float* sc = a.scores + ((long long)(b * a.Hq + h)) * a.max_pages;
+  int32_t* out = a.sel_pages + ((long long)(b * a.Hq + h)) * a.max_sel;
+  if (tid == 0) a.sel_count[b * a.Hq + h] = Kp;
+  if (Kp == 0) return;
+  if (Kp == P) {
+    for (int i = tid; i < P; i += 256) out[i] = i;
+    return;
+  }
+
+  __shared__ uint32_t key_s[SEL_LDS_PAGES];
+  __shared__ uint32_t hist[SEL_NB];
+  __shared__ uint32_t wsum[16];
+  __shared__ uint32_t red_lo[4], red_hi[4];
+  __shared__ uint32_t sh_bkt, sh_need, sh_pop, sh_n, sh_T, sh_need_eq;
+  __shared__ uint32_t ck[SEL_CAP];
+  __shared__ int32_t ci[SEL_CAP];
+
+  uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+  for (int i = tid; i < P; i += 256) {
+    const uint32_t k = tw_float_key(sc[i]);
+    key_s[i] = k;
+    lo = k < lo ? k : lo;
+    hi = k > hi ? k : hi;
+  }
+  lo = ~tw_wave_max_u32(~lo);
+  hi = tw_wave_max_u32(hi);
+  if (lane == 0) { red_lo[wave] = lo; red_hi[wave] = hi; }
+  if (tid == 0) sh_n = 0;
+  __syncthreads();
+  uint32_t klo = red_lo[0], khi = red_hi[0];
+#pragma unroll
+  for (int w = 1; w < 4; ++w) { klo = red_lo[w] < klo ? red_lo[w] : klo; khi = red_hi[w] > khi ? red_hi[w] : khi; }
+
+  uint32_t need = (uint32_t)Kp, T = 0, need_eq = 0;
+#pragma unroll 1
+  for (int pass = 0;; ++pass) {
+    // every pass drops the live minimum or maximum, so 64 passes are never reached
+    if (klo == khi || pass == 64) { T = klo; need_eq = need; break; }      // everything left ties
+    const float smn = tw_key_float(klo), smx = tw_key_float(khi);
+    const float scale = (float)SEL_NB / (smx - smn);
+    for (int i = tid; i < SEL_NB; i += 256) hist[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < P; i += 256) {
+      const uint32_t k = key_s[i];
+      if (k >= klo && k <= khi) {
+        int bk = (int)((tw_key_float(k) - smn) * scale);
+        bk = bk > SEL_NB - 1 ? SEL_NB - 1 : (bk < 0 ? 0 : bk);
+        atomicAdd(&hist[bk], 1u);
+      }
+    }
+    __syncthreads();
+    // thread t owns the 8 buckets 2047-8t .. 2040-8t, walked downwards
+    uint32_t c[8], mine = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { c[j] = hist[SEL_NB - 1 - (8 * tid + j)]; mine += c[j]; }
+    uint32_t total;
+    const uint32_t incl = tw_block_scan_u32(mine, wsum, &total);
+    uint32_t above = incl - mine;
+    if (above < need && incl >= need) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        if (above < need && above + c[j] >= need) { sh_bkt = SEL_NB - 1 - (8 * tid + j); sh_need = need - above; sh_pop = c[j]; }
+        above += c[j];
+      }
+    }
+    __syncthreads();
+    const int bkt = (int)sh_bkt;
+    need = sh_need;
+    const uint32_t pop = sh_pop;
+    // narrow to the keys of that bucket; collect them when few enough for the exact finish
+    const bool small = pop <= SEL_CAP && pop != need;
+    uint32_t nlo = 0xFFFFFFFFu, nhi = 0u;
+    for (int i = tid; i < P; i += 256) {
+      const uint32_t k = key_s[i];
+      if (k >= klo && k <= khi) {
+        int bk = (int)((tw_key_float(k) - smn) * scale);
+        bk = bk > SEL_NB - 1 ? SEL_NB - 1 : (bk < 0 ? 0 : bk);
+        if (bk == bkt) {
+          nlo = k < nlo ? k : nlo;
+          nhi = k > nhi ? k : nhi;
+          if (small) { const uint32_t at = atomicAdd(&sh_n, 1u); if (at < SEL_CAP) { ck[at] = k; ci[at] = i; } }
+        }
+      }
+    }
+    nlo = ~tw_wave_max_u32(~nlo);
+    nhi = tw_wave_max_u32(nhi);
+    if (lane == 0) { red_lo[wave] = nlo; red_hi[wave] = nhi; }
+    __syncthreads();
+    klo = red_lo[0]; khi = red_hi[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) { klo = red_lo[w] < klo ? red_lo[w] : klo; khi = red_hi[w] > khi ? red_hi[w] : khi; }
+    if (pop == need) { T = klo; need_eq = 0xFFFFFFFFu; break; }   // the whole bucket is taken
+    if (small) {
+      // exact: the candidate of rank need-1 (by bound, then by lower page id) is the last one taken
+      if (tid < (int)pop) {
+        const uint32_t kx = ck[tid];
+        const int ix = ci[tid];
+        uint32_t rank = 0, eq_lower = 0;
+        for (uint32_t j = 0; j < pop; ++j) {
+          const uint32_t kj = ck[j];
+          const int ij = ci[j];
+          rank += (kj > kx || (kj == kx && ij < ix)) ? 1u : 0u;
+          eq_lower += (kj == kx && ij < ix) ? 1u : 0u;
+        }
+        if (rank == need - 1) { sh_T = kx; sh_need_eq = eq_lower + 1; }
+      }
+      __syncthreads();
+      T = sh_T;
+      need_eq = sh_need_eq;
+      break;
+    }
+    __syncthreads();                              // red_* and hist are rewritten by the next pass
+  }
+
+  // ---- ordered emit: thread t owns the contiguous pages [t*E, (t+1)*E)
+  const int E = (P + 255) / 256;
+  const int i0 = tid * E, i1 = (i0 + E < P) ? i0 + E : P;
+  uint32_t gt = 0, eq = 0;
+  for (int i = i0; i < i1; ++i) { const uint32_t k = key_s[i]; gt += k > T ? 1u : 0u; eq += k == T ? 1u : 0u; }
+  uint32_t total;
+  const uint32_t incl = tw_block_scan_u32(gt | (eq << 16), wsum, &total);
+  uint32_t gt_before = (incl & 0xFFFFu) - gt, eq_before = (incl >> 16) - eq;
+  for (int i = i0; i < i1; ++i) {
+    const uint32_t k = key_s[i];
+    if (k > T || (k == T && eq_before < need_eq)) {
+      const uint32_t pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
+      if (pos < (uint32_t)a.max_sel) out[pos] = i;
+    }
+    gt_before += k > T ? 1u : 0u;
+    eq_before += k == T ? 1u : 0u;
+  }
+}
+
 template <int G>
 void launch_score(const ScoreArgs& a, dim3 grid, hipStream_t s) {
   hipLaunchKernelGGL(page_score_kernel<G>, grid, dim3(256), 0, s, a);
@@ -194,6 +351,9 @@ extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, con
   sa.sel_pages = sel_pages; sa.sel_count = sel_count;
   sa.Hq = d.Hq; sa.max_pages = d.max_pages; sa.max_sel = max_sel;
   tw_prof_before(TW_K_PAGE_SELECT, s);
-  hipLaunchKernelGGL(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+  if (d.max_pages <= SEL_LDS_PAGES)
+    hipLaunchKernelGGL(page_select_lds_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+  else
+    hipLaunchKernelGGL(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
   return tw_prof_after(s);
 }

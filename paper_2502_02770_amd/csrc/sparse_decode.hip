@@ -247,28 +247,58 @@ struct CombineArgs {
   int Hq, Hkv, G;
 };
 
-// One 128-thread block per (sequence, query head); thread = output dim.
-__global__ __launch_bounds__(128) void combine_kernel(CombineArgs a) {
-  const int b = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
+// One 256-thread block per (sequence, query head): 8 item lanes x 32 lanes of
+// 4 output dims.  Each item lane folds every 8th partial with a running
+// maximum; the 8 lanes are then merged through LDS.
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, il = tid >> 5, dl = tid & 31;
   const int g = h / a.G, hh = h % a.G, gi = b * a.Hkv + g, qh = b * a.Hq + h;
   const int i0 = a.ws_prefix[gi], i1 = a.ws_prefix[gi + 1];
   if (i1 - i0 == 1) return;                     // written by the decode kernel itself
+  uint2* out2 = (uint2*)(a.out + (long long)qh * 128);
   if (i1 == i0) {                               // empty list
-    a.out[(long long)qh * 128 + d] = 0;
-    if (a.lse && d == 0) a.lse[qh] = -__builtin_inff();
+    if (il == 0) out2[dl] = make_uint2(0u, 0u);
+    if (a.lse && tid == 0) a.lse[qh] = -__builtin_inff();
     return;
   }
-  float M = kNegBig;
-  for (int i = i0; i < i1; ++i) M = fmaxf(M, a.ws_ml[(long long)i * a.G + hh].x);
-  float L = 0.f, o = 0.f;
-  for (int i = i0; i < i1; ++i) {
+  const float4* acc4 = (const float4*)a.ws_acc;
+  float m = kNegBig, l = 0.f;
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+  for (int i = i0 + il; i < i1; i += 8) {
     const float2 ml = a.ws_ml[(long long)i * a.G + hh];
-    const float sc = tw_exp2(ml.x - M);
-    L = __builtin_fmaf(ml.y, sc, L);
-    o = __builtin_fmaf(a.ws_acc[((long long)i * a.G + hh) * 128 + d], sc, o);
+    const float4 v = acc4[((long long)i * a.G + hh) * 32 + dl];
+    const float mn = fmaxf(m, ml.x);
+    const float so = tw_exp2(m - mn), sn = tw_exp2(ml.x - mn);
+    l = __builtin_fmaf(l, so, ml.y * sn);
+    o.x = __builtin_fmaf(o.x, so, v.x * sn); o.y = __builtin_fmaf(o.y, so, v.y * sn);
+    o.z = __builtin_fmaf(o.z, so, v.z * sn); o.w = __builtin_fmaf(o.w, so, v.w * sn);
+    m = mn;
   }
-  a.out[(long long)qh * 128 + d] = (uint16_t)tw_f32_to_bf16(L > 0.f ? o / L : 0.f);
-  if (a.lse && d == 0) a.lse[qh] = L > 0.f ? (M + __log2f(L)) * kLn2 : -__builtin_inff();
+  __shared__ float4 so4[8][32];
+  __shared__ float2 sml[8];
+  so4[il][dl] = o;
+  if (dl == 0) sml[il] = make_float2(m, l);
+  __syncthreads();
+  if (il == 0) {
+    float M = sml[0].x;
+#pragma unroll
+    for (int j = 1; j < 8; ++j) M = fmaxf(M, sml[j].x);
+    float L = 0.f;
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float sc = tw_exp2(sml[j].x - M);
+      const float4 v = so4[j][dl];
+      L = __builtin_fmaf(sml[j].y, sc, L);
+      r.x = __builtin_fmaf(v.x, sc, r.x); r.y = __builtin_fmaf(v.y, sc, r.y);
+      r.z = __builtin_fmaf(v.z, sc, r.z); r.w = __builtin_fmaf(v.w, sc, r.w);
+    }
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+    out2[dl] = make_uint2(tw_f32_to_bf16(r.x * inv) | (tw_f32_to_bf16(r.y * inv) << 16),
+                          tw_f32_to_bf16(r.z * inv) | (tw_f32_to_bf16(r.w * inv) << 16));
+    if (a.lse && dl == 0) a.lse[qh] = L > 0.f ? (M + __log2f(L)) * kLn2 : -__builtin_inff();
+  }
 }
 
 template <int G>
@@ -331,6 +361,6 @@ extern "C" int twilight_sparse_decode(const twilight_kv_t* kv, const void* q, co
   c.ws_prefix = a.ws_prefix; c.ws_ml = a.ws_ml; c.ws_acc = (const float*)a.ws_acc;
   c.out = (uint16_t*)out; c.lse = lse; c.Hq = d.Hq; c.Hkv = d.Hkv; c.G = d.G;
   tw_prof_before(TW_K_COMBINE, s);
-  hipLaunchKernelGGL(combine_kernel, dim3(d.Hq, d.batch), dim3(128), 0, s, c);
+  hipLaunchKernelGGL(combine_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, c);
   return tw_prof_after(s);
 }

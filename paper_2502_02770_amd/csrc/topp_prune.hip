@@ -386,6 +386,264 @@ __global__ __launch_bounds__(TP_THREADS) void topp_kernel(ToppArgs a) {
 #undef TP_LOAD
 }
 
+
+// ------------------------------------------------------------------ fused top-p + union
+// One workgroup per (sequence, KV head): the G query heads are handled by
+// teams of 256 threads that run side by side (at most 4 at a time), each
+// keeping its head's candidate scores in registers (thread t of a team owns
+// the contiguous slots [t*EPT, (t+1)*EPT)).  Same threshold search as
+// topp_kernel with 9 bits per pass; the kept tokens then set bits in a
+// shared LDS bitmap from which the group's sorted union is emitted.
+struct FusedArgs {
+  const float* scores;
+  const int32_t* sel_pages;
+  const int32_t* sel_count;
+  const int32_t* seq_lens;
+  int32_t* kept_count;
+  int32_t* kept_idx;          // or nullptr
+  int32_t* union_count;
+  int32_t* union_idx;
+  uint32_t* status;
+  int Hq, Hkv, max_pages, max_sel, cand_stride, kept_stride, union_stride;
+  float p;
+};
+
+constexpr int FP_TEAM = 256;                  // threads per team (4 waves)
+constexpr int FP_NB = 512;                    // buckets per pass
+constexpr int FP_CAP = 256;                   // exact resolve handles up to this many scores
+constexpr int FP_BITMAP_WORDS = 6144;         // 196608 tokens
+
+// distance to the max logit in 2^-22 units, saturating at 32 (27 bits)
+__device__ __forceinline__ uint32_t fp_rank(float m, float s) {
+  const float d = __fsub_rn(m, s);
+  return d >= 32.f ? 0x07FFFFFFu : (uint32_t)(d * 4194304.f);
+}
+
+template <int G, int EPT>
+__global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(FusedArgs a) {
+  constexpr int TEAMS = G < 4 ? G : 4;
+  constexpr int ROUNDS = G / TEAMS;
+  constexpr int NT = TEAMS * FP_TEAM;
+  const int b = blockIdx.x / a.Hkv, g = blockIdx.x % a.Hkv;
+  const int tid = threadIdx.x, team = tid / FP_TEAM, tt = tid % FP_TEAM, lane = tid & 63, tw = tt >> 6;
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
+  const int nwords = (ntok + 31) >> 5;
+
+  __shared__ unsigned long long histM[TEAMS][FP_NB];
+  __shared__ uint32_t histC[TEAMS][FP_NB];
+  __shared__ unsigned long long cand_mass[TEAMS][FP_CAP];
+  __shared__ uint32_t cand_key[TEAMS][FP_CAP];
+  __shared__ uint32_t bitmap[FP_BITMAP_WORDS];
+  __shared__ unsigned long long ws64[TEAMS][4];
+  __shared__ uint32_t ws32[16];
+  __shared__ float redf[TEAMS][4];
+  __shared__ uint32_t redu[TEAMS][4];
+  __shared__ uint32_t sh_bkt[TEAMS], sh_pop[TEAMS], sh_n[TEAMS];
+  __shared__ unsigned long long sh_A[TEAMS];
+
+  for (int i = tid; i < nwords; i += NT) bitmap[i] = 0;
+
+#pragma unroll 1
+  for (int round = 0; round < ROUNDS; ++round) {
+    const int h = g * G + round * TEAMS + team;
+    const int bh = b * a.Hq + h;
+    int count = a.sel_count[bh];
+    if (count > a.max_sel) count = a.max_sel;
+    if (count < 0) count = 0;
+    const int N = count * TW_PAGE;
+    const float* row = a.scores + (long long)bh * a.cand_stride;
+    const int c0 = tt * EPT;                          // first candidate slot of this thread
+
+    // ---- scores into registers; logical pages of the owned slots
+    float s[EPT];
+    int pg[EPT / 16];
+#pragma unroll
+    for (int v = 0; v < EPT / 4; ++v) {
+      float4 x = make_float4(-__builtin_inff(), -__builtin_inff(), -__builtin_inff(), -__builtin_inff());
+      if (c0 + 4 * v < N) x = *(const float4*)(row + c0 + 4 * v);    // N is a multiple of 16
+      s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
+    }
+#pragma unroll
+    for (int v = 0; v < EPT / 16; ++v)
+      pg[v] = (c0 + 16 * v < N) ? a.sel_pages[(long long)bh * a.max_sel + (c0 >> 4) + v] : 0;
+
+    // ---- team max
+    float m = s[0];
+#pragma unroll
+    for (int e = 1; e < EPT; ++e) m = fmaxf(m, s[e]);
+    m = tw_wave_max_f(m);
+    if (lane == 0) redf[team][tw] = m;
+    if (tt == 0) sh_n[team] = 0;
+    __syncthreads();
+    m = fmaxf(fmaxf(redf[team][0], redf[team][1]), fmaxf(redf[team][2], redf[team][3]));
+
+    uint32_t T = 0;
+    bool searching;
+    if (!(m > -__builtin_inff())) { T = 0xFFFFFFFFu; searching = false; }
+    else if (a.p >= 1.0f) { T = kKeyNegInf + 1u; searching = false; }
+    else searching = true;
+
+    // ---- radix bisection, 9 bits per pass; all teams walk the passes together
+    uint32_t prefix = 0, pop = 0;
+    unsigned long long A = 0, target = 0;
+    int shift = 18, level = 0;
+    bool active = searching;
+#pragma unroll 1
+    for (;;) {
+      if (active) { histM[team][tt] = 0; histM[team][tt + 256] = 0; histC[team][tt] = 0; histC[team][tt + 256] = 0; }
+      __syncthreads();
+      if (active) {
+        const uint32_t himask = level == 0 ? 0u : (0xFFFFFFFFu << (shift + 9));
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+          if (s[e] > -__builtin_inff()) {
+            const uint32_t r = fp_rank(m, s[e]);
+            if ((r & himask) == prefix) {
+              const uint32_t bk = (r >> shift) & (FP_NB - 1);
+              atomicAdd(&histM[team][bk], tp_mass(m, s[e]));
+              atomicAdd(&histC[team][bk], 1u);
+            }
+          }
+        }
+      }
+      __syncthreads();
+      unsigned long long m0 = 0, m1 = 0;
+      if (active) { m0 = histM[team][2 * tt]; m1 = histM[team][2 * tt + 1]; }
+      unsigned long long total;
+      const unsigned long long incl = tw_group_scan_u64<4>(m0 + m1, ws64[team], tw, &total);
+      if (active) {
+        if (level == 0) {
+          const double t = ceil((double)a.p * (double)total);
+          target = t < 1.0 ? 1ull : (unsigned long long)t;
+          if (target > total) target = total;
+        }
+        const unsigned long long before = A + incl - (m0 + m1);
+        if (before < target && before + m0 >= target) {
+          sh_bkt[team] = 2 * tt; sh_A[team] = before; sh_pop[team] = histC[team][2 * tt];
+        } else if (before + m0 < target && before + m0 + m1 >= target) {
+          sh_bkt[team] = 2 * tt + 1; sh_A[team] = before + m0; sh_pop[team] = histC[team][2 * tt + 1];
+        }
+      }
+      __syncthreads();
+      bool more = false;
+      if (active) {
+        prefix |= sh_bkt[team] << shift;
+        A = sh_A[team];
+        pop = sh_pop[team];
+        more = pop > FP_CAP && level < 2;
+        if (more) { ++level; shift -= 9; } else active = false;
+      }
+      if (!__syncthreads_or(more ? 1 : 0)) break;
+    }
+
+    // ---- exact resolve among the `pop` scores whose rank matches `prefix` above bit `shift`
+    const uint32_t fmask = 0xFFFFFFFFu << shift;
+    const bool small = searching && pop <= FP_CAP;
+    uint32_t kmin = 0xFFFFFFFFu;
+    if (searching) {
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        if (s[e] > -__builtin_inff() && (fp_rank(m, s[e]) & fmask) == prefix) {
+          const uint32_t k = tw_float_key(s[e]);
+          kmin = k < kmin ? k : kmin;
+          if (small) {
+            const uint32_t at = atomicAdd(&sh_n[team], 1u);
+            if (at < FP_CAP) { cand_key[team][at] = k; cand_mass[team][at] = tp_mass(m, s[e]); }
+          }
+        }
+      }
+    }
+    __syncthreads();
+    uint32_t best = 0;
+    if (small) {
+      const uint32_t cn = sh_n[team] < FP_CAP ? sh_n[team] : FP_CAP;
+      if (tt < (int)cn) {
+        const uint32_t kx = cand_key[team][tt];
+        unsigned long long S = 0;
+        for (uint32_t j = 0; j < cn; ++j)
+          if (cand_key[team][j] >= kx) S += cand_mass[team][j];
+        if (A + S >= target) best = kx;
+      }
+    } else if (searching) {
+      best = ~kmin;                       // more than FP_CAP scores within 2^-22: keep them all (min key)
+    }
+    best = tw_wave_max_u32(best);
+    if (lane == 0) redu[team][tw] = best;
+    __syncthreads();
+    if (searching) {
+      uint32_t r = redu[team][0];
+      r = redu[team][1] > r ? redu[team][1] : r;
+      r = redu[team][2] > r ? redu[team][2] : r;
+      r = redu[team][3] > r ? redu[team][3] : r;
+      T = small ? r : ~r;
+    }
+
+    // ---- kept flags, count, optional ascending list; union bits
+    uint32_t cnt = 0;
+    uint32_t keep = 0;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      const bool k = (c0 + e < N) && tw_float_key(s[e]) >= T;
+      keep |= (k ? 1u : 0u) << e;
+      cnt += k ? 1u : 0u;
+    }
+    uint32_t total;
+    const uint32_t incl = tw_group_scan_u32<4>(cnt, ws32 + 4 * team, tw, &total);
+    if (keep) {
+      int32_t* out = a.kept_idx ? a.kept_idx + (long long)bh * a.kept_stride : nullptr;
+      uint32_t pos = incl - cnt;
+#pragma unroll
+      for (int e = 0; e < EPT; ++e) {
+        if ((keep >> e) & 1u) {
+          const int tok = pg[e >> 4] * TW_PAGE + (e & 15);
+          if (out && pos < (uint32_t)a.kept_stride) out[pos] = tok;
+          ++pos;
+          if (tok < FP_BITMAP_WORDS * 32) atomicOr(&bitmap[tok >> 5], 1u << (tok & 31));
+        }
+      }
+    }
+    if (tt == 0) {
+      uint32_t kc = total;
+      if (a.kept_idx && kc > (uint32_t)a.kept_stride) { atomicOr(a.status, TW_STATUS_KEPT_TRUNCATED); kc = a.kept_stride; }
+      a.kept_count[bh] = (int32_t)kc;
+    }
+    __syncthreads();
+  }
+
+  // ---- sorted union from the bitmap: thread t owns a contiguous run of words
+  const int wpt = (nwords + NT - 1) / NT;
+  const int w0 = tid * wpt;
+  uint32_t cnt = 0;
+  for (int i = 0; i < wpt; ++i) cnt += (w0 + i < nwords) ? __popc(bitmap[w0 + i]) : 0;
+  uint32_t total;
+  const uint32_t incl = tw_block_scan_u32(cnt, ws32, &total);
+  int32_t* out = a.union_idx + (long long)blockIdx.x * a.union_stride;
+  uint32_t pos = incl - cnt;
+  for (int i = 0; i < wpt && cnt; ++i) {
+    uint32_t w = (w0 + i < nwords) ? bitmap[w0 + i] : 0u;
+    while (w) {
+      const int bit = __ffs(w) - 1;
+      w &= w - 1;
+      if (pos < (uint32_t)a.union_stride) out[pos] = (w0 + i) * 32 + bit;
+      ++pos;
+    }
+  }
+  if (tid == 0) {
+    if (total > (uint32_t)a.union_stride) { atomicOr(a.status, TW_STATUS_UNION_TRUNCATED); total = a.union_stride; }
+    a.union_count[blockIdx.x] = (int32_t)total;
+  }
+}
+
+template <int G>
+void launch_fused(const FusedArgs& a, int groups, int cand_stride, hipStream_t s) {
+  constexpr int NT = (G < 4 ? G : 4) * FP_TEAM;
+  if (cand_stride <= FP_TEAM * 16) hipLaunchKernelGGL((prune_fused_kernel<G, 16>), dim3(groups), dim3(NT), 0, s, a);
+  else                             hipLaunchKernelGGL((prune_fused_kernel<G, 32>), dim3(groups), dim3(NT), 0, s, a);
+}
+
 // ------------------------------------------------------------------ union
 struct UnionArgs {
   const float* scores;
@@ -540,6 +798,24 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
   uint32_t* thr = (uint32_t*)((char*)ws + (((size_t)d.batch * d.Hq * cand_stride * 4 + 255) & ~(size_t)255));
 
   if (int e = run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, nullptr, s)) return e;
+
+  // per-head page lists short enough for registers and sequences that fit the LDS bitmap:
+  // one fused top-p + union launch
+  if (!full && cand_stride <= FP_TEAM * 32 && (long long)d.max_pages * TW_PAGE <= FP_BITMAP_WORDS * 32ll) {
+    FusedArgs f;
+    f.scores = scores; f.sel_pages = sel_pages; f.sel_count = sel_count; f.seq_lens = kv->seq_lens;
+    f.kept_count = kept_count; f.kept_idx = kept_idx; f.union_count = union_count; f.union_idx = union_idx;
+    f.status = status; f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_sel;
+    f.cand_stride = cand_stride; f.kept_stride = kept_stride; f.union_stride = union_stride; f.p = p;
+    tw_prof_before(TW_K_TOPP, s);
+    switch (d.G) {
+      case 1: launch_fused<1>(f, d.batch * d.Hkv, cand_stride, s); break;
+      case 2: launch_fused<2>(f, d.batch * d.Hkv, cand_stride, s); break;
+      case 4: launch_fused<4>(f, d.batch * d.Hkv, cand_stride, s); break;
+      default: launch_fused<8>(f, d.batch * d.Hkv, cand_stride, s); break;
+    }
+    return tw_prof_after(s);
+  }
 
   ToppArgs t;
   t.scores = scores; t.sel_pages = sel_pages; t.sel_count = sel_count; t.seq_lens = kv->seq_lens;

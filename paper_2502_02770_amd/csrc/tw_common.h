@@ -88,30 +88,102 @@ __device__ __forceinline__ uint32_t tw_float_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// ---- wave64 primitives on DPP (no LDS traffic)
+#define TW_DPP_ROW_SHR(n) (0x110 + (n))
+#define TW_DPP_BCAST15 0x142      // lane 15 of each row -> the next row
+#define TW_DPP_BCAST31 0x143      // lane 31 -> rows 2 and 3
+
+// Inclusive prefix sum over the 64 lanes.
+__device__ __forceinline__ uint32_t tw_wave_scan_u32(uint32_t x) {
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, TW_DPP_ROW_SHR(1), 0xF, 0xF, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, TW_DPP_ROW_SHR(2), 0xF, 0xF, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, TW_DPP_ROW_SHR(4), 0xF, 0xF, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, TW_DPP_ROW_SHR(8), 0xF, 0xF, true);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, TW_DPP_BCAST15, 0xA, 0xF, false);
+  x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, TW_DPP_BCAST31, 0xC, 0xF, false);
+  return x;
+}
+template <int CTRL, int ROWMASK, bool BC>
+__device__ __forceinline__ unsigned long long tw_dpp64(unsigned long long x) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)x, CTRL, ROWMASK, 0xF, BC);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(x >> 32), CTRL, ROWMASK, 0xF, BC);
+  return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned long long tw_wave_scan_u64(unsigned long long x) {
+  x += tw_dpp64<TW_DPP_ROW_SHR(1), 0xF, true>(x);
+  x += tw_dpp64<TW_DPP_ROW_SHR(2), 0xF, true>(x);
+  x += tw_dpp64<TW_DPP_ROW_SHR(4), 0xF, true>(x);
+  x += tw_dpp64<TW_DPP_ROW_SHR(8), 0xF, true>(x);
+  x += tw_dpp64<TW_DPP_BCAST15, 0xA, false>(x);
+  x += tw_dpp64<TW_DPP_BCAST31, 0xC, false>(x);
+  return x;
+}
+// Reductions over the 64 lanes; every lane gets the result.
+__device__ __forceinline__ float tw_wave_max_f(float v) {
+  v = fmaxf(v, tw_dpp_f<TW_DPP_XOR1>(v));
+  v = fmaxf(v, tw_dpp_f<TW_DPP_XOR2>(v));
+  v = fmaxf(v, tw_dpp_f<TW_DPP_HALF_MIRROR>(v));
+  v = fmaxf(v, tw_dpp_f<TW_DPP_MIRROR>(v));
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  v = fmaxf(v, __shfl_xor(v, 32, 64));
+  return v;
+}
+__device__ __forceinline__ float tw_wave_min_f(float v) { return -tw_wave_max_f(-v); }
+__device__ __forceinline__ uint32_t tw_wave_max_u32(uint32_t v) {
+  uint32_t y;
+  y = (uint32_t)tw_dpp_i<TW_DPP_XOR1>((int)v); v = y > v ? y : v;
+  y = (uint32_t)tw_dpp_i<TW_DPP_XOR2>((int)v); v = y > v ? y : v;
+  y = (uint32_t)tw_dpp_i<TW_DPP_HALF_MIRROR>((int)v); v = y > v ? y : v;
+  y = (uint32_t)tw_dpp_i<TW_DPP_MIRROR>((int)v); v = y > v ? y : v;
+  y = (uint32_t)__shfl_xor((int)v, 16, 64); v = y > v ? y : v;
+  y = (uint32_t)__shfl_xor((int)v, 32, 64); v = y > v ? y : v;
+  return v;
+}
+
+// Inclusive scan of one u32 per thread over a group of NW consecutive waves
+// (a whole block, or a team inside it).  `wsum` points at the group's NW
+// words of LDS scratch; w = wave index inside the group.  EVERY thread of
+// the block must call it (two block barriers inside).
+template <int NW>
+__device__ __forceinline__ uint32_t tw_group_scan_u32(uint32_t v, uint32_t* wsum, int w, uint32_t* total) {
+  const uint32_t x = tw_wave_scan_u32(v);
+  if ((threadIdx.x & 63) == 63) wsum[w] = x;
+  __syncthreads();
+  uint32_t off = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) { const uint32_t t = wsum[i]; off += i < w ? t : 0u; tot += t; }
+  __syncthreads();
+  *total = tot;
+  return x + off;
+}
+template <int NW>
+__device__ __forceinline__ unsigned long long tw_group_scan_u64(unsigned long long v, unsigned long long* wsum, int w,
+                                                                unsigned long long* total) {
+  const unsigned long long x = tw_wave_scan_u64(v);
+  if ((threadIdx.x & 63) == 63) wsum[w] = x;
+  __syncthreads();
+  unsigned long long off = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) { const unsigned long long t = wsum[i]; off += i < w ? t : 0ull; tot += t; }
+  __syncthreads();
+  *total = tot;
+  return x + off;
+}
+
 // Block-wide inclusive scan of one u32 per thread, blockDim.x a multiple of 64
-// and at most 1024.  `wsum` is LDS scratch of 17 words.  Returns the inclusive
+// and at most 1024.  `wsum` is LDS scratch of 16 words.  Returns the inclusive
 // prefix; *total gets the block sum.  Ends with a barrier, so it can be called
 // again at once with the same scratch.
 __device__ __forceinline__ uint32_t tw_block_scan_u32(uint32_t v, uint32_t* wsum, uint32_t* total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  uint32_t x = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    uint32_t y = __shfl_up(x, o, 64);
-    if (lane >= o) x += y;
-  }
-  if (lane == 63) wsum[wave] = x;
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const uint32_t x = tw_wave_scan_u32(v);
+  if ((threadIdx.x & 63) == 63) wsum[wave] = x;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t run = 0;
-    for (int w = 0; w < nw; ++w) { uint32_t t = wsum[w]; wsum[w] = run; run += t; }
-    wsum[16] = run;
-  }
+  uint32_t off = 0, tot = 0;
+  for (int i = 0; i < nw; ++i) { const uint32_t t = wsum[i]; off += i < wave ? t : 0u; tot += t; }
   __syncthreads();
-  x += wsum[wave];
-  *total = wsum[16];
-  __syncthreads();
-  return x;
+  *total = tot;
+  return x + off;
 }
 
 #endif  // __HIPCC__
