@@ -129,6 +129,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel table to stderr")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run plain 256 MiB device copies (known traffic, for scaling rocprofv3 --pmc counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the decode hot path shards by (sequence, KV head) "
@@ -139,6 +141,13 @@ def main():
     torch.cuda.set_device(0)
 
     w, cache, st, q, step, setup = build_state(a.config, a.scale, a.seed, a.batch)
+    if a.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)          # elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()

@@ -11,7 +11,7 @@ import os
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libtwilight.so")
+LIB_PATH = os.environ.get("TWILIGHT_LIB") or os.path.join(_PKG, "libtwilight.so")   # override: tuning builds
 
 TW_WS_SELECT, TW_WS_PRUNE, TW_WS_DECODE = 0, 1, 2
 TW_STATUS_UNION_TRUNCATED, TW_STATUS_KEPT_TRUNCATED = 1, 2

@@ -274,9 +274,10 @@ __global__ __launch_bounds__(TP_THREADS) void topp_kernel(ToppArgs a) {
         const float s = TP_LOAD(e);
         if (s > -__builtin_inff()) {
           const uint32_t r = tp_rank(m, s);
-          if ((r & himask) == prefix) {
+          const unsigned long long w = tp_mass(m, s);   // 0 when ~28 below the max: cannot move the threshold
+          if (w != 0 && (r & himask) == prefix) {
             const uint32_t bk = (r >> shift) & ((1u << nbits) - 1u);
-            atomicAdd(&histM[bk], tp_mass(m, s));
+            atomicAdd(&histM[bk], w);
             atomicAdd(&histC[bk], 1u);
           }
         }
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(TP_THREADS) void topp_kernel(ToppArgs a) {
 #pragma unroll
       for (int e = 0; e < iters; ++e) {
         const float s = TP_LOAD(e);
-        if (s > -__builtin_inff() && (tp_rank(m, s) & fmask) == prefix) {
+        if (s > -__builtin_inff() && tp_mass(m, s) != 0 && (tp_rank(m, s) & fmask) == prefix) {
           const uint32_t at = atomicAdd(&sh_n, 1u);
           if (at < 64) { cand_key[at] = tw_float_key(s); cand_mass[at] = tp_mass(m, s); }
         }
@@ -340,7 +341,7 @@ __global__ __launch_bounds__(TP_THREADS) void topp_kernel(ToppArgs a) {
 #pragma unroll
       for (int e = 0; e < iters; ++e) {
         const float s = TP_LOAD(e);
-        if (s > -__builtin_inff() && (tp_rank(m, s) & fmask) == prefix) {
+        if (s > -__builtin_inff() && tp_mass(m, s) != 0 && (tp_rank(m, s) & fmask) == prefix) {
           const uint32_t k = tw_float_key(s);
           kmin = k < kmin ? k : kmin;
         }
@@ -410,7 +411,7 @@ struct FusedArgs {
 
 constexpr int FP_TEAM = 256;                  // threads per team (4 waves)
 constexpr int FP_NB = 512;                    // buckets per pass
-constexpr int FP_CAP = 256;                   // exact resolve handles up to this many scores
+constexpr int FP_CAP = 64;                    // exact resolve handles up to this many scores
 constexpr int FP_BITMAP_WORDS = 6144;         // 196608 tokens
 
 // distance to the max logit in 2^-22 units, saturating at 32 (27 bits)
@@ -470,6 +471,7 @@ __global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(
     for (int v = 0; v < EPT / 16; ++v)
       pg[v] = (c0 + 16 * v < N) ? a.sel_pages[(long long)bh * a.max_sel + (c0 >> 4) + v] : 0;
 
+    TW_STAMP(0);
     // ---- team max
     float m = s[0];
 #pragma unroll
@@ -486,6 +488,7 @@ __global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(
     else if (a.p >= 1.0f) { T = kKeyNegInf + 1u; searching = false; }
     else searching = true;
 
+    TW_STAMP(1);
     // ---- radix bisection, 9 bits per pass; all teams walk the passes together
     uint32_t prefix = 0, pop = 0;
     unsigned long long A = 0, target = 0;
@@ -501,15 +504,19 @@ __global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(
         for (int e = 0; e < EPT; ++e) {
           if (s[e] > -__builtin_inff()) {
             const uint32_t r = fp_rank(m, s[e]);
-            if ((r & himask) == prefix) {
+            // scores whose fixed-point mass is 0 (about 28 below the max) cannot move the
+            // threshold; leaving them out also keeps a far-away bulk off a single bucket
+            const unsigned long long w = tp_mass(m, s[e]);
+            if (w != 0 && (r & himask) == prefix) {
               const uint32_t bk = (r >> shift) & (FP_NB - 1);
-              atomicAdd(&histM[team][bk], tp_mass(m, s[e]));
+              atomicAdd(&histM[team][bk], w);
               atomicAdd(&histC[team][bk], 1u);
             }
           }
         }
       }
       __syncthreads();
+      TW_STAMP(2 + 2 * level);
       unsigned long long m0 = 0, m1 = 0;
       if (active) { m0 = histM[team][2 * tt]; m1 = histM[team][2 * tt + 1]; }
       unsigned long long total;
@@ -536,9 +543,11 @@ __global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(
         more = pop > FP_CAP && level < 2;
         if (more) { ++level; shift -= 9; } else active = false;
       }
+      TW_STAMP(3 + 2 * (level - (more ? 1 : 0)));
       if (!__syncthreads_or(more ? 1 : 0)) break;
     }
 
+    TW_STAMP(8);
     // ---- exact resolve among the `pop` scores whose rank matches `prefix` above bit `shift`
     const uint32_t fmask = 0xFFFFFFFFu << shift;
     const bool small = searching && pop <= FP_CAP;
@@ -546,23 +555,26 @@ __global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(
     if (searching) {
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
-        if (s[e] > -__builtin_inff() && (fp_rank(m, s[e]) & fmask) == prefix) {
+        const unsigned long long w = s[e] > -__builtin_inff() ? tp_mass(m, s[e]) : 0ull;
+        if (w != 0 && (fp_rank(m, s[e]) & fmask) == prefix) {
           const uint32_t k = tw_float_key(s[e]);
           kmin = k < kmin ? k : kmin;
           if (small) {
             const uint32_t at = atomicAdd(&sh_n[team], 1u);
-            if (at < FP_CAP) { cand_key[team][at] = k; cand_mass[team][at] = tp_mass(m, s[e]); }
+            if (at < FP_CAP) { cand_key[team][at] = k; cand_mass[team][at] = w; }
           }
         }
       }
     }
     __syncthreads();
+    TW_STAMP(9);
     uint32_t best = 0;
     if (small) {
       const uint32_t cn = sh_n[team] < FP_CAP ? sh_n[team] : FP_CAP;
       if (tt < (int)cn) {
         const uint32_t kx = cand_key[team][tt];
         unsigned long long S = 0;
+#pragma unroll 8
         for (uint32_t j = 0; j < cn; ++j)
           if (cand_key[team][j] >= kx) S += cand_mass[team][j];
         if (A + S >= target) best = kx;
@@ -581,6 +593,7 @@ __global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(
       T = small ? r : ~r;
     }
 
+    TW_STAMP(10);
     // ---- kept flags, count, optional ascending list; union bits
     uint32_t cnt = 0;
     uint32_t keep = 0;
@@ -613,6 +626,7 @@ __global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(
     __syncthreads();
   }
 
+  TW_STAMP(11);
   // ---- sorted union from the bitmap: thread t owns a contiguous run of words
   const int wpt = (nwords + NT - 1) / NT;
   const int w0 = tid * wpt;
@@ -631,6 +645,7 @@ __global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(
       ++pos;
     }
   }
+  TW_STAMP(12);
   if (tid == 0) {
     if (total > (uint32_t)a.union_stride) { atomicOr(a.status, TW_STATUS_UNION_TRUNCATED); total = a.union_stride; }
     a.union_count[blockIdx.x] = (int32_t)total;
@@ -767,6 +782,12 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
 }
 
 }  // namespace
+
+#ifdef TW_PHASE_TIMING
+extern "C" int twilight_debug_stamps_prune(unsigned long long* host_out) {
+  return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(tw_dbg_stamps), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : -1;
+}
+#endif
 
 extern "C" int twilight_int4_score(const twilight_kv_t* kv, const void* q, const int32_t* sel_pages,
                                    const int32_t* sel_count, int32_t max_sel, float* scores, int32_t* dots,

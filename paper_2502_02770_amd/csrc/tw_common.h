@@ -88,6 +88,15 @@ __device__ __forceinline__ uint32_t tw_float_key(float f) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Phase time stamps for tuning builds (-DTW_PHASE_TIMING): thread 0 of block 0
+// records the 100 MHz wall clock; read back with twilight_debug_stamps().
+#ifdef TW_PHASE_TIMING
+static __device__ unsigned long long tw_dbg_stamps[64];
+#define TW_STAMP(k) do { if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) tw_dbg_stamps[k] = wall_clock64(); } while (0)
+#else
+#define TW_STAMP(k) do { } while (0)
+#endif
+
 // ---- wave64 primitives on DPP (no LDS traffic)
 #define TW_DPP_ROW_SHR(n) (0x110 + (n))
 #define TW_DPP_BCAST15 0x142      // lane 15 of each row -> the next row
