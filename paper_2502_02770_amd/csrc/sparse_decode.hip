@@ -13,6 +13,7 @@
 // of the group share every loaded row, and each 16-lane row keeps its own
 // online-softmax state; states are merged by log-sum-exp, first inside the
 // workgroup, then across items by the combine kernel.
+#include <stdlib.h>
 #include "tw_common.h"
 
 namespace {
@@ -41,15 +42,51 @@ struct DecodeArgs {
 
 __device__ __forceinline__ float tw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <int G>
-__global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
+// row_newbcast:k - lane k of each row of 16 to all lanes of the row
+template <int K>
+__device__ __forceinline__ float tw_row_bcast(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x150 + K, 0xF, 0xF, false));
+}
+#define TW_DPP_ROR4 0x124
+#define TW_DPP_ROR8 0x128
+
+template <int G, int WPS>
+__global__ __launch_bounds__(256, WPS) void sparse_decode_kernel(DecodeArgs a) {
+  constexpr int R = (G + 3) / 4;                 // score values a lane ends up owning per sub-block
+  constexpr int HB = G < 4 ? G : 4;              // heads merged through LDS at a time
   extern __shared__ int32_t prefix[];            // [NG + 1]
-  __shared__ uint32_t wsum[17];
+  __shared__ uint32_t wsum[16];
+  __shared__ uint32_t red3[3][4];
   __shared__ int32_t rows[DEC_MAX_CHUNK];
-  __shared__ float4 mrg_acc[4][G][32];           // per wave: merged accumulators
-  __shared__ float2 mrg_ml[4][G];
+  __shared__ float smax[2][4][8];                // [buffer][wave][head]
+  __shared__ float4 macc[16][HB][32];            // per 16-lane row: accumulators of HB heads
+  __shared__ float ml_s[16][8];                  // per row: softmax denominators
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, seg = tid & 15, rg = tid >> 4;
   const bool dense = a.union_idx == nullptr;
+  const bool b3 = seg & 8, b2 = seg & 4, b1 = seg & 2, b0 = seg & 1;
+  const int my_t = seg >> 2, my_hc = seg & 3;
+
+  // ---- chunk length: the shortest of {c0, 2c0, 4c0} (<= 512) whose item count fits the grid,
+  //      so that short lists are spread over all workgroups and long ones amortise the merge
+  uint32_t n0 = 0, n1 = 0, n2 = 0;
+  const int c0 = a.chunk;
+  for (int gi = tid; gi < a.NG; gi += 256) {
+    int cnt;
+    if (dense) { cnt = a.seq_lens[gi / a.Hkv]; if (cnt > a.max_pages * TW_PAGE) cnt = a.max_pages * TW_PAGE; }
+    else { cnt = a.union_count[gi]; if (cnt > a.union_stride) cnt = a.union_stride; }
+    if (cnt < 0) cnt = 0;
+    n0 += (cnt + c0 - 1) / c0; n1 += (cnt + 2 * c0 - 1) / (2 * c0); n2 += (cnt + 4 * c0 - 1) / (4 * c0);
+  }
+  n0 = tw_wave_scan_u32(n0); n1 = tw_wave_scan_u32(n1); n2 = tw_wave_scan_u32(n2);
+  if (lane == 63) { red3[0][wave] = n0; red3[1][wave] = n1; red3[2][wave] = n2; }
+  __syncthreads();
+  n0 = red3[0][0] + red3[0][1] + red3[0][2] + red3[0][3];
+  n1 = red3[1][0] + red3[1][1] + red3[1][2] + red3[1][3];
+  int chunk = c0;
+  if (n0 > gridDim.x && 2 * c0 <= DEC_MAX_CHUNK) {
+    chunk = 2 * c0;
+    if (n1 > gridDim.x && 4 * c0 <= DEC_MAX_CHUNK) chunk = 4 * c0;
+  }
 
   // ---- item map: exclusive prefix of per-group chunk counts
   uint32_t run = 0;
@@ -58,15 +95,10 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
     uint32_t c = 0;
     if (gi < a.NG) {
       int cnt;
-      if (dense) {
-        cnt = a.seq_lens[gi / a.Hkv];
-        if (cnt > a.max_pages * TW_PAGE) cnt = a.max_pages * TW_PAGE;
-      } else {
-        cnt = a.union_count[gi];
-        if (cnt > a.union_stride) cnt = a.union_stride;
-      }
+      if (dense) { cnt = a.seq_lens[gi / a.Hkv]; if (cnt > a.max_pages * TW_PAGE) cnt = a.max_pages * TW_PAGE; }
+      else { cnt = a.union_count[gi]; if (cnt > a.union_stride) cnt = a.union_stride; }
       if (cnt < 0) cnt = 0;
-      c = (uint32_t)((cnt + a.chunk - 1) / a.chunk);
+      c = (uint32_t)((cnt + chunk - 1) / chunk);
     }
     uint32_t total;
     const uint32_t incl = tw_block_scan_u32(c, wsum, &total);
@@ -90,11 +122,11 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
     int cnt;
     if (dense) { cnt = a.seq_lens[b]; if (cnt > a.max_pages * TW_PAGE) cnt = a.max_pages * TW_PAGE; }
     else { cnt = a.union_count[gi]; if (cnt > a.union_stride) cnt = a.union_stride; }
-    const int t0 = ck * a.chunk;
-    const int len = cnt - t0 < a.chunk ? cnt - t0 : a.chunk;
+    const int t0 = ck * chunk;
+    const int len = cnt - t0 < chunk ? cnt - t0 : chunk;
 
     // ---- stage the chunk's token rows (pool row ids) in LDS
-    for (int i = tid; i < a.chunk; i += 256) {
+    for (int i = tid; i < chunk; i += 256) {
       int r = -1;
       if (i < len) {
         const int tok = dense ? t0 + i : a.union_idx[(long long)gi * a.union_stride + t0 + i];
@@ -114,13 +146,15 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) q[h][i] *= kLog2eRsqrtD;
     }
-    float m[G], l[G], acc[G][8];
+    float acc[G][8], M[G], Mmine[R], lacc[R];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      m[h] = kNegBig; l[h] = 0.f;
+      M[h] = kNegBig;
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[h][i] = 0.f;
     }
+#pragma unroll
+    for (int r = 0; r < R; ++r) { Mmine[r] = kNegBig; lacc[r] = 0.f; }
     __syncthreads();
 
     const int nsub = (len + 63) >> 6;
@@ -139,7 +173,12 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
           vr[t] = make_uint4(0, 0, 0, 0);
         }
       }
-      float s[4][G];
+      // ---- partial dot products of this lane's 8 dims: val[t*4 + h%4][h/4]
+      float val[16][R];
+#pragma unroll
+      for (int c = 0; c < 16; ++c)
+#pragma unroll
+        for (int r = 0; r < R; ++r) val[c][r] = 0.f;
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         float kf[8];
@@ -149,22 +188,84 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
           float d = 0.f;
 #pragma unroll
           for (int i = 0; i < 8; ++i) d = __builtin_fmaf(q[h][i], kf[i], d);
-          d = tw_row16_sum(d);
-          s[t][h] = rr[t] >= 0 ? d : -__builtin_inff();
+          val[t * 4 + (h & 3)][h >> 2] = d;
         }
       }
-      float pw[4][G];
+      // ---- transposing reduction over the 16 lanes of the row: each step a lane keeps the half
+      //      of the values selected by one bit of its lane id and adds the partner's copy of it;
+      //      lane c ends with the full sum of value c
+      float s_mine[R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        float a8[8], a4[4], a2[2];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float keep = b3 ? val[j + 8][r] : val[j][r], send = b3 ? val[j][r] : val[j + 8][r];
+          a8[j] = keep + tw_dpp_f<TW_DPP_MIRROR>(send);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float keep = b2 ? a8[j + 4] : a8[j], send = b2 ? a8[j] : a8[j + 4];
+          a4[j] = keep + tw_dpp_f<TW_DPP_HALF_MIRROR>(send);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const float keep = b1 ? a4[j + 2] : a4[j], send = b1 ? a4[j] : a4[j + 2];
+          a2[j] = keep + tw_dpp_f<TW_DPP_XOR2>(send);
+        }
+        const float keep = b0 ? a2[1] : a2[0], send = b0 ? a2[0] : a2[1];
+        s_mine[r] = keep + tw_dpp_f<TW_DPP_XOR1>(send);
+      }
+      const bool valid = rows[sb * 64 + my_t * 16 + rg] >= 0;
+      // ---- maximum per head over the sub-block: over t inside the row, the 4 rows of the wave, the 4 waves
+      const int buf = sb & 1;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        float mx = valid ? s_mine[r] : -__builtin_inff();
+        mx = fmaxf(mx, tw_dpp_f<TW_DPP_ROR4>(mx));
+        mx = fmaxf(mx, tw_dpp_f<TW_DPP_ROR8>(mx));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        if (lane < 4 && r * 4 + lane < G) smax[buf][wave][r * 4 + lane] = mx;
+      }
+      __syncthreads();
+      float sc[G];
 #pragma unroll
       for (int h = 0; h < G; ++h) {
-        const float mn = fmaxf(fmaxf(fmaxf(s[0][h], s[1][h]), fmaxf(s[2][h], s[3][h])), m[h]);
-        const float sc = tw_exp2(m[h] - mn);
-        m[h] = mn;
-        float ps = 0.f;
+        const float ms = fmaxf(fmaxf(smax[buf][0][h], smax[buf][1][h]), fmaxf(smax[buf][2][h], smax[buf][3][h]));
+        const float mn = fmaxf(M[h], ms);
+        sc[h] = tw_exp2(M[h] - mn);
+        M[h] = mn;
+      }
+      float p_mine[R];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) { pw[t][h] = tw_exp2(s[t][h] - mn); ps += pw[t][h]; }
-        l[h] = __builtin_fmaf(l[h], sc, ps);
+      for (int r = 0; r < R; ++r) {
+        const int hh = (r * 4 + my_hc) < G ? (r * 4 + my_hc) : 0;
+        const float ms = fmaxf(fmaxf(smax[buf][0][hh], smax[buf][1][hh]), fmaxf(smax[buf][2][hh], smax[buf][3][hh]));
+        const float mn = fmaxf(Mmine[r], ms);
+        lacc[r] *= tw_exp2(Mmine[r] - mn);
+        Mmine[r] = mn;
+        p_mine[r] = valid ? tw_exp2(s_mine[r] - mn) : 0.f;
+        lacc[r] += p_mine[r];
+      }
+      if (sb > 0) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc[h][i] *= sc;
+        for (int h = 0; h < G; ++h)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[h][i] *= sc[h];
+      }
+      // ---- every lane needs the 4 x G weights of its row: broadcast them lane by lane
+      float pb[16][R];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        pb[0][r] = tw_row_bcast<0>(p_mine[r]);   pb[1][r] = tw_row_bcast<1>(p_mine[r]);
+        pb[2][r] = tw_row_bcast<2>(p_mine[r]);   pb[3][r] = tw_row_bcast<3>(p_mine[r]);
+        pb[4][r] = tw_row_bcast<4>(p_mine[r]);   pb[5][r] = tw_row_bcast<5>(p_mine[r]);
+        pb[6][r] = tw_row_bcast<6>(p_mine[r]);   pb[7][r] = tw_row_bcast<7>(p_mine[r]);
+        pb[8][r] = tw_row_bcast<8>(p_mine[r]);   pb[9][r] = tw_row_bcast<9>(p_mine[r]);
+        pb[10][r] = tw_row_bcast<10>(p_mine[r]); pb[11][r] = tw_row_bcast<11>(p_mine[r]);
+        pb[12][r] = tw_row_bcast<12>(p_mine[r]); pb[13][r] = tw_row_bcast<13>(p_mine[r]);
+        pb[14][r] = tw_row_bcast<14>(p_mine[r]); pb[15][r] = tw_row_bcast<15>(p_mine[r]);
       }
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -173,68 +274,49 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
 #pragma unroll
         for (int h = 0; h < G; ++h)
 #pragma unroll
-          for (int i = 0; i < 8; ++i) acc[h][i] = __builtin_fmaf(pw[t][h], vf[i], acc[h][i]);
+          for (int i = 0; i < 8; ++i) acc[h][i] = __builtin_fmaf(pb[t * 4 + (h & 3)][h >> 2], vf[i], acc[h][i]);
       }
     }
 
-    // ---- merge the 4 token rows of a wave (lanes l, l^16, l^32, l^48)
+    // ---- merge the 16 rows of the workgroup: all share the running maxima, so plain sums
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      float mw = fmaxf(m[h], __shfl_xor(m[h], 16, 64));
-      mw = fmaxf(mw, __shfl_xor(mw, 32, 64));
-      const float sc = tw_exp2(m[h] - mw);
-      float lw = l[h] * sc;
-      lw += __shfl_xor(lw, 16, 64);
-      lw += __shfl_xor(lw, 32, 64);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        float v = acc[h][i] * sc;
-        v += __shfl_xor(v, 16, 64);
-        v += __shfl_xor(v, 32, 64);
-        acc[h][i] = v;
-      }
-      if (lane < 16) {
-        mrg_acc[wave][h][seg * 2] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
-        mrg_acc[wave][h][seg * 2 + 1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
-        if (seg == 0) mrg_ml[wave][h] = make_float2(mw, lw);
-      }
+    for (int r = 0; r < R; ++r) {
+      float lr = lacc[r];
+      lr += tw_dpp_f<TW_DPP_ROR4>(lr);
+      lr += tw_dpp_f<TW_DPP_ROR8>(lr);
+      if (seg < 4 && r * 4 + seg < G) ml_s[rg][r * 4 + seg] = lr;
     }
-    __syncthreads();
-    // ---- merge the 4 waves: thread (h = rg, seg) for rg < G
-    if (rg < G) {
-      const int h = rg;
-      float M = fmaxf(fmaxf(mrg_ml[0][h].x, mrg_ml[1][h].x), fmaxf(mrg_ml[2][h].x, mrg_ml[3][h].x));
-      float L = 0.f, o[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) o[i] = 0.f;
+    for (int hb = 0; hb < G; hb += HB) {
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float sc = tw_exp2(mrg_ml[w][h].x - M);
-        L = __builtin_fmaf(mrg_ml[w][h].y, sc, L);
-        const float4 a0 = mrg_acc[w][h][seg * 2], a1 = mrg_acc[w][h][seg * 2 + 1];
-        o[0] = __builtin_fmaf(a0.x, sc, o[0]); o[1] = __builtin_fmaf(a0.y, sc, o[1]);
-        o[2] = __builtin_fmaf(a0.z, sc, o[2]); o[3] = __builtin_fmaf(a0.w, sc, o[3]);
-        o[4] = __builtin_fmaf(a1.x, sc, o[4]); o[5] = __builtin_fmaf(a1.y, sc, o[5]);
-        o[6] = __builtin_fmaf(a1.z, sc, o[6]); o[7] = __builtin_fmaf(a1.w, sc, o[7]);
+      for (int h = 0; h < HB; ++h) {
+        macc[rg][h][seg * 2] = make_float4(acc[hb + h][0], acc[hb + h][1], acc[hb + h][2], acc[hb + h][3]);
+        macc[rg][h][seg * 2 + 1] = make_float4(acc[hb + h][4], acc[hb + h][5], acc[hb + h][6], acc[hb + h][7]);
       }
-      const int qh = b * a.Hq + g * G + h;
-      if (nchunks == 1) {                       // the item is the whole list: final result
-        const float inv = L > 0.f ? 1.0f / L : 0.f;
-        uint4 w;
-        w.x = tw_f32_to_bf16(o[0] * inv) | (tw_f32_to_bf16(o[1] * inv) << 16);
-        w.y = tw_f32_to_bf16(o[2] * inv) | (tw_f32_to_bf16(o[3] * inv) << 16);
-        w.z = tw_f32_to_bf16(o[4] * inv) | (tw_f32_to_bf16(o[5] * inv) << 16);
-        w.w = tw_f32_to_bf16(o[6] * inv) | (tw_f32_to_bf16(o[7] * inv) << 16);
-        a.out[(long long)qh * 16 + seg] = w;
-        if (a.lse && seg == 0) a.lse[qh] = L > 0.f ? (M + __log2f(L)) * kLn2 : -__builtin_inff();
-      } else {
-        float4* dst = a.ws_acc + ((long long)item * G + h) * 32;
-        dst[seg * 2] = make_float4(o[0], o[1], o[2], o[3]);
-        dst[seg * 2 + 1] = make_float4(o[4], o[5], o[6], o[7]);
-        if (seg == 0) a.ws_ml[(long long)item * G + h] = make_float2(M, L);
+      __syncthreads();
+      // thread -> 2 adjacent output dims of one head
+      const float2* m2 = (const float2*)&macc[0][0][0];
+      for (int c2 = tid; c2 < HB * 64; c2 += 256) {
+        const int h = hb + c2 / 64, d2 = c2 % 64;
+        float ox = 0.f, oy = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+          const float2 v = m2[w * (HB * 64) + c2];
+          ox += v.x; oy += v.y;
+          L += ml_s[w][h];
+        }
+        const int qh = b * a.Hq + g * G + h;
+        if (nchunks == 1) {                     // the item is the whole list: final result
+          const float inv = L > 0.f ? 1.0f / L : 0.f;
+          ((uint32_t*)a.out)[(long long)qh * 64 + d2] = tw_f32_to_bf16(ox * inv) | (tw_f32_to_bf16(oy * inv) << 16);
+          if (a.lse && d2 == 0) a.lse[qh] = L > 0.f ? (M[h >= G ? 0 : h] + __log2f(L)) * kLn2 : -__builtin_inff();
+        } else {
+          ((float2*)a.ws_acc)[((long long)item * G + h) * 64 + d2] = make_float2(ox, oy);
+          if (d2 == 0) a.ws_ml[(long long)item * G + h] = make_float2(M[h >= G ? 0 : h], L);
+        }
       }
+      __syncthreads();                          // macc / rows / ml_s are reused
     }
-    __syncthreads();                            // rows / mrg_* are reused by the next item
   }
 }
 
@@ -303,7 +385,9 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
 
 template <int G>
 void launch_decode(const DecodeArgs& a, int grid, size_t lds, hipStream_t s) {
-  hipLaunchKernelGGL(sparse_decode_kernel<G>, dim3(grid), dim3(256), lds, s, a);
+  static const bool cap = getenv("TW_DECODE_CAP") != nullptr;     // tuning switch: cap registers for 4 waves per SIMD
+  if (cap && G <= 4) hipLaunchKernelGGL((sparse_decode_kernel<G, 4>), dim3(grid), dim3(256), lds, s, a);
+  else               hipLaunchKernelGGL((sparse_decode_kernel<G, 1>), dim3(grid), dim3(256), lds, s, a);
 }
 
 }  // namespace

@@ -388,256 +388,299 @@ __global__ __launch_bounds__(TP_THREADS) void topp_kernel(ToppArgs a) {
 }
 
 
-// ------------------------------------------------------------------ fused top-p + union
-// One workgroup per (sequence, KV head): the G query heads are handled by
-// teams of 256 threads that run side by side (at most 4 at a time), each
-// keeping its head's candidate scores in registers (thread t of a team owns
-// the contiguous slots [t*EPT, (t+1)*EPT)).  Same threshold search as
-// topp_kernel with 9 bits per pass; the kept tokens then set bits in a
-// shared LDS bitmap from which the group's sorted union is emitted.
-struct FusedArgs {
+// ------------------------------------------------------------------ top-p per head, scores in registers
+// One 256-thread workgroup per (sequence, query head); thread t owns the
+// contiguous candidate slots [t*EPT, (t+1)*EPT) (whole pages).  Rank (fixed-
+// point distance to the max logit) and softmax numerator of every score are
+// computed once and stay in registers.  Pass 0 buckets the ranks within 8
+// logits of the max at 1/64 logit and only sums up everything further down
+// (no atomics); the crossing bucket is narrowed 9 bits per pass until at most
+// HP_CAP scores remain, which are resolved exactly on the score's own bits.
+// Every wave scans the histogram on its own, so a pass costs one barrier.
+// The kept tokens are written as a bitmap over token positions, which
+// bitmap_union_kernel turns into the sorted union of a KV head's query heads.
+struct HeadArgs {
   const float* scores;
   const int32_t* sel_pages;
   const int32_t* sel_count;
   const int32_t* seq_lens;
   int32_t* kept_count;
   int32_t* kept_idx;          // or nullptr
-  int32_t* union_count;
-  int32_t* union_idx;
+  uint32_t* bitmaps;          // [b][Hq][words_stride]
   uint32_t* status;
-  int Hq, Hkv, max_pages, max_sel, cand_stride, kept_stride, union_stride;
+  int Hq, max_pages, max_sel, cand_stride, kept_stride, words_stride;
   float p;
 };
 
-constexpr int FP_TEAM = 256;                  // threads per team (4 waves)
-constexpr int FP_NB = 512;                    // buckets per pass
-constexpr int FP_CAP = 64;                    // exact resolve handles up to this many scores
-constexpr int FP_BITMAP_WORDS = 6144;         // 196608 tokens
+constexpr int HP_NB = 512;                    // buckets per pass
+constexpr int HP_CAP = 64;                    // exact resolve handles up to this many scores
+constexpr int HP_BITMAP_WORDS = 6144;         // 196608 tokens
+constexpr uint32_t HP_FINE_END = 1u << 25;    // ranks below this (8 logits under the max) get the fine first pass
+constexpr uint32_t HP_NONE = 0xFFFFFFFFu;     // rank of a score that takes no part (invalid slot or zero mass)
 
-// distance to the max logit in 2^-22 units, saturating at 32 (27 bits)
-__device__ __forceinline__ uint32_t fp_rank(float m, float s) {
-  const float d = __fsub_rn(m, s);
-  return d >= 32.f ? 0x07FFFFFFu : (uint32_t)(d * 4194304.f);
+// softmax numerator e in (0, 1] -> 2^-40 fixed point, from the float's own bits
+__device__ __forceinline__ unsigned long long hp_fix(float e) {
+  const uint32_t u = __float_as_uint(e);
+  const int sh = (int)(u >> 23) - 127 + 17;                  // mantissa * 2^(exponent - 23 + 40)
+  const unsigned long long mant = (u & 0x7FFFFFu) | 0x800000u;
+  return sh >= 0 ? mant << sh : (sh > -24 ? mant >> (-sh) : 0ull);
 }
 
-template <int G, int EPT>
-__global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(FusedArgs a) {
-  constexpr int TEAMS = G < 4 ? G : 4;
-  constexpr int ROUNDS = G / TEAMS;
-  constexpr int NT = TEAMS * FP_TEAM;
-  const int b = blockIdx.x / a.Hkv, g = blockIdx.x % a.Hkv;
-  const int tid = threadIdx.x, team = tid / FP_TEAM, tt = tid % FP_TEAM, lane = tid & 63, tw = tt >> 6;
+template <int EPT>
+__global__ __launch_bounds__(256) void topp_head_kernel(HeadArgs a) {
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int bh = b * a.Hq + h;
   const int n = a.seq_lens[b];
   int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
   if (P > a.max_pages) P = a.max_pages;
   const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
   const int nwords = (ntok + 31) >> 5;
+  int count = a.sel_count[bh];
+  if (count > a.max_sel) count = a.max_sel;
+  if (count < 0) count = 0;
+  const int N = count * TW_PAGE;
+  const float* row = a.scores + (long long)bh * a.cand_stride;
+  const int c0 = tid * EPT;
 
-  __shared__ unsigned long long histM[TEAMS][FP_NB];
-  __shared__ uint32_t histC[TEAMS][FP_NB];
-  __shared__ unsigned long long cand_mass[TEAMS][FP_CAP];
-  __shared__ uint32_t cand_key[TEAMS][FP_CAP];
-  __shared__ uint32_t bitmap[FP_BITMAP_WORDS];
-  __shared__ unsigned long long ws64[TEAMS][4];
+  __shared__ unsigned long long histM[HP_NB];
+  __shared__ uint32_t histC[HP_NB];
+  __shared__ unsigned long long cand_mass[HP_CAP];
+  __shared__ uint32_t cand_key[HP_CAP];
+  __shared__ uint32_t bitmap[HP_BITMAP_WORDS];
+  __shared__ unsigned long long tail_s[4];
   __shared__ uint32_t ws32[16];
-  __shared__ float redf[TEAMS][4];
-  __shared__ uint32_t redu[TEAMS][4];
-  __shared__ uint32_t sh_bkt[TEAMS], sh_pop[TEAMS], sh_n[TEAMS];
-  __shared__ unsigned long long sh_A[TEAMS];
+  __shared__ float redf[4];
+  __shared__ uint32_t sh_n, sh_kept;
 
-  for (int i = tid; i < nwords; i += NT) bitmap[i] = 0;
-
-#pragma unroll 1
-  for (int round = 0; round < ROUNDS; ++round) {
-    const int h = g * G + round * TEAMS + team;
-    const int bh = b * a.Hq + h;
-    int count = a.sel_count[bh];
-    if (count > a.max_sel) count = a.max_sel;
-    if (count < 0) count = 0;
-    const int N = count * TW_PAGE;
-    const float* row = a.scores + (long long)bh * a.cand_stride;
-    const int c0 = tt * EPT;                          // first candidate slot of this thread
-
-    // ---- scores into registers; logical pages of the owned slots
-    float s[EPT];
-    int pg[EPT / 16];
+  // ---- scores into registers; logical pages of the owned slots
+  float s[EPT];
+  int pg[EPT / 16];
 #pragma unroll
-    for (int v = 0; v < EPT / 4; ++v) {
-      float4 x = make_float4(-__builtin_inff(), -__builtin_inff(), -__builtin_inff(), -__builtin_inff());
-      if (c0 + 4 * v < N) x = *(const float4*)(row + c0 + 4 * v);    // N is a multiple of 16
-      s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
-    }
+  for (int v = 0; v < EPT / 4; ++v) {
+    float4 x = make_float4(-__builtin_inff(), -__builtin_inff(), -__builtin_inff(), -__builtin_inff());
+    if (c0 + 4 * v < N) x = *(const float4*)(row + c0 + 4 * v);      // N is a multiple of 16
+    s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
+  }
 #pragma unroll
-    for (int v = 0; v < EPT / 16; ++v)
-      pg[v] = (c0 + 16 * v < N) ? a.sel_pages[(long long)bh * a.max_sel + (c0 >> 4) + v] : 0;
+  for (int v = 0; v < EPT / 16; ++v)
+    pg[v] = (c0 + 16 * v < N) ? a.sel_pages[(long long)bh * a.max_sel + (c0 >> 4) + v] : 0;
+  histM[tid] = 0; histM[tid + 256] = 0; histC[tid] = 0; histC[tid + 256] = 0;
+  for (int i = tid; i < nwords; i += 256) bitmap[i] = 0;
+  if (tid == 0) { sh_n = 0; sh_kept = 0; }
 
-    TW_STAMP(0);
-    // ---- team max
-    float m = s[0];
+  float m = s[0];
 #pragma unroll
-    for (int e = 1; e < EPT; ++e) m = fmaxf(m, s[e]);
-    m = tw_wave_max_f(m);
-    if (lane == 0) redf[team][tw] = m;
-    if (tt == 0) sh_n[team] = 0;
-    __syncthreads();
-    m = fmaxf(fmaxf(redf[team][0], redf[team][1]), fmaxf(redf[team][2], redf[team][3]));
+  for (int e = 1; e < EPT; ++e) m = fmaxf(m, s[e]);
+  m = tw_wave_max_f(m);
+  if (lane == 0) redf[wave] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(redf[0], redf[1]), fmaxf(redf[2], redf[3]));
+  TW_STAMP(1);
 
-    uint32_t T = 0;
-    bool searching;
-    if (!(m > -__builtin_inff())) { T = 0xFFFFFFFFu; searching = false; }
-    else if (a.p >= 1.0f) { T = kKeyNegInf + 1u; searching = false; }
-    else searching = true;
+  uint32_t T = 0;
+  bool searching;
+  if (!(m > -__builtin_inff())) { T = 0xFFFFFFFFu; searching = false; }
+  else if (a.p >= 1.0f) { T = kKeyNegInf + 1u; searching = false; }
+  else searching = true;
 
-    TW_STAMP(1);
-    // ---- radix bisection, 9 bits per pass; all teams walk the passes together
-    uint32_t prefix = 0, pop = 0;
-    unsigned long long A = 0, target = 0;
-    int shift = 18, level = 0;
-    bool active = searching;
-#pragma unroll 1
-    for (;;) {
-      if (active) { histM[team][tt] = 0; histM[team][tt + 256] = 0; histC[team][tt] = 0; histC[team][tt + 256] = 0; }
-      __syncthreads();
-      if (active) {
-        const uint32_t himask = level == 0 ? 0u : (0xFFFFFFFFu << (shift + 9));
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-          if (s[e] > -__builtin_inff()) {
-            const uint32_t r = fp_rank(m, s[e]);
-            // scores whose fixed-point mass is 0 (about 28 below the max) cannot move the
-            // threshold; leaving them out also keeps a far-away bulk off a single bucket
-            const unsigned long long w = tp_mass(m, s[e]);
-            if (w != 0 && (r & himask) == prefix) {
-              const uint32_t bk = (r >> shift) & (FP_NB - 1);
-              atomicAdd(&histM[team][bk], w);
-              atomicAdd(&histC[team][bk], 1u);
-            }
-          }
-        }
-      }
-      __syncthreads();
-      TW_STAMP(2 + 2 * level);
-      unsigned long long m0 = 0, m1 = 0;
-      if (active) { m0 = histM[team][2 * tt]; m1 = histM[team][2 * tt + 1]; }
-      unsigned long long total;
-      const unsigned long long incl = tw_group_scan_u64<4>(m0 + m1, ws64[team], tw, &total);
-      if (active) {
-        if (level == 0) {
-          const double t = ceil((double)a.p * (double)total);
-          target = t < 1.0 ? 1ull : (unsigned long long)t;
-          if (target > total) target = total;
-        }
-        const unsigned long long before = A + incl - (m0 + m1);
-        if (before < target && before + m0 >= target) {
-          sh_bkt[team] = 2 * tt; sh_A[team] = before; sh_pop[team] = histC[team][2 * tt];
-        } else if (before + m0 < target && before + m0 + m1 >= target) {
-          sh_bkt[team] = 2 * tt + 1; sh_A[team] = before + m0; sh_pop[team] = histC[team][2 * tt + 1];
-        }
-      }
-      __syncthreads();
-      bool more = false;
-      if (active) {
-        prefix |= sh_bkt[team] << shift;
-        A = sh_A[team];
-        pop = sh_pop[team];
-        more = pop > FP_CAP && level < 2;
-        if (more) { ++level; shift -= 9; } else active = false;
-      }
-      TW_STAMP(3 + 2 * (level - (more ? 1 : 0)));
-      if (!__syncthreads_or(more ? 1 : 0)) break;
-    }
-
-    TW_STAMP(8);
-    // ---- exact resolve among the `pop` scores whose rank matches `prefix` above bit `shift`
-    const uint32_t fmask = 0xFFFFFFFFu << shift;
-    const bool small = searching && pop <= FP_CAP;
-    uint32_t kmin = 0xFFFFFFFFu;
-    if (searching) {
-#pragma unroll
-      for (int e = 0; e < EPT; ++e) {
-        const unsigned long long w = s[e] > -__builtin_inff() ? tp_mass(m, s[e]) : 0ull;
-        if (w != 0 && (fp_rank(m, s[e]) & fmask) == prefix) {
-          const uint32_t k = tw_float_key(s[e]);
-          kmin = k < kmin ? k : kmin;
-          if (small) {
-            const uint32_t at = atomicAdd(&sh_n[team], 1u);
-            if (at < FP_CAP) { cand_key[team][at] = k; cand_mass[team][at] = w; }
-          }
-        }
-      }
-    }
-    __syncthreads();
-    TW_STAMP(9);
-    uint32_t best = 0;
-    if (small) {
-      const uint32_t cn = sh_n[team] < FP_CAP ? sh_n[team] : FP_CAP;
-      if (tt < (int)cn) {
-        const uint32_t kx = cand_key[team][tt];
-        unsigned long long S = 0;
-#pragma unroll 8
-        for (uint32_t j = 0; j < cn; ++j)
-          if (cand_key[team][j] >= kx) S += cand_mass[team][j];
-        if (A + S >= target) best = kx;
-      }
-    } else if (searching) {
-      best = ~kmin;                       // more than FP_CAP scores within 2^-22: keep them all (min key)
-    }
-    best = tw_wave_max_u32(best);
-    if (lane == 0) redu[team][tw] = best;
-    __syncthreads();
-    if (searching) {
-      uint32_t r = redu[team][0];
-      r = redu[team][1] > r ? redu[team][1] : r;
-      r = redu[team][2] > r ? redu[team][2] : r;
-      r = redu[team][3] > r ? redu[team][3] : r;
-      T = small ? r : ~r;
-    }
-
-    TW_STAMP(10);
-    // ---- kept flags, count, optional ascending list; union bits
-    uint32_t cnt = 0;
-    uint32_t keep = 0;
+  if (searching) {                                 // block-uniform
+    // rank and numerator of every score, computed once
+    uint32_t rk[EPT];
+    float ef[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      const bool k = (c0 + e < N) && tw_float_key(s[e]) >= T;
-      keep |= (k ? 1u : 0u) << e;
-      cnt += k ? 1u : 0u;
+      const float d = __fsub_rn(m, s[e]);
+      ef[e] = __expf(-d);
+      rk[e] = (d < 32.f && hp_fix(ef[e]) != 0) ? (uint32_t)(d * 4194304.f) : HP_NONE;
     }
-    uint32_t total;
-    const uint32_t incl = tw_group_scan_u32<4>(cnt, ws32 + 4 * team, tw, &total);
-    if (keep) {
-      int32_t* out = a.kept_idx ? a.kept_idx + (long long)bh * a.kept_stride : nullptr;
-      uint32_t pos = incl - cnt;
+    uint32_t rlo = 0, pop = 0;
+    int shift = 16, pass = 0;
+    unsigned long long A = 0, target = 0;
+#pragma unroll 1
+    for (;;) {
+      if (pass > 0) {
+        histM[tid] = 0; histM[tid + 256] = 0; histC[tid] = 0; histC[tid + 256] = 0;
+        __syncthreads();
+      }
+      unsigned long long below = 0;                // mass past the end of the interval (pass 0 only)
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
-        if ((keep >> e) & 1u) {
-          const int tok = pg[e >> 4] * TW_PAGE + (e & 15);
-          if (out && pos < (uint32_t)a.kept_stride) out[pos] = tok;
-          ++pos;
-          if (tok < FP_BITMAP_WORDS * 32) atomicOr(&bitmap[tok >> 5], 1u << (tok & 31));
+        if (rk[e] != HP_NONE && rk[e] >= rlo) {
+          const uint32_t bk = (rk[e] - rlo) >> shift;
+          const unsigned long long w = hp_fix(ef[e]);
+          if (bk < HP_NB) { atomicAdd(&histM[bk], w); atomicAdd(&histC[bk], 1u); }
+          else below += w;
+        }
+      }
+      if (pass == 0) {
+        below = tw_wave_scan_u64(below);
+        if (lane == 63) tail_s[wave] = below;
+      }
+      __syncthreads();
+      TW_STAMP(2 + pass);
+      // every wave scans the 512 buckets on its own: lane l owns buckets 8l .. 8l+7
+      unsigned long long mb[8], mine = 0;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { mb[k] = histM[8 * lane + k]; mine += mb[k]; }
+      const unsigned long long incl = tw_wave_scan_u64(mine);
+      const unsigned long long total = __shfl(incl, 63, 64);
+      if (pass == 0) {
+        const unsigned long long Z = total + tail_s[0] + tail_s[1] + tail_s[2] + tail_s[3];
+        const double t = ceil((double)a.p * (double)Z);
+        target = t < 1.0 ? 1ull : (unsigned long long)t;
+        if (target > Z) target = Z;
+      }
+      const unsigned long long before = A + incl - mine;
+      const bool hit = before < target && before + mine >= target;
+      const unsigned long long bal = __ballot(hit);
+      bool more = false;
+      if (bal == 0 && pass == 0) {
+        // not enough mass in the fine range: go on with everything below it
+        A += total;
+        rlo = HP_FINE_END; shift = 18;
+        more = true;
+      } else if (bal == 0) {
+        pop = 0xFFFFFFFFu;                          // unreachable: the interval holds the crossing by construction
+      } else {
+        const int src = __ffsll((long long)bal) - 1;
+        unsigned long long cum = before, asel = before;
+        int bsel = 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          if (cum < target && cum + mb[k] >= target) { bsel = k; asel = cum; }
+          cum += mb[k];
+        }
+        const int bucket = 8 * src + __shfl(bsel, src, 64);
+        A = __shfl(asel, src, 64);
+        pop = histC[bucket];
+        rlo += (uint32_t)bucket << shift;
+        if (pop > HP_CAP && shift > 0) { shift = shift >= 9 ? shift - 9 : 0; more = true; }
+      }
+      ++pass;
+      if (!more) break;                             // same decision in every wave
+      __syncthreads();                              // all scans done before the histogram is cleared
+    }
+    // the threshold lies among the `pop` scores with rank in [rlo, rlo + (1 << shift))
+    const uint32_t rhi = rlo + (1u << shift) - 1u;
+    const bool small = pop <= HP_CAP;
+    uint32_t kmin = 0xFFFFFFFFu;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if (rk[e] != HP_NONE && rk[e] >= rlo && rk[e] <= rhi) {
+        const uint32_t k = tw_float_key(s[e]);
+        kmin = k < kmin ? k : kmin;
+        if (small) {
+          const uint32_t at = atomicAdd(&sh_n, 1u);
+          if (at < HP_CAP) { cand_key[at] = k; cand_mass[at] = hp_fix(ef[e]); }
         }
       }
     }
-    if (tt == 0) {
-      uint32_t kc = total;
-      if (a.kept_idx && kc > (uint32_t)a.kept_stride) { atomicOr(a.status, TW_STATUS_KEPT_TRUNCATED); kc = a.kept_stride; }
-      a.kept_count[bh] = (int32_t)kc;
+    if (!small) {                                   // > HP_CAP scores within one rank: keep them all
+      kmin = ~tw_wave_max_u32(~kmin);
+      if (lane == 0) redf[wave] = __uint_as_float(kmin);
     }
     __syncthreads();
+    TW_STAMP(8);
+    if (small) {
+      // every wave resolves on its own: lane x takes candidate x
+      const uint32_t cn = sh_n < HP_CAP ? sh_n : HP_CAP;
+      const uint32_t kx = lane < (int)cn ? cand_key[lane] : 0u;
+      unsigned long long S = 0;
+#pragma unroll 8
+      for (uint32_t j = 0; j < cn; ++j)
+        if (cand_key[j] >= kx) S += cand_mass[j];
+      const uint32_t best = (lane < (int)cn && A + S >= target) ? kx : 0u;
+      T = tw_wave_max_u32(best);
+    } else {
+      uint32_t r = __float_as_uint(redf[0]);
+#pragma unroll
+      for (int w = 1; w < 4; ++w) { const uint32_t y = __float_as_uint(redf[w]); r = y < r ? y : r; }
+      T = r;
+    }
+    TW_STAMP(9);
   }
 
-  TW_STAMP(11);
-  // ---- sorted union from the bitmap: thread t owns a contiguous run of words
-  const int wpt = (nwords + NT - 1) / NT;
+  // ---- kept flags, count, optional ascending list; bitmap over token positions
+  uint32_t cnt = 0, keep = 0;
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) {
+    const bool k = (c0 + e < N) && tw_float_key(s[e]) >= T;
+    keep |= (k ? 1u : 0u) << e;
+    cnt += k ? 1u : 0u;
+  }
+  uint32_t pos = 0;
+  if (a.kept_idx) {                                // ordered positions need a scan over the block
+    uint32_t total;
+    const uint32_t incl = tw_block_scan_u32(cnt, ws32, &total);
+    pos = incl - cnt;
+    if (tid == 0) sh_kept = total;
+  } else {
+    const uint32_t wsumc = tw_wave_scan_u32(cnt);
+    if (lane == 63 && wsumc) atomicAdd(&sh_kept, wsumc);
+  }
+#pragma unroll
+  for (int v = 0; v < EPT / 16; ++v) {
+    const uint32_t mask = (keep >> (16 * v)) & 0xFFFFu;
+    if (mask) {
+      const int tok0 = pg[v] * TW_PAGE;
+      if (tok0 + 15 < HP_BITMAP_WORDS * 32) atomicOr(&bitmap[tok0 >> 5], mask << (tok0 & 31));
+      if (a.kept_idx) {
+        int32_t* out = a.kept_idx + (long long)bh * a.kept_stride;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if ((mask >> e) & 1u) { if (pos < (uint32_t)a.kept_stride) out[pos] = tok0 + e; ++pos; }
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* bm = a.bitmaps + (long long)bh * a.words_stride;
+  for (int i = tid; i < nwords; i += 256) bm[i] = bitmap[i];
+  if (tid == 0) {
+    uint32_t kc = sh_kept;
+    if (a.kept_idx && kc > (uint32_t)a.kept_stride) { atomicOr(a.status, TW_STATUS_KEPT_TRUNCATED); kc = a.kept_stride; }
+    a.kept_count[bh] = (int32_t)kc;
+  }
+  TW_STAMP(12);
+}
+
+// Sorted union of the G per-head bitmaps of one (sequence, KV head); thread t
+// owns a contiguous run of words.
+struct BitmapUnionArgs {
+  const uint32_t* bitmaps;
+  const int32_t* seq_lens;
+  int32_t* union_count;
+  int32_t* union_idx;
+  uint32_t* status;
+  int Hq, Hkv, G, max_pages, words_stride, union_stride;
+};
+
+__global__ __launch_bounds__(1024) void bitmap_union_kernel(BitmapUnionArgs a) {
+  const int b = blockIdx.x / a.Hkv, g = blockIdx.x % a.Hkv, tid = threadIdx.x;
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
+  const int nwords = (ntok + 31) >> 5;
+  __shared__ uint32_t ws32[16];
+  const int wpt = (nwords + 1023) / 1024;
   const int w0 = tid * wpt;
+  const uint32_t* bm = a.bitmaps + ((long long)(b * a.Hq + g * a.G)) * a.words_stride;
   uint32_t cnt = 0;
-  for (int i = 0; i < wpt; ++i) cnt += (w0 + i < nwords) ? __popc(bitmap[w0 + i]) : 0;
+  for (int i = 0; i < wpt; ++i) {
+    if (w0 + i < nwords) {
+      uint32_t w = 0;
+      for (int hh = 0; hh < a.G; ++hh) w |= bm[(long long)hh * a.words_stride + w0 + i];
+      cnt += __popc(w);
+    }
+  }
   uint32_t total;
   const uint32_t incl = tw_block_scan_u32(cnt, ws32, &total);
   int32_t* out = a.union_idx + (long long)blockIdx.x * a.union_stride;
   uint32_t pos = incl - cnt;
   for (int i = 0; i < wpt && cnt; ++i) {
-    uint32_t w = (w0 + i < nwords) ? bitmap[w0 + i] : 0u;
+    if (w0 + i >= nwords) break;
+    uint32_t w = 0;
+    for (int hh = 0; hh < a.G; ++hh) w |= bm[(long long)hh * a.words_stride + w0 + i];
     while (w) {
       const int bit = __ffs(w) - 1;
       w &= w - 1;
@@ -645,18 +688,10 @@ __global__ __launch_bounds__((G < 4 ? G : 4) * FP_TEAM) void prune_fused_kernel(
       ++pos;
     }
   }
-  TW_STAMP(12);
   if (tid == 0) {
     if (total > (uint32_t)a.union_stride) { atomicOr(a.status, TW_STATUS_UNION_TRUNCATED); total = a.union_stride; }
     a.union_count[blockIdx.x] = (int32_t)total;
   }
-}
-
-template <int G>
-void launch_fused(const FusedArgs& a, int groups, int cand_stride, hipStream_t s) {
-  constexpr int NT = (G < 4 ? G : 4) * FP_TEAM;
-  if (cand_stride <= FP_TEAM * 16) hipLaunchKernelGGL((prune_fused_kernel<G, 16>), dim3(groups), dim3(NT), 0, s, a);
-  else                             hipLaunchKernelGGL((prune_fused_kernel<G, 32>), dim3(groups), dim3(NT), 0, s, a);
 }
 
 // ------------------------------------------------------------------ union
@@ -821,20 +856,25 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
   if (int e = run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, nullptr, s)) return e;
 
   // per-head page lists short enough for registers and sequences that fit the LDS bitmap:
-  // one fused top-p + union launch
-  if (!full && cand_stride <= FP_TEAM * 32 && (long long)d.max_pages * TW_PAGE <= FP_BITMAP_WORDS * 32ll) {
-    FusedArgs f;
+  // register-resident top-p per head, then the union of the heads' bitmaps
+  if (!full && cand_stride <= 256 * 32 && (long long)d.max_pages * TW_PAGE <= HP_BITMAP_WORDS * 32ll) {
+    const int words_stride = (d.max_pages + 1) / 2;
+    uint32_t* bitmaps = thr + (((size_t)d.batch * d.Hq + 63) & ~(size_t)63);
+    HeadArgs f;
     f.scores = scores; f.sel_pages = sel_pages; f.sel_count = sel_count; f.seq_lens = kv->seq_lens;
-    f.kept_count = kept_count; f.kept_idx = kept_idx; f.union_count = union_count; f.union_idx = union_idx;
-    f.status = status; f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_sel;
-    f.cand_stride = cand_stride; f.kept_stride = kept_stride; f.union_stride = union_stride; f.p = p;
+    f.kept_count = kept_count; f.kept_idx = kept_idx; f.bitmaps = bitmaps; f.status = status;
+    f.Hq = d.Hq; f.max_pages = d.max_pages; f.max_sel = max_sel; f.cand_stride = cand_stride;
+    f.kept_stride = kept_stride; f.words_stride = words_stride; f.p = p;
     tw_prof_before(TW_K_TOPP, s);
-    switch (d.G) {
-      case 1: launch_fused<1>(f, d.batch * d.Hkv, cand_stride, s); break;
-      case 2: launch_fused<2>(f, d.batch * d.Hkv, cand_stride, s); break;
-      case 4: launch_fused<4>(f, d.batch * d.Hkv, cand_stride, s); break;
-      default: launch_fused<8>(f, d.batch * d.Hkv, cand_stride, s); break;
-    }
+    if (cand_stride <= 256 * 16) hipLaunchKernelGGL(topp_head_kernel<16>, dim3(d.Hq, d.batch), dim3(256), 0, s, f);
+    else                         hipLaunchKernelGGL(topp_head_kernel<32>, dim3(d.Hq, d.batch), dim3(256), 0, s, f);
+    if (int e = tw_prof_after(s)) return e;
+    BitmapUnionArgs u;
+    u.bitmaps = bitmaps; u.seq_lens = kv->seq_lens; u.union_count = union_count; u.union_idx = union_idx;
+    u.status = status; u.Hq = d.Hq; u.Hkv = d.Hkv; u.G = d.G; u.max_pages = d.max_pages;
+    u.words_stride = words_stride; u.union_stride = union_stride;
+    tw_prof_before(TW_K_UNION, s);
+    hipLaunchKernelGGL(bitmap_union_kernel, dim3(d.batch * d.Hkv), dim3(1024), 0, s, u);
     return tw_prof_after(s);
   }
 
