@@ -44,22 +44,31 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
     tw_unpack8(r, q[h]);
   }
 
-#pragma unroll 2
-  for (int it = 0; it < PS_PAGES_PER_WG / 16; ++it) {
-    const int lp = base + it * 16 + grp;
-    const bool live = lp < P;
-    long long pool = live ? (long long)a.page_table[(long long)b * a.max_pages + lp] : -1;
-    const bool ok = pool >= 0 && pool < a.pool_pages;
-    float mn[8], mx[8];
-    if (ok) {
-      const uint4* pm = a.page_minmax + (pool * a.Hkv + g) * 32;
-      const uint4 rmn = pm[seg], rmx = pm[16 + seg];
-      tw_unpack8(rmn, mn);
-      tw_unpack8(rmx, mx);
-    } else {
+  // page-table entries of this lane's 4 pages first, then all 8 bound loads (clamped addresses,
+  // unconditional) so that they are in flight together; unmapped pages are masked afterwards
+  constexpr int IT = PS_PAGES_PER_WG / 16;
+  long long pool[IT];
+  bool live[IT], ok[IT];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { mn[i] = 0.f; mx[i] = 0.f; }
-    }
+  for (int it = 0; it < IT; ++it) {
+    const int lp = base + it * 16 + grp;
+    live[it] = lp < P;
+    pool[it] = a.page_table[(long long)b * a.max_pages + (live[it] ? lp : P - 1)];
+  }
+  uint4 rmn[IT], rmx[IT];
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    ok[it] = live[it] && pool[it] >= 0 && pool[it] < a.pool_pages;
+    const uint4* pm = a.page_minmax + ((ok[it] ? pool[it] : 0) * a.Hkv + g) * 32;
+    rmn[it] = pm[seg];
+    rmx[it] = pm[16 + seg];
+  }
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int lp = base + it * 16 + grp;
+    float mn[8], mx[8];
+    tw_unpack8(rmn[it], mn);
+    tw_unpack8(rmx[it], mx);
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       float acc = 0.f;
@@ -71,9 +80,9 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
         acc = __builtin_fmaf(q[h][i], v, acc);
       }
       acc = tw_row16_sum(acc);
-      if (seg == 0 && live)
+      if (seg == 0 && live[it])
         a.scores[((long long)(b * a.Hq + g * G + h)) * a.max_pages + lp] =
-            ok ? __fadd_rn(acc, 0.0f) : -3.402823466e38f;   // unmapped page: ranks last
+            ok[it] ? __fadd_rn(acc, 0.0f) : -3.402823466e38f;   // unmapped page: ranks last
     }
   }
 }
@@ -173,7 +182,9 @@ __device__ __forceinline__ float tw_key_float(uint32_t k) {
   return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
 }
 
-__global__ __launch_bounds__(256) void page_select_lds_kernel(SelectArgs a) {
+template <int NT>
+__global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
+  constexpr int NW = NT / 64, BPT = SEL_NB / NT;      // waves; histogram buckets per thread
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = a.seq_lens[b];
   int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
@@ -188,24 +199,33 @@ __global__ __launch_bounds__(256) void page_select_lds_kernel(SelectArgs a) {
   if (tid == 0) a.sel_count[b * a.Hq + h] = Kp;
   if (Kp == 0) return;
   if (Kp == P) {
-    for (int i = tid; i < P; i += 256) out[i] = i;
+    for (int i = tid; i < P; i += NT) out[i] = i;
     return;
   }
 
   __shared__ uint32_t key_s[SEL_LDS_PAGES];
   __shared__ uint32_t hist[SEL_NB];
   __shared__ uint32_t wsum[16];
-  __shared__ uint32_t red_lo[4], red_hi[4];
+  __shared__ uint32_t red_lo[NW], red_hi[NW];
   __shared__ uint32_t sh_bkt, sh_need, sh_pop, sh_n, sh_T, sh_need_eq;
   __shared__ uint32_t ck[SEL_CAP];
   __shared__ int32_t ci[SEL_CAP];
 
   uint32_t lo = 0xFFFFFFFFu, hi = 0u;
-  for (int i = tid; i < P; i += 256) {
-    const uint32_t k = tw_float_key(sc[i]);
-    key_s[i] = k;
-    lo = k < lo ? k : lo;
-    hi = k > hi ? k : hi;
+  for (int base = 0; base < P; base += 8 * NT) {    // 8 clamped loads in flight per thread
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { const int i = base + j * NT + tid; v[j] = sc[i < P ? i : P - 1]; }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int i = base + j * NT + tid;
+      if (i < P) {
+        const uint32_t k = tw_float_key(v[j]);
+        key_s[i] = k;
+        lo = k < lo ? k : lo;
+        hi = k > hi ? k : hi;
+      }
+    }
   }
   lo = ~tw_wave_max_u32(~lo);
   hi = tw_wave_max_u32(hi);
@@ -214,7 +234,7 @@ __global__ __launch_bounds__(256) void page_select_lds_kernel(SelectArgs a) {
   __syncthreads();
   uint32_t klo = red_lo[0], khi = red_hi[0];
 #pragma unroll
-  for (int w = 1; w < 4; ++w) { klo = red_lo[w] < klo ? red_lo[w] : klo; khi = red_hi[w] > khi ? red_hi[w] : khi; }
+  for (int w = 1; w < NW; ++w) { klo = red_lo[w] < klo ? red_lo[w] : klo; khi = red_hi[w] > khi ? red_hi[w] : khi; }
 
   uint32_t need = (uint32_t)Kp, T = 0, need_eq = 0;
 #pragma unroll 1
@@ -223,9 +243,9 @@ __global__ __launch_bounds__(256) void page_select_lds_kernel(SelectArgs a) {
     if (klo == khi || pass == 64) { T = klo; need_eq = need; break; }      // everything left ties
     const float smn = tw_key_float(klo), smx = tw_key_float(khi);
     const float scale = (float)SEL_NB / (smx - smn);
-    for (int i = tid; i < SEL_NB; i += 256) hist[i] = 0;
+    for (int i = tid; i < SEL_NB; i += NT) hist[i] = 0;
     __syncthreads();
-    for (int i = tid; i < P; i += 256) {
+    for (int i = tid; i < P; i += NT) {
       const uint32_t k = key_s[i];
       if (k >= klo && k <= khi) {
         int bk = (int)((tw_key_float(k) - smn) * scale);
@@ -234,17 +254,17 @@ __global__ __launch_bounds__(256) void page_select_lds_kernel(SelectArgs a) {
       }
     }
     __syncthreads();
-    // thread t owns the 8 buckets 2047-8t .. 2040-8t, walked downwards
-    uint32_t c[8], mine = 0;
+    // thread t owns the BPT buckets below 2047 - BPT*t, walked downwards
+    uint32_t c[BPT], mine = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { c[j] = hist[SEL_NB - 1 - (8 * tid + j)]; mine += c[j]; }
+    for (int j = 0; j < BPT; ++j) { c[j] = hist[SEL_NB - 1 - (BPT * tid + j)]; mine += c[j]; }
     uint32_t total;
     const uint32_t incl = tw_block_scan_u32(mine, wsum, &total);
     uint32_t above = incl - mine;
     if (above < need && incl >= need) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        if (above < need && above + c[j] >= need) { sh_bkt = SEL_NB - 1 - (8 * tid + j); sh_need = need - above; sh_pop = c[j]; }
+      for (int j = 0; j < BPT; ++j) {
+        if (above < need && above + c[j] >= need) { sh_bkt = SEL_NB - 1 - (BPT * tid + j); sh_need = need - above; sh_pop = c[j]; }
         above += c[j];
       }
     }
@@ -255,7 +275,7 @@ __global__ __launch_bounds__(256) void page_select_lds_kernel(SelectArgs a) {
     // narrow to the keys of that bucket; collect them when few enough for the exact finish
     const bool small = pop <= SEL_CAP && pop != need;
     uint32_t nlo = 0xFFFFFFFFu, nhi = 0u;
-    for (int i = tid; i < P; i += 256) {
+    for (int i = tid; i < P; i += NT) {
       const uint32_t k = key_s[i];
       if (k >= klo && k <= khi) {
         int bk = (int)((tw_key_float(k) - smn) * scale);
@@ -273,7 +293,7 @@ __global__ __launch_bounds__(256) void page_select_lds_kernel(SelectArgs a) {
     __syncthreads();
     klo = red_lo[0]; khi = red_hi[0];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) { klo = red_lo[w] < klo ? red_lo[w] : klo; khi = red_hi[w] > khi ? red_hi[w] : khi; }
+    for (int w = 1; w < NW; ++w) { klo = red_lo[w] < klo ? red_lo[w] : klo; khi = red_hi[w] > khi ? red_hi[w] : khi; }
     if (pop == need) { T = klo; need_eq = 0xFFFFFFFFu; break; }   // the whole bucket is taken
     if (small) {
       // exact: the candidate of rank need-1 (by bound, then by lower page id) is the last one taken
@@ -298,7 +318,7 @@ __global__ __launch_bounds__(256) void page_select_lds_kernel(SelectArgs a) {
   }
 
   // ---- ordered emit: thread t owns the contiguous pages [t*E, (t+1)*E)
-  const int E = (P + 255) / 256;
+  const int E = (P + NT - 1) / NT;
   const int i0 = tid * E, i1 = (i0 + E < P) ? i0 + E : P;
   uint32_t gt = 0, eq = 0;
   for (int i = i0; i < i1; ++i) { const uint32_t k = key_s[i]; gt += k > T ? 1u : 0u; eq += k == T ? 1u : 0u; }
@@ -351,8 +371,10 @@ extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, con
   sa.sel_pages = sel_pages; sa.sel_count = sel_count;
   sa.Hq = d.Hq; sa.max_pages = d.max_pages; sa.max_sel = max_sel;
   tw_prof_before(TW_K_PAGE_SELECT, s);
-  if (d.max_pages <= SEL_LDS_PAGES)
-    hipLaunchKernelGGL(page_select_lds_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+  if (d.max_pages <= 2048)
+    hipLaunchKernelGGL(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+  else if (d.max_pages <= SEL_LDS_PAGES)
+    hipLaunchKernelGGL(page_select_lds_kernel<1024>, dim3(d.Hq, d.batch), dim3(1024), 0, s, sa);
   else
     hipLaunchKernelGGL(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
   return tw_prof_after(s);

@@ -11,6 +11,7 @@
 //             depend on the order of the atomics), finished by an exact
 //             resolve on the score's own bit pattern inside one wave.
 // union       per (sequence, KV head): bitmap in LDS, ordered emit.
+#include <stdlib.h>
 #include "tw_common.h"
 
 namespace {
@@ -30,6 +31,7 @@ struct ScoreArgs {
   const uint32_t* kq_meta;    // 64 words per (page, head)
   float* scores;              // [b][Hq][cand_stride]
   int32_t* dots;              // [b][Hq][cand_stride][4] or nullptr
+  uint32_t* arrive;           // [b][Hkv] arrival counters of the top-p kernel that follows, or nullptr
   int Hq, Hkv, max_pages, max_sel, cand_stride, pw;   // pw: pages per wave (<= 64)
   long long pool_pages;
 };
@@ -48,6 +50,7 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   int count = P;
   if (!FULL) { count = a.sel_count[b * a.Hq + h0]; if (count > a.max_sel) count = a.max_sel; }
   const int wg_first = blockIdx.x * 4 * a.pw;
+  if (a.arrive && blockIdx.x == 0 && tid == 0) a.arrive[b * a.Hkv + g] = 0;
   if (wg_first >= count) return;
 
   // ---- quantise q of the NH heads to int8 (symmetric, per head)
@@ -112,13 +115,11 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
     const int k = k0 + kk;                     // wave-uniform; pages past the end act as invalid
     const int lp = __builtin_amdgcn_readlane(my_lp, k & 63);
     const int pool = k < npages ? __builtin_amdgcn_readlane(my_pool, k & 63) : -1;
-    uint4 nib = make_uint4(0, 0, 0, 0);
-    uint32_t meta = 0;
-    if (pool >= 0) {
-      const long long blk = ((long long)pool * a.Hkv + g) * 64;
-      nib = a.kq_pool[blk + lane];
-      meta = a.kq_meta[blk + lane];
-    }
+    // unconditional loads (an unmapped page reads pool page 0 and is masked below), so that the
+    // four pages of an unrolled step are in flight together
+    const long long blk = ((long long)(pool >= 0 ? pool : 0) * a.Hkv + g) * 64;
+    const uint4 nib = a.kq_pool[blk + lane];
+    const uint32_t meta = a.kq_meta[blk + lane];
     const int u0 = nib.x & 0x0F0F0F0F, u1 = (nib.x >> 4) & 0x0F0F0F0F;
     const int u2 = nib.y & 0x0F0F0F0F, u3 = (nib.y >> 4) & 0x0F0F0F0F;
     const int u4 = nib.z & 0x0F0F0F0F, u5 = (nib.z >> 4) & 0x0F0F0F0F;
@@ -389,7 +390,7 @@ __global__ __launch_bounds__(TP_THREADS) void topp_kernel(ToppArgs a) {
 
 
 // ------------------------------------------------------------------ top-p per head, scores in registers
-// One 256-thread workgroup per (sequence, query head); thread t owns the
+// One workgroup (256 or 512 threads) per (sequence, query head); thread t owns the
 // contiguous candidate slots [t*EPT, (t+1)*EPT) (whole pages).  Rank (fixed-
 // point distance to the max logit) and softmax numerator of every score are
 // computed once and stay in registers.  Pass 0 buckets the ranks within 8
@@ -407,8 +408,11 @@ struct HeadArgs {
   int32_t* kept_count;
   int32_t* kept_idx;          // or nullptr
   uint32_t* bitmaps;          // [b][Hq][words_stride]
+  uint32_t* arrive;           // [b][Hkv] arrival counters, zero on entry
+  int32_t* union_count;
+  int32_t* union_idx;
   uint32_t* status;
-  int Hq, max_pages, max_sel, cand_stride, kept_stride, words_stride;
+  int Hq, Hkv, max_pages, max_sel, cand_stride, kept_stride, words_stride, union_stride;
   float p;
 };
 
@@ -426,8 +430,9 @@ __device__ __forceinline__ unsigned long long hp_fix(float e) {
   return sh >= 0 ? mant << sh : (sh > -24 ? mant >> (-sh) : 0ull);
 }
 
-template <int EPT>
-__global__ __launch_bounds__(256) void topp_head_kernel(HeadArgs a) {
+template <int NT, int EPT, int G>
+__global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
+  constexpr int NW = NT / 64;
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bh = b * a.Hq + h;
   const int n = a.seq_lens[b];
@@ -447,25 +452,32 @@ __global__ __launch_bounds__(256) void topp_head_kernel(HeadArgs a) {
   __shared__ unsigned long long cand_mass[HP_CAP];
   __shared__ uint32_t cand_key[HP_CAP];
   __shared__ uint32_t bitmap[HP_BITMAP_WORDS];
-  __shared__ unsigned long long tail_s[4];
+  __shared__ unsigned long long tail_s[NW];
   __shared__ uint32_t ws32[16];
-  __shared__ float redf[4];
-  __shared__ uint32_t sh_n, sh_kept;
+  __shared__ float redf[NW];
+  __shared__ uint32_t sh_n, sh_kept, sh_T, sh_last;
 
   // ---- scores into registers; logical pages of the owned slots
+  // (loads do not wait for the list length: anything inside the row is readable, slots at or
+  //  beyond N are masked afterwards)
+  constexpr int NPG = (EPT + 15) / 16;             // pages a thread's slots fall into (a part of one if EPT < 16)
   float s[EPT];
-  int pg[EPT / 16];
+  int pg[NPG];
 #pragma unroll
-  for (int v = 0; v < EPT / 4; ++v) {
-    float4 x = make_float4(-__builtin_inff(), -__builtin_inff(), -__builtin_inff(), -__builtin_inff());
-    if (c0 + 4 * v < N) x = *(const float4*)(row + c0 + 4 * v);      // N is a multiple of 16
+  for (int v = 0; v < EPT / 4; ++v) {              // clamped, unconditional: all loads go out together
+    const int cc = c0 + 4 * v < a.cand_stride ? c0 + 4 * v : a.cand_stride - 4;
+    const float4 x = *(const float4*)(row + cc);
     s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
   }
 #pragma unroll
-  for (int v = 0; v < EPT / 16; ++v)
-    pg[v] = (c0 + 16 * v < N) ? a.sel_pages[(long long)bh * a.max_sel + (c0 >> 4) + v] : 0;
-  histM[tid] = 0; histM[tid + 256] = 0; histC[tid] = 0; histC[tid + 256] = 0;
-  for (int i = tid; i < nwords; i += 256) bitmap[i] = 0;
+  for (int v = 0; v < NPG; ++v) {
+    const int pi = (c0 >> 4) + v < a.max_sel ? (c0 >> 4) + v : a.max_sel - 1;
+    pg[v] = a.sel_pages[(long long)bh * a.max_sel + pi];
+  }
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) s[e] = (c0 + e < N) ? s[e] : -__builtin_inff();
+  for (int i = tid; i < HP_NB; i += NT) { histM[i] = 0; histC[i] = 0; }
+  for (int i = tid; i < nwords; i += NT) bitmap[i] = 0;
   if (tid == 0) { sh_n = 0; sh_kept = 0; }
 
   float m = s[0];
@@ -474,7 +486,9 @@ __global__ __launch_bounds__(256) void topp_head_kernel(HeadArgs a) {
   m = tw_wave_max_f(m);
   if (lane == 0) redf[wave] = m;
   __syncthreads();
-  m = fmaxf(fmaxf(redf[0], redf[1]), fmaxf(redf[2], redf[3]));
+  m = redf[0];
+#pragma unroll
+  for (int w = 1; w < NW; ++w) m = fmaxf(m, redf[w]);
   TW_STAMP(1);
 
   uint32_t T = 0;
@@ -499,7 +513,7 @@ __global__ __launch_bounds__(256) void topp_head_kernel(HeadArgs a) {
 #pragma unroll 1
     for (;;) {
       if (pass > 0) {
-        histM[tid] = 0; histM[tid + 256] = 0; histC[tid] = 0; histC[tid + 256] = 0;
+        for (int i = tid; i < HP_NB; i += NT) { histM[i] = 0; histC[i] = 0; }
         __syncthreads();
       }
       unsigned long long below = 0;                // mass past the end of the interval (pass 0 only)
@@ -525,7 +539,9 @@ __global__ __launch_bounds__(256) void topp_head_kernel(HeadArgs a) {
       const unsigned long long incl = tw_wave_scan_u64(mine);
       const unsigned long long total = __shfl(incl, 63, 64);
       if (pass == 0) {
-        const unsigned long long Z = total + tail_s[0] + tail_s[1] + tail_s[2] + tail_s[3];
+        unsigned long long Z = total;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) Z += tail_s[w];
         const double t = ceil((double)a.p * (double)Z);
         target = t < 1.0 ? 1ull : (unsigned long long)t;
         if (target > Z) target = Z;
@@ -581,22 +597,30 @@ __global__ __launch_bounds__(256) void topp_head_kernel(HeadArgs a) {
     }
     __syncthreads();
     TW_STAMP(8);
-    if (small) {
-      // every wave resolves on its own: lane x takes candidate x
-      const uint32_t cn = sh_n < HP_CAP ? sh_n : HP_CAP;
-      const uint32_t kx = lane < (int)cn ? cand_key[lane] : 0u;
-      unsigned long long S = 0;
-#pragma unroll 8
-      for (uint32_t j = 0; j < cn; ++j)
-        if (cand_key[j] >= kx) S += cand_mass[j];
-      const uint32_t best = (lane < (int)cn && A + S >= target) ? kx : 0u;
-      T = tw_wave_max_u32(best);
-    } else {
-      uint32_t r = __float_as_uint(redf[0]);
+    if (wave == 0) {                                // one wave resolves; the others wait at the barrier
+      if (small) {
+        // lane x takes candidate x: mass of all candidates at least as large as it
+        const uint32_t cn = sh_n < HP_CAP ? sh_n : HP_CAP;
+        const uint32_t kx = lane < (int)cn ? cand_key[lane] : 0u;
+        unsigned long long S = 0;
+#pragma unroll 4
+        for (uint32_t j = 0; j < cn; ++j) {
+          const uint32_t kj = cand_key[j];
+          const unsigned long long wj = cand_mass[j];
+          S += kj >= kx ? wj : 0ull;
+        }
+        const uint32_t best = (lane < (int)cn && A + S >= target) ? kx : 0u;
+        T = tw_wave_max_u32(best);
+      } else {
+        uint32_t r = __float_as_uint(redf[0]);
 #pragma unroll
-      for (int w = 1; w < 4; ++w) { const uint32_t y = __float_as_uint(redf[w]); r = y < r ? y : r; }
-      T = r;
+        for (int w = 1; w < NW; ++w) { const uint32_t y = __float_as_uint(redf[w]); r = y < r ? y : r; }
+        T = r;
+      }
+      if (lane == 0) sh_T = T;
     }
+    __syncthreads();
+    T = sh_T;
     TW_STAMP(9);
   }
 
@@ -619,79 +643,80 @@ __global__ __launch_bounds__(256) void topp_head_kernel(HeadArgs a) {
     if (lane == 63 && wsumc) atomicAdd(&sh_kept, wsumc);
   }
 #pragma unroll
-  for (int v = 0; v < EPT / 16; ++v) {
-    const uint32_t mask = (keep >> (16 * v)) & 0xFFFFu;
+  for (int v = 0; v < NPG; ++v) {
+    constexpr int PB = EPT < 16 ? EPT : 16;        // slots of this thread inside page v
+    const uint32_t mask = (keep >> (16 * v)) & ((1u << PB) - 1u);
     if (mask) {
-      const int tok0 = pg[v] * TW_PAGE;
+      const int tok0 = pg[v] * TW_PAGE + (EPT < 16 ? (c0 & 15) : 0);
       if (tok0 + 15 < HP_BITMAP_WORDS * 32) atomicOr(&bitmap[tok0 >> 5], mask << (tok0 & 31));
       if (a.kept_idx) {
         int32_t* out = a.kept_idx + (long long)bh * a.kept_stride;
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
+        for (int e = 0; e < PB; ++e)
           if ((mask >> e) & 1u) { if (pos < (uint32_t)a.kept_stride) out[pos] = tok0 + e; ++pos; }
       }
     }
   }
   __syncthreads();
   uint32_t* bm = a.bitmaps + (long long)bh * a.words_stride;
-  for (int i = tid; i < nwords; i += 256) bm[i] = bitmap[i];
+  // device-scope (write-through) stores: the group's last head reads these words from another CU
+  for (int i = tid; i < nwords; i += NT) __hip_atomic_store(bm + i, bitmap[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (tid == 0) {
     uint32_t kc = sh_kept;
     if (a.kept_idx && kc > (uint32_t)a.kept_stride) { atomicOr(a.status, TW_STATUS_KEPT_TRUNCATED); kc = a.kept_stride; }
     a.kept_count[bh] = (int32_t)kc;
   }
   TW_STAMP(12);
-}
 
-// Sorted union of the G per-head bitmaps of one (sequence, KV head); thread t
-// owns a contiguous run of words.
-struct BitmapUnionArgs {
-  const uint32_t* bitmaps;
-  const int32_t* seq_lens;
-  int32_t* union_count;
-  int32_t* union_idx;
-  uint32_t* status;
-  int Hq, Hkv, G, max_pages, words_stride, union_stride;
-};
-
-__global__ __launch_bounds__(1024) void bitmap_union_kernel(BitmapUnionArgs a) {
-  const int b = blockIdx.x / a.Hkv, g = blockIdx.x % a.Hkv, tid = threadIdx.x;
-  const int n = a.seq_lens[b];
-  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
-  if (P > a.max_pages) P = a.max_pages;
-  const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
-  const int nwords = (ntok + 31) >> 5;
-  __shared__ uint32_t ws32[16];
-  const int wpt = (nwords + 1023) / 1024;
+  // ---- the last head of the KV head's group to get here turns the G bitmaps into the sorted union
+  const int gi = b * a.Hkv + h / G;
+  // Ordering without cache-wide fences (a device-scope fence writes back / invalidates the whole
+  // L2 and costs several microseconds here): the bitmap words are stored and loaded with
+  // device-scope atomics, which go through to the point where all CUs agree; the barrier below
+  // waits until this block's stores have completed; only then does thread 0 count the arrival.
+  // The last head of the group therefore finds every earlier head's words in place.
+  __syncthreads();
+  if (tid == 0)
+    sh_last = __hip_atomic_fetch_add(a.arrive + gi, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(G - 1) ? 1u : 0u;
+  __syncthreads();
+  if (!sh_last) return;
+  if (tid == 0) __hip_atomic_store(a.arrive + gi, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+  constexpr int WMAX = (HP_BITMAP_WORDS + NT - 1) / NT;
+  const int wpt = (nwords + NT - 1) / NT;
   const int w0 = tid * wpt;
-  const uint32_t* bm = a.bitmaps + ((long long)(b * a.Hq + g * a.G)) * a.words_stride;
-  uint32_t cnt = 0;
-  for (int i = 0; i < wpt; ++i) {
-    if (w0 + i < nwords) {
-      uint32_t w = 0;
-      for (int hh = 0; hh < a.G; ++hh) w |= bm[(long long)hh * a.words_stride + w0 + i];
-      cnt += __popc(w);
-    }
+  const uint32_t* bmg = a.bitmaps + ((long long)(b * a.Hq + (h / G) * G)) * a.words_stride;
+  uint32_t w[WMAX];
+  uint32_t ucnt = 0;
+#pragma unroll
+  for (int i = 0; i < WMAX; ++i) {                 // clamped, unconditional loads; masked afterwards
+    const bool ok = i < wpt && w0 + i < nwords;
+    const int wi = ok ? w0 + i : 0;
+    uint32_t x = 0;
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh)
+      x |= __hip_atomic_load(bmg + (long long)hh * a.words_stride + wi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    w[i] = ok ? x : 0u;
+    ucnt += __popc(w[i]);
   }
-  uint32_t total;
-  const uint32_t incl = tw_block_scan_u32(cnt, ws32, &total);
-  int32_t* out = a.union_idx + (long long)blockIdx.x * a.union_stride;
-  uint32_t pos = incl - cnt;
-  for (int i = 0; i < wpt && cnt; ++i) {
-    if (w0 + i >= nwords) break;
-    uint32_t w = 0;
-    for (int hh = 0; hh < a.G; ++hh) w |= bm[(long long)hh * a.words_stride + w0 + i];
-    while (w) {
-      const int bit = __ffs(w) - 1;
-      w &= w - 1;
-      if (pos < (uint32_t)a.union_stride) out[pos] = (w0 + i) * 32 + bit;
-      ++pos;
+  uint32_t utotal;
+  const uint32_t uincl = tw_block_scan_u32(ucnt, ws32, &utotal);
+  int32_t* uout = a.union_idx + (long long)gi * a.union_stride;
+  uint32_t upos = uincl - ucnt;
+#pragma unroll
+  for (int i = 0; i < WMAX; ++i) {
+    uint32_t x = w[i];
+    while (x) {
+      const int bit = __ffs(x) - 1;
+      x &= x - 1;
+      if (upos < (uint32_t)a.union_stride) uout[upos] = (w0 + i) * 32 + bit;
+      ++upos;
     }
   }
   if (tid == 0) {
-    if (total > (uint32_t)a.union_stride) { atomicOr(a.status, TW_STATUS_UNION_TRUNCATED); total = a.union_stride; }
-    a.union_count[blockIdx.x] = (int32_t)total;
+    if (utotal > (uint32_t)a.union_stride) { atomicOr(a.status, TW_STATUS_UNION_TRUNCATED); utotal = a.union_stride; }
+    a.union_count[gi] = (int32_t)utotal;
   }
+  TW_STAMP(13);
 }
 
 // ------------------------------------------------------------------ union
@@ -792,8 +817,10 @@ void launch_score(const ScoreArgs& a, dim3 grid, bool dots, hipStream_t s) {
 }
 
 int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int32_t* sel_pages,
-              const int32_t* sel_count, int32_t max_sel, float* scores, int32_t* dots, hipStream_t s) {
+              const int32_t* sel_count, int32_t max_sel, float* scores, int32_t* dots, uint32_t* arrive,
+              hipStream_t s) {
   ScoreArgs a;
+  a.arrive = arrive;
   a.q = (const uint16_t*)q; a.sel_pages = sel_pages; a.sel_count = sel_count;
   a.page_table = kv->page_table; a.seq_lens = kv->seq_lens;
   a.kq_pool = (const uint4*)kv->kq_pool; a.kq_meta = (const uint32_t*)kv->kq_meta;
@@ -831,7 +858,7 @@ extern "C" int twilight_int4_score(const twilight_kv_t* kv, const void* q, const
   if (int e = tw_check_kv(kv, &d)) return e;
   if (!q || !scores || !kv->kq_pool || !kv->kq_meta) return TW_EINVAL;
   if (sel_pages && (!sel_count || max_sel <= 0)) return TW_EINVAL;
-  return run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, dots, (hipStream_t)stream);
+  return run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, dots, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const int32_t* sel_pages,
@@ -853,28 +880,35 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
   float* scores = (float*)ws;
   uint32_t* thr = (uint32_t*)((char*)ws + (((size_t)d.batch * d.Hq * cand_stride * 4 + 255) & ~(size_t)255));
 
-  if (int e = run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, nullptr, s)) return e;
+  // arrival counters of the fused top-p / union launch live after the bitmaps
+  const size_t bm_bytes = (((size_t)d.batch * d.Hq * ((size_t)(d.max_pages + 1) / 2) * 4) + 255) & ~(size_t)255;
+  uint32_t* arrive = (uint32_t*)((char*)(thr + (((size_t)d.batch * d.Hq + 63) & ~(size_t)63)) + bm_bytes);
+  if (int e = run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, nullptr, arrive, s)) return e;
 
-  // per-head page lists short enough for registers and sequences that fit the LDS bitmap:
-  // register-resident top-p per head, then the union of the heads' bitmaps
-  if (!full && cand_stride <= 256 * 32 && (long long)d.max_pages * TW_PAGE <= HP_BITMAP_WORDS * 32ll) {
+  // per-head page lists short enough for registers and sequences that fit the LDS bitmap: one
+  // launch does top-p per head and, in the last head of each group to finish, the group's union
+  if (!full && cand_stride <= 1024 * 8 && (long long)d.max_pages * TW_PAGE <= HP_BITMAP_WORDS * 32ll) {
     const int words_stride = (d.max_pages + 1) / 2;
     uint32_t* bitmaps = thr + (((size_t)d.batch * d.Hq + 63) & ~(size_t)63);
     HeadArgs f;
     f.scores = scores; f.sel_pages = sel_pages; f.sel_count = sel_count; f.seq_lens = kv->seq_lens;
-    f.kept_count = kept_count; f.kept_idx = kept_idx; f.bitmaps = bitmaps; f.status = status;
-    f.Hq = d.Hq; f.max_pages = d.max_pages; f.max_sel = max_sel; f.cand_stride = cand_stride;
-    f.kept_stride = kept_stride; f.words_stride = words_stride; f.p = p;
+    f.kept_count = kept_count; f.kept_idx = kept_idx; f.bitmaps = bitmaps; f.arrive = arrive;
+    f.union_count = union_count; f.union_idx = union_idx; f.status = status;
+    f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_sel; f.cand_stride = cand_stride;
+    f.kept_stride = kept_stride; f.words_stride = words_stride; f.union_stride = union_stride; f.p = p;
+    const dim3 grid(d.Hq, d.batch);
     tw_prof_before(TW_K_TOPP, s);
-    if (cand_stride <= 256 * 16) hipLaunchKernelGGL(topp_head_kernel<16>, dim3(d.Hq, d.batch), dim3(256), 0, s, f);
-    else                         hipLaunchKernelGGL(topp_head_kernel<32>, dim3(d.Hq, d.batch), dim3(256), 0, s, f);
-    if (int e = tw_prof_after(s)) return e;
-    BitmapUnionArgs u;
-    u.bitmaps = bitmaps; u.seq_lens = kv->seq_lens; u.union_count = union_count; u.union_idx = union_idx;
-    u.status = status; u.Hq = d.Hq; u.Hkv = d.Hkv; u.G = d.G; u.max_pages = d.max_pages;
-    u.words_stride = words_stride; u.union_stride = union_stride;
-    tw_prof_before(TW_K_UNION, s);
-    hipLaunchKernelGGL(bitmap_union_kernel, dim3(d.batch * d.Hkv), dim3(1024), 0, s, u);
+    if (cand_stride <= 4096) switch (d.G) {
+      case 1: hipLaunchKernelGGL((topp_head_kernel<1024, 4, 1>), grid, dim3(1024), 0, s, f); break;
+      case 2: hipLaunchKernelGGL((topp_head_kernel<1024, 4, 2>), grid, dim3(1024), 0, s, f); break;
+      case 4: hipLaunchKernelGGL((topp_head_kernel<1024, 4, 4>), grid, dim3(1024), 0, s, f); break;
+      default: hipLaunchKernelGGL((topp_head_kernel<1024, 4, 8>), grid, dim3(1024), 0, s, f); break;
+    } else switch (d.G) {
+      case 1: hipLaunchKernelGGL((topp_head_kernel<1024, 8, 1>), grid, dim3(1024), 0, s, f); break;
+      case 2: hipLaunchKernelGGL((topp_head_kernel<1024, 8, 2>), grid, dim3(1024), 0, s, f); break;
+      case 4: hipLaunchKernelGGL((topp_head_kernel<1024, 8, 4>), grid, dim3(1024), 0, s, f); break;
+      default: hipLaunchKernelGGL((topp_head_kernel<1024, 8, 8>), grid, dim3(1024), 0, s, f); break;
+    }
     return tw_prof_after(s);
   }
 

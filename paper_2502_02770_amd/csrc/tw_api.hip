@@ -51,7 +51,8 @@ extern "C" size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, i
     case TW_WS_PRUNE: {
       const size_t bound = max_sel > 0 ? (size_t)max_sel : (size_t)d.max_pages;
       // scores, per-head thresholds, per-head kept bitmaps (one bit per token position)
-      return align256(bh * bound * TW_PAGE * 4) + align256(bh * 4) + align256(bh * ((size_t)(d.max_pages + 1) / 2) * 4) + 256;
+      return align256(bh * bound * TW_PAGE * 4) + align256(bh * 4) + align256(bh * ((size_t)(d.max_pages + 1) / 2) * 4) +
+             align256((size_t)d.batch * d.Hkv * 4) + 512;   // + arrival counters
     }
     case TW_WS_DECODE: {
       const bool dense = union_stride <= 0;

@@ -90,7 +90,12 @@ def run_pipeline(w, cache, with_kept=True):
         max_sel = min(max_sel, cache.max_pages)
     st = T.DecodeStep(cache, max_sel=max_sel, with_kept_idx=with_kept)
     q = w.q.to(dev)
-    st.run(q, w.budget.to(dev), w.p)
+    if cache.v_pool is None:                       # pruner-only workload (no V): stages 1-2
+        if not st.full:
+            st.select(q, w.budget.to(dev))
+        st.prune(q, w.p)
+    else:
+        st.run(q, w.budget.to(dev), w.p)
     torch.cuda.synchronize()
     return st, q
 
@@ -379,3 +384,57 @@ def test_full_size_bench_config_sampled():
             ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
             assert np.abs(out[b, h] - ref).max() <= MAX_ABS
             assert np.linalg.norm(out[b, h] - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
+
+
+def check_sets_and_output(w, cache, st, exact_floor=0.97):
+    """Kept sets vs the oracle (tolerance band), union = union of the GPU's kept sets, attention on them."""
+    G = w.num_q_heads // w.num_kv_heads
+    exact = total = 0
+    out = st.out.cpu().float().numpy().astype(np.float64)
+    for b in range(w.batch):
+        r = oracle_seq(w, b)
+        for h in range(w.num_q_heads):
+            if not w.full_selector:
+                cnt = int(st.sel_count[b, h])
+                assert st.sel_pages[b, h, :cnt].cpu().numpy().tolist() == r["pages"][h].tolist(), (b, h)
+            kept = st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+            exact += check_topp(kept, r["s_hat"][h], r["cand"][h], w.p)
+            total += 1
+        for g in range(w.num_kv_heads):
+            gi = b * w.num_kv_heads + g
+            un = st.union_idx[gi, :int(st.union_count[gi])].cpu().numpy()
+            mine = np.unique(np.concatenate([st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+                                             for h in range(g * G, g * G + G)]))
+            assert un.tolist() == mine.tolist()
+            if cache.v_pool is None:
+                continue
+            for h in range(g * G, g * G + G):
+                ref, _ = O.attention(synth.bits(w.q[b, h]), synth.bits(w.seq_k(b)[:, g]), synth.bits(w.seq_v(b)[:, g]), un)
+                ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
+                assert np.abs(out[b, h] - ref).max() <= MAX_ABS
+                assert np.linalg.norm(out[b, h] - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
+    assert exact >= exact_floor * total
+
+
+@pytest.mark.parametrize("idx,scale,batch", [(2, 1 / 16, None), (3, 1 / 64, 2), (4, 1 / 16, 6)],
+                         ids=["C3_spans", "C4_full_gqa8", "C5_ragged"])
+def test_scaled_benchmark_configs(idx, scale, batch):
+    """The remaining BASELINE configs, shrunk: clustered heavy hitters with a long page list (C3),
+    pruner-only over every token with 8 query heads per KV head (C4), ragged batch in a shared pool (C5)."""
+    w = synth.config(idx, scale=scale, batch=batch)
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache)
+    assert int(st.status.item()) == 0
+    check_sets_and_output(w, cache, st)
+
+
+def test_long_sequence_fallback_paths():
+    """More than 8192 pages and more than 196608 tokens: the streaming page_select, top-p and union
+    kernels (general-length paths) instead of the LDS / register-resident ones."""
+    w = synth.make_workload("long", [200_003], num_q_heads=2, num_kv_heads=1, budget=4096, p=0.9, heavy_frac=0.001,
+                            alpha_range=(0.3, 2.0), seed=23)
+    cache = build_cache(w)
+    assert cache.max_pages > 8192
+    st, q = run_pipeline(w, cache)
+    assert int(st.status.item()) == 0
+    check_sets_and_output(w, cache, st)
