@@ -19,6 +19,12 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch at config C2 from rocprofv3 --pmc FETCH_SIZE (x2.0, calibrated against a
+# plain copy) + WRITE_SIZE, see profiles/c2_decode_step_hbm_traffic.md.  Not measurable live.
+TRAFFIC_C2 = {"page_score": 33110 * 2048 + 2067 * 1024, "int4_score": 31057 * 2048 + 4104 * 1024,
+              "sparse_decode": 19724 * 2048 + 1282 * 1024, "topp": 2795 * 2048 + 1343 * 1024,
+              "page_select": 1080 * 2048 + 264 * 1024}
+
 # Paper context (another machine: one A100, FP16 KV, LongBench-derived prompts) - not a target.
 PAPER_CONTEXT = {"quest_twi_vs_fa2_attention_speedup": 15.8, "quest_twi_vs_quest": 1.4,
                  "hardware": "1x NVIDIA A100", "source": "Section 5.2"}
@@ -200,7 +206,8 @@ def main():
     dom = max(kavg, key=lambda k: kavg[k] * kcalls[k])
     ach = nbytes[dom] / (kavg[dom] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                "frac": ach / HBM_PEAK_GBS,
+                "traffic": TRAFFIC_C2.get(dom) if (a.config == 1 and a.scale == 1.0 and a.batch is None and a.seed == 0) else None,
                 "algorithmic_bytes": nbytes[dom], "avg_kernel_us": kavg[dom] * 1e3}
     per_kernel = {k: {"us": kavg[k] * 1e3, "calls_per_step": kcalls[k], "bytes": nbytes.get(k),
                       "GBps": (nbytes.get(k, 0) / (kavg[k] * 1e-3) / 1e9) if kavg[k] > 0 else None}
