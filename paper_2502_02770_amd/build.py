@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libtwilight.so")
-SOURCES = ["tw_api.hip", "kquant_append.hip", "select_pages.hip", "topp_prune.hip", "sparse_decode.hip"]
+SOURCES = ["tw_api.hip", "kquant_append.hip", "select_pages.hip", "topp_prune.hip", "topp_wide.hip", "sparse_decode.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          # packed fp32 instructions are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -178,9 +178,6 @@ constexpr int SEL_LDS_PAGES = 8192;
 constexpr int SEL_NB = 2048;
 constexpr int SEL_CAP = 256;
 
-__device__ __forceinline__ float tw_key_float(uint32_t k) {
-  return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
-}
 
 template <int NT>
 __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
@@ -241,14 +238,14 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
   for (int pass = 0;; ++pass) {
     // every pass drops the live minimum or maximum, so 64 passes are never reached
     if (klo == khi || pass == 64) { T = klo; need_eq = need; break; }      // everything left ties
-    const float smn = tw_key_float(klo), smx = tw_key_float(khi);
+    const float smn = tw_key_to_float(klo), smx = tw_key_to_float(khi);
     const float scale = (float)SEL_NB / (smx - smn);
     for (int i = tid; i < SEL_NB; i += NT) hist[i] = 0;
     __syncthreads();
     for (int i = tid; i < P; i += NT) {
       const uint32_t k = key_s[i];
       if (k >= klo && k <= khi) {
-        int bk = (int)((tw_key_float(k) - smn) * scale);
+        int bk = (int)((tw_key_to_float(k) - smn) * scale);
         bk = bk > SEL_NB - 1 ? SEL_NB - 1 : (bk < 0 ? 0 : bk);
         atomicAdd(&hist[bk], 1u);
       }
@@ -278,7 +275,7 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
     for (int i = tid; i < P; i += NT) {
       const uint32_t k = key_s[i];
       if (k >= klo && k <= khi) {
-        int bk = (int)((tw_key_float(k) - smn) * scale);
+        int bk = (int)((tw_key_to_float(k) - smn) * scale);
         bk = bk > SEL_NB - 1 ? SEL_NB - 1 : (bk < 0 ? 0 : bk);
         if (bk == bkt) {
           nlo = k < nlo ? k : nlo;

@@ -1,0 +1,42 @@
+// Pieces shared by the top-p kernels (register-resident per-head path and
+// the multi-workgroup path for long candidate rows).
+#pragma once
+#include "tw_common.h"
+
+constexpr uint32_t kKeyNegInf = 0x007FFFFFu;   // tw_float_key(-inf)
+
+constexpr int HP_NB = 512;                     // histogram buckets per pass
+constexpr uint32_t HP_FINE_END = 1u << 25;     // ranks below this (8 logits under the max) get the fine first pass
+constexpr uint32_t HP_NONE = 0xFFFFFFFFu;      // rank of a score that takes no part (invalid slot or zero mass)
+// Words that many workgroups update with atomics (head maxima, counters) sit 128 bytes apart:
+// atomics to one cache line are served one after the other, whatever word they address.
+constexpr int TW_CTR = 32;                     // stride in 32-bit words
+
+// Workspace of twilight_topp_prune (byte offsets).  Both paths use scores,
+// headmax, bitmaps, arrive; the rest belongs to the long-row path.
+struct PruneWs {
+  size_t scores, headmax, bitmaps, arrive, state, ghistM, ghistC, gtail, ulist, ucount, kdef, total;
+  int words_stride;       // bitmap words per head
+};
+PruneWs tw_prune_layout(const TwDims& d, int bound_pages);
+
+#ifdef __HIPCC__
+// softmax numerator e in (0, 1] -> 2^-40 fixed point, from the float's own bits
+__device__ __forceinline__ unsigned long long hp_fix(float e) {
+  const uint32_t u = __float_as_uint(e);
+  const int sh = (int)(u >> 23) - 127 + 17;                  // mantissa * 2^(exponent - 23 + 40)
+  const unsigned long long mant = (u & 0x7FFFFFu) | 0x800000u;
+  return sh >= 0 ? mant << sh : (sh > -24 ? mant >> (-sh) : 0ull);
+}
+// rank of a score: distance to the max logit in 2^-22 units; HP_NONE when the score is
+// invalid or more than 27.5 logits below the max (its 2^-40 fixed-point mass is at most one unit there)
+__device__ __forceinline__ uint32_t hp_rank_only(float m, float s) {
+  const float d = __fsub_rn(m, s);
+  return d < 27.5f ? (uint32_t)(d * 4194304.f) : HP_NONE;
+}
+__device__ __forceinline__ float hp_numer(float m, float s) { return __expf(-__fsub_rn(m, s)); }
+__device__ __forceinline__ uint32_t hp_rank(float m, float s, float* e_out) {
+  *e_out = hp_numer(m, s);
+  return hp_rank_only(m, s);
+}
+#endif

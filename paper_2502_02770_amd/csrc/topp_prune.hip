@@ -12,13 +12,12 @@
 //             resolve on the score's own bit pattern inside one wave.
 // union       per (sequence, KV head): bitmap in LDS, ordered emit.
 #include <stdlib.h>
-#include "tw_common.h"
+#include "topp_common.h"
 
 namespace {
 
 constexpr float kInv127 = 0x1.020408p-7f;    // fp32(1/127)
 constexpr float kRsqrtD = 0x1.6a09e6p-4f;    // fp32(1/sqrt(128))
-constexpr uint32_t kKeyNegInf = 0x007FFFFFu;  // tw_float_key(-inf)
 
 // ------------------------------------------------------------------ int4_score
 struct ScoreArgs {
@@ -32,13 +31,14 @@ struct ScoreArgs {
   float* scores;              // [b][Hq][cand_stride]
   int32_t* dots;              // [b][Hq][cand_stride][4] or nullptr
   uint32_t* arrive;           // [b][Hkv] arrival counters of the top-p kernel that follows, or nullptr
+  uint32_t* headmax;          // [b][Hq] key of each head's largest score (atomicMax), or nullptr
   int Hq, Hkv, max_pages, max_sel, cand_stride, pw;   // pw: pages per wave (<= 64)
   long long pool_pages;
 };
 
 // NH = heads scored per loaded page: 1 with per-head page lists, G when every
 // page is a candidate (the G heads of a KV head then share each load).
-template <int NH, bool FULL, bool DOTS>
+template <int NH, bool FULL, bool DOTS, int UNR>
 __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int b, g, h0;
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   int count = P;
   if (!FULL) { count = a.sel_count[b * a.Hq + h0]; if (count > a.max_sel) count = a.max_sel; }
   const int wg_first = blockIdx.x * 4 * a.pw;
-  if (a.arrive && blockIdx.x == 0 && tid == 0) a.arrive[b * a.Hkv + g] = 0;
+  if (a.arrive && blockIdx.x == 0 && tid == 0) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
   if (wg_first >= count) return;
 
   // ---- quantise q of the NH heads to int8 (symmetric, per head)
@@ -108,10 +108,13 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   int npages = count - first;
   if (npages > a.pw) npages = a.pw;
 
-#pragma unroll 1
-  for (int k0 = 0; k0 < npages; k0 += 4) {
+  float hm[NH];
 #pragma unroll
-   for (int kk = 0; kk < 4; ++kk) {
+  for (int h = 0; h < NH; ++h) hm[h] = -__builtin_inff();
+#pragma unroll 1
+  for (int k0 = 0; k0 < npages; k0 += UNR) {
+#pragma unroll
+   for (int kk = 0; kk < UNR; ++kk) {
     const int k = k0 + kk;                     // wave-uniform; pages past the end act as invalid
     const int lp = __builtin_amdgcn_readlane(my_lp, k & 63);
     const int pool = k < npages ? __builtin_amdgcn_readlane(my_pool, k & 63) : -1;
@@ -142,6 +145,7 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
       float T = __fadd_rn(__fmul_rn(sc, (float)I), __fmul_rn(ze, qsf[h]));
       T = tw_quad_sum(T);
       const float s = valid ? __fmul_rn(T, cc[h]) : -__builtin_inff();
+      if (k < npages) hm[h] = fmaxf(hm[h], s);
       const long long row = ((long long)(b * a.Hq + h0 + h)) * a.cand_stride;
       if (k < npages) {
         if (j == 0) a.scores[row + slot] = s;
@@ -150,244 +154,21 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
     }
    }
   }
-}
-
-// ------------------------------------------------------------------ top-p
-__device__ __forceinline__ unsigned long long tw_wave_sum_u64(unsigned long long v) {
+  if (a.headmax) {
+    // one atomic per head and workgroup: waves reduce through LDS first
+    __shared__ float hm_s[4][NH];
 #pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-
-// Inclusive scan of one u64 per thread over a 1024-thread block.
-__device__ __forceinline__ unsigned long long tw_block_scan_u64(unsigned long long v, unsigned long long* wsum,
-                                                                unsigned long long* total) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  unsigned long long x = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    unsigned long long y = __shfl_up(x, o, 64);
-    if (lane >= o) x += y;
-  }
-  if (lane == 63) wsum[wave] = x;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned long long run = 0;
-    for (int w = 0; w < nw; ++w) { unsigned long long t = wsum[w]; wsum[w] = run; run += t; }
-    wsum[16] = run;
-  }
-  __syncthreads();
-  x += wsum[wave];
-  *total = wsum[16];
-  __syncthreads();
-  return x;
-}
-
-struct ToppArgs {
-  const float* scores;        // [b][Hq][cand_stride]
-  const int32_t* sel_pages;   // or nullptr
-  const int32_t* sel_count;
-  const int32_t* seq_lens;
-  int32_t* kept_count;
-  int32_t* kept_idx;          // or nullptr
-  uint32_t* thr_key;          // [b][Hq] out: kept <=> key(score) >= thr_key
-  uint32_t* status;
-  int Hq, max_pages, max_sel, cand_stride, kept_stride;
-  float p;
-};
-
-constexpr int TP_THREADS = 1024;
-constexpr int TP_NB = 2048;        // buckets per radix pass
-constexpr int TP_EPT = 8;          // register-cached elements per thread
-
-// distance to the max logit in 2^-26 units, saturating at 64
-__device__ __forceinline__ uint32_t tp_rank(float m, float s) {
-  const float d = __fsub_rn(m, s);
-  return d >= 64.f ? 0xFFFFFFFFu : (uint32_t)(d * 67108864.f);
-}
-// softmax numerator in 2^-40 fixed point
-__device__ __forceinline__ unsigned long long tp_mass(float m, float s) {
-  return (unsigned long long)(__expf(__fsub_rn(s, m)) * 1099511627776.f);
-}
-
-template <bool CACHED>
-__global__ __launch_bounds__(TP_THREADS) void topp_kernel(ToppArgs a) {
-  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int bh = b * a.Hq + h;
-  const int n = a.seq_lens[b];
-  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
-  if (P > a.max_pages) P = a.max_pages;
-  int count = P;
-  if (a.sel_pages) { count = a.sel_count[bh]; if (count > a.max_sel) count = a.max_sel; if (count < 0) count = 0; }
-  const int N = count * TW_PAGE;
-  const float* row = a.scores + (long long)bh * a.cand_stride;
-  const int iters = CACHED ? TP_EPT : (N + TP_THREADS - 1) / TP_THREADS;
-
-  __shared__ unsigned long long histM[TP_NB];
-  __shared__ uint32_t histC[TP_NB];
-  __shared__ unsigned long long wsum64[17];
-  __shared__ uint32_t wsum32[17];
-  __shared__ float redf[16];
-  __shared__ uint32_t sh_bkt, sh_pop, sh_T, sh_n;
-  __shared__ unsigned long long sh_A;
-  __shared__ uint32_t cand_key[64];
-  __shared__ unsigned long long cand_mass[64];
-
-  float sreg[CACHED ? TP_EPT : 1];
-  if (CACHED) {
-#pragma unroll
-    for (int e = 0; e < TP_EPT; ++e) {
-      const int i = e * TP_THREADS + tid;
-      sreg[e] = i < N ? row[i] : -__builtin_inff();
+    for (int h = 0; h < NH; ++h) {
+      const float mx = tw_wave_max_f(hm[h]);
+      if (lane == 0) hm_s[wave][h] = mx;
+    }
+    __syncthreads();
+    if (tid < NH) {
+      const float mx = fmaxf(fmaxf(hm_s[0][tid], hm_s[1][tid]), fmaxf(hm_s[2][tid], hm_s[3][tid]));
+      if (mx > -__builtin_inff()) atomicMax(a.headmax + (long long)(b * a.Hq + h0 + tid) * TW_CTR, tw_float_key(mx));
     }
   }
-#define TP_LOAD(e) (CACHED ? sreg[CACHED ? (e) : 0] : ((e) * TP_THREADS + tid < N ? row[(e) * TP_THREADS + tid] : -__builtin_inff()))
-
-  // ---- pass 1: max
-  float m = -__builtin_inff();
-#pragma unroll
-  for (int e = 0; e < iters; ++e) m = fmaxf(m, TP_LOAD(e));
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-  if (lane == 0) redf[wave] = m;
-  __syncthreads();
-  m = redf[0];
-#pragma unroll
-  for (int w = 1; w < 16; ++w) m = fmaxf(m, redf[w]);
-
-  uint32_t T;
-  if (!(m > -__builtin_inff())) {
-    T = 0xFFFFFFFFu;                          // no valid candidate: keep nothing
-  } else if (a.p >= 1.0f) {
-    T = kKeyNegInf + 1u;                      // keep every finite score
-  } else {
-    // ---- radix bisection on rank = (m - s) * 2^26: 11 + 11 + 10 bits
-    uint32_t prefix = 0, pop = 0;
-    unsigned long long A = 0, target = 0;
-    int shift = 21, nbits = 11, level = 0;
-#pragma unroll 1
-    for (;;) {
-      for (int i = tid; i < TP_NB; i += TP_THREADS) { histM[i] = 0; histC[i] = 0; }
-      __syncthreads();
-      const uint32_t himask = level == 0 ? 0u : (0xFFFFFFFFu << (shift + nbits));
-#pragma unroll
-      for (int e = 0; e < iters; ++e) {
-        const float s = TP_LOAD(e);
-        if (s > -__builtin_inff()) {
-          const uint32_t r = tp_rank(m, s);
-          const unsigned long long w = tp_mass(m, s);   // 0 when ~28 below the max: cannot move the threshold
-          if (w != 0 && (r & himask) == prefix) {
-            const uint32_t bk = (r >> shift) & ((1u << nbits) - 1u);
-            atomicAdd(&histM[bk], w);
-            atomicAdd(&histC[bk], 1u);
-          }
-        }
-      }
-      __syncthreads();
-      // thread t owns buckets 2t, 2t+1 (ascending rank = descending score)
-      const unsigned long long m0 = histM[2 * tid], m1 = histM[2 * tid + 1];
-      unsigned long long total;
-      const unsigned long long incl = tw_block_scan_u64(m0 + m1, wsum64, &total);
-      if (level == 0) {                       // total = Z; mass needed = p * Z
-        const double t = ceil((double)a.p * (double)total);
-        target = t < 1.0 ? 1ull : (unsigned long long)t;
-        if (target > total) target = total;
-      }
-      const unsigned long long before = A + incl - (m0 + m1);
-      if (before < target && before + m0 >= target) {
-        sh_bkt = 2 * tid; sh_A = before; sh_pop = histC[2 * tid];
-      } else if (before + m0 < target && before + m0 + m1 >= target) {
-        sh_bkt = 2 * tid + 1; sh_A = before + m0; sh_pop = histC[2 * tid + 1];
-      }
-      __syncthreads();
-      prefix |= sh_bkt << shift;
-      A = sh_A;
-      pop = sh_pop;
-      __syncthreads();
-      if (pop <= 64 || level == 2) break;
-      ++level;
-      if (level == 1) { shift = 10; nbits = 11; } else { shift = 0; nbits = 10; }
-    }
-    // ---- the threshold lies among the `pop` scores whose rank matches
-    // `prefix` down to bit `shift`; mass A lies strictly above them.
-    const uint32_t fmask = shift == 0 ? 0xFFFFFFFFu : (0xFFFFFFFFu << shift);
-    if (pop <= 64) {
-      if (tid == 0) sh_n = 0;
-      __syncthreads();
-#pragma unroll
-      for (int e = 0; e < iters; ++e) {
-        const float s = TP_LOAD(e);
-        if (s > -__builtin_inff() && tp_mass(m, s) != 0 && (tp_rank(m, s) & fmask) == prefix) {
-          const uint32_t at = atomicAdd(&sh_n, 1u);
-          if (at < 64) { cand_key[at] = tw_float_key(s); cand_mass[at] = tp_mass(m, s); }
-        }
-      }
-      __syncthreads();
-      if (wave == 0) {
-        const uint32_t cn = sh_n < 64 ? sh_n : 64;
-        const uint32_t kx = lane < cn ? cand_key[lane] : 0u;
-        unsigned long long S = 0;
-        for (uint32_t jx = 0; jx < cn; ++jx)
-          if (cand_key[jx] >= kx) S += cand_mass[jx];
-        uint32_t best = (lane < cn && A + S >= target) ? kx : 0u;
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) { const uint32_t y = __shfl_xor(best, o, 64); best = y > best ? y : best; }
-        if (lane == 0) sh_T = best;
-      }
-      __syncthreads();
-      T = sh_T;
-    } else {
-      // more than 64 scores within 2^-26 of each other: keep all of them
-      uint32_t kmin = 0xFFFFFFFFu;
-#pragma unroll
-      for (int e = 0; e < iters; ++e) {
-        const float s = TP_LOAD(e);
-        if (s > -__builtin_inff() && tp_mass(m, s) != 0 && (tp_rank(m, s) & fmask) == prefix) {
-          const uint32_t k = tw_float_key(s);
-          kmin = k < kmin ? k : kmin;
-        }
-      }
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) { const uint32_t y = __shfl_xor(kmin, o, 64); kmin = y < kmin ? y : kmin; }
-      if (lane == 0) wsum32[wave] = kmin;
-      __syncthreads();
-      kmin = wsum32[0];
-      for (int w = 1; w < 16; ++w) kmin = wsum32[w] < kmin ? wsum32[w] : kmin;
-      __syncthreads();
-      T = kmin;
-    }
-  }
-
-  // ---- emit: count and (optionally) the ascending token list
-  if (tid == 0) a.thr_key[bh] = T;
-  uint32_t run = 0;
-  int32_t* out = a.kept_idx ? a.kept_idx + (long long)bh * a.kept_stride : nullptr;
-#pragma unroll
-  for (int e = 0; e < iters; ++e) {
-    const int i = e * TP_THREADS + tid;
-    const float s = TP_LOAD(e);
-    const uint32_t f = (i < N && tw_float_key(s) >= T) ? 1u : 0u;
-    uint32_t total;
-    const uint32_t incl = tw_block_scan_u32(f, wsum32, &total);
-    if (f && out) {
-      const uint32_t pos = run + incl - 1;
-      if (pos < (uint32_t)a.kept_stride) {
-        const int pg = a.sel_pages ? a.sel_pages[(long long)bh * a.max_sel + (i >> 4)] : (i >> 4);
-        out[pos] = pg * TW_PAGE + (i & 15);
-      }
-    }
-    run += total;
-  }
-  if (tid == 0) {
-    if (out && run > (uint32_t)a.kept_stride) {
-      atomicOr(a.status, TW_STATUS_KEPT_TRUNCATED);
-      run = a.kept_stride;
-    }
-    a.kept_count[bh] = (int32_t)run;
-  }
-#undef TP_LOAD
 }
-
 
 // ------------------------------------------------------------------ top-p per head, scores in registers
 // One workgroup (256 or 512 threads) per (sequence, query head); thread t owns the
@@ -416,19 +197,8 @@ struct HeadArgs {
   float p;
 };
 
-constexpr int HP_NB = 512;                    // buckets per pass
 constexpr int HP_CAP = 64;                    // exact resolve handles up to this many scores
 constexpr int HP_BITMAP_WORDS = 6144;         // 196608 tokens
-constexpr uint32_t HP_FINE_END = 1u << 25;    // ranks below this (8 logits under the max) get the fine first pass
-constexpr uint32_t HP_NONE = 0xFFFFFFFFu;     // rank of a score that takes no part (invalid slot or zero mass)
-
-// softmax numerator e in (0, 1] -> 2^-40 fixed point, from the float's own bits
-__device__ __forceinline__ unsigned long long hp_fix(float e) {
-  const uint32_t u = __float_as_uint(e);
-  const int sh = (int)(u >> 23) - 127 + 17;                  // mantissa * 2^(exponent - 23 + 40)
-  const unsigned long long mant = (u & 0x7FFFFFu) | 0x800000u;
-  return sh >= 0 ? mant << sh : (sh > -24 ? mant >> (-sh) : 0ull);
-}
 
 template <int NT, int EPT, int G>
 __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
@@ -503,9 +273,7 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
     float ef[EPT];
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      const float d = __fsub_rn(m, s[e]);
-      ef[e] = __expf(-d);
-      rk[e] = (d < 32.f && hp_fix(ef[e]) != 0) ? (uint32_t)(d * 4194304.f) : HP_NONE;
+      rk[e] = hp_rank(m, s[e], &ef[e]);
     }
     uint32_t rlo = 0, pop = 0;
     int shift = 16, pass = 0;
@@ -677,10 +445,10 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   // The last head of the group therefore finds every earlier head's words in place.
   __syncthreads();
   if (tid == 0)
-    sh_last = __hip_atomic_fetch_add(a.arrive + gi, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(G - 1) ? 1u : 0u;
+    sh_last = __hip_atomic_fetch_add(a.arrive + gi * TW_CTR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(G - 1) ? 1u : 0u;
   __syncthreads();
   if (!sh_last) return;
-  if (tid == 0) __hip_atomic_store(a.arrive + gi, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
+  if (tid == 0) __hip_atomic_store(a.arrive + gi * TW_CTR, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   constexpr int WMAX = (HP_BITMAP_WORDS + NT - 1) / NT;
   const int wpt = (nwords + NT - 1) / NT;
   const int w0 = tid * wpt;
@@ -719,88 +487,6 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   TW_STAMP(13);
 }
 
-// ------------------------------------------------------------------ union
-struct UnionArgs {
-  const float* scores;
-  const uint32_t* thr_key;
-  const int32_t* sel_pages;   // or nullptr
-  const int32_t* sel_count;
-  const int32_t* seq_lens;
-  int32_t* union_count;
-  int32_t* union_idx;
-  uint32_t* status;
-  int Hq, Hkv, G, max_pages, max_sel, cand_stride, union_stride;
-};
-
-constexpr int UN_THREADS = 1024;
-constexpr int UN_SEG = 1 << 18;               // tokens per bitmap segment (32 KiB of LDS)
-
-__global__ __launch_bounds__(UN_THREADS) void union_kernel(UnionArgs a) {
-  const int b = blockIdx.x / a.Hkv, g = blockIdx.x % a.Hkv, tid = threadIdx.x;
-  const int n = a.seq_lens[b];
-  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
-  if (P > a.max_pages) P = a.max_pages;
-  const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
-  __shared__ uint32_t bitmap[UN_SEG / 32];
-  __shared__ uint32_t wsum[17];
-  int32_t* out = a.union_idx + (long long)blockIdx.x * a.union_stride;
-  uint32_t run = 0;
-#pragma unroll 1
-  for (int seg0 = 0; seg0 < ntok; seg0 += UN_SEG) {
-    const int seg1 = seg0 + UN_SEG < ntok ? seg0 + UN_SEG : ntok;
-    for (int i = tid; i < UN_SEG / 32; i += UN_THREADS) bitmap[i] = 0;
-    __syncthreads();
-#pragma unroll 1
-    for (int hh = 0; hh < a.G; ++hh) {
-      const int bh = b * a.Hq + g * a.G + hh;
-      const uint32_t T = a.thr_key[bh];
-      const float* row = a.scores + (long long)bh * a.cand_stride;
-      if (a.sel_pages) {
-        int count = a.sel_count[bh];
-        if (count > a.max_sel) count = a.max_sel;
-        const int32_t* pages = a.sel_pages + (long long)bh * a.max_sel;
-        // page slots [s0, s1) whose tokens fall in [seg0, seg1): the list is ascending
-        int lo = 0, hi = count;
-        while (lo < hi) { const int mid = (lo + hi) >> 1; if (pages[mid] * TW_PAGE + TW_PAGE <= seg0) lo = mid + 1; else hi = mid; }
-        const int s0 = lo;
-        hi = count;
-        while (lo < hi) { const int mid = (lo + hi) >> 1; if (pages[mid] * TW_PAGE < seg1) lo = mid + 1; else hi = mid; }
-        const int s1 = lo;
-        for (int c = s0 * TW_PAGE + tid; c < s1 * TW_PAGE; c += UN_THREADS) {
-          if (tw_float_key(row[c]) >= T) {
-            const int t = pages[c >> 4] * TW_PAGE + (c & 15) - seg0;
-            if (t >= 0 && t < UN_SEG) atomicOr(&bitmap[t >> 5], 1u << (t & 31));
-          }
-        }
-      } else {
-        for (int c = seg0 + tid; c < seg1; c += UN_THREADS)
-          if (tw_float_key(row[c]) >= T) { const int t = c - seg0; atomicOr(&bitmap[t >> 5], 1u << (t & 31)); }
-      }
-    }
-    __syncthreads();
-    const int words = (seg1 - seg0 + 31) >> 5;
-#pragma unroll 1
-    for (int wb = 0; wb < words; wb += UN_THREADS) {
-      uint32_t w = wb + tid < words ? bitmap[wb + tid] : 0u;
-      uint32_t total;
-      const uint32_t incl = tw_block_scan_u32(__popc(w), wsum, &total);
-      uint32_t pos = run + incl - __popc(w);
-      while (w) {
-        const int bit = __ffs(w) - 1;
-        w &= w - 1;
-        if (pos < (uint32_t)a.union_stride) out[pos] = seg0 + (wb + tid) * 32 + bit;
-        ++pos;
-      }
-      run += total;
-    }
-    __syncthreads();
-  }
-  if (tid == 0) {
-    if (run > (uint32_t)a.union_stride) { atomicOr(a.status, TW_STATUS_UNION_TRUNCATED); run = a.union_stride; }
-    a.union_count[blockIdx.x] = (int32_t)run;
-  }
-}
-
 // ------------------------------------------------------------------ launches
 int pages_per_wave(long long total_pages_all_rows, int count_bound) {
   // aim for >= ~2048 waves in flight chip-wide, 4..64 pages per wave
@@ -812,15 +498,20 @@ int pages_per_wave(long long total_pages_all_rows, int count_bound) {
 
 template <int NH, bool FULL>
 void launch_score(const ScoreArgs& a, dim3 grid, bool dots, hipStream_t s) {
-  if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true>), grid, dim3(256), 0, s, a);
-  else      hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false>), grid, dim3(256), 0, s, a);
+  // pages in flight per wave: 4, fewer when 8 heads share a page (register budget)
+  static const int unr8 = getenv("TW_INT4_UNR") ? atoi(getenv("TW_INT4_UNR")) : 2;   // tuning switch
+  if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2>), grid, dim3(256), 0, s, a);
+  else if (NH < 8) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 4>), grid, dim3(256), 0, s, a);
+  else if (unr8 == 1) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 1>), grid, dim3(256), 0, s, a);
+  else if (unr8 == 4) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 4>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 2>), grid, dim3(256), 0, s, a);
 }
 
 int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int32_t* sel_pages,
               const int32_t* sel_count, int32_t max_sel, float* scores, int32_t* dots, uint32_t* arrive,
-              hipStream_t s) {
+              uint32_t* headmax, hipStream_t s) {
   ScoreArgs a;
-  a.arrive = arrive;
+  a.arrive = arrive; a.headmax = headmax;
   a.q = (const uint16_t*)q; a.sel_pages = sel_pages; a.sel_count = sel_count;
   a.page_table = kv->page_table; a.seq_lens = kv->seq_lens;
   a.kq_pool = (const uint4*)kv->kq_pool; a.kq_meta = (const uint32_t*)kv->kq_meta;
@@ -845,6 +536,40 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
 
 }  // namespace
 
+
+int tw_prune_wide_init(const TwDims& d, const PruneWs& L, void* ws, hipStream_t s);
+int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv_t* kv, const int32_t* sel_pages,
+                  const int32_t* sel_count, int max_sel, int cand_stride, float p, int32_t* kept_count,
+                  int32_t* kept_idx, int kept_stride, int32_t* union_count, int32_t* union_idx, int union_stride,
+                  uint32_t* status, hipStream_t s);
+
+// Register-resident per-head kernel: per-head lists of at most 8192 candidates on sequences whose
+// position bitmap fits in LDS; everything else takes the multi-workgroup path.
+bool tw_prune_uses_head_kernel(const TwDims& d, bool full, int bound_pages) {
+  return !full && bound_pages * TW_PAGE <= 1024 * 8 && (long long)d.max_pages * TW_PAGE <= HP_BITMAP_WORDS * 32ll;
+}
+
+PruneWs tw_prune_layout(const TwDims& d, int bound_pages) {
+  auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  const size_t bh = (size_t)d.batch * d.Hq;
+  PruneWs L;
+  L.words_stride = (d.max_pages + 1) / 2;
+  size_t o = 0;
+  L.scores = o;  o += al(bh * (size_t)bound_pages * TW_PAGE * 4);
+  L.headmax = o; o += al(bh * TW_CTR * 4);               // (the long-row path clears from here ...)
+  L.arrive = o;  o += al((size_t)d.batch * d.Hkv * TW_CTR * 4);
+  L.bitmaps = o; o += al(bh * (size_t)L.words_stride * 4);
+  L.ghistM = o;  o += al(bh * HP_NB * 8);
+  L.ghistC = o;  o += al(bh * HP_NB * 4);
+  L.gtail = o;   o += al(bh * TW_CTR * 4);
+  L.ucount = o;  o += al(bh * TW_CTR * 4);
+  L.kdef = o;    o += al(bh * TW_CTR * 4);
+  L.state = o;   o += al(bh * 48);                       // (... up to here)
+  L.ulist = o;   o += al(bh * 1024 * 16);
+  L.total = o;
+  return L;
+}
+
 #ifdef TW_PHASE_TIMING
 extern "C" int twilight_debug_stamps_prune(unsigned long long* host_out) {
   return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(tw_dbg_stamps), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : -1;
@@ -858,7 +583,7 @@ extern "C" int twilight_int4_score(const twilight_kv_t* kv, const void* q, const
   if (int e = tw_check_kv(kv, &d)) return e;
   if (!q || !scores || !kv->kq_pool || !kv->kq_meta) return TW_EINVAL;
   if (sel_pages && (!sel_count || max_sel <= 0)) return TW_EINVAL;
-  return run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, dots, nullptr, (hipStream_t)stream);
+  return run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, dots, nullptr, nullptr, (hipStream_t)stream);
 }
 
 extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const int32_t* sel_pages,
@@ -874,22 +599,28 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
   const bool full = sel_pages == nullptr;
   const int bound = full ? d.max_pages : max_sel;
   if ((long long)bound * TW_PAGE > (1ll << 22)) return TW_EINVAL;   // fixed-point mass headroom
-  if (!ws || ws_bytes < twilight_workspace_bytes(TW_WS_PRUNE, kv, full ? 0 : max_sel, 0)) return TW_EWORKSPACE;
+  if (!ws || ws_bytes < tw_prune_layout(d, bound).total) return TW_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   const int cand_stride = bound * TW_PAGE;
-  float* scores = (float*)ws;
-  uint32_t* thr = (uint32_t*)((char*)ws + (((size_t)d.batch * d.Hq * cand_stride * 4 + 255) & ~(size_t)255));
+  const PruneWs L = tw_prune_layout(d, bound);
+  float* scores = (float*)((char*)ws + L.scores);
+  uint32_t* headmax = (uint32_t*)((char*)ws + L.headmax);
+  uint32_t* arrive = (uint32_t*)((char*)ws + L.arrive);
+  const bool use_head = tw_prune_uses_head_kernel(d, full, bound);
 
-  // arrival counters of the fused top-p / union launch live after the bitmaps
-  const size_t bm_bytes = (((size_t)d.batch * d.Hq * ((size_t)(d.max_pages + 1) / 2) * 4) + 255) & ~(size_t)255;
-  uint32_t* arrive = (uint32_t*)((char*)(thr + (((size_t)d.batch * d.Hq + 63) & ~(size_t)63)) + bm_bytes);
-  if (int e = run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, nullptr, arrive, s)) return e;
+  if (!use_head)
+    if (int e = tw_prune_wide_init(d, L, ws, s)) return e;     // clears headmax before the scoring kernel folds into it
+  if (int e = run_score(kv, d, q, sel_pages, sel_count, max_sel, scores, nullptr, use_head ? arrive : nullptr,
+                        use_head ? nullptr : headmax, s)) return e;
+  if (!use_head)
+    return tw_prune_wide(d, L, ws, kv, sel_pages, sel_count, max_sel, cand_stride, p, kept_count, kept_idx, kept_stride,
+                         union_count, union_idx, union_stride, status, s);
 
   // per-head page lists short enough for registers and sequences that fit the LDS bitmap: one
   // launch does top-p per head and, in the last head of each group to finish, the group's union
-  if (!full && cand_stride <= 1024 * 8 && (long long)d.max_pages * TW_PAGE <= HP_BITMAP_WORDS * 32ll) {
-    const int words_stride = (d.max_pages + 1) / 2;
-    uint32_t* bitmaps = thr + (((size_t)d.batch * d.Hq + 63) & ~(size_t)63);
+  {
+    const int words_stride = L.words_stride;
+    uint32_t* bitmaps = (uint32_t*)((char*)ws + L.bitmaps);
     HeadArgs f;
     f.scores = scores; f.sel_pages = sel_pages; f.sel_count = sel_count; f.seq_lens = kv->seq_lens;
     f.kept_count = kept_count; f.kept_idx = kept_idx; f.bitmaps = bitmaps; f.arrive = arrive;
@@ -911,25 +642,4 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
     }
     return tw_prof_after(s);
   }
-
-  ToppArgs t;
-  t.scores = scores; t.sel_pages = sel_pages; t.sel_count = sel_count; t.seq_lens = kv->seq_lens;
-  t.kept_count = kept_count; t.kept_idx = kept_idx; t.thr_key = thr; t.status = status;
-  t.Hq = d.Hq; t.max_pages = d.max_pages; t.max_sel = max_sel; t.cand_stride = cand_stride;
-  t.kept_stride = kept_stride; t.p = p;
-  tw_prof_before(TW_K_TOPP, s);
-  if (cand_stride <= TP_THREADS * TP_EPT)
-    hipLaunchKernelGGL(topp_kernel<true>, dim3(d.Hq, d.batch), dim3(TP_THREADS), 0, s, t);
-  else
-    hipLaunchKernelGGL(topp_kernel<false>, dim3(d.Hq, d.batch), dim3(TP_THREADS), 0, s, t);
-  if (int e = tw_prof_after(s)) return e;
-
-  UnionArgs u;
-  u.scores = scores; u.thr_key = thr; u.sel_pages = sel_pages; u.sel_count = sel_count;
-  u.seq_lens = kv->seq_lens; u.union_count = union_count; u.union_idx = union_idx; u.status = status;
-  u.Hq = d.Hq; u.Hkv = d.Hkv; u.G = d.G; u.max_pages = d.max_pages; u.max_sel = max_sel;
-  u.cand_stride = cand_stride; u.union_stride = union_stride;
-  tw_prof_before(TW_K_UNION, s);
-  hipLaunchKernelGGL(union_kernel, dim3(d.batch * d.Hkv), dim3(UN_THREADS), 0, s, u);
-  return tw_prof_after(s);
 }

@@ -1,0 +1,445 @@
+// Stage 2b/c for long candidate rows (paper: Algorithm 1, Definition 3.3,
+// Appendix B.2): the same threshold search as the register-resident kernel,
+// spread over many workgroups per head.  Used when a head has more than 8192
+// candidates (every token a candidate - the "Full" selector - or very large
+// budgets) or the sequence is too long for the in-LDS bitmap.
+//
+//   wide_init     clears histograms / lists / bitmaps, resets per-head state
+//   (int4_score   also folds the row maximum into headmax with atomicMax)
+//   wide_hist     one pass over the scores: LDS histogram of the current rank
+//                 interval per workgroup, flushed to the head's global one
+//   wide_decide   one wave per head scans the 512 buckets and narrows the
+//                 interval (or finishes when <= 1024 scores are left in it)
+//   wide_emit     second pass: kept for sure -> bitmap, undecided -> a short
+//                 per-head list
+//   wide_resolve  exact finish on the undecided list, sets their bits
+//   bitmap_list   bitmap(s) -> ascending index list (per-head kept list, and
+//                 the union of a KV head's query heads)
+// All sums are 64-bit fixed point and all atomics are integer adds / maxima,
+// so results do not depend on scheduling.
+#include "topp_common.h"
+
+namespace {
+
+struct WideState {           // per head
+  uint32_t rlo, shift, pop, flags, pass, pad;
+  unsigned long long A, target;
+};
+constexpr uint32_t WF_DONE = 1, WF_EMPTY = 4, WF_TIER_ALL = 8;
+constexpr int W_SLOTS = 32;                    // candidate slots per thread
+constexpr int W_CHUNK = 1024 * W_SLOTS;        // per workgroup
+constexpr int W_CAP = 1024;                    // undecided scores resolved exactly
+
+struct WideArgs {
+  const float* scores;
+  const int32_t* sel_pages;   // or nullptr
+  const int32_t* sel_count;
+  const int32_t* seq_lens;
+  const uint32_t* headmax;    // key of the largest score per head, 0 = no valid score
+  WideState* state;
+  unsigned long long* ghistM;
+  uint32_t* ghistC;
+  unsigned long long* gtail;
+  uint4* ulist;               // [bh][W_CAP] {key, token, mass lo, mass hi}
+  uint32_t* ucount;
+  uint32_t* kdef;
+  uint32_t* bitmaps;
+  int32_t* kept_count;
+  uint32_t* status;
+  int Hq, max_pages, max_sel, cand_stride, words_stride;
+  int keep_all;               // p >= 1
+  float p;
+};
+
+__global__ __launch_bounds__(256) void wide_init_kernel(uint4* zero_base, size_t n16, WideState* st, int nbh) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) zero_base[i] = make_uint4(0, 0, 0, 0);
+  if (i < (size_t)nbh) {
+    WideState s;
+    s.rlo = 0; s.shift = 16; s.pop = 0; s.flags = 0; s.pass = 0; s.pad = 0; s.A = 0; s.target = 0;
+    st[i] = s;
+  }
+}
+
+__device__ __forceinline__ int wide_count(const WideArgs& a, int b, int bh) {
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  int count = P;
+  if (a.sel_pages) { count = a.sel_count[bh]; if (count > a.max_sel) count = a.max_sel; if (count < 0) count = 0; }
+  return count;
+}
+
+// 32 contiguous scores of this thread, loaded unconditionally (clamped) and masked to -inf beyond N
+__device__ __forceinline__ void wide_load(const float* row, int c0, int N, int cand_stride, float* s) {
+#pragma unroll
+  for (int v = 0; v < W_SLOTS / 4; ++v) {
+    const int cc = c0 + 4 * v < cand_stride ? c0 + 4 * v : cand_stride - 4;
+    const float4 x = *(const float4*)(row + cc);
+    s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
+  }
+#pragma unroll
+  for (int e = 0; e < W_SLOTS; ++e) s[e] = (c0 + e < N) ? s[e] : -__builtin_inff();
+}
+
+__global__ __launch_bounds__(1024) void wide_hist_kernel(WideArgs a) {
+  const int bh = blockIdx.y, b = bh / a.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const WideState st = a.state[bh];
+  const uint32_t mk = a.headmax[(long long)bh * TW_CTR];
+  if ((st.flags & WF_DONE) || mk == 0) return;
+  const int N = wide_count(a, b, bh) * TW_PAGE;
+  if ((long long)blockIdx.x * W_CHUNK >= N) return;
+  const float m = tw_key_to_float(mk);
+  const int c0 = blockIdx.x * W_CHUNK + tid * W_SLOTS;
+
+  __shared__ unsigned long long histM[HP_NB];
+  __shared__ uint32_t histC[HP_NB];
+  __shared__ unsigned long long tail_s[16];
+  if (tid < HP_NB) { histM[tid] = 0; histC[tid] = 0; }
+  float s[W_SLOTS];
+  wide_load(a.scores + (long long)bh * a.cand_stride, c0, N, a.cand_stride, s);
+  __syncthreads();
+  unsigned long long below = 0;
+#pragma unroll
+  for (int e = 0; e < W_SLOTS; ++e) {
+    const uint32_t r = hp_rank_only(m, s[e]);       // the exponential only for scores that take part
+    if (r != HP_NONE && r >= st.rlo) {
+      const uint32_t bk = (r - st.rlo) >> st.shift;
+      if (bk < HP_NB) {
+        atomicAdd(&histM[bk], hp_fix(hp_numer(m, s[e])));
+        atomicAdd(&histC[bk], 1u);
+      } else if (st.pass == 0) {
+        below += hp_fix(hp_numer(m, s[e]));
+      }
+    }
+  }
+  below = tw_wave_scan_u64(below);
+  if (lane == 63) tail_s[wave] = below;
+  __syncthreads();
+  if (tid < HP_NB) {
+    const uint32_t c = histC[tid];
+    if (c) { atomicAdd(&a.ghistM[(long long)bh * HP_NB + tid], histM[tid]); atomicAdd(&a.ghistC[(long long)bh * HP_NB + tid], c); }
+  }
+  if (tid == 0 && st.pass == 0) {                 // mass below the fine range counts towards Z
+    unsigned long long t = 0;
+    for (int w = 0; w < 16; ++w) t += tail_s[w];
+    if (t) atomicAdd(&a.gtail[(long long)bh * (TW_CTR / 2)], t);
+  }
+}
+
+// One wave per head: scan the 512 buckets (lane l owns 8l .. 8l+7), find the one where the
+// mass reaches the target, narrow the interval to it.
+__global__ __launch_bounds__(64) void wide_decide_kernel(WideArgs a) {
+  const int bh = blockIdx.x, lane = threadIdx.x;
+  WideState st = a.state[bh];
+  if (st.flags & WF_DONE) return;
+  if (a.headmax[(long long)bh * TW_CTR] == 0) { if (lane == 0) { st.flags = WF_DONE | WF_EMPTY; a.state[bh] = st; } return; }
+  unsigned long long* gm = a.ghistM + (long long)bh * HP_NB;
+  uint32_t* gc = a.ghistC + (long long)bh * HP_NB;
+  unsigned long long mb[8], mine = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { mb[k] = gm[8 * lane + k]; mine += mb[k]; }
+  const unsigned long long incl = tw_wave_scan_u64(mine);
+  const unsigned long long total = __shfl(incl, 63, 64);
+  if (st.pass == 0) {
+    const unsigned long long Z = total + a.gtail[(long long)bh * (TW_CTR / 2)];
+    const double t = ceil((double)a.p * (double)Z);
+    st.target = t < 1.0 ? 1ull : (unsigned long long)t;
+    if (st.target > Z) st.target = Z;
+  }
+  const unsigned long long before = st.A + incl - mine;
+  const bool hit = before < st.target && before + mine >= st.target;
+  const unsigned long long bal = __ballot(hit);
+  bool again = false;
+  if (bal == 0 && st.pass == 0) {                 // not enough mass in the fine range: go on below it
+    st.A += total; st.rlo = HP_FINE_END; st.shift = 18; again = true;
+  } else if (bal == 0) {
+    st.flags |= WF_DONE | WF_TIER_ALL;            // unreachable: the interval holds the crossing by construction
+  } else {
+    const int src = __ffsll((long long)bal) - 1;
+    unsigned long long cum = before, asel = before;
+    int bsel = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (cum < st.target && cum + mb[k] >= st.target) { bsel = k; asel = cum; }
+      cum += mb[k];
+    }
+    const int bucket = 8 * src + __shfl(bsel, src, 64);
+    st.A = __shfl(asel, src, 64);
+    st.pop = gc[bucket];
+    st.rlo += (uint32_t)bucket << st.shift;
+    if (st.pop <= (uint32_t)W_CAP) st.flags |= WF_DONE;
+    else if (st.shift == 0) st.flags |= WF_DONE | WF_TIER_ALL;   // > W_CAP scores of one rank: keep them all
+    else { st.shift = st.shift >= 9 ? st.shift - 9 : 0; again = true; }
+  }
+  st.pass += 1;
+  if (again) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { gm[8 * lane + k] = 0; gc[8 * lane + k] = 0; }
+  }
+  if (lane == 0) a.state[bh] = st;
+}
+
+__global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
+  const int bh = blockIdx.y, b = bh / a.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const WideState st = a.state[bh];
+  const uint32_t mk = a.headmax[(long long)bh * TW_CTR];
+  if (mk == 0) return;                            // no valid score: bitmap stays empty
+  const int count = wide_count(a, b, bh);
+  const int N = count * TW_PAGE;
+  if ((long long)blockIdx.x * W_CHUNK >= N) return;
+  const float m = tw_key_to_float(mk);
+  const int c0 = blockIdx.x * W_CHUNK + tid * W_SLOTS;
+  // a search that did not finish in the passes given keeps its whole interval
+  const bool tier = (st.flags & WF_TIER_ALL) || !(st.flags & WF_DONE);
+  const uint32_t rhi = st.rlo + (st.shift >= 32 ? 0xFFFFFFFFu : (1u << st.shift)) - 1u;
+  float s[W_SLOTS];
+  wide_load(a.scores + (long long)bh * a.cand_stride, c0, N, a.cand_stride, s);
+  int pg[2] = {0, 0};
+  if (a.sel_pages) {
+#pragma unroll
+    for (int v = 0; v < 2; ++v) {
+      const int pi = (c0 >> 4) + v < a.max_sel ? (c0 >> 4) + v : a.max_sel - 1;
+      pg[v] = a.sel_pages[(long long)bh * a.max_sel + pi];
+    }
+  }
+  uint32_t mask = 0;
+#pragma unroll
+  for (int e = 0; e < W_SLOTS; ++e) {
+    const bool valid = s[e] > -__builtin_inff();
+    bool keep;
+    if (a.keep_all) keep = valid;
+    else {
+      const uint32_t r = hp_rank_only(m, s[e]);
+      const bool part = valid && r != HP_NONE;
+      keep = part && (r < st.rlo || (tier && r <= rhi));
+      const bool und = part && !tier && r >= st.rlo && r <= rhi;
+      // undecided: onto the head's list; one atomic per wave reserves the slots of all its lanes
+      const unsigned long long ub = __ballot(und);
+      uint32_t ubase = 0;
+      if (ub) {
+        const int leader = __ffsll((long long)ub) - 1;
+        if (lane == leader) ubase = atomicAdd(&a.ucount[(long long)bh * TW_CTR], (uint32_t)__popcll(ub));
+        ubase = __shfl(ubase, leader, 64);
+      }
+      if (und) {
+        const uint32_t at = ubase + (uint32_t)__popcll(ub & ((1ull << lane) - 1ull));
+        if (at < (uint32_t)W_CAP) {
+          const unsigned long long w = hp_fix(hp_numer(m, s[e]));
+          const int tok = a.sel_pages ? pg[e >> 4] * TW_PAGE + (e & 15) : c0 + e;
+          a.ulist[(long long)bh * W_CAP + at] = make_uint4(tw_float_key(s[e]), (uint32_t)tok, (uint32_t)w, (uint32_t)(w >> 32));
+        }
+      }
+    }
+    mask |= (keep ? 1u : 0u) << e;
+  }
+  uint32_t* bm = a.bitmaps + (long long)bh * a.words_stride;
+  if (a.sel_pages) {                              // two pages, one 16-bit half word each
+    unsigned short* bm16 = (unsigned short*)bm;
+    if ((c0 >> 4) < count && (pg[0] >> 1) < a.words_stride) bm16[pg[0]] = (unsigned short)(mask & 0xFFFFu);
+    if ((c0 >> 4) + 1 < count && (pg[1] >> 1) < a.words_stride) bm16[pg[1]] = (unsigned short)(mask >> 16);
+  } else if (c0 < N && (c0 >> 5) < a.words_stride) {
+    bm[c0 >> 5] = mask;                           // slots are token positions
+  }
+  uint32_t cnt = tw_wave_scan_u32(__popc(mask));
+  __shared__ uint32_t wc[16];
+  if (lane == 63) wc[wave] = cnt;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t t = 0;
+    for (int w = 0; w < 16; ++w) t += wc[w];
+    if (t) atomicAdd(&a.kdef[(long long)bh * TW_CTR], t);
+  }
+}
+
+__global__ __launch_bounds__(1024) void wide_resolve_kernel(WideArgs a) {
+  const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const WideState st = a.state[bh];
+  __shared__ uint32_t keys[W_CAP];
+  __shared__ unsigned long long mass[W_CAP];
+  __shared__ uint32_t red[16];
+  const bool search = !a.keep_all && a.headmax[(long long)bh * TW_CTR] != 0 && (st.flags & WF_DONE) && !(st.flags & WF_TIER_ALL);
+  uint32_t cn = 0;
+  if (search) { cn = a.ucount[(long long)bh * TW_CTR]; if (cn > (uint32_t)W_CAP) cn = W_CAP; }
+  uint4 mine = make_uint4(0, 0, 0, 0);
+  if (tid < (int)cn) {
+    mine = a.ulist[(long long)bh * W_CAP + tid];
+    keys[tid] = mine.x;
+    mass[tid] = (unsigned long long)mine.z | ((unsigned long long)mine.w << 32);
+  }
+  __syncthreads();
+  uint32_t best = 0;
+  if (tid < (int)cn) {
+    unsigned long long S = 0;
+#pragma unroll 8
+    for (uint32_t j = 0; j < cn; ++j) S += keys[j] >= mine.x ? mass[j] : 0ull;
+    if (st.A + S >= st.target) best = mine.x;
+  }
+  best = tw_wave_max_u32(best);
+  if (lane == 0) red[wave] = best;
+  __syncthreads();
+  uint32_t T = red[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) T = red[w] > T ? red[w] : T;
+  __syncthreads();
+  uint32_t add = 0;
+  if (tid < (int)cn && mine.x >= T && (mine.y >> 5) < (uint32_t)a.words_stride) {
+    atomicOr(&a.bitmaps[(long long)bh * a.words_stride + (mine.y >> 5)], 1u << (mine.y & 31));
+    add = 1;
+  }
+  add = tw_wave_scan_u32(add);
+  if (lane == 63) red[wave] = add;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t t = a.kdef[(long long)bh * TW_CTR];
+    for (int w = 0; w < 16; ++w) t += red[w];
+    a.kept_count[bh] = (int32_t)t;
+  }
+}
+
+struct ListArgs {
+  const uint32_t* bitmaps;
+  const int32_t* seq_lens;
+  int32_t* count_out;         // or nullptr (count already known)
+  int32_t* idx_out;
+  uint32_t* status;
+  int rows_per_seq, maps_per_row, max_pages, words_stride, out_stride;
+  uint32_t trunc_bit;
+};
+
+// Row r: OR of NB consecutive bitmaps (r * maps_per_row ...) -> ascending positions.  One
+// workgroup per (segment of 256 words, row): it first counts the bits of the row's earlier
+// segments (its output offset), then stages its own positions in LDS and copies them out
+// coalesced.  The workgroup of the last segment also writes the count.
+constexpr int BL_SEG = 256;
+template <int NB>
+__global__ __launch_bounds__(256) void bitmap_list_kernel(ListArgs a) {
+  const int row = blockIdx.y, seg = blockIdx.x, b = row / a.rows_per_seq, tid = threadIdx.x;
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
+  const int nwords = (ntok + 31) >> 5;
+  const int nseg = (nwords + BL_SEG - 1) / BL_SEG;
+  if (seg >= nseg && !(seg == 0 && nseg == 0)) return;
+  __shared__ uint32_t ws32[16];
+  __shared__ int32_t stage[BL_SEG * 32];
+  const uint32_t* bm = a.bitmaps + (long long)row * a.maps_per_row * a.words_stride;
+  int32_t* out = a.idx_out + (long long)row * a.out_stride;
+  // bits before this segment
+  uint32_t before = 0;
+  for (int s0 = 0; s0 < seg; s0 += 4) {             // 4 clamped loads in flight
+    uint32_t x[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool ok = s0 + j < seg;
+      const int wi = ok ? (s0 + j) * BL_SEG + tid : 0;
+      uint32_t v = 0;
+#pragma unroll
+      for (int hh = 0; hh < NB; ++hh) v |= bm[(long long)hh * a.words_stride + wi];
+      x[j] = ok ? v : 0u;
+    }
+    before += __popc(x[0]) + __popc(x[1]) + __popc(x[2]) + __popc(x[3]);
+  }
+  const int wi = seg * BL_SEG + tid;
+  uint32_t w = 0;
+  if (wi < nwords) {
+#pragma unroll
+    for (int hh = 0; hh < NB; ++hh) w |= bm[(long long)hh * a.words_stride + wi];
+  }
+  uint32_t base_total, total;
+  tw_block_scan_u32(before, ws32, &base_total);
+  const uint32_t incl = tw_block_scan_u32(__popc(w), ws32, &total);
+  uint32_t pos = incl - __popc(w);
+  while (w) {
+    const int bit = __ffs(w) - 1;
+    w &= w - 1;
+    stage[pos++] = wi * 32 + bit;
+  }
+  __syncthreads();
+  for (uint32_t i = tid; i < total; i += 256)
+    if (base_total + i < (uint32_t)a.out_stride) out[base_total + i] = stage[i];
+  if (tid == 0 && seg == (nseg > 0 ? nseg - 1 : 0)) {
+    uint32_t run = base_total + total;
+    if (run > (uint32_t)a.out_stride) { atomicOr(a.status, a.trunc_bit); run = a.out_stride; }
+    if (a.count_out) a.count_out[row] = (int32_t)run;
+  }
+}
+
+template <int NB>
+void launch_list(const ListArgs& a, int rows, hipStream_t s) {
+  const int max_words = (a.max_pages + 1) / 2;
+  int segs = (max_words + BL_SEG - 1) / BL_SEG;
+  if (segs < 1) segs = 1;
+  hipLaunchKernelGGL(bitmap_list_kernel<NB>, dim3(segs, rows), dim3(256), 0, s, a);
+}
+
+}  // namespace
+
+// Everything after the scores have been written (and headmax filled by the scoring kernel).
+// tw_prune_wide_init must have been enqueued BEFORE the scoring kernel.
+int tw_prune_wide_init(const TwDims& d, const PruneWs& L, void* ws, hipStream_t s) {
+  const size_t n16 = (L.state - L.headmax) / 16;
+  const int nbh = d.batch * d.Hq;
+  const size_t n = n16 > (size_t)nbh ? n16 : (size_t)nbh;
+  tw_prof_before(TW_K_TOPP, s);
+  hipLaunchKernelGGL(wide_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+                     (uint4*)((char*)ws + L.headmax), n16, (WideState*)((char*)ws + L.state), nbh);
+  return tw_prof_after(s);
+}
+
+int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv_t* kv, const int32_t* sel_pages,
+                  const int32_t* sel_count, int max_sel, int cand_stride, float p, int32_t* kept_count,
+                  int32_t* kept_idx, int kept_stride, int32_t* union_count, int32_t* union_idx, int union_stride,
+                  uint32_t* status, hipStream_t s) {
+  char* base = (char*)ws;
+  WideArgs a;
+  a.scores = (const float*)(base + L.scores); a.sel_pages = sel_pages; a.sel_count = sel_count; a.seq_lens = kv->seq_lens;
+  a.headmax = (const uint32_t*)(base + L.headmax); a.state = (WideState*)(base + L.state);
+  a.ghistM = (unsigned long long*)(base + L.ghistM); a.ghistC = (uint32_t*)(base + L.ghistC);
+  a.gtail = (unsigned long long*)(base + L.gtail); a.ulist = (uint4*)(base + L.ulist);
+  a.ucount = (uint32_t*)(base + L.ucount); a.kdef = (uint32_t*)(base + L.kdef);
+  a.bitmaps = (uint32_t*)(base + L.bitmaps); a.kept_count = kept_count; a.status = status;
+  a.Hq = d.Hq; a.max_pages = d.max_pages; a.max_sel = max_sel; a.cand_stride = cand_stride;
+  a.words_stride = L.words_stride; a.keep_all = p >= 1.0f ? 1 : 0; a.p = p;
+  const int nbh = d.batch * d.Hq;
+  const dim3 wide_grid((cand_stride + W_CHUNK - 1) / W_CHUNK, nbh);
+  if (!a.keep_all) {
+    // pass 0, then up to two more: a restart below the fine range and / or a 9-bit refinement
+    for (int pass = 0; pass < 3; ++pass) {
+      tw_prof_before(TW_K_TOPP, s);
+      hipLaunchKernelGGL(wide_hist_kernel, wide_grid, dim3(1024), 0, s, a);
+      if (int e = tw_prof_after(s)) return e;
+      tw_prof_before(TW_K_TOPP, s);
+      hipLaunchKernelGGL(wide_decide_kernel, dim3(nbh), dim3(64), 0, s, a);
+      if (int e = tw_prof_after(s)) return e;
+    }
+  }
+  tw_prof_before(TW_K_TOPP, s);
+  hipLaunchKernelGGL(wide_emit_kernel, wide_grid, dim3(1024), 0, s, a);
+  if (int e = tw_prof_after(s)) return e;
+  tw_prof_before(TW_K_TOPP, s);
+  hipLaunchKernelGGL(wide_resolve_kernel, dim3(nbh), dim3(1024), 0, s, a);
+  if (int e = tw_prof_after(s)) return e;
+
+  ListArgs l;
+  l.bitmaps = a.bitmaps; l.seq_lens = kv->seq_lens; l.status = status; l.max_pages = d.max_pages;
+  l.words_stride = L.words_stride;
+  if (kept_idx) {
+    l.count_out = kept_count; l.idx_out = kept_idx; l.rows_per_seq = d.Hq; l.maps_per_row = 1; l.out_stride = kept_stride;
+    l.trunc_bit = TW_STATUS_KEPT_TRUNCATED;
+    tw_prof_before(TW_K_UNION, s);
+    launch_list<1>(l, nbh, s);
+    if (int e = tw_prof_after(s)) return e;
+  }
+  l.count_out = union_count; l.idx_out = union_idx; l.rows_per_seq = d.Hkv; l.maps_per_row = d.G; l.out_stride = union_stride;
+  l.trunc_bit = TW_STATUS_UNION_TRUNCATED;
+  tw_prof_before(TW_K_UNION, s);
+  switch (d.G) {
+    case 1: launch_list<1>(l, d.batch * d.Hkv, s); break;
+    case 2: launch_list<2>(l, d.batch * d.Hkv, s); break;
+    case 4: launch_list<4>(l, d.batch * d.Hkv, s); break;
+    default: launch_list<8>(l, d.batch * d.Hkv, s); break;
+  }
+  return tw_prof_after(s);
+}

@@ -1,6 +1,6 @@
 // Host-side pieces shared by the entry points: argument checks, workspace
 // sizes, error strings, and the optional per-kernel event timing.
-#include "tw_common.h"
+#include "topp_common.h"
 
 int tw_decode_chunk(bool dense);
 long long tw_decode_max_items(const TwDims& d, bool dense, int union_stride);
@@ -49,10 +49,8 @@ extern "C" size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, i
     case TW_WS_SELECT:
       return align256(bh * d.max_pages * 4);
     case TW_WS_PRUNE: {
-      const size_t bound = max_sel > 0 ? (size_t)max_sel : (size_t)d.max_pages;
-      // scores, per-head thresholds, per-head kept bitmaps (one bit per token position)
-      return align256(bh * bound * TW_PAGE * 4) + align256(bh * 4) + align256(bh * ((size_t)(d.max_pages + 1) / 2) * 4) +
-             align256((size_t)d.batch * d.Hkv * 4) + 512;   // + arrival counters
+      const int bound = max_sel > 0 ? max_sel : d.max_pages;
+      return tw_prune_layout(d, bound).total;
     }
     case TW_WS_DECODE: {
       const bool dense = union_stride <= 0;

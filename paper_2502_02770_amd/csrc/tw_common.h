@@ -97,6 +97,11 @@ static __device__ unsigned long long tw_dbg_stamps[64];
 #define TW_STAMP(k) do { } while (0)
 #endif
 
+// inverse of tw_float_key
+__device__ __forceinline__ float tw_key_to_float(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+}
+
 // ---- wave64 primitives on DPP (no LDS traffic)
 #define TW_DPP_ROW_SHR(n) (0x110 + (n))
 #define TW_DPP_BCAST15 0x142      // lane 15 of each row -> the next row
