@@ -18,7 +18,7 @@ struct PruneWs {
   size_t scores, headmax, bitmaps, arrive, state, ghistM, ghistC, gtail, ulist, ucount, kdef, total;
   int words_stride;       // bitmap words per head
 };
-PruneWs tw_prune_layout(const TwDims& d, int bound_pages);
+PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full);
 
 #ifdef __HIPCC__
 // softmax numerator e in (0, 1] -> 2^-40 fixed point, from the float's own bits

@@ -549,7 +549,7 @@ bool tw_prune_uses_head_kernel(const TwDims& d, bool full, int bound_pages) {
   return !full && bound_pages * TW_PAGE <= 1024 * 8 && (long long)d.max_pages * TW_PAGE <= HP_BITMAP_WORDS * 32ll;
 }
 
-PruneWs tw_prune_layout(const TwDims& d, int bound_pages) {
+PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full) {
   auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
   const size_t bh = (size_t)d.batch * d.Hq;
   PruneWs L;
@@ -559,9 +559,14 @@ PruneWs tw_prune_layout(const TwDims& d, int bound_pages) {
   L.headmax = o; o += al(bh * TW_CTR * 4);               // (the long-row path clears from here ...)
   L.arrive = o;  o += al((size_t)d.batch * d.Hkv * TW_CTR * 4);
   L.bitmaps = o; o += al(bh * (size_t)L.words_stride * 4);
-  L.ghistM = o;  o += al(bh * HP_NB * 8);
-  L.ghistC = o;  o += al(bh * HP_NB * 4);
-  L.gtail = o;   o += al(bh * TW_CTR * 4);
+  if (tw_prune_uses_head_kernel(d, full, bound_pages)) {     // the long-row buffers are not needed
+    L.ghistM = L.ghistC = L.gtail = L.ucount = L.kdef = L.state = L.ulist = o;
+    L.total = o;
+    return L;
+  }
+  L.ghistM = o;  o += al(bh * 2048 * 8);
+  L.ghistC = o;  o += al(bh * 2048 * 4);
+  L.gtail = o;
   L.ucount = o;  o += al(bh * TW_CTR * 4);
   L.kdef = o;    o += al(bh * TW_CTR * 4);
   L.state = o;   o += al(bh * 48);                       // (... up to here)
@@ -599,10 +604,10 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
   const bool full = sel_pages == nullptr;
   const int bound = full ? d.max_pages : max_sel;
   if ((long long)bound * TW_PAGE > (1ll << 22)) return TW_EINVAL;   // fixed-point mass headroom
-  if (!ws || ws_bytes < tw_prune_layout(d, bound).total) return TW_EWORKSPACE;
+  if (!ws || ws_bytes < tw_prune_layout(d, bound, full).total) return TW_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   const int cand_stride = bound * TW_PAGE;
-  const PruneWs L = tw_prune_layout(d, bound);
+  const PruneWs L = tw_prune_layout(d, bound, full);
   float* scores = (float*)((char*)ws + L.scores);
   uint32_t* headmax = (uint32_t*)((char*)ws + L.headmax);
   uint32_t* arrive = (uint32_t*)((char*)ws + L.arrive);

@@ -8,7 +8,7 @@
 //   (int4_score   also folds the row maximum into headmax with atomicMax)
 //   wide_hist     one pass over the scores: LDS histogram of the current rank
 //                 interval per workgroup, flushed to the head's global one
-//   wide_decide   one wave per head scans the 512 buckets and narrows the
+//   wide_decide   one wave per head scans the 2048 buckets and narrows the
 //                 interval (or finishes when <= 1024 scores are left in it)
 //   wide_emit     second pass: kept for sure -> bitmap, undecided -> a short
 //                 per-head list
@@ -29,6 +29,8 @@ constexpr uint32_t WF_DONE = 1, WF_EMPTY = 4, WF_TIER_ALL = 8;
 constexpr int W_SLOTS = 32;                    // candidate slots per thread
 constexpr int W_CHUNK = 1024 * W_SLOTS;        // per workgroup
 constexpr int W_CAP = 1024;                    // undecided scores resolved exactly
+constexpr int W_NB = 2048;                     // buckets per pass: pass 0 covers every rank (32 logits at 1/64)
+constexpr int W_BITS = 11;
 
 struct WideArgs {
   const float* scores;
@@ -39,7 +41,6 @@ struct WideArgs {
   WideState* state;
   unsigned long long* ghistM;
   uint32_t* ghistC;
-  unsigned long long* gtail;
   uint4* ulist;               // [bh][W_CAP] {key, token, mass lo, mass hi}
   uint32_t* ucount;
   uint32_t* kdef;
@@ -70,16 +71,20 @@ __device__ __forceinline__ int wide_count(const WideArgs& a, int b, int bh) {
   return count;
 }
 
-// 32 contiguous scores of this thread, loaded unconditionally (clamped) and masked to -inf beyond N
-__device__ __forceinline__ void wide_load(const float* row, int c0, int N, int cand_stride, float* s) {
+// A workgroup covers W_CHUNK consecutive candidate slots; thread t owns 8 groups of 4 slots,
+// group v at chunk + v*4096 + 4t, so that every load instruction of a wave reads 1 KiB
+// contiguous.  Loaded unconditionally (clamped) and masked to -inf at and beyond N.
+__device__ __forceinline__ int wide_slot(int chunk0, int v, int tid) { return chunk0 + v * 4096 + tid * 4; }
+__device__ __forceinline__ void wide_load(const float* row, int chunk0, int tid, int N, int cand_stride, float* s) {
 #pragma unroll
   for (int v = 0; v < W_SLOTS / 4; ++v) {
-    const int cc = c0 + 4 * v < cand_stride ? c0 + 4 * v : cand_stride - 4;
-    const float4 x = *(const float4*)(row + cc);
-    s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
+    const int c = wide_slot(chunk0, v, tid);
+    const float4 x = *(const float4*)(row + (c < cand_stride ? c : cand_stride - 4));
+    s[4 * v] = c < N ? x.x : -__builtin_inff();     // N is a multiple of 16: a group is inside or outside
+    s[4 * v + 1] = c < N ? x.y : -__builtin_inff();
+    s[4 * v + 2] = c < N ? x.z : -__builtin_inff();
+    s[4 * v + 3] = c < N ? x.w : -__builtin_inff();
   }
-#pragma unroll
-  for (int e = 0; e < W_SLOTS; ++e) s[e] = (c0 + e < N) ? s[e] : -__builtin_inff();
 }
 
 __global__ __launch_bounds__(1024) void wide_hist_kernel(WideArgs a) {
@@ -90,92 +95,79 @@ __global__ __launch_bounds__(1024) void wide_hist_kernel(WideArgs a) {
   const int N = wide_count(a, b, bh) * TW_PAGE;
   if ((long long)blockIdx.x * W_CHUNK >= N) return;
   const float m = tw_key_to_float(mk);
-  const int c0 = blockIdx.x * W_CHUNK + tid * W_SLOTS;
+  const int chunk0 = blockIdx.x * W_CHUNK;
 
-  __shared__ unsigned long long histM[HP_NB];
-  __shared__ uint32_t histC[HP_NB];
-  __shared__ unsigned long long tail_s[16];
-  if (tid < HP_NB) { histM[tid] = 0; histC[tid] = 0; }
+  __shared__ unsigned long long histM[W_NB];
+  __shared__ uint32_t histC[W_NB];
+  for (int i = tid; i < W_NB; i += 1024) { histM[i] = 0; histC[i] = 0; }
   float s[W_SLOTS];
-  wide_load(a.scores + (long long)bh * a.cand_stride, c0, N, a.cand_stride, s);
+  wide_load(a.scores + (long long)bh * a.cand_stride, chunk0, tid, N, a.cand_stride, s);
   __syncthreads();
-  unsigned long long below = 0;
 #pragma unroll
   for (int e = 0; e < W_SLOTS; ++e) {
     const uint32_t r = hp_rank_only(m, s[e]);       // the exponential only for scores that take part
     if (r != HP_NONE && r >= st.rlo) {
       const uint32_t bk = (r - st.rlo) >> st.shift;
-      if (bk < HP_NB) {
+      if (bk < W_NB) {
         atomicAdd(&histM[bk], hp_fix(hp_numer(m, s[e])));
         atomicAdd(&histC[bk], 1u);
-      } else if (st.pass == 0) {
-        below += hp_fix(hp_numer(m, s[e]));
       }
     }
   }
-  below = tw_wave_scan_u64(below);
-  if (lane == 63) tail_s[wave] = below;
   __syncthreads();
-  if (tid < HP_NB) {
-    const uint32_t c = histC[tid];
-    if (c) { atomicAdd(&a.ghistM[(long long)bh * HP_NB + tid], histM[tid]); atomicAdd(&a.ghistC[(long long)bh * HP_NB + tid], c); }
-  }
-  if (tid == 0 && st.pass == 0) {                 // mass below the fine range counts towards Z
-    unsigned long long t = 0;
-    for (int w = 0; w < 16; ++w) t += tail_s[w];
-    if (t) atomicAdd(&a.gtail[(long long)bh * (TW_CTR / 2)], t);
+  for (int i = tid; i < W_NB; i += 1024) {
+    const uint32_t c = histC[i];
+    if (c) { atomicAdd(&a.ghistM[(long long)bh * W_NB + i], histM[i]); atomicAdd(&a.ghistC[(long long)bh * W_NB + i], c); }
   }
 }
 
-// One wave per head: scan the 512 buckets (lane l owns 8l .. 8l+7), find the one where the
+// One wave per head: scan the 2048 buckets (lane l owns 32l .. 32l+31), find the one where the
 // mass reaches the target, narrow the interval to it.
 __global__ __launch_bounds__(64) void wide_decide_kernel(WideArgs a) {
+  constexpr int BPL = W_NB / 64;
   const int bh = blockIdx.x, lane = threadIdx.x;
   WideState st = a.state[bh];
   if (st.flags & WF_DONE) return;
   if (a.headmax[(long long)bh * TW_CTR] == 0) { if (lane == 0) { st.flags = WF_DONE | WF_EMPTY; a.state[bh] = st; } return; }
-  unsigned long long* gm = a.ghistM + (long long)bh * HP_NB;
-  uint32_t* gc = a.ghistC + (long long)bh * HP_NB;
-  unsigned long long mb[8], mine = 0;
+  unsigned long long* gm = a.ghistM + (long long)bh * W_NB;
+  uint32_t* gc = a.ghistC + (long long)bh * W_NB;
+  unsigned long long mb[BPL], mine = 0;
 #pragma unroll
-  for (int k = 0; k < 8; ++k) { mb[k] = gm[8 * lane + k]; mine += mb[k]; }
+  for (int k = 0; k < BPL; ++k) { mb[k] = gm[BPL * lane + k]; mine += mb[k]; }
   const unsigned long long incl = tw_wave_scan_u64(mine);
   const unsigned long long total = __shfl(incl, 63, 64);
-  if (st.pass == 0) {
-    const unsigned long long Z = total + a.gtail[(long long)bh * (TW_CTR / 2)];
-    const double t = ceil((double)a.p * (double)Z);
+  if (st.pass == 0) {                             // pass 0 sees every score that has mass: total = Z
+    const double t = ceil((double)a.p * (double)total);
     st.target = t < 1.0 ? 1ull : (unsigned long long)t;
-    if (st.target > Z) st.target = Z;
+    if (st.target > total) st.target = total;
   }
   const unsigned long long before = st.A + incl - mine;
   const bool hit = before < st.target && before + mine >= st.target;
   const unsigned long long bal = __ballot(hit);
   bool again = false;
-  if (bal == 0 && st.pass == 0) {                 // not enough mass in the fine range: go on below it
-    st.A += total; st.rlo = HP_FINE_END; st.shift = 18; again = true;
-  } else if (bal == 0) {
+  if (bal == 0) {
     st.flags |= WF_DONE | WF_TIER_ALL;            // unreachable: the interval holds the crossing by construction
   } else {
     const int src = __ffsll((long long)bal) - 1;
     unsigned long long cum = before, asel = before;
     int bsel = 0;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
+    for (int k = 0; k < BPL; ++k) {
       if (cum < st.target && cum + mb[k] >= st.target) { bsel = k; asel = cum; }
       cum += mb[k];
     }
-    const int bucket = 8 * src + __shfl(bsel, src, 64);
+    const int bucket = BPL * src + __shfl(bsel, src, 64);
     st.A = __shfl(asel, src, 64);
     st.pop = gc[bucket];
     st.rlo += (uint32_t)bucket << st.shift;
     if (st.pop <= (uint32_t)W_CAP) st.flags |= WF_DONE;
     else if (st.shift == 0) st.flags |= WF_DONE | WF_TIER_ALL;   // > W_CAP scores of one rank: keep them all
-    else { st.shift = st.shift >= 9 ? st.shift - 9 : 0; again = true; }
+    else { st.shift = st.shift >= W_BITS ? st.shift - W_BITS : 0; again = true; }
   }
   st.pass += 1;
   if (again) {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) { gm[8 * lane + k] = 0; gc[8 * lane + k] = 0; }
+    for (int k = 0; k < BPL; ++k) { gm[BPL * lane + k] = 0; gc[BPL * lane + k] = 0; }
   }
   if (lane == 0) a.state[bh] = st;
 }
@@ -189,21 +181,22 @@ __global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
   const int N = count * TW_PAGE;
   if ((long long)blockIdx.x * W_CHUNK >= N) return;
   const float m = tw_key_to_float(mk);
-  const int c0 = blockIdx.x * W_CHUNK + tid * W_SLOTS;
+  const int chunk0 = blockIdx.x * W_CHUNK;
   // a search that did not finish in the passes given keeps its whole interval
   const bool tier = (st.flags & WF_TIER_ALL) || !(st.flags & WF_DONE);
   const uint32_t rhi = st.rlo + (st.shift >= 32 ? 0xFFFFFFFFu : (1u << st.shift)) - 1u;
   float s[W_SLOTS];
-  wide_load(a.scores + (long long)bh * a.cand_stride, c0, N, a.cand_stride, s);
-  int pg[2] = {0, 0};
-  if (a.sel_pages) {
+  wide_load(a.scores + (long long)bh * a.cand_stride, chunk0, tid, N, a.cand_stride, s);
+  int pg[W_SLOTS / 4];                            // logical page of each group of 4 slots (page lists only)
 #pragma unroll
-    for (int v = 0; v < 2; ++v) {
-      const int pi = (c0 >> 4) + v < a.max_sel ? (c0 >> 4) + v : a.max_sel - 1;
-      pg[v] = a.sel_pages[(long long)bh * a.max_sel + pi];
+  for (int v = 0; v < W_SLOTS / 4; ++v) {
+    pg[v] = 0;
+    if (a.sel_pages) {
+      const int pi = wide_slot(chunk0, v, tid) >> 4;
+      pg[v] = a.sel_pages[(long long)bh * a.max_sel + (pi < a.max_sel ? pi : a.max_sel - 1)];
     }
   }
-  uint32_t mask = 0;
+  uint32_t mask = 0;                              // bit e: slot e of this thread is kept
 #pragma unroll
   for (int e = 0; e < W_SLOTS; ++e) {
     const bool valid = s[e] > -__builtin_inff();
@@ -226,20 +219,31 @@ __global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
         const uint32_t at = ubase + (uint32_t)__popcll(ub & ((1ull << lane) - 1ull));
         if (at < (uint32_t)W_CAP) {
           const unsigned long long w = hp_fix(hp_numer(m, s[e]));
-          const int tok = a.sel_pages ? pg[e >> 4] * TW_PAGE + (e & 15) : c0 + e;
+          const int slot = wide_slot(chunk0, e >> 2, tid) + (e & 3);
+          const int tok = a.sel_pages ? pg[e >> 2] * TW_PAGE + (slot & 15) : slot;
           a.ulist[(long long)bh * W_CAP + at] = make_uint4(tw_float_key(s[e]), (uint32_t)tok, (uint32_t)w, (uint32_t)(w >> 32));
         }
       }
     }
     mask |= (keep ? 1u : 0u) << e;
   }
+  // bitmap: the 4 bits of a group join those of the neighbouring lanes (4 lanes = one page of 16
+  // slots, 8 lanes = one word of 32 slots) through DPP, then one lane stores
   uint32_t* bm = a.bitmaps + (long long)bh * a.words_stride;
-  if (a.sel_pages) {                              // two pages, one 16-bit half word each
-    unsigned short* bm16 = (unsigned short*)bm;
-    if ((c0 >> 4) < count && (pg[0] >> 1) < a.words_stride) bm16[pg[0]] = (unsigned short)(mask & 0xFFFFu);
-    if ((c0 >> 4) + 1 < count && (pg[1] >> 1) < a.words_stride) bm16[pg[1]] = (unsigned short)(mask >> 16);
-  } else if (c0 < N && (c0 >> 5) < a.words_stride) {
-    bm[c0 >> 5] = mask;                           // slots are token positions
+#pragma unroll
+  for (int v = 0; v < W_SLOTS / 4; ++v) {
+    const int c = wide_slot(chunk0, v, tid);
+    uint32_t x = ((mask >> (4 * v)) & 0xFu) << (4 * (lane & 7));
+    x |= (uint32_t)tw_dpp_i<TW_DPP_XOR1>((int)x);
+    x |= (uint32_t)tw_dpp_i<TW_DPP_XOR2>((int)x);
+    if (a.sel_pages) {                            // one 16-bit half word per selected page
+      const uint32_t half = (x >> (16 * ((lane >> 2) & 1))) & 0xFFFFu;
+      if ((lane & 3) == 0 && (c >> 4) < count && (pg[v] >> 1) < a.words_stride)
+        ((unsigned short*)bm)[pg[v]] = (unsigned short)half;
+    } else {                                      // slots are token positions: one word per 8 lanes
+      x |= (uint32_t)tw_dpp_i<TW_DPP_HALF_MIRROR>((int)x);
+      if ((lane & 7) == 0 && c < N && (c >> 5) < a.words_stride) bm[c >> 5] = x;
+    }
   }
   uint32_t cnt = tw_wave_scan_u32(__popc(mask));
   __shared__ uint32_t wc[16];
@@ -397,7 +401,7 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
   a.scores = (const float*)(base + L.scores); a.sel_pages = sel_pages; a.sel_count = sel_count; a.seq_lens = kv->seq_lens;
   a.headmax = (const uint32_t*)(base + L.headmax); a.state = (WideState*)(base + L.state);
   a.ghistM = (unsigned long long*)(base + L.ghistM); a.ghistC = (uint32_t*)(base + L.ghistC);
-  a.gtail = (unsigned long long*)(base + L.gtail); a.ulist = (uint4*)(base + L.ulist);
+  a.ulist = (uint4*)(base + L.ulist);
   a.ucount = (uint32_t*)(base + L.ucount); a.kdef = (uint32_t*)(base + L.kdef);
   a.bitmaps = (uint32_t*)(base + L.bitmaps); a.kept_count = kept_count; a.status = status;
   a.Hq = d.Hq; a.max_pages = d.max_pages; a.max_sel = max_sel; a.cand_stride = cand_stride;
@@ -405,7 +409,8 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
   const int nbh = d.batch * d.Hq;
   const dim3 wide_grid((cand_stride + W_CHUNK - 1) / W_CHUNK, nbh);
   if (!a.keep_all) {
-    // pass 0, then up to two more: a restart below the fine range and / or a 9-bit refinement
+    // pass 0 locates the 1/64-logit bucket of the threshold; two 11-bit refinements at most follow
+    // (a head stops as soon as <= 1024 scores are left; its later passes return at once)
     for (int pass = 0; pass < 3; ++pass) {
       tw_prof_before(TW_K_TOPP, s);
       hipLaunchKernelGGL(wide_hist_kernel, wide_grid, dim3(1024), 0, s, a);

@@ -50,7 +50,7 @@ extern "C" size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, i
       return align256(bh * d.max_pages * 4);
     case TW_WS_PRUNE: {
       const int bound = max_sel > 0 ? max_sel : d.max_pages;
-      return tw_prune_layout(d, bound).total;
+      return tw_prune_layout(d, bound, max_sel <= 0).total;
     }
     case TW_WS_DECODE: {
       const bool dense = union_stride <= 0;
