@@ -438,3 +438,70 @@ def test_long_sequence_fallback_paths():
     st, q = run_pipeline(w, cache)
     assert int(st.status.item()) == 0
     check_sets_and_output(w, cache, st)
+
+
+def test_empty_sequence_in_batch_and_zero_budget():
+    """A sequence of length 0 and a zero budget: nothing selected, nothing kept, zero output rows."""
+    T = _T()
+    w = synth.make_workload("empty", [300, 1, 64], budget=[64, 16, 0], p=0.9, shuffle_pool=True, seed=29)
+    cache = build_cache(w)
+    dev = cache.k_pool.device
+    cache.seq_lens[1] = 0                                          # sequence 1 is empty for this step
+    st = T.DecodeStep(cache, max_sel=8, with_kept_idx=True)
+    q = w.q.to(dev)
+    st.out.fill_(1.0)
+    st.run(q, w.budget.to(dev), w.p)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    assert st.sel_count[1].cpu().tolist() == [0] * w.num_q_heads and st.sel_count[2].cpu().tolist() == [0] * w.num_q_heads
+    assert int(st.kept_count[1:].sum()) == 0 and int(st.union_count[w.num_kv_heads:].sum()) == 0
+    assert not st.out[1:].cpu().float().numpy().any()
+    assert np.all(np.isneginf(st.lse[1:].cpu().numpy()))
+    # sequence 0 is untouched by its neighbours
+    r = oracle_seq(w, 0)
+    for h in range(w.num_q_heads):
+        assert st.sel_pages[0, h, :int(st.sel_count[0, h])].cpu().numpy().tolist() == r["pages"][h].tolist()
+        check_topp(st.kept_idx[0, h, :int(st.kept_count[0, h])].cpu().numpy(), r["s_hat"][h], r["cand"][h], w.p)
+
+
+def test_multi_step_decode_with_growing_cache():
+    """Real decode pattern: every step appends one token per sequence (crossing page boundaries),
+    advances seq_lens on the device, and runs select -> prune -> attend; the last step is checked
+    against the oracle run on the final cache."""
+    T = _T()
+    steps = 21
+    w = synth.make_workload("grow", [150, 47], budget=96, p=0.9, heavy_frac=0.05, alpha_range=(0.5, 2.5),
+                            shuffle_pool=True, seed=31)
+    dev = "cuda"
+    final = w.seq_lens.clone()
+    start_len = final - steps
+    cache = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, start_len, w.num_pool_pages, dev)
+    k, v = w.k.to(dev), w.v.to(dev)
+    zero = torch.zeros(w.batch, dtype=torch.int32, device=dev)
+    offs = torch.tensor(w.seq_offsets[:-1], dtype=torch.int32, device=dev)
+    cache.append(k, v, zero, cache.seq_lens, offs, int(start_len.max()))           # prefill
+    st = T.DecodeStep(cache, max_sel=6, with_kept_idx=True)
+    q = w.q.to(dev)
+    one = torch.ones(w.batch, dtype=torch.int32, device=dev)
+    budget = w.budget.to(dev)
+    for i in range(steps):
+        pos = cache.seq_lens.clone()
+        cache.append(k, v, pos, one, offs + pos, 1)
+        cache.seq_lens += 1                                                          # the caller advances the lengths
+        st.run(q, budget, w.p)
+    torch.cuda.synchronize()
+    assert cache.seq_lens.cpu().tolist() == final.tolist()
+    check_cache(w, cache)
+    check_sets_and_output(w, cache, st, exact_floor=0.95)
+
+
+def test_long_row_path_is_deterministic():
+    w = synth.make_workload("det_full", [9000], num_q_heads=8, num_kv_heads=2, p=0.9, heavy_frac=0.01,
+                            alpha_cycle=[0.0, 0.5, 2.0, 6.0], full_selector=True, seed=37)
+    cache = build_cache(w)
+    a, q = run_pipeline(w, cache)
+    b, _ = run_pipeline(w, cache)
+    for name in ("kept_count", "kept_idx", "union_count", "union_idx", "out"):
+        x, y = getattr(a, name), getattr(b, name)
+        assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
+                           y.view(torch.int16) if y.dtype == torch.bfloat16 else y), name
