@@ -211,7 +211,9 @@ int twilight_abi_version(void);
 
 /*
  * Per-kernel timing with HIP events recorded on the launch stream, for
- * benchmarks.  mode 0 = off (default), 1 = bracket every kernel.  While on,
+ * benchmarks.  mode 0 = off (default), 1 = bracket every kernel, 2 = bracket
+ * only the kernel id given to twilight_prof_select (two events per step
+ * instead of two per kernel, so the step time is hardly disturbed).  While on,
  * each launch adds one record {kernel id, start event, stop event} (at most
  * TW_PROF_MAX_RECORDS between two collects; further launches are not timed).
  * twilight_prof_collect synchronises the events, writes up to `cap` records
@@ -229,6 +231,7 @@ int twilight_abi_version(void);
 #define TW_K_COMBINE 7
 #define TW_K_COUNT 8
 int twilight_prof_enable(int mode);
+int twilight_prof_select(int kernel_id);
 int twilight_prof_collect(int32_t* kernel_ids /*host*/, float* ms /*host*/, int32_t cap);
 const char* twilight_kernel_name(int kernel_id);
 

@@ -55,11 +55,12 @@ def lib():
     L.twilight_strerror.restype = ctypes.c_char_p
     L.twilight_abi_version.restype = ctypes.c_int
     L.twilight_prof_enable.argtypes = [ctypes.c_int]
+    L.twilight_prof_select.argtypes = [ctypes.c_int]
     L.twilight_prof_collect.argtypes = [_vp, _vp, _i32]
     L.twilight_kernel_name.argtypes = [ctypes.c_int]
     L.twilight_kernel_name.restype = ctypes.c_char_p
     for f in ("twilight_kquant_append", "twilight_select_pages", "twilight_int4_score", "twilight_topp_prune",
-              "twilight_sparse_decode", "twilight_prof_enable", "twilight_prof_collect"):
+              "twilight_sparse_decode", "twilight_prof_enable", "twilight_prof_select", "twilight_prof_collect"):
         getattr(L, f).restype = ctypes.c_int
     _lib = L
     return L
@@ -130,6 +131,10 @@ def twilight_sparse_decode(kv, q, union_count, union_idx, union_stride, out, lse
 
 def twilight_prof_enable(mode):
     _check(lib().twilight_prof_enable(int(mode)))
+
+
+def twilight_prof_select(kernel_name):
+    _check(lib().twilight_prof_select(KERNEL_NAMES.index(kernel_name)))
 
 
 def twilight_prof_collect(cap=65536):

@@ -90,8 +90,15 @@ ProfRec g_rec[TW_PROF_MAX_RECORDS];
 int g_created = 0;   // events exist for records [0, g_created)
 }  // namespace
 
+int g_only = -1;     // mode 2: the one kernel id that is timed
+
+extern "C" int twilight_prof_select(int kernel_id) {
+  g_only = kernel_id;
+  return TW_OK;
+}
+
 extern "C" int twilight_prof_enable(int mode) {
-  g_mode = mode ? 1 : 0;
+  g_mode = mode < 0 || mode > 2 ? 1 : mode;
   g_n = 0;
   g_open = false;
   return TW_OK;
@@ -100,6 +107,7 @@ extern "C" int twilight_prof_enable(int mode) {
 void tw_prof_before(int kernel_id, hipStream_t s) {
   g_open = false;
   if (!g_mode || g_n >= TW_PROF_MAX_RECORDS) return;
+  if (g_mode == 2 && kernel_id != g_only) return;
   if (g_n >= g_created) {
     if (hipEventCreate(&g_rec[g_n].e0) != hipSuccess) return;
     if (hipEventCreate(&g_rec[g_n].e1) != hipSuccess) return;
