@@ -30,7 +30,10 @@ PAPER_CONTEXT = {"quest_twi_vs_fa2_attention_speedup": 15.8, "quest_twi_vs_quest
                  "hardware": "1x NVIDIA A100", "source": "Section 5.2"}
 
 
-def build_state(cfg_idx, scale, seed, batch):
+def build_state(cfg_idx, scale, seed, batch, layers):
+    """`layers` independent copies of the layer's cache (same contents, different memory).  Successive steps
+    rotate over them, as the layers of a model do, so that a step finds its pools in HBM and not in the
+    256 MB memory-side cache left warm by the previous step over the very same addresses."""
     import torch
     import paper_2502_02770_amd as T
     from workloads import synth
@@ -38,32 +41,39 @@ def build_state(cfg_idx, scale, seed, batch):
     w = synth.config(cfg_idx, scale=scale, seed=seed, batch=batch)
     gen_s = time.time() - t0
     dev = "cuda:0"
-    cache = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev,
-                      need_v=w.v.numel() > 0)
     t0 = time.time()
     k = w.k.to(dev)
     v = w.v.to(dev) if w.v.numel() else None
     torch.cuda.synchronize()
     h2d_s = time.time() - t0
-    # prefill: every token but the last of each sequence; the step appends the last one
     start = torch.zeros(w.batch, dtype=torch.int32, device=dev)
     offs = torch.tensor(w.seq_offsets[:-1], dtype=torch.int32, device=dev)
-    cache.append(k, v, start, cache.seq_lens - 1, offs, int(w.seq_lens.max()) - 1)
+    max_sel = None if w.full_selector else min(int(max(-(-int(b) // 16) for b in w.budget)), w.page_table.shape[1])
+    caches, steps = [], []
+    for _ in range(layers):
+        cache = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev,
+                          need_v=w.v.numel() > 0)
+        # prefill: every token but the last of each sequence; the step appends the last one
+        cache.append(k, v, start, cache.seq_lens - 1, offs, int(w.seq_lens.max()) - 1)
+        caches.append(cache)
+        steps.append(T.DecodeStep(cache, max_sel=max_sel, with_kept_idx=False, with_lse=False))
     torch.cuda.synchronize()
     last = torch.tensor([w.seq_offsets[b + 1] - 1 for b in range(w.batch)], dtype=torch.int64, device=dev)
     k_last = k[last].contiguous()
     v_last = v[last].contiguous() if v is not None else None
     del k, v
     torch.cuda.empty_cache()
-    max_sel = None if w.full_selector else min(int(max(-(-int(b) // 16) for b in w.budget)), cache.max_pages)
-    st = T.DecodeStep(cache, max_sel=max_sel, with_kept_idx=False, with_lse=False)
     q = w.q.to(dev)
     budget = w.budget.to(dev)
     one = torch.ones(w.batch, dtype=torch.int32, device=dev)
-    pos = (cache.seq_lens - 1).contiguous()
+    pos = (caches[0].seq_lens - 1).contiguous()
     rows = torch.arange(w.batch, dtype=torch.int32, device=dev)
+    turn = [0]
 
     def step():
+        i = turn[0] % layers
+        turn[0] += 1
+        cache, st = caches[i], steps[i]
         cache.append(k_last, v_last, pos, one, rows, 1)
         if not st.full:
             st.select(q, budget)
@@ -71,7 +81,12 @@ def build_state(cfg_idx, scale, seed, batch):
         if v_last is not None:
             st.attend(q)
 
-    return w, cache, st, q, step, dict(gen_s=gen_s, h2d_s=h2d_s)
+    def dense():
+        i = turn[0] % layers
+        turn[0] += 1
+        steps[i].dense(q)
+
+    return w, caches[0], steps[0], q, step, dense, dict(gen_s=gen_s, h2d_s=h2d_s)
 
 
 def algorithmic_bytes(w, cache, st):
@@ -133,6 +148,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=4,
+                    help="independent copies of the cache that successive steps rotate over (1 = same memory every step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--calib-copy", action="store_true",
@@ -146,7 +163,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    w, cache, st, q, step, setup = build_state(a.config, a.scale, a.seed, a.batch)
+    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers))
     if a.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
@@ -208,7 +225,7 @@ def main():
     if w.v.numel():
         T.twilight_prof_enable(1)
         for _ in range(max(3, a.steps // 10)):
-            st.dense(q)
+            dense()
         torch.cuda.synchronize()
         d = [ms for name, ms in T.twilight_prof_collect() if name == "sparse_decode"]
         T.twilight_prof_enable(0)
@@ -240,7 +257,7 @@ def main():
                                   int(w.seq_lens[0]) if len(set(w.seq_lens.tolist())) == 1 else "ragged",
                                   int(w.budget[0]) if len(set(w.budget.tolist())) == 1 else "n/8", w.p,
                                   "" if a.scale == 1.0 else " (scale %g)" % a.scale),
-                   "config_index": a.config, "seed": a.seed},
+                   "config_index": a.config, "seed": a.seed, "layers_rotated": max(1, a.layers)},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "us_per_layer_events_off": ms_plain * 1e3,

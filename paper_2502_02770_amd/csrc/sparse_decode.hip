@@ -383,11 +383,31 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
   }
 }
 
+// The grid is persistent (a workgroup strides over the items), so it must not exceed what is
+// resident at once: workgroups that wait for a slot would start their share only after an
+// earlier one has finished all of its own.
+template <int G, int WPS>
+int decode_blocks_per_cu(size_t lds) {
+  static int occ = 0;
+  static size_t occ_lds = 0;
+  if (occ == 0 || occ_lds != lds) {
+    int n = 0;
+    occ_lds = lds;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, sparse_decode_kernel<G, WPS>, 256, lds) != hipSuccess || n < 1) n = 1;
+    occ = n > 4 ? 4 : n;
+  }
+  return occ;
+}
+
 template <int G>
-void launch_decode(const DecodeArgs& a, int grid, size_t lds, hipStream_t s) {
+void launch_decode(const DecodeArgs& a, long long max_items, size_t lds, hipStream_t s) {
   static const bool cap = getenv("TW_DECODE_CAP") != nullptr;     // tuning switch: cap registers for 4 waves per SIMD
-  if (cap && G <= 4) hipLaunchKernelGGL((sparse_decode_kernel<G, 4>), dim3(grid), dim3(256), lds, s, a);
-  else               hipLaunchKernelGGL((sparse_decode_kernel<G, 1>), dim3(grid), dim3(256), lds, s, a);
+  const bool capped = cap && G <= 4;
+  long long grid = (long long)tw_num_cus() * (capped ? decode_blocks_per_cu<G, 4>(lds) : decode_blocks_per_cu<G, 1>(lds));
+  if (grid > max_items) grid = max_items;
+  if (grid < 1) grid = 1;
+  if (capped) hipLaunchKernelGGL((sparse_decode_kernel<G, 4>), dim3((unsigned)grid), dim3(256), lds, s, a);
+  else        hipLaunchKernelGGL((sparse_decode_kernel<G, 1>), dim3((unsigned)grid), dim3(256), lds, s, a);
 }
 
 }  // namespace
@@ -428,16 +448,13 @@ extern "C" int twilight_sparse_decode(const twilight_kv_t* kv, const void* q, co
   a.ws_acc = (float4*)((char*)ws + prefix_bytes + ml_bytes);
   a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.union_stride = union_stride;
   a.NG = NG; a.chunk = tw_decode_chunk(dense); a.pool_pages = d.pool_pages;
-  long long grid = (long long)tw_num_cus() * 4;
-  if (grid > max_items) grid = max_items;
-  if (grid < 1) grid = 1;
   const size_t lds = (size_t)(NG + 1) * 4;
   tw_prof_before(TW_K_DECODE, s);
   switch (d.G) {
-    case 1: launch_decode<1>(a, (int)grid, lds, s); break;
-    case 2: launch_decode<2>(a, (int)grid, lds, s); break;
-    case 4: launch_decode<4>(a, (int)grid, lds, s); break;
-    default: launch_decode<8>(a, (int)grid, lds, s); break;
+    case 1: launch_decode<1>(a, max_items, lds, s); break;
+    case 2: launch_decode<2>(a, max_items, lds, s); break;
+    case 4: launch_decode<4>(a, max_items, lds, s); break;
+    default: launch_decode<8>(a, max_items, lds, s); break;
   }
   if (int e = tw_prof_after(s)) return e;
 

@@ -11,6 +11,9 @@ constexpr uint32_t HP_NONE = 0xFFFFFFFFu;      // rank of a score that takes no 
 // Words that many workgroups update with atomics (head maxima, counters) sit 128 bytes apart:
 // atomics to one cache line are served one after the other, whatever word they address.
 constexpr int TW_CTR = 32;                     // stride in 32-bit words
+// The long-row path's per-head maximum is folded by every scoring workgroup: spread over this
+// many words per head (workgroup x folds into word x % HM_SLOTS); readers take the max of them.
+constexpr int HM_SLOTS = 32;
 
 // Workspace of twilight_topp_prune (byte offsets).  Both paths use scores,
 // headmax, bitmaps, arrive; the rest belongs to the long-row path.

@@ -31,10 +31,40 @@ struct ScoreArgs {
   float* scores;              // [b][Hq][cand_stride]
   int32_t* dots;              // [b][Hq][cand_stride][4] or nullptr
   uint32_t* arrive;           // [b][Hkv] arrival counters of the top-p kernel that follows, or nullptr
-  uint32_t* headmax;          // [b][Hq] key of each head's largest score (atomicMax), or nullptr
+  uint32_t* headmax;          // [b][Hq][HM_SLOTS] keys whose maximum is the head's largest score (atomicMax), or nullptr
   int Hq, Hkv, max_pages, max_sel, cand_stride, pw;   // pw: pages per wave (<= 64)
   long long pool_pages;
 };
+
+// q of NH consecutive heads -> int8 (symmetric per head: sq = max|q| * (1/127), round half even),
+// 4 values per word, and c = sq / sqrt(128) per head.  Called by all 256 threads of the block.
+template <int NH>
+__device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32], float* red, float* c_s) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#pragma unroll 1
+  for (int h = 0; h < NH; ++h) {
+    float v = 0.f;
+    if (tid < 128) v = __uint_as_float((uint32_t)q[h * 128 + tid] << 16);
+    float av = fabsf(v);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) av = fmaxf(av, __shfl_xor(av, o, 64));
+    if (lane == 0) red[wave] = av;
+    __syncthreads();
+    const float amax = fmaxf(red[0], red[1]);
+    const float sq = __fmul_rn(amax, kInv127);
+    if (tid < 128) {
+      int qi = 0;
+      if (sq > 0.f) {
+        float t = rintf(__fdiv_rn(v, sq));
+        t = fminf(fmaxf(t, -127.f), 127.f);
+        qi = (int)t;
+      }
+      ((int8_t*)qi_s[h])[tid] = (int8_t)qi;
+    }
+    if (tid == 0) c_s[h] = __fmul_rn(sq, kRsqrtD);
+    __syncthreads();
+  }
+}
 
 // NH = heads scored per loaded page: 1 with per-head page lists, G when every
 // page is a candidate (the G heads of a KV head then share each load).
@@ -57,29 +87,7 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   __shared__ int qi_s[NH][32];
   __shared__ float red[4];
   __shared__ float c_s[NH];
-#pragma unroll 1
-  for (int h = 0; h < NH; ++h) {
-    float v = 0.f;
-    if (tid < 128) v = __uint_as_float((uint32_t)a.q[((long long)(b * a.Hq + h0 + h)) * 128 + tid] << 16);
-    float av = fabsf(v);
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) av = fmaxf(av, __shfl_xor(av, o, 64));
-    if (lane == 0) red[wave] = av;
-    __syncthreads();
-    const float amax = fmaxf(red[0], red[1]);
-    const float sq = __fmul_rn(amax, kInv127);
-    if (tid < 128) {
-      int qi = 0;
-      if (sq > 0.f) {
-        float t = rintf(__fdiv_rn(v, sq));
-        t = fminf(fmaxf(t, -127.f), 127.f);
-        qi = (int)t;
-      }
-      ((int8_t*)qi_s[h])[tid] = (int8_t)qi;
-    }
-    if (tid == 0) c_s[h] = __fmul_rn(sq, kRsqrtD);
-    __syncthreads();
-  }
+  tw_quantize_q<NH>(a.q + ((long long)(b * a.Hq + h0)) * 128, qi_s, red, c_s);
   const int j = lane & 3;                       // this lane's group of 32 dims
   int qw[NH][8];
   float qsf[NH], cc[NH];
@@ -165,7 +173,152 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
     __syncthreads();
     if (tid < NH) {
       const float mx = fmaxf(fmaxf(hm_s[0][tid], hm_s[1][tid]), fmaxf(hm_s[2][tid], hm_s[3][tid]));
-      if (mx > -__builtin_inff()) atomicMax(a.headmax + (long long)(b * a.Hq + h0 + tid) * TW_CTR, tw_float_key(mx));
+      if (mx > -__builtin_inff())
+        atomicMax(a.headmax + ((long long)(b * a.Hq + h0 + tid) * HM_SLOTS + (blockIdx.x & (HM_SLOTS - 1))) * TW_CTR, tw_float_key(mx));
+    }
+  }
+}
+
+// ------------------------------------------------------------------ int4_score on the matrix cores
+// Every page a candidate and 4 or 8 query heads per KV head: per page the scores are a small dense
+// contraction, [heads x 128 dims] . [128 dims x 16 tokens], which on the vector ALU costs 8 dot4
+// per lane and head and 64 registers of query words (8 heads: 130 VGPRs, 3 waves per SIMD, too few
+// pages in flight to keep HBM busy).  Here v_mfma_i32_16x16x32_i8 does the integer part.  The four
+// groups of 32 dims have their own (scale, zero), so their dot products must stay apart: row
+// 4*h + j of the A operand carries head h's query words of group j and zeros elsewhere, and lane
+// (k-block j', token t) supplies group j' of token t as B; four MFMAs (one per 8-dim word of the
+// groups) accumulate I_j[h][t].  The result lands with lane (h, t) holding I_0..I_3: scale/zero,
+// the fixed-order sum and the store need no cross-lane step.  Same integers and the same fp32
+// operations as the vector kernel, so the scores are bit-identical.
+typedef int tw_i32x4 __attribute__((ext_vector_type(4)));
+
+template <int NHG, bool DOTS, int UNR>           // NHG groups of 4 heads
+__global__ __launch_bounds__(256) void int4_score_mfma_kernel(ScoreArgs a) {
+  constexpr int NH = 4 * NHG;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.y / a.Hkv, g = blockIdx.y % a.Hkv, h0 = g * NH;
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  const int count = P;
+  const int wg_first = blockIdx.x * 4 * a.pw;
+  if (a.arrive && blockIdx.x == 0 && tid == 0) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
+  if (wg_first >= count) return;
+
+  __shared__ int qi_s[NH][32];
+  __shared__ float red[4];
+  __shared__ float c_s[NH];
+  tw_quantize_q<NH>(a.q + ((long long)(b * a.Hq + h0)) * 128, qi_s, red, c_s);
+
+  const int kb = lane >> 4, t = lane & 15;       // B operand / result: k-block (= group of dims) or head, token
+  // A operand: row m = lane & 15 = 4 * head + group; this lane's k-block only meets its own group
+  long aw[NHG][4];
+  {
+    const int hl = t >> 2, j = t & 3;
+#pragma unroll
+    for (int hg = 0; hg < NHG; ++hg)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        uint32_t lo = (uint32_t)qi_s[hg * 4 + hl][8 * j + 2 * w], hi = (uint32_t)qi_s[hg * 4 + hl][8 * j + 2 * w + 1];
+        if (kb != j) { lo = 0; hi = 0; }
+        aw[hg][w] = (long)(((unsigned long long)hi << 32) | lo);
+      }
+  }
+  // result side: this lane's head is kb (+ 4 per head group); sums of its query words per group
+  float qsf[NHG][4], cc[NHG];
+#pragma unroll
+  for (int hg = 0; hg < NHG; ++hg) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int qs = 0;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) qs = __builtin_amdgcn_sdot4(qi_s[hg * 4 + kb][8 * j + k], 0x01010101, qs, false);
+      qsf[hg][j] = (float)qs;
+    }
+    cc[hg] = c_s[hg * 4 + kb];
+  }
+
+  // ---- this wave's pages: lane k holds the k-th one (logical id, pool id)
+  const int first = wg_first + wave * a.pw;
+  int my_lp = -1, my_pool = -1;
+  if (lane < a.pw && first + lane < count) {
+    my_lp = first + lane;
+    const int pp = a.page_table[(long long)b * a.max_pages + my_lp];
+    if (pp >= 0 && pp < a.pool_pages) my_pool = pp;
+  }
+  int npages = count - first;
+  if (npages > a.pw) npages = a.pw;
+
+  float hm[NHG];
+#pragma unroll
+  for (int hg = 0; hg < NHG; ++hg) hm[hg] = -__builtin_inff();
+#pragma unroll 1
+  for (int k0 = 0; k0 < npages; k0 += UNR) {
+    uint4 nib[UNR], mt[UNR];
+    int lpv[UNR];
+    bool okv[UNR];
+#pragma unroll
+    for (int kk = 0; kk < UNR; ++kk) {           // unconditional loads (an absent page reads pool page 0, masked below)
+      const int k = k0 + kk;
+      lpv[kk] = __builtin_amdgcn_readlane(my_lp, k & 63);
+      const int pool = k < npages ? __builtin_amdgcn_readlane(my_pool, k & 63) : -1;
+      okv[kk] = pool >= 0;
+      const long long blk = ((long long)(pool >= 0 ? pool : 0) * a.Hkv + g) * 64;
+      nib[kk] = a.kq_pool[blk + t * 4 + kb];                   // group kb of token t: 32 codes
+      mt[kk] = ((const uint4*)a.kq_meta)[(blk >> 2) + t];      // token t: 4 x (scale | zero << 16)
+    }
+#pragma unroll
+    for (int kk = 0; kk < UNR; ++kk) {
+      const int k = k0 + kk;
+      if (k < npages) {                          // wave-uniform
+        const uint32_t wv[4] = {nib[kk].x, nib[kk].y, nib[kk].z, nib[kk].w};
+        long bw[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+          bw[w] = (long)(((unsigned long long)((wv[w] >> 4) & 0x0F0F0F0Fu) << 32) | (wv[w] & 0x0F0F0F0Fu));
+        const uint32_t mv[4] = {mt[kk].x, mt[kk].y, mt[kk].z, mt[kk].w};
+        const int tok = lpv[kk] * TW_PAGE + t;
+        const bool valid = okv[kk] && tok < n;
+        const long long slot = (long long)(first + k) * TW_PAGE + t;
+#pragma unroll
+        for (int hg = 0; hg < NHG; ++hg) {
+          tw_i32x4 c = {0, 0, 0, 0};
+#pragma unroll
+          for (int w = 0; w < 4; ++w) c = __builtin_amdgcn_mfma_i32_16x16x32_i8(aw[hg][w], bw[w], c, 0, 0, 0);
+          float T[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float sc = __half2float(__ushort_as_half((unsigned short)(mv[j] & 0xFFFFu)));
+            const float ze = __half2float(__ushort_as_half((unsigned short)(mv[j] >> 16)));
+            T[j] = __fadd_rn(__fmul_rn(sc, (float)c[j]), __fmul_rn(ze, qsf[hg][j]));
+          }
+          const float ssum = __fadd_rn(__fadd_rn(T[0], T[1]), __fadd_rn(T[2], T[3]));
+          const float s = valid ? __fmul_rn(ssum, cc[hg]) : -__builtin_inff();
+          hm[hg] = fmaxf(hm[hg], s);
+          const long long row = ((long long)(b * a.Hq + h0 + hg * 4 + kb)) * a.cand_stride;
+          a.scores[row + slot] = s;
+          if (DOTS) ((tw_i32x4*)a.dots)[row + slot] = valid ? c : tw_i32x4{0, 0, 0, 0};
+        }
+      }
+    }
+  }
+  if (a.headmax) {
+    // one atomic per head and workgroup: 16-lane rows (one head each), then the waves through LDS
+    __shared__ float hm_s[4][NH];
+#pragma unroll
+    for (int hg = 0; hg < NHG; ++hg) {
+      float mx = hm[hg];
+      mx = fmaxf(mx, tw_dpp_f<TW_DPP_XOR1>(mx));
+      mx = fmaxf(mx, tw_dpp_f<TW_DPP_XOR2>(mx));
+      mx = fmaxf(mx, tw_dpp_f<TW_DPP_HALF_MIRROR>(mx));
+      mx = fmaxf(mx, tw_dpp_f<TW_DPP_MIRROR>(mx));
+      if (t == 0) hm_s[wave][hg * 4 + kb] = mx;
+    }
+    __syncthreads();
+    if (tid < NH) {
+      const float mx = fmaxf(fmaxf(hm_s[0][tid], hm_s[1][tid]), fmaxf(hm_s[2][tid], hm_s[3][tid]));
+      if (mx > -__builtin_inff())
+        atomicMax(a.headmax + ((long long)(b * a.Hq + h0 + tid) * HM_SLOTS + (blockIdx.x & (HM_SLOTS - 1))) * TW_CTR, tw_float_key(mx));
     }
   }
 }
@@ -524,8 +677,18 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
   a.pw = pages_per_wave((long long)bound * d.batch * (full ? d.Hkv : d.Hq), bound);
   dim3 grid((bound + 4 * a.pw - 1) / (4 * a.pw), d.batch * (full ? d.Hkv : d.Hq));
   tw_prof_before(TW_K_INT4_SCORE, s);
+  static const bool valu_only = getenv("TW_INT4_VALU") != nullptr;   // tuning switch: vector-ALU kernel for every G
   if (!full) launch_score<1, false>(a, grid, dots != nullptr, s);
-  else switch (d.G) {
+  else if (d.G >= 4 && !valu_only) {               // matrix-core kernel: 4 or 8 heads share every page
+    // 8 pages in flight per wave (the kernel needs few registers, so 4 to 7 waves per SIMD stay resident)
+    if (d.G == 4) {
+      if (dots) hipLaunchKernelGGL((int4_score_mfma_kernel<1, true, 4>), grid, dim3(256), 0, s, a);
+      else      hipLaunchKernelGGL((int4_score_mfma_kernel<1, false, 8>), grid, dim3(256), 0, s, a);
+    } else {
+      if (dots) hipLaunchKernelGGL((int4_score_mfma_kernel<2, true, 4>), grid, dim3(256), 0, s, a);
+      else      hipLaunchKernelGGL((int4_score_mfma_kernel<2, false, 8>), grid, dim3(256), 0, s, a);
+    }
+  } else switch (d.G) {
     case 1: launch_score<1, true>(a, grid, dots != nullptr, s); break;
     case 2: launch_score<2, true>(a, grid, dots != nullptr, s); break;
     case 4: launch_score<4, true>(a, grid, dots != nullptr, s); break;
@@ -556,10 +719,11 @@ PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full) {
   L.words_stride = (d.max_pages + 1) / 2;
   size_t o = 0;
   L.scores = o;  o += al(bh * (size_t)bound_pages * TW_PAGE * 4);
-  L.headmax = o; o += al(bh * TW_CTR * 4);               // (the long-row path clears from here ...)
+  const bool head = tw_prune_uses_head_kernel(d, full, bound_pages);
+  L.headmax = o; o += head ? 256 : al(bh * HM_SLOTS * TW_CTR * 4);   // (the long-row path clears from here ...)
   L.arrive = o;  o += al((size_t)d.batch * d.Hkv * TW_CTR * 4);
   L.bitmaps = o; o += al(bh * (size_t)L.words_stride * 4);
-  if (tw_prune_uses_head_kernel(d, full, bound_pages)) {     // the long-row buffers are not needed
+  if (head) {                                                // the long-row buffers are not needed
     L.ghistM = L.ghistC = L.gtail = L.ucount = L.kdef = L.state = L.ulist = o;
     L.total = o;
     return L;
@@ -570,7 +734,7 @@ PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full) {
   L.ucount = o;  o += al(bh * TW_CTR * 4);
   L.kdef = o;    o += al(bh * TW_CTR * 4);
   L.state = o;   o += al(bh * 48);                       // (... up to here)
-  L.ulist = o;   o += al(bh * 1024 * 16);
+  L.ulist = o;   o += al(bh * 4096 * 8);
   L.total = o;
   return L;
 }

@@ -9,10 +9,12 @@
 //   wide_hist     one pass over the scores: LDS histogram of the current rank
 //                 interval per workgroup, flushed to the head's global one
 //   wide_decide   one wave per head scans the 2048 buckets and narrows the
-//                 interval (or finishes when <= 1024 scores are left in it)
+//                 interval (or finishes when <= 4096 scores are left in it,
+//                 which one pass achieves on rows of a million smooth scores)
 //   wide_emit     second pass: kept for sure -> bitmap, undecided -> a short
 //                 per-head list
-//   wide_resolve  exact finish on the undecided list, sets their bits
+//   wide_resolve  finish on the undecided list inside one workgroup (narrowing
+//                 in LDS, then exact on the scores' own bits), sets their bits
 //   bitmap_list   bitmap(s) -> ascending index list (per-head kept list, and
 //                 the union of a KV head's query heads)
 // All sums are 64-bit fixed point and all atomics are integer adds / maxima,
@@ -22,13 +24,13 @@
 namespace {
 
 struct WideState {           // per head
-  uint32_t rlo, shift, pop, flags, pass, pad;
+  uint32_t rlo, shift, pop, flags, pass, mk;    // mk: key of the head's largest score (0 = none), set by the first decide
   unsigned long long A, target;
 };
 constexpr uint32_t WF_DONE = 1, WF_EMPTY = 4, WF_TIER_ALL = 8;
 constexpr int W_SLOTS = 32;                    // candidate slots per thread
 constexpr int W_CHUNK = 1024 * W_SLOTS;        // per workgroup
-constexpr int W_CAP = 1024;                    // undecided scores resolved exactly
+constexpr int W_CAP = 4096;                    // undecided scores that the resolve kernel takes
 constexpr int W_NB = 2048;                     // buckets per pass: pass 0 covers every rank (32 logits at 1/64)
 constexpr int W_BITS = 11;
 
@@ -37,11 +39,11 @@ struct WideArgs {
   const int32_t* sel_pages;   // or nullptr
   const int32_t* sel_count;
   const int32_t* seq_lens;
-  const uint32_t* headmax;    // key of the largest score per head, 0 = no valid score
+  const uint32_t* headmax;    // [bh][HM_SLOTS] (padded): max = key of the head's largest score, 0 = no valid score
   WideState* state;
   unsigned long long* ghistM;
   uint32_t* ghistC;
-  uint4* ulist;               // [bh][W_CAP] {key, token, mass lo, mass hi}
+  uint2* ulist;               // [bh][W_CAP] {key, token}
   uint32_t* ucount;
   uint32_t* kdef;
   uint32_t* bitmaps;
@@ -57,9 +59,15 @@ __global__ __launch_bounds__(256) void wide_init_kernel(uint4* zero_base, size_t
   if (i < n16) zero_base[i] = make_uint4(0, 0, 0, 0);
   if (i < (size_t)nbh) {
     WideState s;
-    s.rlo = 0; s.shift = 16; s.pop = 0; s.flags = 0; s.pass = 0; s.pad = 0; s.A = 0; s.target = 0;
+    s.rlo = 0; s.shift = 16; s.pop = 0; s.flags = 0; s.pass = 0; s.mk = 0; s.A = 0; s.target = 0;
     st[i] = s;
   }
+}
+
+// the head's largest score: maximum over the words the scoring workgroups folded into
+__device__ __forceinline__ uint32_t wide_headmax(const uint32_t* headmax, int bh, int lane) {
+  const uint32_t v = lane < HM_SLOTS ? headmax[((long long)bh * HM_SLOTS + lane) * TW_CTR] : 0u;
+  return tw_wave_max_u32(v);
 }
 
 __device__ __forceinline__ int wide_count(const WideArgs& a, int b, int bh) {
@@ -90,10 +98,11 @@ __device__ __forceinline__ void wide_load(const float* row, int chunk0, int tid,
 __global__ __launch_bounds__(1024) void wide_hist_kernel(WideArgs a) {
   const int bh = blockIdx.y, b = bh / a.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const WideState st = a.state[bh];
-  const uint32_t mk = a.headmax[(long long)bh * TW_CTR];
-  if ((st.flags & WF_DONE) || mk == 0) return;
+  if (st.flags & WF_DONE) return;
   const int N = wide_count(a, b, bh) * TW_PAGE;
   if ((long long)blockIdx.x * W_CHUNK >= N) return;
+  const uint32_t mk = wide_headmax(a.headmax, bh, lane);
+  if (mk == 0) return;
   const float m = tw_key_to_float(mk);
   const int chunk0 = blockIdx.x * W_CHUNK;
 
@@ -128,7 +137,8 @@ __global__ __launch_bounds__(64) void wide_decide_kernel(WideArgs a) {
   const int bh = blockIdx.x, lane = threadIdx.x;
   WideState st = a.state[bh];
   if (st.flags & WF_DONE) return;
-  if (a.headmax[(long long)bh * TW_CTR] == 0) { if (lane == 0) { st.flags = WF_DONE | WF_EMPTY; a.state[bh] = st; } return; }
+  st.mk = wide_headmax(a.headmax, bh, lane);
+  if (st.mk == 0) { if (lane == 0) { st.flags = WF_DONE | WF_EMPTY; a.state[bh] = st; } return; }
   unsigned long long* gm = a.ghistM + (long long)bh * W_NB;
   uint32_t* gc = a.ghistC + (long long)bh * W_NB;
   unsigned long long mb[BPL], mine = 0;
@@ -175,12 +185,11 @@ __global__ __launch_bounds__(64) void wide_decide_kernel(WideArgs a) {
 __global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
   const int bh = blockIdx.y, b = bh / a.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const WideState st = a.state[bh];
-  const uint32_t mk = a.headmax[(long long)bh * TW_CTR];
-  if (mk == 0) return;                            // no valid score: bitmap stays empty
+  if (!a.keep_all && st.mk == 0) return;          // no valid score: bitmap stays empty
   const int count = wide_count(a, b, bh);
   const int N = count * TW_PAGE;
   if ((long long)blockIdx.x * W_CHUNK >= N) return;
-  const float m = tw_key_to_float(mk);
+  const float m = tw_key_to_float(st.mk);
   const int chunk0 = blockIdx.x * W_CHUNK;
   // a search that did not finish in the passes given keeps its whole interval
   const bool tier = (st.flags & WF_TIER_ALL) || !(st.flags & WF_DONE);
@@ -196,36 +205,42 @@ __global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
       pg[v] = a.sel_pages[(long long)bh * a.max_sel + (pi < a.max_sel ? pi : a.max_sel - 1)];
     }
   }
-  uint32_t mask = 0;                              // bit e: slot e of this thread is kept
+  uint32_t mask = 0, umask = 0;                   // bit e: slot e of this thread is kept / undecided
 #pragma unroll
   for (int e = 0; e < W_SLOTS; ++e) {
     const bool valid = s[e] > -__builtin_inff();
-    bool keep;
+    bool keep, und = false;
     if (a.keep_all) keep = valid;
     else {
       const uint32_t r = hp_rank_only(m, s[e]);
       const bool part = valid && r != HP_NONE;
       keep = part && (r < st.rlo || (tier && r <= rhi));
-      const bool und = part && !tier && r >= st.rlo && r <= rhi;
-      // undecided: onto the head's list; one atomic per wave reserves the slots of all its lanes
-      const unsigned long long ub = __ballot(und);
+      und = part && !tier && r >= st.rlo && r <= rhi;
+    }
+    mask |= (keep ? 1u : 0u) << e;
+    umask |= (und ? 1u : 0u) << e;
+  }
+  // undecided scores go onto the head's list: one atomic per wave reserves room for all its lanes
+  {
+    const uint32_t mine = __popc(umask);
+    const uint32_t incl = tw_wave_scan_u32(mine);
+    const uint32_t wtotal = __shfl(incl, 63, 64);
+    if (wtotal) {                                   // wave-uniform
       uint32_t ubase = 0;
-      if (ub) {
-        const int leader = __ffsll((long long)ub) - 1;
-        if (lane == leader) ubase = atomicAdd(&a.ucount[(long long)bh * TW_CTR], (uint32_t)__popcll(ub));
-        ubase = __shfl(ubase, leader, 64);
-      }
-      if (und) {
-        const uint32_t at = ubase + (uint32_t)__popcll(ub & ((1ull << lane) - 1ull));
-        if (at < (uint32_t)W_CAP) {
-          const unsigned long long w = hp_fix(hp_numer(m, s[e]));
-          const int slot = wide_slot(chunk0, e >> 2, tid) + (e & 3);
-          const int tok = a.sel_pages ? pg[e >> 2] * TW_PAGE + (slot & 15) : slot;
-          a.ulist[(long long)bh * W_CAP + at] = make_uint4(tw_float_key(s[e]), (uint32_t)tok, (uint32_t)w, (uint32_t)(w >> 32));
+      if (lane == 63) ubase = atomicAdd(&a.ucount[(long long)bh * TW_CTR], wtotal);
+      uint32_t at = __shfl(ubase, 63, 64) + incl - mine;
+#pragma unroll
+      for (int e = 0; e < W_SLOTS; ++e) {
+        if ((umask >> e) & 1u) {
+          if (at < (uint32_t)W_CAP) {
+            const int slot = wide_slot(chunk0, e >> 2, tid) + (e & 3);
+            const int tok = a.sel_pages ? pg[e >> 2] * TW_PAGE + (slot & 15) : slot;
+            a.ulist[(long long)bh * W_CAP + at] = make_uint2(tw_float_key(s[e]), (uint32_t)tok);
+          }
+          ++at;
         }
       }
     }
-    mask |= (keep ? 1u : 0u) << e;
   }
   // bitmap: the 4 bits of a group join those of the neighbouring lanes (4 lanes = one page of 16
   // slots, 8 lanes = one word of 32 slots) through DPP, then one lane stores
@@ -256,40 +271,126 @@ __global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
   }
 }
 
+// One workgroup per head.  The undecided scores (rank inside the interval that the passes over
+// the whole row ended with) sit in registers, 4 per thread; the interval is narrowed 9 bits per
+// round with a 512-bucket LDS histogram until at most 64 scores are left, and those are compared
+// exactly on the scores' own bits: T = the largest key whose upper set reaches the target mass.
+constexpr int WR_EPT = W_CAP / 1024;
+constexpr int WR_CAP = 64;
 __global__ __launch_bounds__(1024) void wide_resolve_kernel(WideArgs a) {
   const int bh = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const WideState st = a.state[bh];
-  __shared__ uint32_t keys[W_CAP];
-  __shared__ unsigned long long mass[W_CAP];
+  __shared__ unsigned long long histM[HP_NB];
+  __shared__ uint32_t histC[HP_NB];
+  __shared__ unsigned long long cand_mass[WR_CAP];
+  __shared__ uint32_t cand_key[WR_CAP];
   __shared__ uint32_t red[16];
-  const bool search = !a.keep_all && a.headmax[(long long)bh * TW_CTR] != 0 && (st.flags & WF_DONE) && !(st.flags & WF_TIER_ALL);
+  __shared__ uint32_t sh_n, sh_T;
+  const bool search = !a.keep_all && st.mk != 0 && (st.flags & WF_DONE) && !(st.flags & WF_TIER_ALL);
   uint32_t cn = 0;
   if (search) { cn = a.ucount[(long long)bh * TW_CTR]; if (cn > (uint32_t)W_CAP) cn = W_CAP; }
-  uint4 mine = make_uint4(0, 0, 0, 0);
-  if (tid < (int)cn) {
-    mine = a.ulist[(long long)bh * W_CAP + tid];
-    keys[tid] = mine.x;
-    mass[tid] = (unsigned long long)mine.z | ((unsigned long long)mine.w << 32);
-  }
-  __syncthreads();
-  uint32_t best = 0;
-  if (tid < (int)cn) {
-    unsigned long long S = 0;
-#pragma unroll 8
-    for (uint32_t j = 0; j < cn; ++j) S += keys[j] >= mine.x ? mass[j] : 0ull;
-    if (st.A + S >= st.target) best = mine.x;
-  }
-  best = tw_wave_max_u32(best);
-  if (lane == 0) red[wave] = best;
-  __syncthreads();
-  uint32_t T = red[0];
+  const float m = tw_key_to_float(st.mk);
+  uint32_t key[WR_EPT], tok[WR_EPT], rk[WR_EPT];
+  float ef[WR_EPT];
 #pragma unroll
-  for (int w = 1; w < 16; ++w) T = red[w] > T ? red[w] : T;
+  for (int e = 0; e < WR_EPT; ++e) {
+    const uint32_t i = (uint32_t)(e * 1024 + tid);
+    const uint2 x = a.ulist[(long long)bh * W_CAP + (i < cn ? i : 0u)];   // cn = 0: slot 0 is inside the buffer, masked
+    key[e] = x.x; tok[e] = x.y;
+    rk[e] = i < cn ? hp_rank(m, tw_key_to_float(x.x), &ef[e]) : HP_NONE;
+  }
+  if (tid == 0) sh_n = 0;
   __syncthreads();
+  uint32_t T = 0xFFFFFFFFu;                         // nothing from the list unless a threshold is found
+  if (cn > 0) {                                     // block-uniform
+    uint32_t rlo = st.rlo, pop = cn;
+    int shift = (int)st.shift;
+    unsigned long long A = st.A;
+    const unsigned long long target = st.target;
+#pragma unroll 1
+    while (pop > (uint32_t)WR_CAP && shift > 0) {
+      const int nshift = shift >= 9 ? shift - 9 : 0;
+      const uint32_t nb = 1u << (shift - nshift);   // buckets that cover the interval
+      for (int i = tid; i < HP_NB; i += 1024) { histM[i] = 0; histC[i] = 0; }
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < WR_EPT; ++e) {
+        if (rk[e] != HP_NONE && rk[e] >= rlo) {
+          const uint32_t bk = (rk[e] - rlo) >> nshift;
+          if (bk < nb) { atomicAdd(&histM[bk], hp_fix(ef[e])); atomicAdd(&histC[bk], 1u); }
+        }
+      }
+      __syncthreads();
+      unsigned long long mb[8], mine = 0;           // every wave scans on its own: lane l owns buckets 8l .. 8l+7
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { mb[k] = histM[8 * lane + k]; mine += mb[k]; }
+      const unsigned long long incl = tw_wave_scan_u64(mine);
+      const unsigned long long before = A + incl - mine;
+      const bool hit = before < target && before + mine >= target;
+      const unsigned long long bal = __ballot(hit);
+      if (bal == 0) { pop = 0xFFFFFFFFu; shift = nshift; break; }   // unreachable: the interval holds the crossing
+      const int src = __ffsll((long long)bal) - 1;
+      unsigned long long cum = before, asel = before;
+      int bsel = 0;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        if (cum < target && cum + mb[k] >= target) { bsel = k; asel = cum; }
+        cum += mb[k];
+      }
+      const int bucket = 8 * src + __shfl(bsel, src, 64);
+      A = __shfl(asel, src, 64);
+      pop = histC[bucket];
+      rlo += (uint32_t)bucket << nshift;
+      shift = nshift;
+      __syncthreads();                              // all scans done before the histogram is cleared
+    }
+    const uint32_t rhi = rlo + (1u << shift) - 1u;
+    const bool small = pop <= (uint32_t)WR_CAP;
+    uint32_t kmin = 0xFFFFFFFFu;
+#pragma unroll
+    for (int e = 0; e < WR_EPT; ++e) {
+      if (rk[e] != HP_NONE && rk[e] >= rlo && rk[e] <= rhi) {
+        kmin = key[e] < kmin ? key[e] : kmin;
+        if (small) {
+          const uint32_t at = atomicAdd(&sh_n, 1u);
+          if (at < (uint32_t)WR_CAP) { cand_key[at] = key[e]; cand_mass[at] = hp_fix(ef[e]); }
+        }
+      }
+    }
+    if (!small) {                                   // more than WR_CAP scores of one rank: keep them all
+      kmin = ~tw_wave_max_u32(~kmin);
+      if (lane == 0) red[wave] = kmin;
+    }
+    __syncthreads();
+    if (wave == 0) {
+      if (small) {
+        const uint32_t n = sh_n < (uint32_t)WR_CAP ? sh_n : (uint32_t)WR_CAP;
+        const uint32_t kx = lane < (int)n ? cand_key[lane] : 0u;
+        unsigned long long S = 0;
+#pragma unroll 4
+        for (uint32_t j = 0; j < n; ++j) S += cand_key[j] >= kx ? cand_mass[j] : 0ull;
+        const uint32_t best = (lane < (int)n && A + S >= target) ? kx : 0u;
+        T = tw_wave_max_u32(best);
+      } else {
+        uint32_t r = red[0];
+#pragma unroll
+        for (int w = 1; w < 16; ++w) r = red[w] < r ? red[w] : r;
+        T = r;
+      }
+      if (lane == 0) sh_T = T;
+    }
+    __syncthreads();
+    T = sh_T;
+    if (T == 0) T = 0xFFFFFFFFu;                    // unreachable (the interval holds the crossing): keep none of the list
+    __syncthreads();                                // red is reused below
+  }
   uint32_t add = 0;
-  if (tid < (int)cn && mine.x >= T && (mine.y >> 5) < (uint32_t)a.words_stride) {
-    atomicOr(&a.bitmaps[(long long)bh * a.words_stride + (mine.y >> 5)], 1u << (mine.y & 31));
-    add = 1;
+#pragma unroll
+  for (int e = 0; e < WR_EPT; ++e) {
+    if (rk[e] != HP_NONE && key[e] >= T && (tok[e] >> 5) < (uint32_t)a.words_stride) {
+      atomicOr(&a.bitmaps[(long long)bh * a.words_stride + (tok[e] >> 5)], 1u << (tok[e] & 31));
+      add += 1;
+    }
   }
   add = tw_wave_scan_u32(add);
   if (lane == 63) red[wave] = add;
@@ -401,7 +502,7 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
   a.scores = (const float*)(base + L.scores); a.sel_pages = sel_pages; a.sel_count = sel_count; a.seq_lens = kv->seq_lens;
   a.headmax = (const uint32_t*)(base + L.headmax); a.state = (WideState*)(base + L.state);
   a.ghistM = (unsigned long long*)(base + L.ghistM); a.ghistC = (uint32_t*)(base + L.ghistC);
-  a.ulist = (uint4*)(base + L.ulist);
+  a.ulist = (uint2*)(base + L.ulist);
   a.ucount = (uint32_t*)(base + L.ucount); a.kdef = (uint32_t*)(base + L.kdef);
   a.bitmaps = (uint32_t*)(base + L.bitmaps); a.kept_count = kept_count; a.status = status;
   a.Hq = d.Hq; a.max_pages = d.max_pages; a.max_sel = max_sel; a.cand_stride = cand_stride;
@@ -410,7 +511,8 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
   const dim3 wide_grid((cand_stride + W_CHUNK - 1) / W_CHUNK, nbh);
   if (!a.keep_all) {
     // pass 0 locates the 1/64-logit bucket of the threshold; two 11-bit refinements at most follow
-    // (a head stops as soon as <= 1024 scores are left; its later passes return at once)
+    // (a head stops as soon as <= 4096 scores are left, normally after pass 0; its later passes
+    //  return at once)
     for (int pass = 0; pass < 3; ++pass) {
       tw_prof_before(TW_K_TOPP, s);
       hipLaunchKernelGGL(wide_hist_kernel, wide_grid, dim3(1024), 0, s, a);
