@@ -21,8 +21,8 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch at config C2 from rocprofv3 --pmc FETCH_SIZE (x2.0, calibrated against a
 # plain copy) + WRITE_SIZE, see profiles/c2_decode_step_hbm_traffic.md.  Not measurable live.
-TRAFFIC_C2 = {"page_score": 33110 * 2048 + 2067 * 1024, "int4_score": 31057 * 2048 + 4104 * 1024,
-              "sparse_decode": 19724 * 2048 + 1282 * 1024, "topp": 2795 * 2048 + 1343 * 1024,
+TRAFFIC_C2 = {"page_score": 33111 * 2048 + 2062 * 1024, "int4_score": 20585 * 2048 + 4200 * 1024,
+              "sparse_decode": 19725 * 2048 + 1282 * 1024, "topp": 2786 * 2048 + 1343 * 1024,
               "page_select": 1080 * 2048 + 264 * 1024}
 
 # Paper context (another machine: one A100, FP16 KV, LongBench-derived prompts) - not a target.

@@ -642,9 +642,11 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
 
 // ------------------------------------------------------------------ launches
 int pages_per_wave(long long total_pages_all_rows, int count_bound) {
-  // aim for >= ~2048 waves in flight chip-wide, 4..64 pages per wave
+  // 4..64 pages per wave, at least ~8192 waves chip-wide (one per wave slot: measured at
+  // 65536 candidate pages, 8 pages per wave beat 16 by 15 %; ragged batches whose bound is far
+  // above the mean list length do best with long waves, fewer of which are empty)
   int pw = 64;
-  while (pw > 4 && total_pages_all_rows / pw < 4096) pw >>= 1;
+  while (pw > 4 && total_pages_all_rows / pw < 8192) pw >>= 1;
   while (pw > 4 && pw / 2 >= count_bound) pw >>= 1;
   return pw;
 }
@@ -675,6 +677,8 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
   const int bound = full ? d.max_pages : max_sel;
   a.cand_stride = bound * TW_PAGE;
   a.pw = pages_per_wave((long long)bound * d.batch * (full ? d.Hkv : d.Hq), bound);
+  static const int pw_env = getenv("TW_INT4_PW") ? atoi(getenv("TW_INT4_PW")) : 0;   // tuning switch
+  if (pw_env >= 4 && pw_env <= 64) a.pw = pw_env;
   dim3 grid((bound + 4 * a.pw - 1) / (4 * a.pw), d.batch * (full ? d.Hkv : d.Hq));
   tw_prof_before(TW_K_INT4_SCORE, s);
   static const bool valu_only = getenv("TW_INT4_VALU") != nullptr;   // tuning switch: vector-ALU kernel for every G
