@@ -27,12 +27,14 @@ struct ScoreArgs {
 
 template <int G>
 __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
-  const int b = blockIdx.z, g = blockIdx.y;
+  // KV head fastest in dispatch order: the 8 heads' bounds of a pool page are 4 KiB contiguous,
+  // and the workgroups that read them start next to each other
+  const int b = blockIdx.z, g = blockIdx.x;
   const int tid = threadIdx.x, seg = tid & 15, grp = tid >> 4;   // grp: 0..15 page slot in the WG
   const int n = a.seq_lens[b];
   int P = (n + TW_PAGE - 1) / TW_PAGE;
   if (P > a.max_pages) P = a.max_pages;
-  const int base = blockIdx.x * PS_PAGES_PER_WG;
+  const int base = blockIdx.y * PS_PAGES_PER_WG;
   if (base >= P) return;
 
   // q of the G heads, the 8 dims of this lane; the sign decides which corner
@@ -353,7 +355,7 @@ extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, con
   a.q = (const uint32_t*)q; a.page_minmax = (const uint4*)kv->page_minmax;
   a.page_table = kv->page_table; a.seq_lens = kv->seq_lens; a.scores = (float*)ws;
   a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.pool_pages = d.pool_pages;
-  dim3 grid((d.max_pages + PS_PAGES_PER_WG - 1) / PS_PAGES_PER_WG, d.Hkv, d.batch);
+  dim3 grid(d.Hkv, (d.max_pages + PS_PAGES_PER_WG - 1) / PS_PAGES_PER_WG, d.batch);
   tw_prof_before(TW_K_PAGE_SCORE, s);
   switch (d.G) {
     case 1: launch_score<1>(a, grid, s); break;
