@@ -106,8 +106,10 @@ def algorithmic_bytes(w, cache, st):
         ncand = int(st.sel_count.sum().item()) * 16
         out["int4_score"] = ncand * 80 + ncand * 4
     out["page_select"] = pages * Hq * 4
-    out["topp"] = ncand * 4
-    out["union"] = ncand * 4 + int(st.union_count.sum().item()) * 4
+    # register-resident top-p reads each score once; the long-row path reads the row twice
+    # (one histogram pass, one pass that writes the kept bitmap) - its launches are summed per step
+    out["topp"] = ncand * 4 * (2 if st.full or ncand / (w.batch * Hq) > 8192 else 1)
+    out["union"] = tokens * Hq // 8 + int(st.union_count.sum().item()) * 4      # long-row path: kept bitmaps in, index lists out
     U = int(st.union_count.sum().item())
     out["sparse_decode"] = U * (512 + 4)
     out["combine"] = 0
@@ -231,17 +233,21 @@ def main():
         T.twilight_prof_enable(0)
         dense_us = sum(d[1:]) / max(1, len(d) - 1) * 1e3
 
-    ach = nbytes[dom] / (dom_avg * 1e-3) / 1e9
+    # a kernel id launched several times per step (the long-row top-p) is priced per step:
+    # all its launches' time against the bytes the stage moves per step
+    dom_calls = kcalls[dom]
+    ach = nbytes[dom] / (dom_avg * dom_calls * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS,
                 "traffic": TRAFFIC_C2.get(dom) if (a.config == 1 and a.scale == 1.0 and a.batch is None and a.seed == 0) else None,
-                "algorithmic_bytes": nbytes[dom], "avg_kernel_us": dom_avg * 1e3, "launches_timed": len(dom_ms)}
+                "algorithmic_bytes": nbytes[dom], "avg_kernel_us": dom_avg * 1e3, "launches_per_step": dom_calls,
+                "launches_timed": len(dom_ms)}
     per_kernel = {k: {"us": kavg[k] * 1e3, "calls_per_step": kcalls[k], "bytes": nbytes.get(k),
-                      "GBps": (nbytes.get(k, 0) / (kavg[k] * 1e-3) / 1e9) if kavg[k] > 0 else None}
+                      "GBps": (nbytes.get(k, 0) / (kavg[k] * kcalls[k] * 1e-3) / 1e9) if kavg[k] > 0 else None}
                   for k in kavg}
     if a.breakdown:
         for k, v in per_kernel.items():
-            sys.stderr.write("%-16s %9.2f us  %12s B  %8.1f GB/s\n" % (k, v["us"], v["bytes"], v["GBps"] or 0))
+            sys.stderr.write("%-16s %9.2f us x %-4.3g %12s B  %8.1f GB/s\n" % (k, v["us"], v["calls_per_step"], v["bytes"], v["GBps"] or 0))
         sys.stderr.write("sum of kernels %.2f us; step %.2f us (events on the dominant kernel) / %.2f us (events off); dense %s us\n"
                          % (sum(v["us"] * v["calls_per_step"] for v in per_kernel.values()), ms_per_step * 1e3,
                             ms_plain * 1e3, dense_us))
