@@ -347,6 +347,7 @@ struct HeadArgs {
   int32_t* union_idx;
   uint32_t* status;
   int Hq, Hkv, max_pages, max_sel, cand_stride, kept_stride, words_stride, union_stride;
+  int n_above, n_upto;        // this launch takes the heads with n_above < candidates <= n_upto
   float p;
 };
 
@@ -367,6 +368,7 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   if (count > a.max_sel) count = a.max_sel;
   if (count < 0) count = 0;
   const int N = count * TW_PAGE;
+  if (N <= a.n_above || N > a.n_upto) return;     // another launch's head (block-uniform)
   const float* row = a.scores + (long long)bh * a.cand_stride;
   const int c0 = tid * EPT;
 
@@ -801,6 +803,23 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
     f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_sel; f.cand_stride = cand_stride;
     f.kept_stride = kept_stride; f.words_stride = words_stride; f.union_stride = union_stride; f.p = p;
     const dim3 grid(d.Hq, d.batch);
+    f.n_above = -1; f.n_upto = cand_stride;
+    // Many heads with a bound above 4096 candidates (ragged batches): the 1024-thread kernel leaves
+    // room for one workgroup per CU.  Heads of at most 4096 candidates then go to a 512-thread
+    // launch of their own (two per CU), the longer ones to the 1024-thread launch.
+    const bool split = cand_stride > 4096 && (long long)d.batch * d.Hq > 2ll * tw_num_cus();
+    if (split) {
+      f.n_upto = 4096;
+      tw_prof_before(TW_K_TOPP, s);
+      switch (d.G) {
+        case 1: hipLaunchKernelGGL((topp_head_kernel<512, 8, 1>), grid, dim3(512), 0, s, f); break;
+        case 2: hipLaunchKernelGGL((topp_head_kernel<512, 8, 2>), grid, dim3(512), 0, s, f); break;
+        case 4: hipLaunchKernelGGL((topp_head_kernel<512, 8, 4>), grid, dim3(512), 0, s, f); break;
+        default: hipLaunchKernelGGL((topp_head_kernel<512, 8, 8>), grid, dim3(512), 0, s, f); break;
+      }
+      if (int e = tw_prof_after(s)) return e;
+      f.n_above = 4096; f.n_upto = cand_stride;
+    }
     tw_prof_before(TW_K_TOPP, s);
     if (cand_stride <= 4096) switch (d.G) {
       case 1: hipLaunchKernelGGL((topp_head_kernel<1024, 4, 1>), grid, dim3(1024), 0, s, f); break;

@@ -428,6 +428,19 @@ def test_scaled_benchmark_configs(idx, scale, batch):
     check_sets_and_output(w, cache, st)
 
 
+def test_many_heads_mixed_row_lengths_split_launch():
+    """More than two heads per CU and a candidate bound above 4096: top-p runs as two launches, heads of
+    at most 4096 candidates in 512-thread workgroups, longer ones in 1024-thread workgroups."""
+    lens = [40_000, 70_000] + [600 + 150 * i for i in range(16)]            # 18 sequences x 32 heads = 576 heads
+    w = synth.make_workload("mixed", lens, budget=[n // 8 for n in lens], p=0.95, heavy_frac=0.01,
+                            alpha_range=(0.0, 3.0), shuffle_pool=True, seed=31)
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache)
+    assert int(st.status.item()) == 0
+    assert st.max_sel * 16 > 4096 and w.batch * w.num_q_heads > 512
+    check_sets_and_output(w, cache, st)
+
+
 def test_long_sequence_fallback_paths():
     """More than 8192 pages and more than 196608 tokens: the streaming page_select, top-p and union
     kernels (general-length paths) instead of the LDS / register-resident ones."""
