@@ -35,7 +35,6 @@ QGROUP = 32         # dims sharing one (scale, zero)
 NGROUPS = HEAD_DIM // QGROUP
 
 F32 = np.float32
-_INV15 = F32(1.0 / 15.0)              # fp32 nearest to 1/15
 _INV127 = F32(1.0 / 127.0)            # fp32 nearest to 1/127
 _RSQRT_D = F32(1.0 / np.sqrt(128.0))  # fp32 nearest to 1/sqrt(128)
 
@@ -62,17 +61,21 @@ def f32_to_bf16(x):
 # "Dequantization": dynamic, fp16 scale and zero).  Granularity: per token,
 # per KV head, per group of 32 dims.
 # --------------------------------------------------------------------------
-def quantize_k(k_bits):
-    """k_bits uint16[n,128] -> (u uint8[n,128] in 0..15, scale f16[n,4], zero f16[n,4]).
+def quantize_k(k_bits, bits=4):
+    """k_bits uint16[n,128] -> (u uint8[n,128] in 0..L, scale f16[n,4], zero f16[n,4]), L = 2^bits - 1.
 
-    Per group of 32: mn, mx; scale = fp16((mx-mn) * (1/15)); zero = fp16(mn);
-    u = clamp(rint((x - zero) * (1/scale)), 0, 15); scale == 0 -> u = 0.
+    Per group of 32: mn, mx; scale = fp16((mx-mn) * (1/L)); zero = fp16(mn);
+    u = clamp(rint((x - zero) * (1/scale)), 0, L); scale == 0 -> u = 0.
     All fp32, each operation rounded on its own; rint is round-half-even.
+    bits = 4 is the method's choice; 2 and 8 are the other widths of its
+    bit-width study of the estimator (Section 4.2, Figure 6).
     """
+    L = (1 << bits) - 1
+    inv_l = F32(1.0 / L)                      # fp32 nearest to 1/L
     x = bf16_to_f32(k_bits).reshape(-1, NGROUPS, QGROUP)
     mn = x.min(axis=-1)
     mx = x.max(axis=-1)
-    scale = ((mx - mn) * _INV15).astype(np.float16)
+    scale = ((mx - mn) * inv_l).astype(np.float16)
     zero = mn.astype(np.float16)
     sf = scale.astype(np.float32)
     zf = zero.astype(np.float32)
@@ -80,13 +83,13 @@ def quantize_k(k_bits):
     inv = np.zeros_like(sf)
     inv[ok] = F32(1.0) / sf[ok]
     t = (x - zf[..., None]) * inv[..., None]
-    u = np.clip(np.rint(t), 0, 15).astype(np.uint8)
+    u = np.clip(np.rint(t), 0, L).astype(np.uint8)
     u[~ok] = 0
     return u.reshape(-1, HEAD_DIM), scale, zero
 
 
 def dequantize_k(u, scale, zero):
-    """x_hat = u*scale + zero, in float64 (exact: 4-bit x 11-bit + 11-bit)."""
+    """x_hat = u*scale + zero, in float64 (exact: at most 8-bit x 11-bit + 11-bit)."""
     u = np.asarray(u).reshape(-1, NGROUPS, QGROUP).astype(np.float64)
     s = np.asarray(scale).astype(np.float64)[..., None]
     z = np.asarray(zero).astype(np.float64)[..., None]
@@ -300,7 +303,7 @@ def true_mass(q_bits, k_bits, idx):
 # Whole pipeline for one sequence (Figure 5): select -> prune -> union ->
 # attend.  GQA: query head h reads KV head h // G.
 # --------------------------------------------------------------------------
-def twilight_decode(q_bits, k_bits, v_bits, budget_tokens, p, full_selector=False):
+def twilight_decode(q_bits, k_bits, v_bits, budget_tokens, p, full_selector=False, bits=4):
     """q_bits uint16[Hq,128]; k_bits, v_bits uint16[n,Hkv,128].
 
     Returns a dict with every intermediate, all in logical coordinates:
@@ -308,6 +311,7 @@ def twilight_decode(q_bits, k_bits, v_bits, budget_tokens, p, full_selector=Fals
       s_hat[h], kept[h], tau[h], union[g], out float64[Hq,128], lse[Hq],
       out_bf16 uint16[Hq,128].
     full_selector=True skips stage 1 (every token is a candidate).
+    bits: width of the quantised K copy the estimate is taken from (4 = the method).
     """
     Hq = q_bits.shape[0]
     n, Hkv, _ = k_bits.shape
@@ -315,7 +319,7 @@ def twilight_decode(q_bits, k_bits, v_bits, budget_tokens, p, full_selector=Fals
     r = dict(u=[], scale=[], zero=[], mn=[], mx=[], U=[], pages=[], cand=[],
              s_hat=[], kept=[], tau=[], union=[])
     for g in range(Hkv):
-        u, sc, ze = quantize_k(k_bits[:, g])
+        u, sc, ze = quantize_k(k_bits[:, g], bits)
         mn, mx = page_minmax(k_bits[:, g])
         r["u"].append(u); r["scale"].append(sc); r["zero"].append(ze)
         r["mn"].append(mn); r["mx"].append(mx)

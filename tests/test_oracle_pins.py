@@ -94,6 +94,46 @@ def test_int4_round_trip_bound_and_invariants(rng):
     assert np.all(np.abs(s.astype(np.float64) - rng15) <= rng15 * 2.0 ** -10 + 1e-8)
 
 
+@pytest.mark.parametrize("bits", [2, 8])
+def test_other_estimator_widths_grid_bound_and_levels(rng, bits):
+    """The 2- and 8-bit copies of the bit-width study (Section 4.2, Figure 6) follow the 4-bit recipe with
+    L = 2^bits - 1 levels: exact recovery on a power-of-two grid, half-a-step round trip, end points."""
+    L = (1 << bits) - 1
+    step = 2.0 ** -(bits - 1)                      # -1 + step*code is exact in bf16 for code <= 255
+    codes = rng.integers(0, L + 1, (50, 4, 32))
+    codes[:, :, 0] = 0
+    codes[:, :, 1] = L
+    row = (-1.0 + step * codes).astype(np.float32).reshape(50, 128)
+    u, s, z = O.quantize_k(_bf16_bits(row), bits)
+    assert np.all(s == np.float16(step)) and np.all(z == np.float16(-1.0))
+    assert np.array_equal(u.reshape(50, 4, 32), codes)
+    assert np.array_equal(O.dequantize_k(u, s, z), row.astype(np.float64))
+    # random data: bound, nearest level, end points
+    x = (rng.standard_normal((2000, 128)) * np.exp(rng.uniform(-3, 3, (2000, 1)))).astype(np.float32)
+    kb = _bf16_bits(x)
+    xb = O.bf16_to_f32(kb).astype(np.float64)
+    u, s, z = O.quantize_k(kb, bits)
+    assert u.max() <= L
+    xh = O.dequantize_k(u, s, z)
+    sg = np.repeat(s.astype(np.float64), 32, axis=1)
+    zg = np.repeat(z.astype(np.float64), 32, axis=1)
+    g = xb.reshape(-1, 4, 32)
+    mn = np.repeat(g.min(-1), 32, axis=1)
+    assert np.all(np.abs(xb - xh) <= 0.5 * sg + np.abs(mn) * 2.0 ** -11 + L * sg * 2.0 ** -11 + 1e-7)
+    lv = zg[..., None] + sg[..., None] * np.arange(L + 1)[None, None, :]
+    assert np.all(np.abs(xb - xh) <= np.abs(xb[..., None] - lv).min(-1) + 1e-6 * (np.abs(xb) + sg))
+    ug = u.reshape(-1, 4, 32)
+    ii, jj = np.indices(g.shape[:2])
+    assert np.all(ug[ii, jj, g.argmin(-1)] == 0)
+    # scale carries an fp16 rounding of up to 2^-11 relative, i.e. at most 255 * 2^-11 < 1/2 step at
+    # the top: the maximum still lands on L
+    pos = s.astype(np.float32) > 0
+    assert np.all(ug[ii, jj, g.argmax(-1)][pos] == L)
+    # coarser copies estimate worse: mean squared error falls with the width
+    err = {b: np.mean((xb - O.dequantize_k(*O.quantize_k(kb, b))) ** 2) for b in (2, 4, 8)}
+    assert err[2] > 10 * err[4] > 100 * err[8]
+
+
 def test_int4_rint_is_half_even():
     # group 0: min 0, max 15 -> scale 1, zero 0; values k + 0.5 must round to even k
     row = np.zeros(128, np.float32)
