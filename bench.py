@@ -30,7 +30,7 @@ PAPER_CONTEXT = {"quest_twi_vs_fa2_attention_speedup": 15.8, "quest_twi_vs_quest
                  "hardware": "1x NVIDIA A100", "source": "Section 5.2"}
 
 
-def build_state(cfg_idx, scale, seed, batch, layers):
+def build_state(cfg_idx, scale, seed, batch, layers, bits=4):
     """`layers` independent copies of the layer's cache (same contents, different memory).  Successive steps
     rotate over them, as the layers of a model do, so that a step finds its pools in HBM and not in the
     256 MB memory-side cache left warm by the previous step over the very same addresses."""
@@ -52,7 +52,7 @@ def build_state(cfg_idx, scale, seed, batch, layers):
     caches, steps = [], []
     for _ in range(layers):
         cache = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev,
-                          need_v=w.v.numel() > 0)
+                          need_v=w.v.numel() > 0, quant_bits=bits)
         # prefill: every token but the last of each sequence; the step appends the last one
         cache.append(k, v, start, cache.seq_lens - 1, offs, int(w.seq_lens.max()) - 1)
         caches.append(cache)
@@ -89,7 +89,7 @@ def build_state(cfg_idx, scale, seed, batch, layers):
     return w, caches[0], steps[0], q, step, dense, dict(gen_s=gen_s, h2d_s=h2d_s)
 
 
-def algorithmic_bytes(w, cache, st):
+def algorithmic_bytes(w, cache, st, bits=4):
     """Bytes each kernel must move per launch (per-unit figures x units, data-dependent ones read back)."""
     import torch
     Hq, Hkv = w.num_q_heads, w.num_kv_heads
@@ -100,11 +100,11 @@ def algorithmic_bytes(w, cache, st):
     out["page_score"] = pages * Hkv * 512 + pages * Hq * 4
     if st.full:
         cand = tokens * Hkv            # group-shared loads
-        out["int4_score"] = cand * 80 + tokens * Hq * 4
+        out["int4_score"] = cand * (16 * bits + 16) + tokens * Hq * 4
         ncand = tokens * Hq
     else:
         ncand = int(st.sel_count.sum().item()) * 16
-        out["int4_score"] = ncand * 80 + ncand * 4
+        out["int4_score"] = ncand * (16 * bits + 16) + ncand * 4
     out["page_select"] = pages * Hq * 4
     # register-resident top-p reads each score once; the long-row path reads the row twice
     # (one histogram pass, one pass that writes the kept bitmap) - its launches are summed per step
@@ -152,6 +152,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--layers", type=int, default=4,
                     help="independent copies of the cache that successive steps rotate over (1 = same memory every step)")
+    ap.add_argument("--bits", type=int, default=4, choices=[2, 4, 8],
+                    help="width of the quantised K copy the pruner scores from (4 = the method; 2 and 8: its bit-width study)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--calib-copy", action="store_true",
@@ -165,7 +167,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers))
+    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits)
     if a.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
@@ -195,6 +197,18 @@ def main():
     kcalls = {k: len(v) / a.steps for k, v in kern.items()}
     dom = max(kavg_all, key=lambda k: kavg_all[k] * kcalls[k])
 
+    # attention mass that the attended sets capture (per query head: exp(lse over its group's union - lse over
+    # all tokens), both from twilight_sparse_decode): the quantity the estimator's precision is judged by
+    captured = None
+    if w.v.numel():
+        lse_s = torch.zeros(w.batch, w.num_q_heads, dtype=torch.float32, device="cuda:0")
+        lse_d = torch.zeros_like(lse_s)
+        T.twilight_sparse_decode(cache.kv, q, st.union_count, st.union_idx, st.union_stride, st.out, lse_s, st.ws_decode)
+        st.dense(q, lse=lse_d)
+        torch.cuda.synchronize()
+        m = torch.exp(lse_s - lse_d).cpu()
+        captured = {"mean": float(m.mean()), "min": float(m.min()), "p10": float(m.flatten().kthvalue(max(1, m.numel() // 10)).values)}
+
     # ---- timed region: K steps; HIP events (on the launch stream) around the dominant kernel only,
     # so the event pairs do not stretch the step the way bracketing all seven launches does
     T.twilight_prof_select(dom)
@@ -220,7 +234,7 @@ def main():
     ms_plain = (time.perf_counter() - t0) * 1e3 / a.steps
 
     kavg = dict(kavg_all)
-    nbytes, stats = algorithmic_bytes(w, cache, st)
+    nbytes, stats = algorithmic_bytes(w, cache, st, a.bits)
 
     # dense decode attention through the same kernel, for the "below dense" comparison
     dense_us = None
@@ -257,7 +271,7 @@ def main():
         "metric": "sparse decode-attention us/layer and achieved HBM GB/s vs peak (1 MI355X)",
         "value": ms_per_step * 1e3, "unit": "us/layer", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 KV, int4 K estimate, fp32 accumulate", "data": "synthetic",
+        "dtype": "bf16 KV, int%d K estimate, fp32 accumulate" % a.bits, "data": "synthetic",
         "config": {"workload": "%s: batch %d, %d q / %d kv heads, head_dim 128, context %s, page 16, budget %s, p=%g%s"
                                % (w.name, w.batch, w.num_q_heads, w.num_kv_heads,
                                   int(w.seq_lens[0]) if len(set(w.seq_lens.tolist())) == 1 else "ragged",
@@ -271,6 +285,8 @@ def main():
         "dense_decode_GBps": (nbytes["dense_decode"] / (dense_us * 1e-6) / 1e9) if dense_us else None,
         "per_kernel": per_kernel,
         "workload_stats": stats,
+        "estimator_bits": a.bits,
+        "attention_mass_captured": captured,
         "paper_context": PAPER_CONTEXT,
         "setup_seconds": setup,
     }

@@ -20,7 +20,7 @@
  *   - The caller owns every buffer.  The library allocates nothing, frees
  *     nothing, copies nothing between host and device and never synchronises;
  *     all work is enqueued on `stream`.
- *   - head_dim must be 128, page_size 16, quant_group 32,
+ *   - head_dim must be 128, page_size 16, quant_group 32, quant_bits 0/4, 2 or 8,
  *     num_q_heads / num_kv_heads one of 1, 2, 4, 8.
  *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
  *   - Token indices are logical positions in their sequence (0 .. len-1);
@@ -57,11 +57,18 @@ extern "C" {
 /*
  * Paged KV cache of one layer.  Layouts (all row-major, page = 16 tokens):
  *   k_pool, v_pool  bf16 [num_pool_pages][num_kv_heads][16][128]
- *   kq_pool         u8   [num_pool_pages][num_kv_heads][16][64]
- *                   INT4 codes 0..15 of K.  Dims 8w..8w+7 of a token form the
- *                   32-bit little-endian word w (w = 0..15); its byte k
- *                   (k = 0..3) holds code[8w+k] in the low nibble and
- *                   code[8w+k+4] in the high nibble.
+ *   kq_pool         u8   [num_pool_pages][num_kv_heads][16][16 * quant_bits]
+ *                   codes 0..2^quant_bits-1 of K (quant_bits = 4: the method's
+ *                   INT4 copy, 64 bytes per token).  32-bit little-endian words:
+ *                   4 bits: dims 8w..8w+7 form word w (w = 0..15); byte k
+ *                           (k = 0..3) holds code[8w+k] in the low nibble and
+ *                           code[8w+k+4] in the high nibble.
+ *                   2 bits: dims 16w..16w+15 form word w (w = 0..7); byte i
+ *                           holds code[16w+4k+i] at bits 2k..2k+1, k = 0..3.
+ *                   8 bits: dims 4w..4w+3 form word w (w = 0..31), byte i =
+ *                           code[4w+i].
+ *                   The 2- and 8-bit copies are the other widths of the
+ *                   paper's bit-width study of the estimator (Section 4.2).
  *   kq_meta         fp16 [num_pool_pages][num_kv_heads][16][4][2]
  *                   (scale, zero) of each group of 32 dims:
  *                   K ~ code * scale + zero           (Appendix B.1)
@@ -78,7 +85,7 @@ typedef struct twilight_kv {
   int32_t page_size;         /* 16  */
   int32_t quant_group;       /* 32  */
   int32_t max_pages_per_seq; /* row length of page_table */
-  int32_t reserved;          /* 0 */
+  int32_t quant_bits;        /* width of the kq_pool codes: 4 (0 means 4), 2 or 8 */
   int64_t num_pool_pages;
   const int32_t* page_table;
   const int32_t* seq_lens;

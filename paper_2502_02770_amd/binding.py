@@ -23,7 +23,7 @@ _vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ct
 
 class twilight_kv_t(ctypes.Structure):
     _fields_ = [("batch", _i32), ("num_q_heads", _i32), ("num_kv_heads", _i32), ("head_dim", _i32),
-                ("page_size", _i32), ("quant_group", _i32), ("max_pages_per_seq", _i32), ("reserved", _i32),
+                ("page_size", _i32), ("quant_group", _i32), ("max_pages_per_seq", _i32), ("quant_bits", _i32),
                 ("num_pool_pages", _i64), ("page_table", _vp), ("seq_lens", _vp), ("k_pool", _vp),
                 ("v_pool", _vp), ("kq_pool", _vp), ("kq_meta", _vp), ("page_minmax", _vp)]
 
@@ -83,12 +83,12 @@ def _check(code):
 
 
 def make_kv(batch, num_q_heads, num_kv_heads, max_pages_per_seq, num_pool_pages, page_table, seq_lens,
-            k_pool=None, v_pool=None, kq_pool=None, kq_meta=None, page_minmax=None):
+            k_pool=None, v_pool=None, kq_pool=None, kq_meta=None, page_minmax=None, quant_bits=4):
     """Fill a twilight_kv_t from torch tensors (which the caller keeps alive)."""
     kv = twilight_kv_t()
     kv.batch, kv.num_q_heads, kv.num_kv_heads = batch, num_q_heads, num_kv_heads
     kv.head_dim, kv.page_size, kv.quant_group = 128, 16, 32
-    kv.max_pages_per_seq, kv.reserved, kv.num_pool_pages = max_pages_per_seq, 0, num_pool_pages
+    kv.max_pages_per_seq, kv.quant_bits, kv.num_pool_pages = max_pages_per_seq, quant_bits, num_pool_pages
     for name, t in (("page_table", page_table), ("seq_lens", seq_lens), ("k_pool", k_pool), ("v_pool", v_pool),
                     ("kq_pool", kq_pool), ("kq_meta", kq_meta), ("page_minmax", page_minmax)):
         setattr(kv, name, None if t is None else t.data_ptr())

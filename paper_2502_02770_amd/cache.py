@@ -12,7 +12,7 @@ class PagedKV:
     """The pools of include/twilight.h's twilight_kv_t, owned as torch tensors."""
 
     def __init__(self, num_q_heads, num_kv_heads, page_table, seq_lens, num_pool_pages, device="cuda",
-                 need_v=True):
+                 need_v=True, quant_bits=4):
         dev = torch.device(device)
         self.Hq, self.Hkv = int(num_q_heads), int(num_kv_heads)
         self.page_table = page_table.to(dev, torch.int32).contiguous()
@@ -22,11 +22,13 @@ class PagedKV:
         P, H = self.num_pool_pages, self.Hkv
         self.k_pool = torch.zeros(P, H, 16, 128, dtype=torch.bfloat16, device=dev)
         self.v_pool = torch.zeros(P, H, 16, 128, dtype=torch.bfloat16, device=dev) if need_v else None
-        self.kq_pool = torch.zeros(P, H, 16, 64, dtype=torch.uint8, device=dev)
+        self.quant_bits = int(quant_bits)
+        self.kq_pool = torch.zeros(P, H, 16, 16 * self.quant_bits, dtype=torch.uint8, device=dev)
         self.kq_meta = torch.zeros(P, H, 16, 4, 2, dtype=torch.float16, device=dev)
         self.page_minmax = torch.zeros(P, H, 2, 128, dtype=torch.bfloat16, device=dev)
         self.kv = B.make_kv(self.batch, self.Hq, self.Hkv, self.max_pages, P, self.page_table, self.seq_lens,
-                            self.k_pool, self.v_pool, self.kq_pool, self.kq_meta, self.page_minmax)
+                            self.k_pool, self.v_pool, self.kq_pool, self.kq_meta, self.page_minmax,
+                            quant_bits=self.quant_bits)
 
     def append(self, k_new, v_new, start_pos, n_new, new_offsets, max_new):
         """twilight_kquant_append; does not advance seq_lens."""

@@ -1,6 +1,7 @@
 // Stage 4: append K/V rows, INT4-quantise K, maintain per-page key bounds.
-// Paper: Section 4.2 (extra INT4 asymmetric K cache), Appendix B.1
-// (dynamic quantisation, fp16 scale and zero, nibble packing).
+// Paper: Section 4.2 (extra INT4 asymmetric K cache; 2- and 8-bit copies for
+// its bit-width study), Appendix B.1 (dynamic quantisation, fp16 scale and
+// zero, nibble packing).
 //
 // One workgroup = one (sequence, KV head, logical page): 256 threads =
 // 16 token slots x 16 lanes; a lane owns 8 consecutive dims (one 16-byte
@@ -18,14 +19,18 @@ struct AppendArgs {
   const int32_t* page_table;
   uint4* k_pool;            // or nullptr
   uint4* v_pool;
-  uint32_t* kq_pool;        // 16 words per token
+  uint32_t* kq_pool;        // 4 * BITS words per token
   uint32_t* kq_meta;        // 4 words (scale | zero << 16) per token
   uint4* page_minmax;       // [page][Hkv][2][16 lanes]
   int Hkv, max_pages;
   long long pool_pages;
 };
 
+template <int BITS>
 __global__ __launch_bounds__(256) void kquant_append_kernel(AppendArgs a) {
+  constexpr float kLevels = (float)((1 << BITS) - 1);
+  // fp32 nearest to 1/levels
+  constexpr float kInvLevels = BITS == 4 ? 0x1.111112p-4f : (BITS == 2 ? 0x1.555556p-2f : 0x1.010102p-8f);
   const int b = blockIdx.z, g = blockIdx.y;
   const int tid = threadIdx.x, ts = tid >> 4, seg = tid & 15;
   const int start = a.start_pos[b], nn = a.n_new[b];
@@ -56,24 +61,40 @@ __global__ __launch_bounds__(256) void kquant_append_kernel(AppendArgs a) {
   for (int i = 1; i < 8; ++i) { lmn = fminf(lmn, x[i]); lmx = fmaxf(lmx, x[i]); }
   const float gmn = tw_quad_min(lmn), gmx = tw_quad_max(lmx);
 
-  const __half hs = __float2half_rn(__fmul_rn(__fsub_rn(gmx, gmn), 0x1.111112p-4f /* fp32(1/15) */));
+  const __half hs = __float2half_rn(__fmul_rn(__fsub_rn(gmx, gmn), kInvLevels));
   const __half hz = __float2half_rn(gmn);
   const float sf = __half2float(hs), zf = __half2float(hz);
-  uint32_t word = 0;
+  uint32_t u[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) u[i] = 0;
   if (sf > 0.0f) {
     const float inv = __fdiv_rn(1.0f, sf);
-    uint32_t u[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       float t = rintf(__fmul_rn(__fsub_rn(x[i], zf), inv));
-      t = fminf(fmaxf(t, 0.0f), 15.0f);
+      t = fminf(fmaxf(t, 0.0f), kLevels);
       u[i] = (uint32_t)t;
     }
+  }
+  // pack this lane's 8 codes (the layouts are stated with twilight_kv_t)
+  uint32_t word = 0, word2 = 0;
+  if (BITS == 4) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) word |= (u[k] | (u[k + 4] << 4)) << (8 * k);
+  } else if (BITS == 8) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) { word |= u[k] << (8 * k); word2 |= u[k + 4] << (8 * k); }
+  } else {
+    // 16 dims per word: the even lane of a pair brings bit positions 0..3 of every byte, the odd lane 4..7
+#pragma unroll
+    for (int k = 0; k < 4; ++k) word |= (u[k] | (u[k + 4] << 2)) << (8 * k);
+    word <<= (seg & 1) * 4;
+    word |= (uint32_t)tw_dpp_i<TW_DPP_XOR1>((int)word);
   }
   if (is_new) {
-    a.kq_pool[slot * 16 + seg] = word;
+    if (BITS == 4) a.kq_pool[slot * 16 + seg] = word;
+    else if (BITS == 8) ((uint2*)a.kq_pool)[slot * 16 + seg] = make_uint2(word, word2);
+    else if ((seg & 1) == 0) a.kq_pool[slot * 8 + (seg >> 1)] = word;
     if ((seg & 3) == 0)
       a.kq_meta[slot * 4 + (seg >> 2)] =
           (uint32_t)__half_as_ushort(hs) | ((uint32_t)__half_as_ushort(hz) << 16);
@@ -156,6 +177,9 @@ extern "C" int twilight_kquant_append(const twilight_kv_t* kv, const void* k_new
   if (pages > d.max_pages) pages = d.max_pages;
   hipStream_t s = (hipStream_t)stream;
   tw_prof_before(TW_K_KQUANT_APPEND, s);
-  hipLaunchKernelGGL(kquant_append_kernel, dim3(pages, d.Hkv, d.batch), dim3(256), 0, s, a);
+  const dim3 grid(pages, d.Hkv, d.batch);
+  if (d.bits == 4)      hipLaunchKernelGGL(kquant_append_kernel<4>, grid, dim3(256), 0, s, a);
+  else if (d.bits == 8) hipLaunchKernelGGL(kquant_append_kernel<8>, grid, dim3(256), 0, s, a);
+  else                  hipLaunchKernelGGL(kquant_append_kernel<2>, grid, dim3(256), 0, s, a);
   return tw_prof_after(s);
 }

@@ -68,7 +68,7 @@ __device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32]
 
 // NH = heads scored per loaded page: 1 with per-head page lists, G when every
 // page is a candidate (the G heads of a KV head then share each load).
-template <int NH, bool FULL, bool DOTS, int UNR>
+template <int NH, bool FULL, bool DOTS, int UNR, int BITS = 4>
 __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int b, g, h0;
@@ -89,7 +89,7 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   __shared__ float c_s[NH];
   tw_quantize_q<NH>(a.q + ((long long)(b * a.Hq + h0)) * 128, qi_s, red, c_s);
   const int j = lane & 3;                       // this lane's group of 32 dims
-  int qw[NH][8];
+  int qw[NH][8], qs128[NH];
   float qsf[NH], cc[NH];
 #pragma unroll
   for (int h = 0; h < NH; ++h) {
@@ -100,6 +100,7 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
       qs = __builtin_amdgcn_sdot4(qw[h][k], 0x01010101, qs, false);
     }
     qsf[h] = (float)qs;
+    qs128[h] = BITS == 8 ? 128 * qs : 0;        // 8-bit codes enter the signed dot4 as code - 128
     cc[h] = c_s[h];
   }
 
@@ -129,12 +130,24 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
     // unconditional loads (an unmapped page reads pool page 0 and is masked below), so that the
     // four pages of an unrolled step are in flight together
     const long long blk = ((long long)(pool >= 0 ? pool : 0) * a.Hkv + g) * 64;
-    const uint4 nib = a.kq_pool[blk + lane];
+    // this lane's group of 32 codes as 8 dot4 operands (4 dims each, in the order of qw)
+    int u0, u1, u2, u3, u4, u5, u6, u7;
+    if (BITS == 4) {
+      const uint4 nib = a.kq_pool[blk + lane];
+      u0 = nib.x & 0x0F0F0F0F; u1 = (nib.x >> 4) & 0x0F0F0F0F;
+      u2 = nib.y & 0x0F0F0F0F; u3 = (nib.y >> 4) & 0x0F0F0F0F;
+      u4 = nib.z & 0x0F0F0F0F; u5 = (nib.z >> 4) & 0x0F0F0F0F;
+      u6 = nib.w & 0x0F0F0F0F; u7 = (nib.w >> 4) & 0x0F0F0F0F;
+    } else if (BITS == 2) {
+      const uint2 cr = ((const uint2*)a.kq_pool)[blk + lane];
+      u0 = cr.x & 0x03030303; u1 = (cr.x >> 2) & 0x03030303; u2 = (cr.x >> 4) & 0x03030303; u3 = (cr.x >> 6) & 0x03030303;
+      u4 = cr.y & 0x03030303; u5 = (cr.y >> 2) & 0x03030303; u6 = (cr.y >> 4) & 0x03030303; u7 = (cr.y >> 6) & 0x03030303;
+    } else {
+      const uint4 c0 = a.kq_pool[(blk + lane) * 2], c1 = a.kq_pool[(blk + lane) * 2 + 1];
+      u0 = c0.x ^ 0x80808080; u1 = c0.y ^ 0x80808080; u2 = c0.z ^ 0x80808080; u3 = c0.w ^ 0x80808080;
+      u4 = c1.x ^ 0x80808080; u5 = c1.y ^ 0x80808080; u6 = c1.z ^ 0x80808080; u7 = c1.w ^ 0x80808080;
+    }
     const uint32_t meta = a.kq_meta[blk + lane];
-    const int u0 = nib.x & 0x0F0F0F0F, u1 = (nib.x >> 4) & 0x0F0F0F0F;
-    const int u2 = nib.y & 0x0F0F0F0F, u3 = (nib.y >> 4) & 0x0F0F0F0F;
-    const int u4 = nib.z & 0x0F0F0F0F, u5 = (nib.z >> 4) & 0x0F0F0F0F;
-    const int u6 = nib.w & 0x0F0F0F0F, u7 = (nib.w >> 4) & 0x0F0F0F0F;
     const float sc = __half2float(__ushort_as_half((unsigned short)(meta & 0xFFFFu)));
     const float ze = __half2float(__ushort_as_half((unsigned short)(meta >> 16)));
     const int tok = lp * TW_PAGE + (lane >> 2);
@@ -142,7 +155,7 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
     const long long slot = (long long)(first + k) * TW_PAGE + (lane >> 2);
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
-      int I = __builtin_amdgcn_sdot4(qw[h][0], u0, 0, false);
+      int I = __builtin_amdgcn_sdot4(qw[h][0], u0, qs128[h], false);
       I = __builtin_amdgcn_sdot4(qw[h][1], u1, I, false);
       I = __builtin_amdgcn_sdot4(qw[h][2], u2, I, false);
       I = __builtin_amdgcn_sdot4(qw[h][3], u3, I, false);
@@ -654,10 +667,17 @@ int pages_per_wave(long long total_pages_all_rows, int count_bound) {
 }
 
 template <int NH, bool FULL>
-void launch_score(const ScoreArgs& a, dim3 grid, bool dots, hipStream_t s) {
+void launch_score(const ScoreArgs& a, dim3 grid, bool dots, int bits, hipStream_t s) {
   // pages in flight per wave: 4, fewer when 8 heads share a page (register budget)
   static const int unr8 = getenv("TW_INT4_UNR") ? atoi(getenv("TW_INT4_UNR")) : 2;   // tuning switch
-  if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2>), grid, dim3(256), 0, s, a);
+  if (bits == 2) {
+    if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2, 2>), grid, dim3(256), 0, s, a);
+    else      hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 2, 2>), grid, dim3(256), 0, s, a);
+  } else if (bits == 8) {
+    if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2, 8>), grid, dim3(256), 0, s, a);
+    else      hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 2, 8>), grid, dim3(256), 0, s, a);
+  }
+  else if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2>), grid, dim3(256), 0, s, a);
   else if (NH < 8) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 4>), grid, dim3(256), 0, s, a);
   else if (unr8 == 1) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 1>), grid, dim3(256), 0, s, a);
   else if (unr8 == 4) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 4>), grid, dim3(256), 0, s, a);
@@ -684,8 +704,8 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
   dim3 grid((bound + 4 * a.pw - 1) / (4 * a.pw), d.batch * (full ? d.Hkv : d.Hq));
   tw_prof_before(TW_K_INT4_SCORE, s);
   static const bool valu_only = getenv("TW_INT4_VALU") != nullptr;   // tuning switch: vector-ALU kernel for every G
-  if (!full) launch_score<1, false>(a, grid, dots != nullptr, s);
-  else if (d.G >= 4 && !valu_only) {               // matrix-core kernel: 4 or 8 heads share every page
+  if (!full) launch_score<1, false>(a, grid, dots != nullptr, d.bits, s);
+  else if (d.G >= 4 && d.bits == 4 && !valu_only) {               // matrix-core kernel: 4 or 8 heads share every page
     // 8 pages in flight per wave (the kernel needs few registers, so 4 to 7 waves per SIMD stay resident)
     if (d.G == 4) {
       if (dots) hipLaunchKernelGGL((int4_score_mfma_kernel<1, true, 4>), grid, dim3(256), 0, s, a);
@@ -695,10 +715,10 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
       else      hipLaunchKernelGGL((int4_score_mfma_kernel<2, false, 8>), grid, dim3(256), 0, s, a);
     }
   } else switch (d.G) {
-    case 1: launch_score<1, true>(a, grid, dots != nullptr, s); break;
-    case 2: launch_score<2, true>(a, grid, dots != nullptr, s); break;
-    case 4: launch_score<4, true>(a, grid, dots != nullptr, s); break;
-    default: launch_score<8, true>(a, grid, dots != nullptr, s); break;
+    case 1: launch_score<1, true>(a, grid, dots != nullptr, d.bits, s); break;
+    case 2: launch_score<2, true>(a, grid, dots != nullptr, d.bits, s); break;
+    case 4: launch_score<4, true>(a, grid, dots != nullptr, d.bits, s); break;
+    default: launch_score<8, true>(a, grid, dots != nullptr, d.bits, s); break;
   }
   return tw_prof_after(s);
 }

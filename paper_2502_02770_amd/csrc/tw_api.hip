@@ -16,6 +16,8 @@ int tw_check_kv(const twilight_kv_t* kv, TwDims* d) {
   if (kv->num_pool_pages <= 0 || kv->num_pool_pages * kv->num_kv_heads * TW_PAGE > 0x7FFFFFFFll) return TW_EINVAL;
   if ((long long)kv->batch * kv->num_q_heads > 65535ll) return TW_EINVAL;   // grid.y limit
   if (!kv->page_table || !kv->seq_lens) return TW_EINVAL;
+  if (kv->quant_bits != 0 && kv->quant_bits != 2 && kv->quant_bits != 4 && kv->quant_bits != 8) return TW_EINVAL;
+  d->bits = kv->quant_bits ? kv->quant_bits : 4;
   d->batch = kv->batch; d->Hq = kv->num_q_heads; d->Hkv = kv->num_kv_heads; d->G = G;
   d->max_pages = kv->max_pages_per_seq; d->pool_pages = kv->num_pool_pages;
   return TW_OK;

@@ -11,7 +11,7 @@
 
 // ---------------------------------------------------------------- host side
 struct TwDims {
-  int batch, Hq, Hkv, G, max_pages;
+  int batch, Hq, Hkv, G, max_pages, bits;      // bits: width of the quantised K codes (2, 4, 8)
   long long pool_pages;
 };
 

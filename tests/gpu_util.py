@@ -8,11 +8,11 @@ from oracle import twilight_oracle as O
 from workloads import synth
 
 
-def build_cache(w, device="cuda", upto=None):
+def build_cache(w, device="cuda", upto=None, bits=4):
     """PagedKV filled through twilight_kquant_append from a workload."""
     import paper_2502_02770_amd as T
     cache = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, device,
-                      need_v=w.v.numel() > 0)
+                      need_v=w.v.numel() > 0, quant_bits=bits)
     k = w.k.to(device)
     v = w.v.to(device) if w.v.numel() else None
     cache.fill(k, v, w.seq_offsets)
@@ -30,12 +30,19 @@ def gather_logical(pool, page_table_row, n):
     return x[:n]
 
 
-def unpack_codes(kq):
-    """u8 [..., 64] packed as documented (word w, byte k: dim 8w+k low nibble, 8w+k+4 high) -> u8 [..., 128]."""
-    a = np.asarray(kq).reshape(*kq.shape[:-1], 16, 4)
-    lo = a & 0x0F
-    hi = a >> 4
-    return np.concatenate([lo, hi], axis=-1).reshape(*kq.shape[:-1], 128)
+def unpack_codes(kq, bits=4):
+    """u8 [..., 16*bits] packed as documented with twilight_kv_t -> codes u8 [..., 128]."""
+    lead = kq.shape[:-1]
+    a = np.asarray(kq)
+    if bits == 4:      # word w, byte k: dim 8w+k low nibble, 8w+k+4 high nibble
+        a = a.reshape(*lead, 16, 4)
+        return np.concatenate([a & 0x0F, a >> 4], axis=-1).reshape(*lead, 128)
+    if bits == 8:      # byte = code, in dim order
+        return a.reshape(*lead, 128)
+    # 2 bits: word w, byte i, bit pair k: dim 16w + 4k + i
+    a = a.reshape(*lead, 8, 1, 4)
+    k = np.arange(4, dtype=np.uint8).reshape(4, 1)
+    return ((a >> (2 * k)) & 3).reshape(*lead, 128)
 
 
 def u16(t):

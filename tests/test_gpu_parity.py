@@ -33,13 +33,13 @@ def small_workloads():
                               alpha_cycle=[0.0, 0.5, 2.0, 6.0], seed=7)
 
 
-def check_cache(w, cache):
+def check_cache(w, cache, bits=4):
     kq = cache.kq_pool.cpu(); meta = cache.kq_meta.cpu(); mm = cache.page_minmax.cpu()
     kp = cache.k_pool.cpu(); vp = cache.v_pool.cpu() if cache.v_pool is not None else None
     for b in range(w.batch):
         n = int(w.seq_lens[b])
         row = w.page_table[b]
-        codes = unpack_codes(gather_logical(kq, row, n).numpy())          # [n, Hkv, 128]
+        codes = unpack_codes(gather_logical(kq, row, n).numpy(), bits)    # [n, Hkv, 128]
         mt = gather_logical(meta, row, n)                                  # [n, Hkv, 4, 2] fp16
         kl = gather_logical(kp, row, n)
         assert torch.equal(kl.view(torch.int16), w.seq_k(b).view(torch.int16))
@@ -48,7 +48,7 @@ def check_cache(w, cache):
         P = (n + 15) // 16
         for g in range(w.num_kv_heads):
             kb = synth.bits(w.seq_k(b)[:, g])
-            u, s, z = O.quantize_k(kb)
+            u, s, z = O.quantize_k(kb, bits)
             assert np.array_equal(codes[:, g], u), (w.name, b, g)
             assert np.array_equal(u16(mt[:, g, :, 0]), s.view(np.uint16))
             assert np.array_equal(u16(mt[:, g, :, 1]), z.view(np.uint16))
@@ -118,7 +118,21 @@ def check_topp(kept_gpu, s_hat, cand, p):
 
 @pytest.mark.parametrize("w", list(small_workloads()), ids=lambda w: w.name)
 def test_pipeline_against_oracle(w):
-    cache = build_cache(w)
+    pipeline_against_oracle(w, 4)
+
+
+@pytest.mark.parametrize("bits", [2, 8])
+@pytest.mark.parametrize("w", [list(small_workloads())[i] for i in (0, 1, 3)], ids=lambda w: w.name)
+def test_other_estimator_widths_pipeline(w, bits):
+    """The 2- and 8-bit K copies of the paper's bit-width study (Section 4.2): codes, scale / zero,
+    integer dots and scores bit-exact, sets and outputs to the same bars as the 4-bit path."""
+    cache = build_cache(w, bits=bits)
+    check_cache(w, cache, bits)
+    pipeline_against_oracle(w, bits, cache)
+
+
+def pipeline_against_oracle(w, bits, cache=None):
+    cache = cache or build_cache(w, bits=bits)
     st, q = run_pipeline(w, cache)
     assert int(st.status.item()) == 0
     G = w.num_q_heads // w.num_kv_heads
@@ -127,7 +141,7 @@ def test_pipeline_against_oracle(w):
     out = st.out.cpu(); lse = st.lse.cpu().numpy()
     pscores = st.ws_select.cpu().numpy().view(np.float32)
     for b in range(w.batch):
-        r = oracle_seq(w, b)
+        r = oracle_seq(w, b, bits=bits)
         n = int(w.seq_lens[b])
         P = (n + 15) // 16
         for h in range(w.num_q_heads):
@@ -163,10 +177,11 @@ def test_pipeline_against_oracle(w):
                 assert abs(lse[b, h] - rl) <= 1e-3 * max(1.0, abs(rl))
 
 
-@pytest.mark.parametrize("w", list(small_workloads())[:2], ids=lambda w: w.name)
-def test_int4_dots_bit_exact_list_and_full(w):
+@pytest.mark.parametrize("bits", [4, 2, 8])
+@pytest.mark.parametrize("w", [list(small_workloads())[i] for i in (0, 1, 3)], ids=lambda w: w.name)
+def test_int4_dots_bit_exact_list_and_full(w, bits):
     T = _T()
-    cache = build_cache(w)
+    cache = build_cache(w, bits=bits)
     dev = cache.k_pool.device
     q = w.q.to(dev)
     # full mode: every page is a candidate, the G heads of a KV head share the loads
@@ -181,7 +196,7 @@ def test_int4_dots_bit_exact_list_and_full(w):
         n = int(w.seq_lens[b])
         for h in range(w.num_q_heads):
             kb = synth.bits(w.seq_k(b)[:, h // G])
-            u, s, z = O.quantize_k(kb)
+            u, s, z = O.quantize_k(kb, bits)
             qi, sq = O.quantize_q(synth.bits(w.q[b, h]))
             I, Qs = O.int4_dots(qi, u)
             assert np.array_equal(dots[b, h, :n], I)
