@@ -30,7 +30,7 @@ PAPER_CONTEXT = {"quest_twi_vs_fa2_attention_speedup": 15.8, "quest_twi_vs_quest
                  "hardware": "1x NVIDIA A100", "source": "Section 5.2"}
 
 
-def build_state(cfg_idx, scale, seed, batch, layers, bits=4):
+def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_selector=False):
     """`layers` independent copies of the layer's cache (same contents, different memory).  Successive steps
     rotate over them, as the layers of a model do, so that a step finds its pools in HBM and not in the
     256 MB memory-side cache left warm by the previous step over the very same addresses."""
@@ -39,6 +39,10 @@ def build_state(cfg_idx, scale, seed, batch, layers, bits=4):
     from workloads import synth
     t0 = time.time()
     w = synth.config(cfg_idx, scale=scale, seed=seed, batch=batch)
+    if p is not None:
+        w.p = float(p)
+    if full_selector:
+        w.full_selector = True          # no page selector: every token is a candidate of the pruner
     gen_s = time.time() - t0
     dev = "cuda:0"
     t0 = time.time()
@@ -154,6 +158,9 @@ def main():
                     help="independent copies of the cache that successive steps rotate over (1 = same memory every step)")
     ap.add_argument("--bits", type=int, default=4, choices=[2, 4, 8],
                     help="width of the quantised K copy the pruner scores from (4 = the method; 2 and 8: its bit-width study)")
+    ap.add_argument("--p", type=float, default=None, help="override the config's top-p threshold (C3 is swept over p)")
+    ap.add_argument("--full-selector", action="store_true",
+                    help="skip the page selector: the pruner sees every token (the paper's pruner on top of full attention)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--calib-copy", action="store_true",
@@ -167,7 +174,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits)
+    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits, a.p, a.full_selector)
     if a.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
@@ -250,6 +257,29 @@ def main():
     # a kernel id launched several times per step (the long-row top-p) is priced per step:
     # all its launches' time against the bytes the stage moves per step
     dom_calls = kcalls[dom]
+    # the two ways of sharing work inside a GQA group (Appendix B.2): every head over the group's union
+    # (built, used by the step) against every head over its own kept set
+    variants = None
+    if w.v.numel() and not st.full:
+        sv = T.DecodeStep(cache, max_sel=st.max_sel, with_kept_idx=True, with_lse=False)
+        sv.select(q, w.budget.to("cuda:0"))
+        sv.prune(q, w.p)
+        res = {}
+        for name, fn in (("group_union", sv.attend), ("per_head", sv.attend_per_head)):
+            for _ in range(3):
+                fn(q)
+            T.twilight_prof_enable(1)
+            for _ in range(20):
+                fn(q)
+            torch.cuda.synchronize()
+            r = T.twilight_prof_collect()
+            T.twilight_prof_enable(0)
+            res[name + "_us"] = sum(ms for k, ms in r) / 20 * 1e3            # decode + combine
+        res["group_union_rows"] = int(sv.union_count.sum().item())
+        res["per_head_rows"] = int(sv.kept_count.sum().item())
+        variants = res
+        del sv
+
     ach = nbytes[dom] / (dom_avg * dom_calls * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS,
@@ -275,7 +305,7 @@ def main():
         "config": {"workload": "%s: batch %d, %d q / %d kv heads, head_dim 128, context %s, page 16, budget %s, p=%g%s"
                                % (w.name, w.batch, w.num_q_heads, w.num_kv_heads,
                                   int(w.seq_lens[0]) if len(set(w.seq_lens.tolist())) == 1 else "ragged",
-                                  int(w.budget[0]) if len(set(w.budget.tolist())) == 1 else "n/8", w.p,
+                                  ("all tokens" if w.full_selector else int(w.budget[0])) if len(set(w.budget.tolist())) == 1 else "n/8", w.p,
                                   "" if a.scale == 1.0 else " (scale %g)" % a.scale),
                    "config_index": a.config, "seed": a.seed, "layers_rotated": max(1, a.layers)},
         "roofline": roofline,
@@ -287,6 +317,7 @@ def main():
         "workload_stats": stats,
         "estimator_bits": a.bits,
         "attention_mass_captured": captured,
+        "gqa_attention_variants": variants,
         "paper_context": PAPER_CONTEXT,
         "setup_seconds": setup,
     }

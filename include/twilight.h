@@ -205,12 +205,28 @@ int twilight_sparse_decode(const twilight_kv_t* kv, const void* q, const int32_t
                            const int32_t* union_idx, int32_t union_stride, void* out, float* lse,
                            void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * The "head-wise varlen" alternative of Appendix B.2: every query head
+ * attends over its OWN kept set instead of its group's union (same
+ * arithmetic, one list per query head; the K/V rows of a KV head are then
+ * loaded once per query head that kept them instead of once per group).
+ *   kept_count     i32 [batch][num_q_heads]
+ *   kept_idx       i32 [batch][num_q_heads][kept_stride], ascending token
+ *                  positions, as written by twilight_topp_prune
+ *   ws             >= twilight_workspace_bytes(TW_WS_DECODE_PER_HEAD, kv, 0, kept_stride)
+ */
+int twilight_sparse_decode_per_head(const twilight_kv_t* kv, const void* q, const int32_t* kept_count,
+                                    const int32_t* kept_idx, int32_t kept_stride, void* out, float* lse,
+                                    void* ws, size_t ws_bytes, void* stream);
+
 /* Workspace sizes (host-only query; no GPU needed). */
 #define TW_WS_SELECT 0
 #define TW_WS_PRUNE 1
 #define TW_WS_DECODE 2
+#define TW_WS_DECODE_PER_HEAD 3
 /*  max_sel: as passed to the call (0 with sel_pages == NULL);
- *  union_stride: as passed to sparse_decode (0 for dense). */
+ *  union_stride: as passed to sparse_decode (0 for dense), kept_stride for
+ *  TW_WS_DECODE_PER_HEAD. */
 size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, int32_t max_sel, int32_t union_stride);
 
 const char* twilight_strerror(int code);

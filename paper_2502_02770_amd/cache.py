@@ -72,6 +72,7 @@ class DecodeStep:
         self.out = torch.zeros(c.batch, c.Hq, 128, dtype=torch.bfloat16, device=dev)
         self.lse = torch.zeros(c.batch, c.Hq, dtype=torch.float32, device=dev) if with_lse else None
         self._ws_dense = None
+        self._ws_per_head = None
 
     def select(self, q, budget):
         B.twilight_select_pages(self.cache.kv, q, budget, self.sel_pages, self.sel_count, self.max_sel, self.ws_select)
@@ -84,6 +85,16 @@ class DecodeStep:
     def attend(self, q):
         B.twilight_sparse_decode(self.cache.kv, q, self.union_count, self.union_idx, self.union_stride, self.out,
                                  self.lse, self.ws_decode)
+
+    def attend_per_head(self, q):
+        """Every query head over its own kept set (needs with_kept_idx=True) instead of the group's union."""
+        assert self.kept_idx is not None, "DecodeStep(with_kept_idx=True) keeps the per-head lists"
+        if self._ws_per_head is None:
+            self._ws_per_head = torch.empty(
+                B.twilight_workspace_bytes(B.TW_WS_DECODE_PER_HEAD, self.cache.kv, 0, self.kept_stride),
+                dtype=torch.uint8, device=self.out.device)
+        B.twilight_sparse_decode_per_head(self.cache.kv, q, self.kept_count, self.kept_idx, self.kept_stride,
+                                          self.out, self.lse, self._ws_per_head)
 
     def run(self, q, budget, p):
         if not self.full:

@@ -13,6 +13,9 @@
 // of the group share every loaded row, and each 16-lane row keeps its own
 // online-softmax state; states are merged by log-sum-exp, first inside the
 // workgroup, then across items by the combine kernel.
+//
+// The same kernel serves the per-head variant ("head-wise varlen" of Appendix
+// B.2): one list per query head, G = 1, list l reads KV head l / group size.
 #include <stdlib.h>
 #include "tw_common.h"
 
@@ -37,6 +40,7 @@ struct DecodeArgs {
   float2* ws_ml;              // [items][G]
   float4* ws_acc;             // [items][G][32 x float4]
   int Hq, Hkv, max_pages, union_stride, NG, chunk;
+  int LH, kv_div;             // lists per sequence (Hkv, or Hq with one list per query head); list l reads KV head l / kv_div
   long long pool_pages;
 };
 
@@ -72,7 +76,7 @@ __global__ __launch_bounds__(256, WPS) void sparse_decode_kernel(DecodeArgs a) {
   const int c0 = a.chunk;
   for (int gi = tid; gi < a.NG; gi += 256) {
     int cnt;
-    if (dense) { cnt = a.seq_lens[gi / a.Hkv]; if (cnt > a.max_pages * TW_PAGE) cnt = a.max_pages * TW_PAGE; }
+    if (dense) { cnt = a.seq_lens[gi / a.LH]; if (cnt > a.max_pages * TW_PAGE) cnt = a.max_pages * TW_PAGE; }
     else { cnt = a.union_count[gi]; if (cnt > a.union_stride) cnt = a.union_stride; }
     if (cnt < 0) cnt = 0;
     n0 += (cnt + c0 - 1) / c0; n1 += (cnt + 2 * c0 - 1) / (2 * c0); n2 += (cnt + 4 * c0 - 1) / (4 * c0);
@@ -95,7 +99,7 @@ __global__ __launch_bounds__(256, WPS) void sparse_decode_kernel(DecodeArgs a) {
     uint32_t c = 0;
     if (gi < a.NG) {
       int cnt;
-      if (dense) { cnt = a.seq_lens[gi / a.Hkv]; if (cnt > a.max_pages * TW_PAGE) cnt = a.max_pages * TW_PAGE; }
+      if (dense) { cnt = a.seq_lens[gi / a.LH]; if (cnt > a.max_pages * TW_PAGE) cnt = a.max_pages * TW_PAGE; }
       else { cnt = a.union_count[gi]; if (cnt > a.union_stride) cnt = a.union_stride; }
       if (cnt < 0) cnt = 0;
       c = (uint32_t)((cnt + chunk - 1) / chunk);
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(256, WPS) void sparse_decode_kernel(DecodeArgs a) {
     // group of this item: last gi with prefix[gi] <= item
     int lo = 0, hi = a.NG;
     while (hi - lo > 1) { const int mid = (lo + hi) >> 1; if (prefix[mid] <= item) lo = mid; else hi = mid; }
-    const int gi = lo, b = gi / a.Hkv, g = gi % a.Hkv;
+    const int gi = lo, b = gi / a.LH, l = gi % a.LH, g = l / a.kv_div;   // list l of sequence b, KV head g
     const int ck = item - prefix[gi];
     const int nchunks = prefix[gi + 1] - prefix[gi];
     int cnt;
@@ -141,7 +145,7 @@ __global__ __launch_bounds__(256, WPS) void sparse_decode_kernel(DecodeArgs a) {
     float q[G][8];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      const uint4 r = a.q[((long long)(b * a.Hq + g * G + h)) * 16 + seg];
+      const uint4 r = a.q[((long long)(b * a.Hq + l * G + h)) * 16 + seg];
       tw_unpack8(r, q[h]);
 #pragma unroll
       for (int i = 0; i < 8; ++i) q[h][i] *= kLog2eRsqrtD;
@@ -305,7 +309,7 @@ __global__ __launch_bounds__(256, WPS) void sparse_decode_kernel(DecodeArgs a) {
           ox += v.x; oy += v.y;
           L += ml_s[w][h];
         }
-        const int qh = b * a.Hq + g * G + h;
+        const int qh = b * a.Hq + l * G + h;
         if (nchunks == 1) {                     // the item is the whole list: final result
           const float inv = L > 0.f ? 1.0f / L : 0.f;
           ((uint32_t*)a.out)[(long long)qh * 64 + d2] = tw_f32_to_bf16(ox * inv) | (tw_f32_to_bf16(oy * inv) << 16);
@@ -422,35 +426,39 @@ long long tw_decode_max_items(const TwDims& d, bool dense, int union_stride) {
   return (long long)d.batch * d.Hkv * ((max_len + chunk - 1) / chunk);
 }
 
-extern "C" int twilight_sparse_decode(const twilight_kv_t* kv, const void* q, const int32_t* union_count,
-                                      const int32_t* union_idx, int32_t union_stride, void* out, float* lse,
-                                      void* ws, size_t ws_bytes, void* stream) {
+static int decode_impl(const twilight_kv_t* kv, const void* q, const int32_t* count, const int32_t* idx, int32_t stride,
+                       void* out, float* lse, void* ws, size_t ws_bytes, void* stream, bool per_head) {
   TwDims d;
   if (int e = tw_check_kv(kv, &d)) return e;
   if (!q || !out || !kv->k_pool || !kv->v_pool) return TW_EINVAL;
-  const bool dense = union_idx == nullptr;
-  if (!dense && (!union_count || union_stride <= 0)) return TW_EINVAL;
-  const int NG = d.batch * d.Hkv;
+  const bool dense = idx == nullptr;
+  if (per_head && dense) return TW_EINVAL;
+  if (!dense && (!count || stride <= 0)) return TW_EINVAL;
+  // one list per KV head shared by its G query heads, or one list per query head
+  const int LH = per_head ? d.Hq : d.Hkv, Gk = per_head ? 1 : d.G;
+  const int NG = d.batch * LH;
   if (NG > 12000) return TW_EINVAL;             // item map must fit in LDS
-  if (!ws || ws_bytes < twilight_workspace_bytes(TW_WS_DECODE, kv, 0, dense ? 0 : union_stride)) return TW_EWORKSPACE;
+  if (!ws || ws_bytes < twilight_workspace_bytes(per_head ? TW_WS_DECODE_PER_HEAD : TW_WS_DECODE, kv, 0, dense ? 0 : stride))
+    return TW_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
 
-  const long long max_items = tw_decode_max_items(d, dense, union_stride);
+  const long long max_items = tw_decode_max_items(d, dense, stride) / d.Hkv * LH;
   const size_t prefix_bytes = (((size_t)(NG + 1) * 4) + 255) & ~(size_t)255;
-  const size_t ml_bytes = (((size_t)max_items * d.G * 8) + 255) & ~(size_t)255;
+  const size_t ml_bytes = (((size_t)max_items * Gk * 8) + 255) & ~(size_t)255;
   DecodeArgs a;
   a.q = (const uint4*)q; a.k_pool = (const uint4*)kv->k_pool; a.v_pool = (const uint4*)kv->v_pool;
   a.page_table = kv->page_table; a.seq_lens = kv->seq_lens;
-  a.union_count = dense ? nullptr : union_count; a.union_idx = union_idx;
+  a.union_count = dense ? nullptr : count; a.union_idx = idx;
   a.out = (uint4*)out; a.lse = lse;
   a.ws_prefix = (int32_t*)ws;
   a.ws_ml = (float2*)((char*)ws + prefix_bytes);
   a.ws_acc = (float4*)((char*)ws + prefix_bytes + ml_bytes);
-  a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.union_stride = union_stride;
+  a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.union_stride = stride;
+  a.LH = LH; a.kv_div = per_head ? d.G : 1;
   a.NG = NG; a.chunk = tw_decode_chunk(dense); a.pool_pages = d.pool_pages;
   const size_t lds = (size_t)(NG + 1) * 4;
   tw_prof_before(TW_K_DECODE, s);
-  switch (d.G) {
+  switch (Gk) {
     case 1: launch_decode<1>(a, max_items, lds, s); break;
     case 2: launch_decode<2>(a, max_items, lds, s); break;
     case 4: launch_decode<4>(a, max_items, lds, s); break;
@@ -460,8 +468,20 @@ extern "C" int twilight_sparse_decode(const twilight_kv_t* kv, const void* q, co
 
   CombineArgs c;
   c.ws_prefix = a.ws_prefix; c.ws_ml = a.ws_ml; c.ws_acc = (const float*)a.ws_acc;
-  c.out = (uint16_t*)out; c.lse = lse; c.Hq = d.Hq; c.Hkv = d.Hkv; c.G = d.G;
+  c.out = (uint16_t*)out; c.lse = lse; c.Hq = d.Hq; c.Hkv = LH; c.G = Gk;
   tw_prof_before(TW_K_COMBINE, s);
   hipLaunchKernelGGL(combine_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, c);
   return tw_prof_after(s);
+}
+
+extern "C" int twilight_sparse_decode(const twilight_kv_t* kv, const void* q, const int32_t* union_count,
+                                      const int32_t* union_idx, int32_t union_stride, void* out, float* lse,
+                                      void* ws, size_t ws_bytes, void* stream) {
+  return decode_impl(kv, q, union_count, union_idx, union_stride, out, lse, ws, ws_bytes, stream, false);
+}
+
+extern "C" int twilight_sparse_decode_per_head(const twilight_kv_t* kv, const void* q, const int32_t* kept_count,
+                                               const int32_t* kept_idx, int32_t kept_stride, void* out, float* lse,
+                                               void* ws, size_t ws_bytes, void* stream) {
+  return decode_impl(kv, q, kept_count, kept_idx, kept_stride, out, lse, ws, ws_bytes, stream, true);
 }

@@ -59,6 +59,11 @@ extern "C" size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, i
       const size_t items = (size_t)tw_decode_max_items(d, dense, union_stride);
       return align256((size_t)(d.batch * d.Hkv + 1) * 4) + align256(items * d.G * 8) + align256(items * d.G * 128 * 4);
     }
+    case TW_WS_DECODE_PER_HEAD: {
+      if (union_stride <= 0) return 0;
+      const size_t items = (size_t)tw_decode_max_items(d, false, union_stride) / d.Hkv * d.Hq;
+      return align256((size_t)(d.batch * d.Hq + 1) * 4) + align256(items * 8) + align256(items * 128 * 4);
+    }
     default:
       return 0;
   }

@@ -297,6 +297,28 @@ def test_attention_with_oracle_sets_and_dense():
         assert np.allclose(l[b], rl, rtol=1e-3, atol=1e-3)
 
 
+@pytest.mark.parametrize("w", [list(small_workloads())[i] for i in (1, 3)], ids=lambda w: w.name)
+def test_per_head_attention_variant(w):
+    """Head-wise varlen (Appendix B.2's alternative): each query head attends over its own kept set.
+    Same arithmetic as Definition 3.1 on that set; compared with the oracle's attention over it."""
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache)
+    st.attend_per_head(q)
+    torch.cuda.synchronize()
+    out = st.out.cpu(); lse = st.lse.cpu().numpy()
+    G = w.num_q_heads // w.num_kv_heads
+    for b in range(w.batch):
+        for h in range(w.num_q_heads):
+            g = h // G
+            kept = st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+            ref, rl = O.attention(synth.bits(w.q[b, h]), synth.bits(w.seq_k(b)[:, g]), synth.bits(w.seq_v(b)[:, g]), kept)
+            ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
+            got = out[b, h].float().numpy().astype(np.float64)
+            assert np.abs(got - ref).max() <= MAX_ABS
+            assert np.linalg.norm(got - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
+            assert abs(lse[b, h] - rl) <= 1e-3 * max(1.0, abs(rl))
+
+
 def test_p1_full_budget_reproduces_dense_attention():
     T = _T()
     w = synth.make_workload("p1", [530, 99], budget=10 ** 6, p=1.0, shuffle_pool=True, seed=17)
