@@ -30,7 +30,7 @@ PAPER_CONTEXT = {"quest_twi_vs_fa2_attention_speedup": 15.8, "quest_twi_vs_quest
                  "hardware": "1x NVIDIA A100", "source": "Section 5.2"}
 
 
-def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_selector=False):
+def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_selector=False, offload=False):
     """`layers` independent copies of the layer's cache (same contents, different memory).  Successive steps
     rotate over them, as the layers of a model do, so that a step finds its pools in HBM and not in the
     256 MB memory-side cache left warm by the previous step over the very same addresses."""
@@ -56,7 +56,7 @@ def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_select
     caches, steps = [], []
     for _ in range(layers):
         cache = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev,
-                          need_v=w.v.numel() > 0, quant_bits=bits)
+                          need_v=w.v.numel() > 0, quant_bits=bits, offload_kv=offload)
         # prefill: every token but the last of each sequence; the step appends the last one
         cache.append(k, v, start, cache.seq_lens - 1, offs, int(w.seq_lens.max()) - 1)
         caches.append(cache)
@@ -161,6 +161,8 @@ def main():
     ap.add_argument("--p", type=float, default=None, help="override the config's top-p threshold (C3 is swept over p)")
     ap.add_argument("--full-selector", action="store_true",
                     help="skip the page selector: the pruner sees every token (the paper's pruner on top of full attention)")
+    ap.add_argument("--offload", action="store_true",
+                    help="bf16 K/V pools in pinned host memory (the paper's offloading scenario); attention is then bound by the host link")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--calib-copy", action="store_true",
@@ -174,7 +176,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits, a.p, a.full_selector)
+    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits, a.p, a.full_selector, a.offload)
     if a.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
@@ -307,7 +309,8 @@ def main():
                                   int(w.seq_lens[0]) if len(set(w.seq_lens.tolist())) == 1 else "ragged",
                                   ("all tokens" if w.full_selector else int(w.budget[0])) if len(set(w.budget.tolist())) == 1 else "n/8", w.p,
                                   "" if a.scale == 1.0 else " (scale %g)" % a.scale),
-                   "config_index": a.config, "seed": a.seed, "layers_rotated": max(1, a.layers)},
+                   "config_index": a.config, "seed": a.seed, "layers_rotated": max(1, a.layers),
+                   "kv_offloaded_to_host": bool(a.offload)},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "us_per_layer_events_off": ms_plain * 1e3,

@@ -229,6 +229,17 @@ int twilight_sparse_decode_per_head(const twilight_kv_t* kv, const void* q, cons
  *  TW_WS_DECODE_PER_HEAD. */
 size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, int32_t max_sel, int32_t union_stride);
 
+/*
+ * Offloaded KV cache (the paper's offloading scenario, its appendix on
+ * efficiency with the KV cache in CPU memory): k_pool / v_pool may live in
+ * PINNED HOST memory (hipHostMalloc); the kernels then fetch only the rows of
+ * the kept tokens over the host link, while the quantised K copy, its
+ * scale/zero and the page bounds stay in device memory.  This call returns
+ * the device-side address of such an allocation (hipHostGetDevicePointer) for
+ * use in twilight_kv_t; TW_EINVAL if host_ptr (host) is not mapped pinned memory.
+ */
+int twilight_pinned_device_pointer(void* host_ptr, void** device_ptr /* host, out */);
+
 const char* twilight_strerror(int code);
 int twilight_abi_version(void);
 

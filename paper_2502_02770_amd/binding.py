@@ -51,6 +51,8 @@ def lib():
     L.twilight_sparse_decode.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
     L.twilight_sparse_decode_per_head.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
     L.twilight_workspace_bytes.argtypes = [ctypes.c_int, kvp, _i32, _i32]
+    L.twilight_pinned_device_pointer.argtypes = [_vp, ctypes.POINTER(_vp)]
+    L.twilight_pinned_device_pointer.restype = ctypes.c_int
     L.twilight_workspace_bytes.restype = _sz
     L.twilight_strerror.argtypes = [ctypes.c_int]
     L.twilight_strerror.restype = ctypes.c_char_p
@@ -92,8 +94,21 @@ def make_kv(batch, num_q_heads, num_kv_heads, max_pages_per_seq, num_pool_pages,
     kv.max_pages_per_seq, kv.quant_bits, kv.num_pool_pages = max_pages_per_seq, quant_bits, num_pool_pages
     for name, t in (("page_table", page_table), ("seq_lens", seq_lens), ("k_pool", k_pool), ("v_pool", v_pool),
                     ("kq_pool", kq_pool), ("kq_meta", kq_meta), ("page_minmax", page_minmax)):
-        setattr(kv, name, None if t is None else t.data_ptr())
+        if t is None:
+            setattr(kv, name, None)
+        elif t.is_cuda:
+            setattr(kv, name, t.data_ptr())
+        else:                                       # offloaded K/V: pinned host memory, addressed from the device
+            assert name in ("k_pool", "v_pool") and t.is_pinned(), "only k_pool / v_pool may be (pinned) host tensors"
+            setattr(kv, name, pinned_device_pointer(t))
     return kv
+
+
+def pinned_device_pointer(t):
+    """Device-side address of a pinned host tensor (twilight_pinned_device_pointer)."""
+    out = ctypes.c_void_p()
+    _check(lib().twilight_pinned_device_pointer(ctypes.c_void_p(t.data_ptr()), ctypes.byref(out)))
+    return out.value
 
 
 def twilight_workspace_bytes(which, kv, max_sel=0, union_stride=0):

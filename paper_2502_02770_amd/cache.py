@@ -12,7 +12,7 @@ class PagedKV:
     """The pools of include/twilight.h's twilight_kv_t, owned as torch tensors."""
 
     def __init__(self, num_q_heads, num_kv_heads, page_table, seq_lens, num_pool_pages, device="cuda",
-                 need_v=True, quant_bits=4):
+                 need_v=True, quant_bits=4, offload_kv=False):
         dev = torch.device(device)
         self.Hq, self.Hkv = int(num_q_heads), int(num_kv_heads)
         self.page_table = page_table.to(dev, torch.int32).contiguous()
@@ -20,8 +20,11 @@ class PagedKV:
         self.batch, self.max_pages = self.page_table.shape
         self.num_pool_pages = int(num_pool_pages)
         P, H = self.num_pool_pages, self.Hkv
-        self.k_pool = torch.zeros(P, H, 16, 128, dtype=torch.bfloat16, device=dev)
-        self.v_pool = torch.zeros(P, H, 16, 128, dtype=torch.bfloat16, device=dev) if need_v else None
+        # offload_kv: the bf16 K/V pools live in pinned host memory and are read over the host link
+        kv_args = dict(dtype=torch.bfloat16, pin_memory=True) if offload_kv else dict(dtype=torch.bfloat16, device=dev)
+        self.device = dev
+        self.k_pool = torch.zeros(P, H, 16, 128, **kv_args)
+        self.v_pool = torch.zeros(P, H, 16, 128, **kv_args) if need_v else None
         self.quant_bits = int(quant_bits)
         self.kq_pool = torch.zeros(P, H, 16, 16 * self.quant_bits, dtype=torch.uint8, device=dev)
         self.kq_meta = torch.zeros(P, H, 16, 4, 2, dtype=torch.float16, device=dev)
@@ -36,7 +39,7 @@ class PagedKV:
 
     def fill(self, k, v, seq_offsets):
         """Build the whole cache from logical K/V [total, Hkv, 128] (sequences concatenated)."""
-        dev = self.k_pool.device
+        dev = self.device
         start = torch.zeros(self.batch, dtype=torch.int32, device=dev)
         offs = torch.tensor(seq_offsets[:-1], dtype=torch.int32, device=dev)
         self.append(k, v, start, self.seq_lens, offs, int(self.seq_lens.max().item()))
@@ -47,7 +50,7 @@ class DecodeStep:
     select -> prune -> attend through the C ABI."""
 
     def __init__(self, cache, max_sel=None, union_stride=None, with_kept_idx=False, with_lse=True):
-        c, dev = cache, cache.k_pool.device
+        c, dev = cache, cache.device
         self.cache = c
         self.full = max_sel is None
         self.max_sel = 0 if self.full else int(max_sel)
@@ -108,7 +111,7 @@ class DecodeStep:
         c = self.cache
         if self._ws_dense is None:
             self._ws_dense = torch.empty(B.twilight_workspace_bytes(B.TW_WS_DECODE, c.kv, 0, 0), dtype=torch.uint8,
-                                         device=c.k_pool.device)
+                                         device=c.device)
         out = self.out if out is None else out
         B.twilight_sparse_decode(c.kv, q, None, None, 0, out, lse, self._ws_dense)
         return out

@@ -37,6 +37,17 @@ int tw_num_cus() {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+extern "C" int twilight_pinned_device_pointer(void* host_ptr, void** device_ptr) {
+  if (!host_ptr || !device_ptr) return TW_EINVAL;
+  void* dp = nullptr;
+  if (hipHostGetDevicePointer(&dp, host_ptr, 0) != hipSuccess || !dp) {
+    (void)hipGetLastError();                       // not pinned / not mapped: leave no sticky error behind
+    return TW_EINVAL;
+  }
+  *device_ptr = dp;
+  return TW_OK;
+}
+
 extern "C" size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, int32_t max_sel, int32_t union_stride) {
   TwDims d;
   // the pointers are not needed for sizing: check the shape fields only

@@ -84,7 +84,7 @@ def test_kquant_incremental_append_equals_bulk():
 
 def run_pipeline(w, cache, with_kept=True):
     T = _T()
-    dev = cache.k_pool.device
+    dev = cache.device
     max_sel = None if w.full_selector else int(max(-(-int(b) // 16) for b in w.budget))
     if max_sel is not None:
         max_sel = min(max_sel, cache.max_pages)
@@ -182,7 +182,7 @@ def pipeline_against_oracle(w, bits, cache=None):
 def test_int4_dots_bit_exact_list_and_full(w, bits):
     T = _T()
     cache = build_cache(w, bits=bits)
-    dev = cache.k_pool.device
+    dev = cache.device
     q = w.q.to(dev)
     # full mode: every page is a candidate, the G heads of a KV head share the loads
     stride = cache.max_pages * 16
@@ -257,7 +257,7 @@ def test_attention_with_oracle_sets_and_dense():
     T = _T()
     w = synth.make_workload("attn", [1300, 70, 640], budget=lambda n: n // 2, p=0.9, shuffle_pool=True, seed=13)
     cache = build_cache(w)
-    dev = cache.k_pool.device
+    dev = cache.device
     q = w.q.to(dev)
     G = w.num_q_heads // w.num_kv_heads
     rs = [oracle_seq(w, b) for b in range(w.batch)]
@@ -317,6 +317,28 @@ def test_per_head_attention_variant(w):
             assert np.abs(got - ref).max() <= MAX_ABS
             assert np.linalg.norm(got - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
             assert abs(lse[b, h] - rl) <= 1e-3 * max(1.0, abs(rl))
+
+
+def test_offloaded_kv_in_pinned_host_memory():
+    """The offloading scenario: bf16 K/V pools in pinned host memory, fetched row by row by the same
+    kernels; quantised copy and page bounds on the device.  Same arithmetic, so results equal the
+    device-resident run bit for bit, and the cache contents equal the oracle's."""
+    T = _T()
+    w = list(small_workloads())[1]
+    ref_cache = build_cache(w)
+    st_ref, q = run_pipeline(w, ref_cache)
+    cache = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, "cuda", offload_kv=True)
+    assert cache.k_pool.is_pinned() and not cache.k_pool.is_cuda
+    cache.fill(w.k.to("cuda"), w.v.to("cuda"), w.seq_offsets)
+    torch.cuda.synchronize()
+    check_cache(w, cache)
+    st, q = run_pipeline(w, cache)
+    assert torch.equal(st.union_count, st_ref.union_count) and torch.equal(st.kept_count, st_ref.kept_count)
+    assert torch.equal(st.out.view(torch.int16), st_ref.out.view(torch.int16))
+    st.dense(q)
+    st_ref.dense(q)
+    torch.cuda.synchronize()
+    assert torch.equal(st.out.view(torch.int16), st_ref.out.view(torch.int16))
 
 
 def test_p1_full_budget_reproduces_dense_attention():
@@ -495,7 +517,7 @@ def test_empty_sequence_in_batch_and_zero_budget():
     T = _T()
     w = synth.make_workload("empty", [300, 1, 64], budget=[64, 16, 0], p=0.9, shuffle_pool=True, seed=29)
     cache = build_cache(w)
-    dev = cache.k_pool.device
+    dev = cache.device
     cache.seq_lens[1] = 0                                          # sequence 1 is empty for this step
     st = T.DecodeStep(cache, max_sel=8, with_kept_idx=True)
     q = w.q.to(dev)
