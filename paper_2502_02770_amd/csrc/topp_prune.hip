@@ -1,16 +1,22 @@
 // Stage 2: the Twilight pruner (paper: Section 4.2, Algorithm 1,
 // Definition 3.3, Appendix B.1 and B.2).
 //
-// int4_score  estimated logits from the INT4 K copy.  One wave = one page per
-//             step: 64 lanes x 16 B = the page's 1 KiB of codes, lane =
-//             (token, group of 32 dims); 8 integer dot4 per lane and head,
-//             scale/zero applied per group, quad DPP sum over the 4 groups.
-// topp        per (sequence, query head): max, then a radix bisection of the
-//             threshold on the fixed-point distance to the max logit (11 bits
-//             per pass, masses in 64-bit fixed point so that sums do not
-//             depend on the order of the atomics), finished by an exact
-//             resolve on the score's own bit pattern inside one wave.
-// union       per (sequence, KV head): bitmap in LDS, ordered emit.
+// int4_score       estimated logits from the quantised K copy.  One wave = one
+//                  page per step: 64 lanes x 16 B = the page's 1 KiB of codes,
+//                  lane = (token, group of 32 dims); 8 integer dot4 per lane
+//                  and head, scale/zero applied per group, quad DPP sum over
+//                  the 4 groups.  Templated on the code width (2 / 4 / 8 bits).
+// int4_score_mfma  the same scores on the matrix cores, used when every page
+//                  is a candidate and 4 or 8 query heads share each page.
+// topp_head        per (sequence, query head), scores in registers: max, then
+//                  a mass histogram over the fixed-point distance to the max
+//                  logit narrows the threshold 9 bits per pass (masses in
+//                  64-bit fixed point, so sums do not depend on the order of
+//                  the atomics), finished by an exact resolve on the scores'
+//                  own bit patterns inside one wave.  Kept tokens go to a
+//                  bitmap; the last head of a KV group to finish ORs the
+//                  group's bitmaps into the sorted union list.
+// Rows too long for registers take the multi-workgroup path in topp_wide.hip.
 #include <stdlib.h>
 #include "topp_common.h"
 
@@ -337,16 +343,17 @@ __global__ __launch_bounds__(256) void int4_score_mfma_kernel(ScoreArgs a) {
 }
 
 // ------------------------------------------------------------------ top-p per head, scores in registers
-// One workgroup (256 or 512 threads) per (sequence, query head); thread t owns the
-// contiguous candidate slots [t*EPT, (t+1)*EPT) (whole pages).  Rank (fixed-
-// point distance to the max logit) and softmax numerator of every score are
-// computed once and stay in registers.  Pass 0 buckets the ranks within 8
-// logits of the max at 1/64 logit and only sums up everything further down
-// (no atomics); the crossing bucket is narrowed 9 bits per pass until at most
-// HP_CAP scores remain, which are resolved exactly on the score's own bits.
-// Every wave scans the histogram on its own, so a pass costs one barrier.
-// The kept tokens are written as a bitmap over token positions, which
-// bitmap_union_kernel turns into the sorted union of a KV head's query heads.
+// One workgroup (1024 threads, or 512 for the short rows of a split launch) per
+// (sequence, query head); thread t owns the contiguous candidate slots
+// [t*EPT, (t+1)*EPT).  Rank (fixed-point distance to the max logit) and softmax
+// numerator of every score are computed once and stay in registers.  Pass 0
+// buckets the ranks within 8 logits of the max at 1/64 logit and only sums up
+// everything further down (no atomics); the crossing bucket is narrowed 9 bits
+// per pass until at most HP_CAP scores remain, which are resolved exactly on the
+// score's own bits.  Every wave scans the histogram on its own, so a pass costs
+// one barrier.  The kept tokens are written as a bitmap over token positions;
+// the last head of a KV group to arrive turns the group's bitmaps into the
+// sorted union.
 struct HeadArgs {
   const float* scores;
   const int32_t* sel_pages;

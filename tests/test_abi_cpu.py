@@ -40,6 +40,9 @@ def test_workspace_sizes(T):
     sparse = T.twilight_workspace_bytes(2, kv, 0, 16384)
     assert sparse >= 64 * (16384 // 64) * 4 * 130 * 4
     assert T.twilight_workspace_bytes(2, kv, 0, 0) > 0
+    # one list per query head instead of one per KV head: same partials in total for the same stride
+    per_head = T.twilight_workspace_bytes(3, kv, 0, 16384)
+    assert per_head >= 8 * 32 * (16384 // 64) * 130 * 4 and T.twilight_workspace_bytes(3, kv, 0, 0) == 0
     bad = T.make_kv(8, 32, 5, 2048, 16384, None, None)           # 32 q heads over 5 kv heads
     assert T.twilight_workspace_bytes(0, bad, 256, 0) == 0
 
@@ -62,5 +65,20 @@ def test_bad_arguments_are_rejected_on_the_host(T):
     assert L.twilight_sparse_decode(ctypes.byref(kv), one, None, one, 64, one, None, one, 1 << 20, None) == -1
     assert L.twilight_sparse_decode(ctypes.byref(kv), one, one, one, 64, one, None, one, 8, None) == -2
     assert L.twilight_int4_score(ctypes.byref(kv), one, one, None, 4, one, None, None) == -1
+    # per-head variant: no dense mode, needs counts, checks its own workspace size
+    assert L.twilight_sparse_decode_per_head(ctypes.byref(kv), one, one, None, 64, one, None, one, 1 << 20, None) == -1
+    assert L.twilight_sparse_decode_per_head(ctypes.byref(kv), one, None, one, 64, one, None, one, 1 << 20, None) == -1
+    assert L.twilight_sparse_decode_per_head(ctypes.byref(kv), one, one, one, 64, one, None, one, 8, None) == -2
+    # code width of the quantised K copy: 0 (= 4), 2, 4, 8 only
+    kv.quant_bits = 3
+    assert L.twilight_select_pages(ctypes.byref(kv), one, one, one, one, 4, one, 1 << 20, None) == -1
+    assert T.twilight_workspace_bytes(0, kv, 4, 0) == 0
+    kv.quant_bits = 8
+    assert T.twilight_workspace_bytes(0, kv, 4, 0) > 0
+    kv.quant_bits = 4
+    # pinned-pointer query: NULL arguments
+    out = ctypes.c_void_p()
+    assert L.twilight_pinned_device_pointer(None, ctypes.byref(out)) == -1
+    assert L.twilight_pinned_device_pointer(one, None) == -1
     with pytest.raises(T.TwilightError):
         T.binding._check(-3)
