@@ -31,6 +31,8 @@ def small_workloads():
                               shuffle_pool=True, seed=6)
     yield synth.make_workload("gqa8", [1500], num_q_heads=16, num_kv_heads=2, budget=512, p=0.95,
                               alpha_cycle=[0.0, 0.5, 2.0, 6.0], seed=7)
+    yield synth.make_workload("gqa2", [900, 130], num_q_heads=8, num_kv_heads=4, budget=320, p=0.85,
+                              heavy_frac=0.02, alpha_range=(0.5, 3.0), shuffle_pool=True, seed=8)
 
 
 def check_cache(w, cache, bits=4):
@@ -339,6 +341,52 @@ def test_offloaded_kv_in_pinned_host_memory():
     st_ref.dense(q)
     torch.cuda.synchronize()
     assert torch.equal(st.out.view(torch.int16), st_ref.out.view(torch.int16))
+
+
+def test_step_replays_from_a_hip_graph():
+    """No call allocates, synchronises or copies: the whole step (append, select, prune, attend) can be
+    captured into a graph.  Replayed several times with eager work in between, every replay must equal
+    the eager result."""
+    T = _T()
+    w = list(small_workloads())[1]
+    cache = build_cache(w)
+    dev = cache.device
+    st = T.DecodeStep(cache, max_sel=int(max(-(-int(b) // 16) for b in w.budget)), with_kept_idx=True)
+    q = w.q.to(dev)
+    budget = w.budget.to(dev)
+    last = torch.tensor([w.seq_offsets[b + 1] - 1 for b in range(w.batch)], dtype=torch.int64, device=dev)
+    k_last, v_last = w.k.to(dev)[last].contiguous(), w.v.to(dev)[last].contiguous()
+    pos = (cache.seq_lens - 1).contiguous()
+    one = torch.ones(w.batch, dtype=torch.int32, device=dev)
+    rows = torch.arange(w.batch, dtype=torch.int32, device=dev)
+
+    def step():
+        cache.append(k_last, v_last, pos, one, rows, 1)
+        st.run(q, budget, w.p)
+
+    step()                                             # eager reference (also warms one-time host queries)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (st.out, st.lse, st.kept_count, st.kept_idx, st.union_count, st.union_idx, st.sel_pages)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for i in range(4):
+        for t in (st.out, st.lse, st.kept_count, st.union_count):
+            t.fill_(7)                                 # eager work between replays: results must be rewritten
+        scratch = torch.randn(1 << 16, device=dev).sum()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        now = (st.out, st.lse, st.kept_count, st.kept_idx, st.union_count, st.union_idx, st.sel_pages)
+        for a, b in zip(now, ref):
+            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a, b.view(torch.int32) if b.dtype == torch.float32 else b), i
+        del scratch
 
 
 def test_p1_full_budget_reproduces_dense_attention():
