@@ -25,6 +25,11 @@ TRAFFIC_C2 = {"page_score": 33111 * 2048 + 2062 * 1024, "int4_score": 20585 * 20
               "sparse_decode": 19725 * 2048 + 1282 * 1024, "topp": 2786 * 2048 + 1343 * 1024,
               "page_select": 1080 * 2048 + 264 * 1024}
 
+# Median kernel durations (us) of the same C2 step under rocprofv3 --kernel-trace, from
+# profiles/c2_decode_step_kernel_trace.md: an event pair brackets dispatch latency too and reads ~2.5-3.5 us more.
+ROCPROF_US_C2 = {"page_score": 17.2, "int4_score": 14.8, "sparse_decode": 15.3, "topp": 11.6, "page_select": 8.4,
+                 "kquant_append": 5.2, "combine": 3.9}
+
 # Paper context (another machine: one A100, FP16 KV, LongBench-derived prompts) - not a target.
 PAPER_CONTEXT = {"quest_twi_vs_fa2_attention_speedup": 15.8, "quest_twi_vs_quest": 1.4,
                  "hardware": "1x NVIDIA A100", "source": "Section 5.2"}
@@ -163,6 +168,7 @@ def main():
                     help="skip the page selector: the pruner sees every token (the paper's pruner on top of full attention)")
     ap.add_argument("--offload", action="store_true",
                     help="bf16 K/V pools in pinned host memory (the paper's offloading scenario); attention is then bound by the host link")
+    ap.add_argument("--graph", action="store_true", help="also time the steps replayed from HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel table to stderr")
     ap.add_argument("--calib-copy", action="store_true",
@@ -234,6 +240,31 @@ def main():
     dom_ms = [ms for name, ms in recs if name == dom]
     dom_avg = sum(dom_ms) / len(dom_ms)
 
+    # the same steps replayed from HIP graphs (one per cache copy): launch gaps removed
+    ms_graph = None
+    if a.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graphs = []
+        with torch.cuda.stream(side):
+            for _ in range(max(1, a.layers)):
+                step()                               # the copy this graph will cover, once eagerly
+            side.synchronize()
+            for _ in range(max(1, a.layers)):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    step()
+                graphs.append(g)
+        torch.cuda.synchronize()
+        for i in range(a.warmup):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(a.steps):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) * 1e3 / a.steps
+
     # same K steps without the event pairs (launch-to-launch pipelining undisturbed)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -283,10 +314,13 @@ def main():
         del sv
 
     ach = nbytes[dom] / (dom_avg * dom_calls * 1e-3) / 1e9
+    default_cfg = (a.config == 1 and a.scale == 1.0 and a.batch is None and a.seed == 0 and a.bits == 4 and a.p is None
+                   and not a.full_selector and not a.offload)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS,
-                "traffic": TRAFFIC_C2.get(dom) if (a.config == 1 and a.scale == 1.0 and a.batch is None and a.seed == 0) else None,
+                "traffic": TRAFFIC_C2.get(dom) if default_cfg else None,
                 "algorithmic_bytes": nbytes[dom], "avg_kernel_us": dom_avg * 1e3, "launches_per_step": dom_calls,
+                "rocprofv3_kernel_us": ROCPROF_US_C2.get(dom) if default_cfg else None,
                 "launches_timed": len(dom_ms)}
     per_kernel = {k: {"us": kavg[k] * 1e3, "calls_per_step": kcalls[k], "bytes": nbytes.get(k),
                       "GBps": (nbytes.get(k, 0) / (kavg[k] * kcalls[k] * 1e-3) / 1e9) if kavg[k] > 0 else None}
@@ -314,6 +348,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "us_per_layer_events_off": ms_plain * 1e3,
+        "us_per_layer_graph_replay": None if ms_graph is None else ms_graph * 1e3,
         "dense_decode_us": dense_us,
         "dense_decode_GBps": (nbytes["dense_decode"] / (dense_us * 1e-6) / 1e9) if dense_us else None,
         "per_kernel": per_kernel,
