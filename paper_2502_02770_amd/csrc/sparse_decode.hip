@@ -40,6 +40,7 @@ struct DecodeArgs {
   float2* ws_ml;              // [items][G]
   float4* ws_acc;             // [items][G][32 x float4]
   int Hq, Hkv, max_pages, union_stride, NG, chunk;
+  int fix_chunk;              // tuning: use `chunk` as given
   int LH, kv_div;             // lists per sequence (Hkv, or Hq with one list per query head); list l reads KV head l / kv_div
   long long pool_pages;
 };
@@ -54,8 +55,8 @@ __device__ __forceinline__ float tw_row_bcast(float v) {
 #define TW_DPP_ROR4 0x124
 #define TW_DPP_ROR8 0x128
 
-template <int G, int WPS>
-__global__ __launch_bounds__(256, WPS) void sparse_decode_kernel(DecodeArgs a) {
+template <int G>
+__global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
   constexpr int R = (G + 3) / 4;                 // score values a lane ends up owning per sub-block
   constexpr int HB = G < 4 ? G : 4;              // heads merged through LDS at a time
   extern __shared__ int32_t prefix[];            // [NG + 1]
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256, WPS) void sparse_decode_kernel(DecodeArgs a) {
   n0 = red3[0][0] + red3[0][1] + red3[0][2] + red3[0][3];
   n1 = red3[1][0] + red3[1][1] + red3[1][2] + red3[1][3];
   int chunk = c0;
-  if (n0 > gridDim.x && 2 * c0 <= DEC_MAX_CHUNK) {
+  if (!a.fix_chunk && n0 > gridDim.x && 2 * c0 <= DEC_MAX_CHUNK) {
     chunk = 2 * c0;
     if (n1 > gridDim.x && 4 * c0 <= DEC_MAX_CHUNK) chunk = 4 * c0;
   }
@@ -390,14 +391,14 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
 // The grid is persistent (a workgroup strides over the items), so it must not exceed what is
 // resident at once: workgroups that wait for a slot would start their share only after an
 // earlier one has finished all of its own.
-template <int G, int WPS>
+template <int G>
 int decode_blocks_per_cu(size_t lds) {
   static int occ = 0;
   static size_t occ_lds = 0;
   if (occ == 0 || occ_lds != lds) {
     int n = 0;
     occ_lds = lds;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, sparse_decode_kernel<G, WPS>, 256, lds) != hipSuccess || n < 1) n = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, sparse_decode_kernel<G>, 256, lds) != hipSuccess || n < 1) n = 1;
     occ = n > 4 ? 4 : n;
   }
   return occ;
@@ -405,20 +406,21 @@ int decode_blocks_per_cu(size_t lds) {
 
 template <int G>
 void launch_decode(const DecodeArgs& a, long long max_items, size_t lds, hipStream_t s) {
-  static const bool cap = getenv("TW_DECODE_CAP") != nullptr;     // tuning switch: cap registers for 4 waves per SIMD
-  const bool capped = cap && G <= 4;
-  long long grid = (long long)tw_num_cus() * (capped ? decode_blocks_per_cu<G, 4>(lds) : decode_blocks_per_cu<G, 1>(lds));
+  long long grid = (long long)tw_num_cus() * decode_blocks_per_cu<G>(lds);
   if (grid > max_items) grid = max_items;
   if (grid < 1) grid = 1;
-  if (capped) hipLaunchKernelGGL((sparse_decode_kernel<G, 4>), dim3((unsigned)grid), dim3(256), lds, s, a);
-  else        hipLaunchKernelGGL((sparse_decode_kernel<G, 1>), dim3((unsigned)grid), dim3(256), lds, s, a);
+  hipLaunchKernelGGL((sparse_decode_kernel<G>), dim3((unsigned)grid), dim3(256), lds, s, a);
 }
 
 }  // namespace
 
 // Items are `chunk` list entries: short for sparse lists (many small items keep
 // all CUs busy on short, latency-bound gathers), longer for the dense sweep.
-int tw_decode_chunk(bool dense) { return dense ? 256 : 64; }
+int tw_decode_chunk(bool dense) {
+  static const int c0 = getenv("TW_DECODE_C0") ? atoi(getenv("TW_DECODE_C0")) : 0;   // tuning switch
+  if (!dense && (c0 == 64 || c0 == 128 || c0 == 256 || c0 == 512)) return c0;
+  return dense ? 256 : 64;
+}
 
 long long tw_decode_max_items(const TwDims& d, bool dense, int union_stride) {
   const int chunk = tw_decode_chunk(dense);
@@ -456,6 +458,8 @@ static int decode_impl(const twilight_kv_t* kv, const void* q, const int32_t* co
   a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.union_stride = stride;
   a.LH = LH; a.kv_div = per_head ? d.G : 1;
   a.NG = NG; a.chunk = tw_decode_chunk(dense); a.pool_pages = d.pool_pages;
+  static const bool fixed_c0 = getenv("TW_DECODE_C0") != nullptr;   // tuning switch: chunk length as given
+  a.fix_chunk = (!dense && fixed_c0) ? 1 : 0;
   const size_t lds = (size_t)(NG + 1) * 4;
   tw_prof_before(TW_K_DECODE, s);
   switch (Gk) {

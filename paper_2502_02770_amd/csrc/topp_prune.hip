@@ -676,7 +676,6 @@ int pages_per_wave(long long total_pages_all_rows, int count_bound) {
 template <int NH, bool FULL>
 void launch_score(const ScoreArgs& a, dim3 grid, bool dots, int bits, hipStream_t s) {
   // pages in flight per wave: 4, fewer when 8 heads share a page (register budget)
-  static const int unr8 = getenv("TW_INT4_UNR") ? atoi(getenv("TW_INT4_UNR")) : 2;   // tuning switch
   if (bits == 2) {
     if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2, 2>), grid, dim3(256), 0, s, a);
     else      hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 2, 2>), grid, dim3(256), 0, s, a);
@@ -686,8 +685,6 @@ void launch_score(const ScoreArgs& a, dim3 grid, bool dots, int bits, hipStream_
   }
   else if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2>), grid, dim3(256), 0, s, a);
   else if (NH < 8) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 4>), grid, dim3(256), 0, s, a);
-  else if (unr8 == 1) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 1>), grid, dim3(256), 0, s, a);
-  else if (unr8 == 4) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 4>), grid, dim3(256), 0, s, a);
   else hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 2>), grid, dim3(256), 0, s, a);
 }
 
