@@ -43,7 +43,7 @@ struct ScoreArgs {
 };
 
 // q of NH consecutive heads -> int8 (symmetric per head: sq = max|q| * (1/127), round half even),
-// 4 values per word, and c = sq / sqrt(128) per head.  Called by all 256 threads of the block.
+// 4 values per word, and c = sq / sqrt(128) per head.  Called by all threads of the block (>= 128).
 template <int NH>
 __device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32], float* red, float* c_s) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -54,7 +54,7 @@ __device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32]
     float av = fabsf(v);
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) av = fmaxf(av, __shfl_xor(av, o, 64));
-    if (lane == 0) red[wave] = av;
+    if (lane == 0 && wave < 2) red[wave] = av;     // the 128 values sit in waves 0 and 1
     __syncthreads();
     const float amax = fmaxf(red[0], red[1]);
     const float sq = __fmul_rn(amax, kInv127);
@@ -70,6 +70,46 @@ __device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32]
     if (tid == 0) c_s[h] = __fmul_rn(sq, kRsqrtD);
     __syncthreads();
   }
+}
+
+// One lane's group of 32 codes of slot (token, group) `idx` of the pool, as 8 dot4 operands
+// (4 dims each, in the order of the query words); 8-bit codes come out as code - 128.
+template <int BITS>
+__device__ __forceinline__ void tw_load_codes(const uint4* kq_pool, long long idx, int (&u)[8]) {
+  if (BITS == 4) {
+    const uint4 nib = kq_pool[idx];
+    u[0] = nib.x & 0x0F0F0F0F; u[1] = (nib.x >> 4) & 0x0F0F0F0F;
+    u[2] = nib.y & 0x0F0F0F0F; u[3] = (nib.y >> 4) & 0x0F0F0F0F;
+    u[4] = nib.z & 0x0F0F0F0F; u[5] = (nib.z >> 4) & 0x0F0F0F0F;
+    u[6] = nib.w & 0x0F0F0F0F; u[7] = (nib.w >> 4) & 0x0F0F0F0F;
+  } else if (BITS == 2) {
+    const uint2 cr = ((const uint2*)kq_pool)[idx];
+    u[0] = cr.x & 0x03030303; u[1] = (cr.x >> 2) & 0x03030303; u[2] = (cr.x >> 4) & 0x03030303; u[3] = (cr.x >> 6) & 0x03030303;
+    u[4] = cr.y & 0x03030303; u[5] = (cr.y >> 2) & 0x03030303; u[6] = (cr.y >> 4) & 0x03030303; u[7] = (cr.y >> 6) & 0x03030303;
+  } else {
+    const uint4 c0 = kq_pool[idx * 2], c1 = kq_pool[idx * 2 + 1];
+    u[0] = c0.x ^ 0x80808080; u[1] = c0.y ^ 0x80808080; u[2] = c0.z ^ 0x80808080; u[3] = c0.w ^ 0x80808080;
+    u[4] = c1.x ^ 0x80808080; u[5] = c1.y ^ 0x80808080; u[6] = c1.z ^ 0x80808080; u[7] = c1.w ^ 0x80808080;
+  }
+}
+// I = sum over the group's 32 dims of q * code (i0 = 128 * sum q for 8-bit codes, else 0)
+__device__ __forceinline__ int tw_group_dot(const int (&qw)[8], const int (&u)[8], int i0) {
+  int I = __builtin_amdgcn_sdot4(qw[0], u[0], i0, false);
+  I = __builtin_amdgcn_sdot4(qw[1], u[1], I, false);
+  I = __builtin_amdgcn_sdot4(qw[2], u[2], I, false);
+  I = __builtin_amdgcn_sdot4(qw[3], u[3], I, false);
+  I = __builtin_amdgcn_sdot4(qw[4], u[4], I, false);
+  I = __builtin_amdgcn_sdot4(qw[5], u[5], I, false);
+  I = __builtin_amdgcn_sdot4(qw[6], u[6], I, false);
+  I = __builtin_amdgcn_sdot4(qw[7], u[7], I, false);
+  return I;
+}
+// the group's term of the score: fl(scale * I) + fl(zero * sum q), summed over the 4 groups of the
+// token (the 4 lanes of a quad) in the fixed order (T0 + T1) + (T2 + T3)
+__device__ __forceinline__ float tw_token_sum(uint32_t meta, int I, float qsf) {
+  const float sc = __half2float(__ushort_as_half((unsigned short)(meta & 0xFFFFu)));
+  const float ze = __half2float(__ushort_as_half((unsigned short)(meta >> 16)));
+  return tw_quad_sum(__fadd_rn(__fmul_rn(sc, (float)I), __fmul_rn(ze, qsf)));
 }
 
 // NH = heads scored per loaded page: 1 with per-head page lists, G when every
@@ -136,41 +176,16 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
     // unconditional loads (an unmapped page reads pool page 0 and is masked below), so that the
     // four pages of an unrolled step are in flight together
     const long long blk = ((long long)(pool >= 0 ? pool : 0) * a.Hkv + g) * 64;
-    // this lane's group of 32 codes as 8 dot4 operands (4 dims each, in the order of qw)
-    int u0, u1, u2, u3, u4, u5, u6, u7;
-    if (BITS == 4) {
-      const uint4 nib = a.kq_pool[blk + lane];
-      u0 = nib.x & 0x0F0F0F0F; u1 = (nib.x >> 4) & 0x0F0F0F0F;
-      u2 = nib.y & 0x0F0F0F0F; u3 = (nib.y >> 4) & 0x0F0F0F0F;
-      u4 = nib.z & 0x0F0F0F0F; u5 = (nib.z >> 4) & 0x0F0F0F0F;
-      u6 = nib.w & 0x0F0F0F0F; u7 = (nib.w >> 4) & 0x0F0F0F0F;
-    } else if (BITS == 2) {
-      const uint2 cr = ((const uint2*)a.kq_pool)[blk + lane];
-      u0 = cr.x & 0x03030303; u1 = (cr.x >> 2) & 0x03030303; u2 = (cr.x >> 4) & 0x03030303; u3 = (cr.x >> 6) & 0x03030303;
-      u4 = cr.y & 0x03030303; u5 = (cr.y >> 2) & 0x03030303; u6 = (cr.y >> 4) & 0x03030303; u7 = (cr.y >> 6) & 0x03030303;
-    } else {
-      const uint4 c0 = a.kq_pool[(blk + lane) * 2], c1 = a.kq_pool[(blk + lane) * 2 + 1];
-      u0 = c0.x ^ 0x80808080; u1 = c0.y ^ 0x80808080; u2 = c0.z ^ 0x80808080; u3 = c0.w ^ 0x80808080;
-      u4 = c1.x ^ 0x80808080; u5 = c1.y ^ 0x80808080; u6 = c1.z ^ 0x80808080; u7 = c1.w ^ 0x80808080;
-    }
+    int u[8];
+    tw_load_codes<BITS>(a.kq_pool, blk + lane, u);
     const uint32_t meta = a.kq_meta[blk + lane];
-    const float sc = __half2float(__ushort_as_half((unsigned short)(meta & 0xFFFFu)));
-    const float ze = __half2float(__ushort_as_half((unsigned short)(meta >> 16)));
     const int tok = lp * TW_PAGE + (lane >> 2);
     const bool valid = pool >= 0 && tok < n;
     const long long slot = (long long)(first + k) * TW_PAGE + (lane >> 2);
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
-      int I = __builtin_amdgcn_sdot4(qw[h][0], u0, qs128[h], false);
-      I = __builtin_amdgcn_sdot4(qw[h][1], u1, I, false);
-      I = __builtin_amdgcn_sdot4(qw[h][2], u2, I, false);
-      I = __builtin_amdgcn_sdot4(qw[h][3], u3, I, false);
-      I = __builtin_amdgcn_sdot4(qw[h][4], u4, I, false);
-      I = __builtin_amdgcn_sdot4(qw[h][5], u5, I, false);
-      I = __builtin_amdgcn_sdot4(qw[h][6], u6, I, false);
-      I = __builtin_amdgcn_sdot4(qw[h][7], u7, I, false);
-      float T = __fadd_rn(__fmul_rn(sc, (float)I), __fmul_rn(ze, qsf[h]));
-      T = tw_quad_sum(T);
+      const int I = tw_group_dot(qw[h], u, qs128[h]);
+      const float T = tw_token_sum(meta, I, qsf[h]);
       const float s = valid ? __fmul_rn(T, cc[h]) : -__builtin_inff();
       if (k < npages) hm[h] = fmaxf(hm[h], s);
       const long long row = ((long long)(b * a.Hq + h0 + h)) * a.cand_stride;
@@ -374,41 +389,72 @@ struct HeadArgs {
 constexpr int HP_CAP = 64;                    // exact resolve handles up to this many scores
 constexpr int HP_BITMAP_WORDS = 6144;         // 196608 tokens
 
-// Shared scratch of the threshold search below.
-template <int NT>
-struct HpShared {
-  unsigned long long histM[HP_NB];
-  uint32_t histC[HP_NB];
-  unsigned long long cand_mass[HP_CAP];
-  uint32_t cand_key[HP_CAP];
-  unsigned long long tail_s[NT / 64];
-  float redf[NT / 64];
-  uint32_t sh_n, sh_T;
-};
-
-// The top-p threshold of one head whose scores sit in registers (s[e], -inf = no candidate):
-// returns the key T such that the kept set is {key(s) >= T} (0xFFFFFFFF: nothing to keep).
-// Called by all NT threads of the block (barriers inside); histM / histC must be zero and
-// sh_n zero on entry (the first barrier inside orders those writes).
-template <int NT, int EPT>
-__device__ __forceinline__ uint32_t hp_threshold(const float (&s)[EPT], float p, HpShared<NT>& sh) {
+template <int NT, int EPT, int G>
+__global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   constexpr int NW = NT / 64;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int bh = b * a.Hq + h;
+  const int n = a.seq_lens[b];
+  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
+  const int nwords = (ntok + 31) >> 5;
+  int count = a.sel_count[bh];
+  if (count > a.max_sel) count = a.max_sel;
+  if (count < 0) count = 0;
+  const int N = count * TW_PAGE;
+  if (N <= a.n_above || N > a.n_upto) return;     // another launch's head (block-uniform)
+  const float* row = a.scores + (long long)bh * a.cand_stride;
+  const int c0 = tid * EPT;
+
+  __shared__ unsigned long long histM[HP_NB];
+  __shared__ uint32_t histC[HP_NB];
+  __shared__ unsigned long long cand_mass[HP_CAP];
+  __shared__ uint32_t cand_key[HP_CAP];
+  __shared__ uint32_t bitmap[HP_BITMAP_WORDS];
+  __shared__ unsigned long long tail_s[NW];
+  __shared__ uint32_t ws32[16];
+  __shared__ float redf[NW];
+  __shared__ uint32_t sh_n, sh_kept, sh_T, sh_last;
+
+  // ---- scores into registers; logical pages of the owned slots
+  // (loads do not wait for the list length: anything inside the row is readable, slots at or
+  //  beyond N are masked afterwards)
+  constexpr int NPG = (EPT + 15) / 16;             // pages a thread's slots fall into (a part of one if EPT < 16)
+  float s[EPT];
+  int pg[NPG];
+#pragma unroll
+  for (int v = 0; v < EPT / 4; ++v) {              // clamped, unconditional: all loads go out together
+    const int cc = c0 + 4 * v < a.cand_stride ? c0 + 4 * v : a.cand_stride - 4;
+    const float4 x = *(const float4*)(row + cc);
+    s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
+  }
+#pragma unroll
+  for (int v = 0; v < NPG; ++v) {
+    const int pi = (c0 >> 4) + v < a.max_sel ? (c0 >> 4) + v : a.max_sel - 1;
+    pg[v] = a.sel_pages[(long long)bh * a.max_sel + pi];
+  }
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) s[e] = (c0 + e < N) ? s[e] : -__builtin_inff();
+  for (int i = tid; i < HP_NB; i += NT) { histM[i] = 0; histC[i] = 0; }
+  for (int i = tid; i < nwords; i += NT) bitmap[i] = 0;
+  if (tid == 0) { sh_n = 0; sh_kept = 0; }
+
   float m = s[0];
 #pragma unroll
   for (int e = 1; e < EPT; ++e) m = fmaxf(m, s[e]);
   m = tw_wave_max_f(m);
-  if (lane == 0) sh.redf[wave] = m;
+  if (lane == 0) redf[wave] = m;
   __syncthreads();
-  m = sh.redf[0];
+  m = redf[0];
 #pragma unroll
-  for (int w = 1; w < NW; ++w) m = fmaxf(m, sh.redf[w]);
+  for (int w = 1; w < NW; ++w) m = fmaxf(m, redf[w]);
   TW_STAMP(1);
 
   uint32_t T = 0;
   bool searching;
   if (!(m > -__builtin_inff())) { T = 0xFFFFFFFFu; searching = false; }
-  else if (p >= 1.0f) { T = kKeyNegInf + 1u; searching = false; }
+  else if (a.p >= 1.0f) { T = kKeyNegInf + 1u; searching = false; }
   else searching = true;
 
   if (searching) {                                 // block-uniform
@@ -425,7 +471,7 @@ __device__ __forceinline__ uint32_t hp_threshold(const float (&s)[EPT], float p,
 #pragma unroll 1
     for (;;) {
       if (pass > 0) {
-        for (int i = tid; i < HP_NB; i += NT) { sh.histM[i] = 0; sh.histC[i] = 0; }
+        for (int i = tid; i < HP_NB; i += NT) { histM[i] = 0; histC[i] = 0; }
         __syncthreads();
       }
       unsigned long long below = 0;                // mass past the end of the interval (pass 0 only)
@@ -434,27 +480,27 @@ __device__ __forceinline__ uint32_t hp_threshold(const float (&s)[EPT], float p,
         if (rk[e] != HP_NONE && rk[e] >= rlo) {
           const uint32_t bk = (rk[e] - rlo) >> shift;
           const unsigned long long w = hp_fix(ef[e]);
-          if (bk < HP_NB) { atomicAdd(&sh.histM[bk], w); atomicAdd(&sh.histC[bk], 1u); }
+          if (bk < HP_NB) { atomicAdd(&histM[bk], w); atomicAdd(&histC[bk], 1u); }
           else below += w;
         }
       }
       if (pass == 0) {
         below = tw_wave_scan_u64(below);
-        if (lane == 63) sh.tail_s[wave] = below;
+        if (lane == 63) tail_s[wave] = below;
       }
       __syncthreads();
       TW_STAMP(2 + pass);
       // every wave scans the 512 buckets on its own: lane l owns buckets 8l .. 8l+7
       unsigned long long mb[8], mine = 0;
 #pragma unroll
-      for (int k = 0; k < 8; ++k) { mb[k] = sh.histM[8 * lane + k]; mine += mb[k]; }
+      for (int k = 0; k < 8; ++k) { mb[k] = histM[8 * lane + k]; mine += mb[k]; }
       const unsigned long long incl = tw_wave_scan_u64(mine);
       const unsigned long long total = __shfl(incl, 63, 64);
       if (pass == 0) {
         unsigned long long Z = total;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) Z += sh.tail_s[w];
-        const double t = ceil((double)p * (double)Z);
+        for (int w = 0; w < NW; ++w) Z += tail_s[w];
+        const double t = ceil((double)a.p * (double)Z);
         target = t < 1.0 ? 1ull : (unsigned long long)t;
         if (target > Z) target = Z;
       }
@@ -480,7 +526,7 @@ __device__ __forceinline__ uint32_t hp_threshold(const float (&s)[EPT], float p,
         }
         const int bucket = 8 * src + __shfl(bsel, src, 64);
         A = __shfl(asel, src, 64);
-        pop = sh.histC[bucket];
+        pop = histC[bucket];
         rlo += (uint32_t)bucket << shift;
         if (pop > HP_CAP && shift > 0) { shift = shift >= 9 ? shift - 9 : 0; more = true; }
       }
@@ -498,95 +544,43 @@ __device__ __forceinline__ uint32_t hp_threshold(const float (&s)[EPT], float p,
         const uint32_t k = tw_float_key(s[e]);
         kmin = k < kmin ? k : kmin;
         if (small) {
-          const uint32_t at = atomicAdd(&sh.sh_n, 1u);
-          if (at < HP_CAP) { sh.cand_key[at] = k; sh.cand_mass[at] = hp_fix(ef[e]); }
+          const uint32_t at = atomicAdd(&sh_n, 1u);
+          if (at < HP_CAP) { cand_key[at] = k; cand_mass[at] = hp_fix(ef[e]); }
         }
       }
     }
     if (!small) {                                   // > HP_CAP scores within one rank: keep them all
       kmin = ~tw_wave_max_u32(~kmin);
-      if (lane == 0) sh.redf[wave] = __uint_as_float(kmin);
+      if (lane == 0) redf[wave] = __uint_as_float(kmin);
     }
     __syncthreads();
     TW_STAMP(8);
     if (wave == 0) {                                // one wave resolves; the others wait at the barrier
       if (small) {
         // lane x takes candidate x: mass of all candidates at least as large as it
-        const uint32_t cn = sh.sh_n < HP_CAP ? sh.sh_n : HP_CAP;
-        const uint32_t kx = lane < (int)cn ? sh.cand_key[lane] : 0u;
+        const uint32_t cn = sh_n < HP_CAP ? sh_n : HP_CAP;
+        const uint32_t kx = lane < (int)cn ? cand_key[lane] : 0u;
         unsigned long long S = 0;
 #pragma unroll 4
         for (uint32_t j = 0; j < cn; ++j) {
-          const uint32_t kj = sh.cand_key[j];
-          const unsigned long long wj = sh.cand_mass[j];
+          const uint32_t kj = cand_key[j];
+          const unsigned long long wj = cand_mass[j];
           S += kj >= kx ? wj : 0ull;
         }
         const uint32_t best = (lane < (int)cn && A + S >= target) ? kx : 0u;
         T = tw_wave_max_u32(best);
       } else {
-        uint32_t r = __float_as_uint(sh.redf[0]);
+        uint32_t r = __float_as_uint(redf[0]);
 #pragma unroll
-        for (int w = 1; w < NW; ++w) { const uint32_t y = __float_as_uint(sh.redf[w]); r = y < r ? y : r; }
+        for (int w = 1; w < NW; ++w) { const uint32_t y = __float_as_uint(redf[w]); r = y < r ? y : r; }
         T = r;
       }
-      if (lane == 0) sh.sh_T = T;
+      if (lane == 0) sh_T = T;
     }
     __syncthreads();
-    T = sh.sh_T;
+    T = sh_T;
     TW_STAMP(9);
   }
-
-  return T;
-}
-
-template <int NT, int EPT, int G>
-__global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
-  constexpr int NW = NT / 64;
-  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int bh = b * a.Hq + h;
-  const int n = a.seq_lens[b];
-  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
-  if (P > a.max_pages) P = a.max_pages;
-  const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
-  const int nwords = (ntok + 31) >> 5;
-  int count = a.sel_count[bh];
-  if (count > a.max_sel) count = a.max_sel;
-  if (count < 0) count = 0;
-  const int N = count * TW_PAGE;
-  if (N <= a.n_above || N > a.n_upto) return;     // another launch's head (block-uniform)
-  const float* row = a.scores + (long long)bh * a.cand_stride;
-  const int c0 = tid * EPT;
-
-  __shared__ HpShared<NT> sh;
-  __shared__ uint32_t bitmap[HP_BITMAP_WORDS];
-  __shared__ uint32_t ws32[16];
-  __shared__ uint32_t sh_kept, sh_last;
-
-  // ---- scores into registers; logical pages of the owned slots
-  // (loads do not wait for the list length: anything inside the row is readable, slots at or
-  //  beyond N are masked afterwards)
-  constexpr int NPG = (EPT + 15) / 16;             // pages a thread's slots fall into (a part of one if EPT < 16)
-  float s[EPT];
-  int pg[NPG];
-#pragma unroll
-  for (int v = 0; v < EPT / 4; ++v) {              // clamped, unconditional: all loads go out together
-    const int cc = c0 + 4 * v < a.cand_stride ? c0 + 4 * v : a.cand_stride - 4;
-    const float4 x = *(const float4*)(row + cc);
-    s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
-  }
-#pragma unroll
-  for (int v = 0; v < NPG; ++v) {
-    const int pi = (c0 >> 4) + v < a.max_sel ? (c0 >> 4) + v : a.max_sel - 1;
-    pg[v] = a.sel_pages[(long long)bh * a.max_sel + pi];
-  }
-#pragma unroll
-  for (int e = 0; e < EPT; ++e) s[e] = (c0 + e < N) ? s[e] : -__builtin_inff();
-  for (int i = tid; i < HP_NB; i += NT) { sh.histM[i] = 0; sh.histC[i] = 0; }
-  for (int i = tid; i < nwords; i += NT) bitmap[i] = 0;
-  if (tid == 0) { sh.sh_n = 0; sh_kept = 0; }
-
-  const uint32_t T = hp_threshold<NT, EPT>(s, a.p, sh);
-  TW_STAMP(9);
 
   // ---- kept flags, count, optional ascending list; bitmap over token positions
   uint32_t cnt = 0, keep = 0;

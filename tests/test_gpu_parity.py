@@ -102,6 +102,16 @@ def run_pipeline(w, cache, with_kept=True):
     return st, q
 
 
+def gpu_scores(cache, st, q):
+    """Estimated scores of the selected pages, [b * Hq * max_sel * 16] fp32, through twilight_int4_score
+    (the pruner keeps its scores in registers when one launch does scoring and top-p)."""
+    T = _T()
+    sc = torch.full((cache.batch, cache.Hq, st.max_sel * 16), 7.0, dtype=torch.float32, device=cache.device)
+    T.twilight_int4_score(cache.kv, q, st.sel_pages, st.sel_count, st.max_sel, sc, None)
+    torch.cuda.synchronize()
+    return sc.cpu().numpy().reshape(-1)
+
+
 def check_topp(kept_gpu, s_hat, cand, p):
     """GPU kept set vs the oracle's, tolerant inside the 1e-6 band around tau*."""
     mask, tau = O.topp_set(s_hat, p)
@@ -138,7 +148,7 @@ def pipeline_against_oracle(w, bits, cache=None):
     st, q = run_pipeline(w, cache)
     assert int(st.status.item()) == 0
     G = w.num_q_heads // w.num_kv_heads
-    scores = st.ws_prune.cpu().numpy().view(np.float32)
+    scores = gpu_scores(cache, st, q)
     cand_stride = st.max_sel * 16
     out = st.out.cpu(); lse = st.lse.cpu().numpy()
     pscores = st.ws_select.cpu().numpy().view(np.float32)
@@ -455,7 +465,7 @@ def test_full_size_bench_config_sampled():
     assert int(st.status.item()) == 0
     G = w.num_q_heads // w.num_kv_heads
     out = st.out.cpu().float().numpy().astype(np.float64)
-    scores = st.ws_prune.cpu().numpy().view(np.float32)
+    scores = gpu_scores(cache, st, q)
     cand_stride = st.max_sel * 16
     for (b, g) in ((0, 0), (3, 5), (7, 7)):
         n = int(w.seq_lens[b])
