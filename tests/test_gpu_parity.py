@@ -455,52 +455,93 @@ def test_results_are_deterministic_run_to_run():
                            y.view(torch.int16) if y.dtype == torch.bfloat16 else y), name
 
 
-def test_full_size_bench_config_sampled():
-    """BASELINE config C2 at full size (batch 8 x 32768, budget 4096, p 0.9), the launch
-    configuration bench.py times; the oracle recomputes sampled (sequence, KV head) groups."""
-    T = _T()
-    w = synth.config(1)
-    cache = build_cache(w)
-    st, q = run_pipeline(w, cache, with_kept=True)
-    assert int(st.status.item()) == 0
+def check_sampled_groups(w, cache, st, q, groups, pages_to_check=(0,)):
+    """Full-size runs: the oracle recomputes the sampled (sequence, KV head) groups stage by stage."""
     G = w.num_q_heads // w.num_kv_heads
-    out = st.out.cpu().float().numpy().astype(np.float64)
-    scores = gpu_scores(cache, st, q)
+    out = st.out.cpu().float().numpy().astype(np.float64) if cache.v_pool is not None else None
+    scores = None if w.full_selector else gpu_scores(cache, st, q)
     cand_stride = st.max_sel * 16
-    for (b, g) in ((0, 0), (3, 5), (7, 7)):
+    for (b, g) in groups:
         n = int(w.seq_lens[b])
-        kb, vb = synth.bits(w.seq_k(b)[:, g]), synth.bits(w.seq_v(b)[:, g])
+        kb = synth.bits(w.seq_k(b)[:, g])
         u, s, z = O.quantize_k(kb)
         mn, mx = O.page_minmax(kb)
-        # cache contents of sampled pages
         row = w.page_table[b]
-        for lp in (0, 1000, 2047):
+        for lp in pages_to_check:                      # cache contents of sampled pages
+            lp = min(lp, (n + 15) // 16 - 1)
             pp = int(row[lp])
             codes = unpack_codes(cache.kq_pool[pp, g].cpu().numpy())
-            assert np.array_equal(codes, u[lp * 16: lp * 16 + 16])
+            nv = min(16, n - lp * 16)
+            assert np.array_equal(codes[:nv], u[lp * 16: lp * 16 + nv])
             assert np.array_equal(u16(cache.page_minmax[pp, g, 0].cpu()), mn[lp])
+            assert np.array_equal(u16(cache.page_minmax[pp, g, 1].cpu()), mx[lp])
         kept_all = []
         for h in range(g * G, g * G + G):
             bh = b * w.num_q_heads + h
-            U = O.page_upper_bounds(synth.bits(w.q[b, h]), mn, mx)
-            pages = O.select_pages(U, int(w.budget[b]), n)
-            cnt = int(st.sel_count[b, h])
-            assert st.sel_pages[b, h, :cnt].cpu().numpy().tolist() == pages.tolist()
+            if w.full_selector:
+                pages = np.arange((n + 15) // 16, dtype=np.int32)
+            else:
+                U = O.page_upper_bounds(synth.bits(w.q[b, h]), mn, mx)
+                pages = O.select_pages(U, int(w.budget[b]), n)
+                cnt = int(st.sel_count[b, h])
+                assert st.sel_pages[b, h, :cnt].cpu().numpy().tolist() == pages.tolist()
             cand = O.candidate_tokens(pages, n)
             qi, sq = O.quantize_q(synth.bits(w.q[b, h]))
             s_hat = O.int4_scores(qi, sq, u[cand], s[cand], z[cand])
-            assert np.array_equal(scores[bh * cand_stride: bh * cand_stride + cnt * 16], s_hat)
+            if scores is not None:
+                sl = scores[bh * cand_stride: bh * cand_stride + len(pages) * 16]
+                tok = (pages[:, None].astype(np.int64) * 16 + np.arange(16)[None]).reshape(-1)
+                assert np.array_equal(sl[tok < n], s_hat)
             kept = st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
             check_topp(kept, s_hat, cand, w.p)
             kept_all.append(kept)
         gi = b * w.num_kv_heads + g
         un = st.union_idx[gi, :int(st.union_count[gi])].cpu().numpy()
         assert un.tolist() == np.unique(np.concatenate(kept_all)).tolist()
+        if out is None:
+            continue
+        vb = synth.bits(w.seq_v(b)[:, g])
         for h in range(g * G, g * G + G):
             ref, _ = O.attention(synth.bits(w.q[b, h]), kb, vb, un)
             ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
             assert np.abs(out[b, h] - ref).max() <= MAX_ABS
             assert np.linalg.norm(out[b, h] - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
+
+
+def test_full_size_bench_config_sampled():
+    """BASELINE config C2 at full size (batch 8 x 32768, budget 4096, p 0.9), the launch
+    configuration bench.py times; the oracle recomputes sampled (sequence, KV head) groups."""
+    w = synth.config(1)
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache, with_kept=True)
+    assert int(st.status.item()) == 0
+    check_sampled_groups(w, cache, st, q, ((0, 0), (3, 5), (7, 7)), pages_to_check=(0, 1000, 2047))
+
+
+def test_full_size_pruner_stress_sampled():
+    """BASELINE config C4 at full size (4 x 262144 tokens, 64 query / 8 KV heads, every token a candidate):
+    matrix-core scoring and the multi-workgroup top-p at the size bench.py --config 3 times."""
+    w = synth.config(3)
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache, with_kept=True)
+    assert int(st.status.item()) == 0
+    check_sampled_groups(w, cache, st, q, ((0, 0), (3, 6)), pages_to_check=(0, 9999, 16383))
+    del st, cache
+    torch.cuda.empty_cache()
+
+
+def test_full_size_ragged_batch_sampled():
+    """BASELINE config C5 at full size (64 ragged sequences in one shuffled pool, budget n/8): the split
+    top-p launch and the balanced decode work list at the size bench.py --config 4 times."""
+    w = synth.config(4)
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache, with_kept=True)
+    assert int(st.status.item()) == 0
+    lens = w.seq_lens.tolist()
+    longest, shortest = int(np.argmax(lens)), int(np.argmin(lens))
+    check_sampled_groups(w, cache, st, q, ((longest, 2), (shortest, 7), (len(lens) // 2, 0)), pages_to_check=(0, 77))
+    del st, cache
+    torch.cuda.empty_cache()
 
 
 def check_sets_and_output(w, cache, st, exact_floor=0.97):
