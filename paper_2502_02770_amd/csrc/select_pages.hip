@@ -96,6 +96,7 @@ struct SelectArgs {
   int32_t* sel_pages;         // [b][Hq][max_sel]
   int32_t* sel_count;
   int Hq, max_pages, max_sel;
+  int p_above, p_upto;        // the LDS kernel takes the heads with p_above < pages <= p_upto
 };
 
 __global__ __launch_bounds__(256) void page_select_kernel(SelectArgs a) {
@@ -188,6 +189,7 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
   const int n = a.seq_lens[b];
   int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
   if (P > a.max_pages) P = a.max_pages;
+  if (P <= a.p_above || P > a.p_upto) return;     // another launch's head (block-uniform)
   const int B = a.budget[b];
   long long kp = B > 0 ? ((long long)B + TW_PAGE - 1) / TW_PAGE : 0;
   if (kp > P) kp = P;
@@ -202,7 +204,7 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
     return;
   }
 
-  __shared__ uint32_t key_s[SEL_LDS_PAGES];
+  __shared__ uint32_t key_s[NT == 256 ? 2048 : SEL_LDS_PAGES];   // the 256-thread variant serves rows of at most 2048 pages
   __shared__ uint32_t hist[SEL_NB];
   __shared__ uint32_t wsum[16];
   __shared__ uint32_t red_lo[NW], red_hi[NW];
@@ -369,6 +371,16 @@ extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, con
   sa.scores = (const float*)ws; sa.seq_lens = kv->seq_lens; sa.budget = budget_tokens;
   sa.sel_pages = sel_pages; sa.sel_count = sel_count;
   sa.Hq = d.Hq; sa.max_pages = d.max_pages; sa.max_sel = max_sel;
+  sa.p_above = -1; sa.p_upto = d.max_pages;
+  // Many heads and rows of up to 8192 pages (ragged batches): the 1024-thread kernel fits two
+  // workgroups per CU; rows of at most 2048 pages go to a 256-thread launch of their own.
+  if (d.max_pages > 2048 && d.max_pages <= SEL_LDS_PAGES && (long long)d.batch * d.Hq > 2ll * tw_num_cus()) {
+    sa.p_upto = 2048;
+    tw_prof_before(TW_K_PAGE_SELECT, s);
+    hipLaunchKernelGGL(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+    if (int e = tw_prof_after(s)) return e;
+    sa.p_above = 2048; sa.p_upto = d.max_pages;
+  }
   tw_prof_before(TW_K_PAGE_SELECT, s);
   if (d.max_pages <= 2048)
     hipLaunchKernelGGL(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
