@@ -76,6 +76,16 @@ def test_bad_arguments_are_rejected_on_the_host(T):
     kv.quant_bits = 8
     assert T.twilight_workspace_bytes(0, kv, 4, 0) > 0
     kv.quant_bits = 4
+    # documented size limits: batch * query heads <= 65535, at most 2^22 candidates per head
+    big = T.make_kv(4096, 32, 8, 16, 16, None, None)
+    big.page_table, big.seq_lens = 4096, 4096
+    big.kq_pool, big.kq_meta, big.page_minmax, big.k_pool, big.v_pool = 4096, 4096, 4096, 4096, 4096
+    assert L.twilight_select_pages(ctypes.byref(big), one, one, one, one, 4, one, 1 << 40, None) == -1
+    long_row = T.make_kv(1, 8, 8, 1 << 20, 1 << 20, None, None)
+    long_row.page_table, long_row.seq_lens = 4096, 4096
+    long_row.kq_pool, long_row.kq_meta, long_row.page_minmax, long_row.k_pool, long_row.v_pool = 4096, 4096, 4096, 4096, 4096
+    assert L.twilight_topp_prune(ctypes.byref(long_row), one, None, None, 0, ctypes.c_float(0.9), one, None, 0, one, one,
+                                 64, one, one, 1 << 40, None) == -1                                # 2^24 candidates
     # pinned-pointer query: NULL arguments
     out = ctypes.c_void_p()
     assert L.twilight_pinned_device_pointer(None, ctypes.byref(out)) == -1
