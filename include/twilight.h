@@ -23,6 +23,12 @@
  *   - head_dim must be 128, page_size 16, quant_group 32, quant_bits 0/4, 2 or 8,
  *     num_q_heads / num_kv_heads one of 1, 2, 4, 8.
  *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
+ *   - Size limits (TW_EINVAL beyond them): batch * num_q_heads <= 65535;
+ *     num_pool_pages * num_kv_heads * 16 < 2^31; at most 2^22 candidate
+ *     tokens per query head in twilight_topp_prune (max_sel * 16, or
+ *     max_pages_per_seq * 16 with sel_pages == NULL); batch * num_kv_heads
+ *     (batch * num_q_heads for the per-head variant) <= 12000 in
+ *     twilight_sparse_decode.
  *   - Token indices are logical positions in their sequence (0 .. len-1);
  *     page ids are logical page numbers (token / 16); both ascending in every
  *     list.  Pool addresses are resolved through page_table in the kernels.
