@@ -35,7 +35,8 @@ PAPER_CONTEXT = {"quest_twi_vs_fa2_attention_speedup": 15.8, "quest_twi_vs_quest
                  "hardware": "1x NVIDIA A100", "source": "Section 5.2"}
 
 
-def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_selector=False, offload=False):
+def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_selector=False, offload=False,
+                separate_append=False):
     """`layers` independent copies of the layer's cache (same contents, different memory).  Successive steps
     rotate over them, as the layers of a model do, so that a step finds its pools in HBM and not in the
     256 MB memory-side cache left warm by the previous step over the very same addresses."""
@@ -78,14 +79,18 @@ def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_select
     pos = (caches[0].seq_lens - 1).contiguous()
     rows = torch.arange(w.batch, dtype=torch.int32, device=dev)
     turn = [0]
+    fused_append = bits == 4 and not separate_append
 
     def step():
         i = turn[0] % layers
         turn[0] += 1
         cache, st = caches[i], steps[i]
-        cache.append(k_last, v_last, pos, one, rows, 1)
-        if not st.full:
-            st.select(q, budget)
+        if fused_append and not st.full:
+            st.append_select(k_last, v_last, pos, q, budget)       # stages 4 + 1 in one launch
+        else:
+            cache.append(k_last, v_last, pos, one, rows, 1)
+            if not st.full:
+                st.select(q, budget)
         st.prune(q, w.p)
         if v_last is not None:
             st.attend(q)
@@ -168,6 +173,8 @@ def main():
                     help="skip the page selector: the pruner sees every token (the paper's pruner on top of full attention)")
     ap.add_argument("--offload", action="store_true",
                     help="bf16 K/V pools in pinned host memory (the paper's offloading scenario); attention is then bound by the host link")
+    ap.add_argument("--separate-append", action="store_true",
+                    help="append the step's token with twilight_kquant_append instead of twilight_append_select")
     ap.add_argument("--graph", action="store_true", help="also time the steps replayed from HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-kernel table to stderr")
@@ -182,7 +189,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits, a.p, a.full_selector, a.offload)
+    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits, a.p, a.full_selector, a.offload, a.separate_append)
     if a.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
@@ -344,7 +351,8 @@ def main():
                                   ("all tokens" if w.full_selector else int(w.budget[0])) if len(set(w.budget.tolist())) == 1 else "n/8", w.p,
                                   "" if a.scale == 1.0 else " (scale %g)" % a.scale),
                    "config_index": a.config, "seed": a.seed, "layers_rotated": max(1, a.layers),
-                   "kv_offloaded_to_host": bool(a.offload)},
+                   "kv_offloaded_to_host": bool(a.offload),
+                   "append": "separate launch" if (a.separate_append or a.bits != 4 or w.full_selector) else "inside page_score"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "us_per_layer_events_off": ms_plain * 1e3,

@@ -147,6 +147,23 @@ int twilight_select_pages(const twilight_kv_t* kv, const void* q, const int32_t*
                           void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The decode step's form of stages 4 + 1 in one launch: append ONE new token
+ * per sequence (as twilight_kquant_append with n_new = 1 would: bf16 K/V rows,
+ * INT4 codes, scale/zero, page bounds - bit for bit the same), then select
+ * pages as twilight_select_pages does, the new token's page included.  Saves
+ * the separate append launch of a decode step.  quant_bits must be 4.
+ *   k_new, v_new   bf16 [batch][num_kv_heads][128] (v_new may be NULL)
+ *   new_pos        i32 [batch] position of the new token, < seq_lens[b]
+ *                  (seq_lens already counts it); negative: nothing appended
+ *                  for that sequence
+ *   the rest       as twilight_select_pages
+ */
+int twilight_append_select(const twilight_kv_t* kv, const void* k_new, const void* v_new, const int32_t* new_pos,
+                           const void* q, const int32_t* budget_tokens,
+                           int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Estimated scores alone (first half of stage 2; Section 4.2 "SpGEMV",
  * Appendix B.1).  q is quantised per head to int8 (sq = max|q| * (1/127),
  * qi = clamp(rint(q / sq), -127, 127)); per token and group j of 32 dims

@@ -3,12 +3,13 @@
 Python side = argument marshalling for the C ABI in include/twilight.h.
 """
 from . import binding
-from .binding import (TwilightError, twilight_kquant_append, twilight_select_pages, twilight_int4_score,
+from .binding import (TwilightError, twilight_kquant_append, twilight_select_pages, twilight_append_select,
+                      twilight_int4_score,
                       twilight_topp_prune, twilight_sparse_decode, twilight_sparse_decode_per_head,
                       twilight_workspace_bytes,
                       twilight_prof_enable, twilight_prof_select, twilight_prof_collect, make_kv)
 from .cache import PagedKV, DecodeStep
 
-__all__ = ["binding", "TwilightError", "twilight_kquant_append", "twilight_select_pages", "twilight_int4_score",
+__all__ = ["binding", "TwilightError", "twilight_kquant_append", "twilight_select_pages", "twilight_append_select", "twilight_int4_score",
            "twilight_topp_prune", "twilight_sparse_decode", "twilight_sparse_decode_per_head", "twilight_workspace_bytes", "twilight_prof_enable",
            "twilight_prof_select", "twilight_prof_collect", "make_kv", "PagedKV", "DecodeStep"]

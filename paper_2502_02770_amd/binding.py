@@ -47,6 +47,7 @@ def lib():
     L.twilight_kquant_append.argtypes = [kvp, _vp, _vp, _vp, _vp, _vp, _i32, _vp]
     L.twilight_select_pages.argtypes = [kvp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
     L.twilight_int4_score.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
+    L.twilight_append_select.argtypes = [kvp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
     L.twilight_topp_prune.argtypes = [kvp, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
     L.twilight_sparse_decode.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
     L.twilight_sparse_decode_per_head.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
@@ -62,7 +63,7 @@ def lib():
     L.twilight_prof_collect.argtypes = [_vp, _vp, _i32]
     L.twilight_kernel_name.argtypes = [ctypes.c_int]
     L.twilight_kernel_name.restype = ctypes.c_char_p
-    for f in ("twilight_kquant_append", "twilight_select_pages", "twilight_int4_score", "twilight_topp_prune",
+    for f in ("twilight_kquant_append", "twilight_select_pages", "twilight_append_select", "twilight_int4_score", "twilight_topp_prune",
               "twilight_sparse_decode", "twilight_sparse_decode_per_head", "twilight_prof_enable", "twilight_prof_select", "twilight_prof_collect"):
         getattr(L, f).restype = ctypes.c_int
     _lib = L
@@ -124,6 +125,12 @@ def twilight_select_pages(kv, q, budget_tokens, sel_pages, sel_count, max_sel, w
     _check(lib().twilight_select_pages(ctypes.byref(kv), _ptr(q), _ptr(budget_tokens), _ptr(sel_pages),
                                        _ptr(sel_count), int(max_sel), _ptr(ws), ws.numel() * ws.element_size(),
                                        _stream()))
+
+
+def twilight_append_select(kv, k_new, v_new, new_pos, q, budget_tokens, sel_pages, sel_count, max_sel, ws):
+    _check(lib().twilight_append_select(ctypes.byref(kv), _ptr(k_new), _ptr(v_new), _ptr(new_pos), _ptr(q),
+                                        _ptr(budget_tokens), _ptr(sel_pages), _ptr(sel_count), int(max_sel), _ptr(ws),
+                                        ws.numel() * ws.element_size(), _stream()))
 
 
 def twilight_int4_score(kv, q, sel_pages, sel_count, max_sel, scores, dots=None):

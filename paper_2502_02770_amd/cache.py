@@ -80,6 +80,11 @@ class DecodeStep:
     def select(self, q, budget):
         B.twilight_select_pages(self.cache.kv, q, budget, self.sel_pages, self.sel_count, self.max_sel, self.ws_select)
 
+    def append_select(self, k_new, v_new, new_pos, q, budget):
+        """One new token per sequence appended and the pages selected in one launch (4-bit copy only)."""
+        B.twilight_append_select(self.cache.kv, k_new, v_new, new_pos, q, budget, self.sel_pages, self.sel_count,
+                                 self.max_sel, self.ws_select)
+
     def prune(self, q, p):
         B.twilight_topp_prune(self.cache.kv, q, self.sel_pages, self.sel_count, self.max_sel, p, self.kept_count,
                               self.kept_idx, self.kept_stride, self.union_count, self.union_idx,

@@ -7,6 +7,7 @@
 // 16 token slots x 16 lanes; a lane owns 8 consecutive dims (one 16-byte
 // load), a quad of lanes owns one quantisation group of 32 dims.
 #include "tw_common.h"
+#include "kquant_common.h"
 
 namespace {
 
@@ -28,9 +29,6 @@ struct AppendArgs {
 
 template <int BITS>
 __global__ __launch_bounds__(256) void kquant_append_kernel(AppendArgs a) {
-  constexpr float kLevels = (float)((1 << BITS) - 1);
-  // fp32 nearest to 1/levels
-  constexpr float kInvLevels = BITS == 4 ? 0x1.111112p-4f : (BITS == 2 ? 0x1.555556p-2f : 0x1.010102p-8f);
   const int b = blockIdx.z, g = blockIdx.y;
   const int tid = threadIdx.x, ts = tid >> 4, seg = tid & 15;
   const int start = a.start_pos[b], nn = a.n_new[b];
@@ -55,49 +53,14 @@ __global__ __launch_bounds__(256) void kquant_append_kernel(AppendArgs a) {
   }
   tw_unpack8(raw, x);
 
-  // group min / max over the 32 dims held by the quad (all 64 lanes take part)
-  float lmn = x[0], lmx = x[0];
-#pragma unroll
-  for (int i = 1; i < 8; ++i) { lmn = fminf(lmn, x[i]); lmx = fmaxf(lmx, x[i]); }
-  const float gmn = tw_quad_min(lmn), gmx = tw_quad_max(lmx);
-
-  const __half hs = __float2half_rn(__fmul_rn(__fsub_rn(gmx, gmn), kInvLevels));
-  const __half hz = __float2half_rn(gmn);
-  const float sf = __half2float(hs), zf = __half2float(hz);
-  uint32_t u[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) u[i] = 0;
-  if (sf > 0.0f) {
-    const float inv = __fdiv_rn(1.0f, sf);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float t = rintf(__fmul_rn(__fsub_rn(x[i], zf), inv));
-      t = fminf(fmaxf(t, 0.0f), kLevels);
-      u[i] = (uint32_t)t;
-    }
-  }
-  // pack this lane's 8 codes (the layouts are stated with twilight_kv_t)
-  uint32_t word = 0, word2 = 0;
-  if (BITS == 4) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) word |= (u[k] | (u[k + 4] << 4)) << (8 * k);
-  } else if (BITS == 8) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) { word |= u[k] << (8 * k); word2 |= u[k + 4] << (8 * k); }
-  } else {
-    // 16 dims per word: the even lane of a pair brings bit positions 0..3 of every byte, the odd lane 4..7
-#pragma unroll
-    for (int k = 0; k < 4; ++k) word |= (u[k] | (u[k + 4] << 2)) << (8 * k);
-    word <<= (seg & 1) * 4;
-    word |= (uint32_t)tw_dpp_i<TW_DPP_XOR1>((int)word);
-  }
+  // quantise (all 64 lanes take part: the quad of lanes that owns a group reduces through DPP)
+  uint32_t word, word2, meta;
+  tw_quantize_lane8<BITS>(x, seg, &word, &word2, &meta);
   if (is_new) {
     if (BITS == 4) a.kq_pool[slot * 16 + seg] = word;
     else if (BITS == 8) ((uint2*)a.kq_pool)[slot * 16 + seg] = make_uint2(word, word2);
     else if ((seg & 1) == 0) a.kq_pool[slot * 8 + (seg >> 1)] = word;
-    if ((seg & 3) == 0)
-      a.kq_meta[slot * 4 + (seg >> 2)] =
-          (uint32_t)__half_as_ushort(hs) | ((uint32_t)__half_as_ushort(hz) << 16);
+    if ((seg & 3) == 0) a.kq_meta[slot * 4 + (seg >> 2)] = meta;
   }
 
   // page bounds: element-wise min / max over the page's token slots

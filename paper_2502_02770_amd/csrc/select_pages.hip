@@ -9,7 +9,12 @@
 // page_select: per (sequence, query head) the Kp largest bounds, ties to the
 //              lower page id, by a 4 x 8-bit radix select on the order-
 //              preserving key, then an ordered compaction (ascending ids).
+//
+// page_score<G, true> also appends the decode step's one new token per sequence on its way
+// (twilight_append_select): the 16 lanes that own the page the token falls into store its K/V
+// rows, quantise K, and fold it into the page's bounds before scoring them.
 #include "tw_common.h"
+#include "kquant_common.h"
 
 namespace {
 
@@ -23,9 +28,18 @@ struct ScoreArgs {
   float* scores;              // [b][Hq][max_pages]
   int Hq, Hkv, max_pages;
   long long pool_pages;
+  // the step's new token (APPEND only): one row per sequence, [b][Hkv][128] bf16
+  const uint4* k_new;
+  const uint4* v_new;         // or nullptr
+  const int32_t* new_pos;     // [b] position of the new token, < 0: none
+  uint4* k_pool;
+  uint4* v_pool;
+  uint32_t* kq_pool;          // INT4 codes, 16 words per token
+  uint32_t* kq_meta;
+  uint4* page_minmax_w;
 };
 
-template <int G>
+template <int G, bool APPEND>
 __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
   // KV head fastest in dispatch order: the 8 heads' bounds of a pool page are 4 KiB contiguous,
   // and the workgroups that read them start next to each other
@@ -64,6 +78,53 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
     const uint4* pm = a.page_minmax + ((ok[it] ? pool[it] : 0) * a.Hkv + g) * 32;
     rmn[it] = pm[seg];
     rmx[it] = pm[16 + seg];
+  }
+  if (APPEND) {
+    // the page of the new token, if it lies in this workgroup's 64 pages: its 16 owner lanes append
+    const int sp = a.new_pos[b];
+    const int off = (sp >> 4) - base;
+    if (sp >= 0 && sp < n && off >= 0 && off < PS_PAGES_PER_WG && (off & 15) == grp) {
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        if (it == (off >> 4) && ok[it]) {
+          const long long row = (long long)b * a.Hkv + g;
+          const uint4 raw = a.k_new[row * 16 + seg];
+          const long long slot = (pool[it] * a.Hkv + g) * TW_PAGE + (sp & 15);
+          a.k_pool[slot * 16 + seg] = raw;
+          if (a.v_new) a.v_pool[slot * 16 + seg] = a.v_new[row * 16 + seg];
+          float x[8];
+          tw_unpack8(raw, x);
+          uint32_t word, word2, meta;
+          tw_quantize_lane8<4>(x, seg, &word, &word2, &meta);
+          a.kq_pool[slot * 16 + seg] = word;
+          if ((seg & 3) == 0) a.kq_meta[slot * 4 + (seg >> 2)] = meta;
+          // bounds: the token alone if it opens the page, else folded into the page's older tokens
+          float mn[8], mx[8];
+          tw_unpack8(rmn[it], mn);
+          tw_unpack8(rmx[it], mx);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            mn[i] = (sp & 15) ? fminf(mn[i], x[i]) : x[i];
+            mx[i] = (sp & 15) ? fmaxf(mx[i], x[i]) : x[i];
+          }
+          // min / max of bf16 values are bf16 values: the top 16 bits are exact
+          uint4 wmn, wmx;
+          wmn.x = (__float_as_uint(mn[0]) >> 16) | (__float_as_uint(mn[1]) & 0xFFFF0000u);
+          wmn.y = (__float_as_uint(mn[2]) >> 16) | (__float_as_uint(mn[3]) & 0xFFFF0000u);
+          wmn.z = (__float_as_uint(mn[4]) >> 16) | (__float_as_uint(mn[5]) & 0xFFFF0000u);
+          wmn.w = (__float_as_uint(mn[6]) >> 16) | (__float_as_uint(mn[7]) & 0xFFFF0000u);
+          wmx.x = (__float_as_uint(mx[0]) >> 16) | (__float_as_uint(mx[1]) & 0xFFFF0000u);
+          wmx.y = (__float_as_uint(mx[2]) >> 16) | (__float_as_uint(mx[3]) & 0xFFFF0000u);
+          wmx.z = (__float_as_uint(mx[4]) >> 16) | (__float_as_uint(mx[5]) & 0xFFFF0000u);
+          wmx.w = (__float_as_uint(mx[6]) >> 16) | (__float_as_uint(mx[7]) & 0xFFFF0000u);
+          uint4* pm = a.page_minmax_w + (pool[it] * a.Hkv + g) * 32;
+          pm[seg] = wmn;
+          pm[16 + seg] = wmx;
+          rmn[it] = wmn;
+          rmx[it] = wmx;
+        }
+      }
+    }
   }
 #pragma unroll
   for (int it = 0; it < IT; ++it) {
@@ -338,18 +399,25 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
 }
 
 template <int G>
-void launch_score(const ScoreArgs& a, dim3 grid, hipStream_t s) {
-  hipLaunchKernelGGL(page_score_kernel<G>, grid, dim3(256), 0, s, a);
+void launch_score(const ScoreArgs& a, dim3 grid, bool append, hipStream_t s) {
+  if (append) hipLaunchKernelGGL((page_score_kernel<G, true>), grid, dim3(256), 0, s, a);
+  else        hipLaunchKernelGGL((page_score_kernel<G, false>), grid, dim3(256), 0, s, a);
 }
 
 }  // namespace
 
-extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
-                                     int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
-                                     void* ws, size_t ws_bytes, void* stream) {
+static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
+                       int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
+                       void* ws, size_t ws_bytes, void* stream,
+                       bool append, const void* k_new, const void* v_new, const int32_t* new_pos) {
   TwDims d;
   if (int e = tw_check_kv(kv, &d)) return e;
   if (!q || !budget_tokens || !sel_pages || !sel_count || max_sel <= 0 || !kv->page_minmax) return TW_EINVAL;
+  if (append) {
+    if (!k_new || !new_pos || !kv->kq_pool || !kv->kq_meta) return TW_EINVAL;
+    if (v_new && !kv->v_pool) return TW_EINVAL;
+    if (d.bits != 4) return TW_EINVAL;            // the fused append writes the 4-bit copy only
+  }
   if (!ws || ws_bytes < twilight_workspace_bytes(TW_WS_SELECT, kv, max_sel, 0)) return TW_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
 
@@ -357,13 +425,17 @@ extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, con
   a.q = (const uint32_t*)q; a.page_minmax = (const uint4*)kv->page_minmax;
   a.page_table = kv->page_table; a.seq_lens = kv->seq_lens; a.scores = (float*)ws;
   a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.pool_pages = d.pool_pages;
+  a.k_new = (const uint4*)k_new; a.v_new = (const uint4*)v_new; a.new_pos = new_pos;
+  a.k_pool = (uint4*)kv->k_pool; a.v_pool = (uint4*)kv->v_pool;
+  a.kq_pool = (uint32_t*)kv->kq_pool; a.kq_meta = (uint32_t*)kv->kq_meta;
+  a.page_minmax_w = (uint4*)kv->page_minmax;
   dim3 grid(d.Hkv, (d.max_pages + PS_PAGES_PER_WG - 1) / PS_PAGES_PER_WG, d.batch);
   tw_prof_before(TW_K_PAGE_SCORE, s);
   switch (d.G) {
-    case 1: launch_score<1>(a, grid, s); break;
-    case 2: launch_score<2>(a, grid, s); break;
-    case 4: launch_score<4>(a, grid, s); break;
-    default: launch_score<8>(a, grid, s); break;
+    case 1: launch_score<1>(a, grid, append, s); break;
+    case 2: launch_score<2>(a, grid, append, s); break;
+    case 4: launch_score<4>(a, grid, append, s); break;
+    default: launch_score<8>(a, grid, append, s); break;
   }
   if (int e = tw_prof_after(s)) return e;
 
@@ -389,4 +461,17 @@ extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, con
   else
     hipLaunchKernelGGL(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
   return tw_prof_after(s);
+}
+
+extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
+                                     int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
+                                     void* ws, size_t ws_bytes, void* stream) {
+  return select_impl(kv, q, budget_tokens, sel_pages, sel_count, max_sel, ws, ws_bytes, stream, false, nullptr, nullptr, nullptr);
+}
+
+extern "C" int twilight_append_select(const twilight_kv_t* kv, const void* k_new, const void* v_new, const int32_t* new_pos,
+                                      const void* q, const int32_t* budget_tokens,
+                                      int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
+                                      void* ws, size_t ws_bytes, void* stream) {
+  return select_impl(kv, q, budget_tokens, sel_pages, sel_count, max_sel, ws, ws_bytes, stream, true, k_new, v_new, new_pos);
 }

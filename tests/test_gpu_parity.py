@@ -399,6 +399,63 @@ def test_step_replays_from_a_hip_graph():
         del scratch
 
 
+def test_append_select_equals_append_then_select():
+    """twilight_append_select (one new token per sequence appended on the selector's way) leaves the cache
+    and the page sets exactly as twilight_kquant_append followed by twilight_select_pages do; new tokens
+    that open a page, sit inside one, end one; a sequence without a new token; then against the oracle."""
+    T = _T()
+    lens = [1009, 48, 33, 2049, 513, 700]                 # last token: mid page, page end, page start, ...
+    w = synth.make_workload("appsel", lens, budget=[max(16, n // 4) for n in lens], p=0.9, heavy_frac=0.02,
+                            alpha_range=(0.0, 3.0), shuffle_pool=True, extra_pool_pages=5, seed=41)
+    dev = "cuda"
+    k, v, q, budget = w.k.to(dev), w.v.to(dev), w.q.to(dev), w.budget.to(dev)
+    last = torch.tensor([w.seq_offsets[b + 1] - 1 for b in range(w.batch)], dtype=torch.int64, device=dev)
+    k_last, v_last = k[last].contiguous(), v[last].contiguous()
+    start = torch.zeros(w.batch, dtype=torch.int32, device=dev)
+    offs = torch.tensor(w.seq_offsets[:-1], dtype=torch.int32, device=dev)
+    rows = torch.arange(w.batch, dtype=torch.int32, device=dev)
+    one = torch.ones(w.batch, dtype=torch.int32, device=dev)
+    max_sel = int(max(-(-int(b) // 16) for b in w.budget))
+
+    def prefilled():
+        c = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev)
+        c.append(k, v, start, c.seq_lens - 1, offs, max(lens) - 1)      # everything but the last token
+        return c
+
+    pos = (torch.tensor(lens, dtype=torch.int32, device=dev) - 1).contiguous()
+    a = prefilled()
+    a.append(k_last, v_last, pos, one, rows, 1)
+    sa = T.DecodeStep(a, max_sel=max_sel)
+    sa.select(q, budget)
+    b_ = prefilled()
+    sb = T.DecodeStep(b_, max_sel=max_sel)
+    sb.append_select(k_last, v_last, pos, q, budget)
+    torch.cuda.synchronize()
+    for name in ("k_pool", "v_pool", "kq_pool", "kq_meta", "page_minmax"):
+        x, y = getattr(a, name), getattr(b_, name)
+        assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), name
+    assert torch.equal(sa.sel_count, sb.sel_count) and torch.equal(sa.sel_pages, sb.sel_pages)
+    pa, pb = sa.ws_select.view(torch.int32).cpu(), sb.ws_select.view(torch.int32).cpu()   # bounds of every page
+    for bi in range(w.batch):
+        for h in range(w.num_q_heads):
+            o = (bi * w.num_q_heads + h) * a.max_pages
+            P = (lens[bi] + 15) // 16
+            assert torch.equal(pa[o:o + P], pb[o:o + P]), (bi, h)
+    check_cache(w, b_)
+    # a sequence without a new token keeps its cache (its last token is then simply missing)
+    c = prefilled()
+    sc = T.DecodeStep(c, max_sel=max_sel)
+    pos2 = pos.clone(); pos2[3] = -1
+    sc.append_select(k_last, v_last, pos2, q, budget)
+    torch.cuda.synchronize()
+    ref = prefilled()
+    pg = int(w.page_table[3, (lens[3] - 1) // 16])
+    assert torch.equal(c.kq_pool[pg], ref.kq_pool[pg]) and torch.equal(c.page_minmax[pg].view(torch.int16), ref.page_minmax[pg].view(torch.int16))
+    # the rest of the step on the fused cache, against the oracle
+    sb2, _ = run_pipeline(w, b_)
+    check_sets_and_output(w, b_, sb2)
+
+
 def test_p1_full_budget_reproduces_dense_attention():
     T = _T()
     w = synth.make_workload("p1", [530, 99], budget=10 ** 6, p=1.0, shuffle_pool=True, seed=17)
