@@ -566,7 +566,7 @@ def check_sampled_groups(w, cache, st, q, groups, pages_to_check=(0,)):
 
 
 def test_full_size_bench_config_sampled():
-    """BASELINE config C2 at full size (batch 8 x 32768, budget 4096, p 0.9), the launch
+    """Benchmark config C2 at full size (batch 8 x 32768, budget 4096, p 0.9), the launch
     configuration bench.py times; the oracle recomputes sampled (sequence, KV head) groups."""
     w = synth.config(1)
     cache = build_cache(w)
@@ -576,7 +576,7 @@ def test_full_size_bench_config_sampled():
 
 
 def test_full_size_pruner_stress_sampled():
-    """BASELINE config C4 at full size (4 x 262144 tokens, 64 query / 8 KV heads, every token a candidate):
+    """Benchmark config C4 at full size (4 x 262144 tokens, 64 query / 8 KV heads, every token a candidate):
     matrix-core scoring and the multi-workgroup top-p at the size bench.py --config 3 times."""
     w = synth.config(3)
     cache = build_cache(w)
@@ -588,7 +588,7 @@ def test_full_size_pruner_stress_sampled():
 
 
 def test_full_size_ragged_batch_sampled():
-    """BASELINE config C5 at full size (64 ragged sequences in one shuffled pool, budget n/8): the split
+    """Benchmark config C5 at full size (64 ragged sequences in one shuffled pool, budget n/8): the split
     top-p launch and the balanced decode work list at the size bench.py --config 4 times."""
     w = synth.config(4)
     cache = build_cache(w)
@@ -634,7 +634,7 @@ def check_sets_and_output(w, cache, st, exact_floor=0.97):
 @pytest.mark.parametrize("idx,scale,batch", [(2, 1 / 16, None), (3, 1 / 64, 2), (4, 1 / 16, 6)],
                          ids=["C3_spans", "C4_full_gqa8", "C5_ragged"])
 def test_scaled_benchmark_configs(idx, scale, batch):
-    """The remaining BASELINE configs, shrunk: clustered heavy hitters with a long page list (C3),
+    """The remaining benchmark configs, shrunk: clustered heavy hitters with a long page list (C3),
     pruner-only over every token with 8 query heads per KV head (C4), ragged batch in a shared pool (C5)."""
     w = synth.config(idx, scale=scale, batch=batch)
     cache = build_cache(w)

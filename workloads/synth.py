@@ -166,7 +166,7 @@ def ragged_lengths(count, lo, hi, seed=0):
     return [int(math.floor(math.exp(math.log(lo) + float(x) * (math.log(hi) - math.log(lo))))) for x in u]
 
 
-# The five benchmark configurations (the benchmark spec `configs`), and `scale`d
+# The five benchmark configurations C1..C5, and `scale`d
 # variants: scale < 1 shrinks contexts and budgets by that factor for tests.
 def config(idx, scale=1.0, seed=0, batch=None):
     def sc(x, lo=PAGE):
