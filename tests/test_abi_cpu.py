@@ -65,6 +65,13 @@ def test_bad_arguments_are_rejected_on_the_host(T):
     assert L.twilight_sparse_decode(ctypes.byref(kv), one, None, one, 64, one, None, one, 1 << 20, None) == -1
     assert L.twilight_sparse_decode(ctypes.byref(kv), one, one, one, 64, one, None, one, 8, None) == -2
     assert L.twilight_int4_score(ctypes.byref(kv), one, one, None, 4, one, None, None) == -1
+    # append + select in one launch: needs the new rows and positions, the 4-bit copy, the select workspace
+    assert L.twilight_append_select(ctypes.byref(kv), None, None, one, one, one, one, one, 4, one, 1 << 20, None) == -1
+    assert L.twilight_append_select(ctypes.byref(kv), one, None, None, one, one, one, one, 4, one, 1 << 20, None) == -1
+    assert L.twilight_append_select(ctypes.byref(kv), one, None, one, one, one, one, one, 4, one, 16, None) == -2
+    kv.quant_bits = 8
+    assert L.twilight_append_select(ctypes.byref(kv), one, None, one, one, one, one, one, 4, one, 1 << 20, None) == -1
+    kv.quant_bits = 4
     # per-head variant: no dense mode, needs counts, checks its own workspace size
     assert L.twilight_sparse_decode_per_head(ctypes.byref(kv), one, one, None, 64, one, None, one, 1 << 20, None) == -1
     assert L.twilight_sparse_decode_per_head(ctypes.byref(kv), one, None, one, 64, one, None, one, 1 << 20, None) == -1
