@@ -638,6 +638,7 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
     sh_last = __hip_atomic_fetch_add(a.arrive + gi * TW_CTR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(G - 1) ? 1u : 0u;
   __syncthreads();
   if (!sh_last) return;
+  TW_STAMP(14);
   if (tid == 0) __hip_atomic_store(a.arrive + gi * TW_CTR, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   constexpr int WMAX = (HP_BITMAP_WORDS + NT - 1) / NT;
   const int wpt = (nwords + NT - 1) / NT;
@@ -656,8 +657,10 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
     w[i] = ok ? x : 0u;
     ucnt += __popc(w[i]);
   }
+  TW_STAMP(15);
   uint32_t utotal;
   const uint32_t uincl = tw_block_scan_u32(ucnt, ws32, &utotal);
+  TW_STAMP(16);
   int32_t* uout = a.union_idx + (long long)gi * a.union_stride;
   uint32_t upos = uincl - ucnt;
 #pragma unroll
