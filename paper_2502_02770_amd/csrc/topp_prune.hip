@@ -129,6 +129,20 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   if (a.arrive && blockIdx.x == 0 && tid == 0) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
   if (wg_first >= count) return;
 
+  // ---- this wave's pages: lane k holds the k-th one (logical id, pool id).  Issued before the
+  //      query is quantised, so that the two dependent loads overlap that prologue.
+  const int first = wg_first + wave * a.pw;
+  int my_lp = -1, my_pool = -1;
+  if (lane < a.pw && first + lane < count) {
+    my_lp = FULL ? first + lane : a.sel_pages[((long long)(b * a.Hq + h0)) * a.max_sel + first + lane];
+    if (my_lp >= 0 && my_lp < P) {
+      const int pp = a.page_table[(long long)b * a.max_pages + my_lp];
+      if (pp >= 0 && pp < a.pool_pages) my_pool = pp;
+    }
+  }
+  int npages = count - first;
+  if (npages > a.pw) npages = a.pw;
+
   // ---- quantise q of the NH heads to int8 (symmetric, per head)
   __shared__ int qi_s[NH][32];
   __shared__ float red[4];
@@ -149,19 +163,6 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
     qs128[h] = BITS == 8 ? 128 * qs : 0;        // 8-bit codes enter the signed dot4 as code - 128
     cc[h] = c_s[h];
   }
-
-  // ---- this wave's pages: lane k holds the k-th one (logical id, pool id)
-  const int first = wg_first + wave * a.pw;
-  int my_lp = -1, my_pool = -1;
-  if (lane < a.pw && first + lane < count) {
-    my_lp = FULL ? first + lane : a.sel_pages[((long long)(b * a.Hq + h0)) * a.max_sel + first + lane];
-    if (my_lp >= 0 && my_lp < P) {
-      const int pp = a.page_table[(long long)b * a.max_pages + my_lp];
-      if (pp >= 0 && pp < a.pool_pages) my_pool = pp;
-    }
-  }
-  int npages = count - first;
-  if (npages > a.pw) npages = a.pw;
 
   float hm[NH];
 #pragma unroll
@@ -239,6 +240,17 @@ __global__ __launch_bounds__(256) void int4_score_mfma_kernel(ScoreArgs a) {
   if (a.arrive && blockIdx.x == 0 && tid == 0) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
   if (wg_first >= count) return;
 
+  // ---- this wave's pages: lane k holds the k-th one (logical id, pool id)
+  const int first = wg_first + wave * a.pw;
+  int my_lp = -1, my_pool = -1;
+  if (lane < a.pw && first + lane < count) {
+    my_lp = first + lane;
+    const int pp = a.page_table[(long long)b * a.max_pages + my_lp];
+    if (pp >= 0 && pp < a.pool_pages) my_pool = pp;
+  }
+  int npages = count - first;
+  if (npages > a.pw) npages = a.pw;
+
   __shared__ int qi_s[NH][32];
   __shared__ float red[4];
   __shared__ float c_s[NH];
@@ -271,17 +283,6 @@ __global__ __launch_bounds__(256) void int4_score_mfma_kernel(ScoreArgs a) {
     }
     cc[hg] = c_s[hg * 4 + kb];
   }
-
-  // ---- this wave's pages: lane k holds the k-th one (logical id, pool id)
-  const int first = wg_first + wave * a.pw;
-  int my_lp = -1, my_pool = -1;
-  if (lane < a.pw && first + lane < count) {
-    my_lp = first + lane;
-    const int pp = a.page_table[(long long)b * a.max_pages + my_lp];
-    if (pp >= 0 && pp < a.pool_pages) my_pool = pp;
-  }
-  int npages = count - first;
-  if (npages > a.pw) npages = a.pw;
 
   float hm[NHG];
 #pragma unroll
