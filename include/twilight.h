@@ -103,9 +103,9 @@ typedef struct twilight_kv {
 } twilight_kv_t;
 
 /*
- * Append new tokens (stage 4; Section 4.2 "extra INT4 asymmetrically
- * quantized K cache", Appendix B.1 "dynamic" quantisation with fp16 scale
- * and zero).  For sequence b the n_new[b] rows starting at row
+ * Append new tokens (stage 4; Section 4.2: the additional asymmetric INT4
+ * copy of K; Appendix B.1: quantised when written, fp16 scale and zero).
+ * For sequence b the n_new[b] rows starting at row
  * new_offsets[b] of k_new / v_new become tokens start_pos[b] ..
  * start_pos[b]+n_new[b]-1.  Written: k_pool, v_pool (bf16 copies), kq_pool,
  * kq_meta, page_minmax of every page touched.  A page that already holds
@@ -115,8 +115,8 @@ typedef struct twilight_kv {
  *
  * Quantisation, per token, KV head and group of 32 dims, fp32 arithmetic,
  * every operation rounded on its own:
- *   scale = fp16((max - min) * (1/15)),  zero = fp16(min),
- *   code  = clamp(rint((x - zero) * (1 / scale)), 0, 15)   (0 if scale == 0).
+ *   scale = fp16((max - min) * (1/L)),  zero = fp16(min),  L = 2^quant_bits - 1 (15),
+ *   code  = clamp(rint((x - zero) * (1 / scale)), 0, L)    (0 if scale == 0).
  * Inputs must be finite with |x| < 3e4 (fp16 range of scale and zero).
  *
  *   k_new, v_new   bf16 [total_new][num_kv_heads][128]; v_new may be NULL
@@ -129,8 +129,8 @@ int twilight_kquant_append(const twilight_kv_t* kv, const void* k_new, const voi
                            int32_t max_new, void* stream);
 
 /*
- * Token selector (stage 1; Section 4.1 "Token Selector ... conservative
- * budget", Section 4 C1: per-page pooling, 16 tokens per page).  For every
+ * Token selector (stage 1; Section 4.1: the base algorithm picks a generous
+ * candidate set; Section 4, challenge C1: pooling per page of 16 tokens).  For every
  * (sequence, query head): U[P] = sum_d max(q_d*min[P,d], q_d*max[P,d]) in
  * fp32 - 16 partial sums of 8 consecutive dims each, left to right, then a
  * pairwise tree over the partials - and the Kp = min(ceil(budget/16), pages)
@@ -164,8 +164,8 @@ int twilight_append_select(const twilight_kv_t* kv, const void* k_new, const voi
                            void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Estimated scores alone (first half of stage 2; Section 4.2 "SpGEMV",
- * Appendix B.1).  q is quantised per head to int8 (sq = max|q| * (1/127),
+ * Estimated scores alone (first half of stage 2; Section 4.2: the sparse
+ * matrix-vector product over the quantised K copy; Appendix B.1).  q is quantised per head to int8 (sq = max|q| * (1/127),
  * qi = clamp(rint(q / sq), -127, 127)); per token and group j of 32 dims
  * I_j = sum qi_d * code_d (int32), Qs_j = sum qi_d;
  *   s_hat = ((T0 + T1) + (T2 + T3)) * (sq * (1/sqrt(128))),
@@ -187,8 +187,10 @@ int twilight_int4_score(const twilight_kv_t* kv, const void* q, const int32_t* s
  * Appendix B.2).  Per (sequence, query head): s_hat as above over the
  * candidates, W = softmax(s_hat) over the candidates, tau* = the largest
  * weight value whose upper set {W >= tau*} has mass >= p, kept = that upper
- * set (all ties at the cut).  The threshold is searched on the bit pattern
- * of s_hat, 8 bits per step, with masses accumulated in 64-bit fixed point.
+ * set (all ties at the cut).  The threshold is found with histograms of the
+ * softmax mass over the distance to the largest score (masses in 64-bit fixed
+ * point, so the result does not depend on the order of accumulation) and an
+ * exact comparison of the last few candidates on the bits of s_hat.
  * p >= 1 keeps every candidate.  Per (sequence, KV head): union = sorted
  * unique union of the kept sets of its query heads.
  *
@@ -229,7 +231,7 @@ int twilight_sparse_decode(const twilight_kv_t* kv, const void* q, const int32_t
                            void* ws, size_t ws_bytes, void* stream);
 
 /*
- * The "head-wise varlen" alternative of Appendix B.2: every query head
+ * The head-wise variable-length alternative of Appendix B.2: every query head
  * attends over its OWN kept set instead of its group's union (same
  * arithmetic, one list per query head; the K/V rows of a KV head are then
  * loaded once per query head that kept them instead of once per group).

@@ -30,7 +30,7 @@ model of Section 4.3.
 import numpy as np
 
 HEAD_DIM = 128      # d
-PAGE = 16           # tokens per page (Section 4: "16 tokens per page")
+PAGE = 16           # tokens per page (Section 4: pages of 16 tokens)
 QGROUP = 32         # dims sharing one (scale, zero)
 NGROUPS = HEAD_DIM // QGROUP
 

@@ -1,7 +1,7 @@
 // Stage 3: variable-budget sparse decode attention over the paged bf16 KV
 // cache (paper: Definition 3.1 restricted to the kept set and renormalised
 // over it; Appendix B.2: every query head of a KV head attends over the
-// group's union, "group-wise varlen"; Section 4.2 load balancing: the
+// group's union, the group-wise variable-length form; Section 4.2 load balancing: the
 // (sequence, KV head) lists are flattened into equal-sized work items).
 //
 // Work item = (group, chunk of `chunk` consecutive list entries).  A
@@ -14,7 +14,7 @@
 // online-softmax state; states are merged by log-sum-exp, first inside the
 // workgroup, then across items by the combine kernel.
 //
-// The same kernel serves the per-head variant ("head-wise varlen" of Appendix
+// The same kernel serves the per-head variant (the head-wise form of Appendix
 // B.2): one list per query head, G = 1, list l reads KV head l / group size.
 #include <stdlib.h>
 #include "tw_common.h"

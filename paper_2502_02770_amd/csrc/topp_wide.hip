@@ -1,7 +1,7 @@
 // Stage 2b/c for long candidate rows (paper: Algorithm 1, Definition 3.3,
 // Appendix B.2): the same threshold search as the register-resident kernel,
 // spread over many workgroups per head.  Used when a head has more than 8192
-// candidates (every token a candidate - the "Full" selector - or very large
+// candidates (every token a candidate - no selector in front - or very large
 // budgets) or the sequence is too long for the in-LDS bitmap.
 //
 //   wide_init     clears histograms / lists / bitmaps, resets per-head state
