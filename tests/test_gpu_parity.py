@@ -501,6 +501,39 @@ def test_degenerate_inputs():
     assert st2.union_idx[w.num_kv_heads * 1, :5].cpu().tolist() == st.union_idx[w.num_kv_heads * 1, :5].cpu().tolist()
 
 
+@pytest.mark.parametrize("full", [False, True], ids=["page_lists", "all_tokens"])
+def test_list_capacity_overflow_sets_status_and_truncates(full):
+    """kept_stride / union_stride smaller than the lists: the status bits are set, counts are cut to the
+    stride and the entries written are the first ones of the untruncated lists (both top-p paths)."""
+    T = _T()
+    w = synth.make_workload("trunc", [9000 if full else 700, 300], num_q_heads=8, num_kv_heads=2, budget=256, p=0.9,
+                            heavy_frac=0.02, alpha_range=(0.5, 2.0), full_selector=full, shuffle_pool=True, seed=43)
+    cache = build_cache(w)
+    ref, q = run_pipeline(w, cache)                          # untruncated reference
+    assert int(ref.status.item()) == 0
+    B = T.binding
+    ks, us = 3, 5
+    i32 = dict(dtype=torch.int32, device=cache.device)
+    kept_count = torch.zeros(w.batch, w.num_q_heads, **i32)
+    kept_idx = torch.full((w.batch, w.num_q_heads, ks), -1, **i32)
+    union_count = torch.zeros(w.batch * w.num_kv_heads, **i32)
+    union_idx = torch.full((w.batch * w.num_kv_heads, us), -1, **i32)
+    status = torch.zeros(1, **i32)
+    B.twilight_topp_prune(cache.kv, q, ref.sel_pages, ref.sel_count, ref.max_sel, w.p, kept_count, kept_idx, ks,
+                          union_count, union_idx, us, status, ref.ws_prune)
+    torch.cuda.synchronize()
+    assert int(status.item()) == (B.TW_STATUS_UNION_TRUNCATED | B.TW_STATUS_KEPT_TRUNCATED)
+    for b in range(w.batch):
+        for h in range(w.num_q_heads):
+            full_n = int(ref.kept_count[b, h])
+            assert int(kept_count[b, h]) == min(full_n, ks)
+            assert kept_idx[b, h, :min(full_n, ks)].tolist() == ref.kept_idx[b, h, :min(full_n, ks)].tolist()
+    for gi in range(w.batch * w.num_kv_heads):
+        full_n = int(ref.union_count[gi])
+        assert int(union_count[gi]) == min(full_n, us)
+        assert union_idx[gi, :min(full_n, us)].tolist() == ref.union_idx[gi, :min(full_n, us)].tolist()
+
+
 def test_results_are_deterministic_run_to_run():
     w = synth.config(0, scale=0.25, seed=3)
     cache = build_cache(w)
