@@ -534,6 +534,48 @@ def test_list_capacity_overflow_sets_status_and_truncates(full):
         assert union_idx[gi, :min(full_n, us)].tolist() == ref.union_idx[gi, :min(full_n, us)].tolist()
 
 
+def test_unmapped_pages_are_skipped():
+    """page_table entries outside [0, num_pool_pages): nothing is written for their tokens, they are never
+    candidates' survivors (their scores are -inf, their page bound ranks last) and attention skips them."""
+    T = _T()
+    w = synth.make_workload("unmapped", [500], budget=512, p=0.9, heavy_frac=0.02, alpha_range=(0.5, 2.0),
+                            shuffle_pool=True, seed=47)
+    w.page_table = w.page_table.clone()
+    holes = {3: -1, 17: int(w.num_pool_pages) + 5}
+    for lp, v in holes.items():
+        w.page_table[0, lp] = v
+    cache = build_cache(w)
+    dev = cache.device
+    mapped = np.array([t for t in range(500) if (t >> 4) not in holes])
+    q = w.q.to(dev)
+    st = T.DecodeStep(cache, max_sel=32, with_kept_idx=True)
+    st.run(q, w.budget.to(dev), 1.0)                         # budget covers the sequence, p = 1: keep every candidate
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    G = w.num_q_heads // w.num_kv_heads
+    for h in range(w.num_q_heads):
+        assert int(st.sel_count[0, h]) == 32                 # all 32 pages listed, the unmapped ones too
+        kept = st.kept_idx[0, h, :int(st.kept_count[0, h])].cpu().numpy()
+        assert kept.tolist() == mapped.tolist()
+    out = st.out.cpu().float().numpy().astype(np.float64)
+    dense_out = torch.zeros_like(st.out)
+    st.dense(q, out=dense_out)
+    torch.cuda.synchronize()
+    for h in range(w.num_q_heads):
+        g = h // G
+        ref, _ = O.attention(synth.bits(w.q[0, h]), synth.bits(w.seq_k(0)[:, g]), synth.bits(w.seq_v(0)[:, g]), mapped)
+        ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
+        for got in (out[0, h], dense_out[0, h].cpu().float().numpy().astype(np.float64)):
+            assert np.abs(got - ref).max() <= MAX_ABS and np.linalg.norm(got - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
+    # a tighter budget: the unmapped pages rank last, so they are not among the selected ones
+    st2 = T.DecodeStep(cache, max_sel=8, with_kept_idx=True)
+    st2.run(q, torch.tensor([128], dtype=torch.int32, device=dev), 0.9)
+    torch.cuda.synchronize()
+    for h in range(w.num_q_heads):
+        pages = st2.sel_pages[0, h, :int(st2.sel_count[0, h])].cpu().tolist()
+        assert len(pages) == 8 and not (set(pages) & set(holes))
+
+
 def test_results_are_deterministic_run_to_run():
     w = synth.config(0, scale=0.25, seed=3)
     cache = build_cache(w)
