@@ -219,7 +219,9 @@ int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const int32_t* s
  * (max, sum, accumulator) triples are merged by log-sum-exp.
  *
  *   union_idx      NULL = dense attention over all seq_lens[b] tokens
- *                  (union_count and union_stride are then ignored)
+ *                  (union_count and union_stride are then ignored).  Entries
+ *                  outside [0, seq_lens[b]) and entries on unmapped pages are
+ *                  skipped; an entry listed twice counts twice.
  *   out            bf16 [batch][num_q_heads][128]
  *   lse            fp32 [batch][num_q_heads] or NULL: natural-log
  *                  log-sum-exp of the scaled logits (-inf for an empty set,

@@ -125,7 +125,9 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
     const int ck = item - prefix[gi];
     const int nchunks = prefix[gi + 1] - prefix[gi];
     int cnt;
-    if (dense) { cnt = a.seq_lens[b]; if (cnt > a.max_pages * TW_PAGE) cnt = a.max_pages * TW_PAGE; }
+    int nseq = a.seq_lens[b];                    // list entries at or beyond the sequence's end are ignored
+    if (nseq > a.max_pages * TW_PAGE) nseq = a.max_pages * TW_PAGE;
+    if (dense) cnt = nseq;
     else { cnt = a.union_count[gi]; if (cnt > a.union_stride) cnt = a.union_stride; }
     const int t0 = ck * chunk;
     const int len = cnt - t0 < chunk ? cnt - t0 : chunk;
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
       int r = -1;
       if (i < len) {
         const int tok = dense ? t0 + i : a.union_idx[(long long)gi * a.union_stride + t0 + i];
-        if (tok >= 0 && (tok >> 4) < a.max_pages) {
+        if (tok >= 0 && tok < nseq) {
           const long long pp = a.page_table[(long long)b * a.max_pages + (tok >> 4)];
           if (pp >= 0 && pp < a.pool_pages) r = (int)((pp * a.Hkv + g) * TW_PAGE + (tok & 15));
         }

@@ -576,6 +576,31 @@ def test_unmapped_pages_are_skipped():
         assert len(pages) == 8 and not (set(pages) & set(holes))
 
 
+def test_attention_ignores_list_entries_outside_the_sequence():
+    T = _T()
+    w = synth.make_workload("badidx", [200], budget=64, p=0.9, seed=53)
+    cache = build_cache(w)
+    dev = cache.device
+    st = T.DecodeStep(cache, max_sel=4, union_stride=16)
+    q = w.q.to(dev)
+    good = [5, 17, 60, 199]
+    lists = [good + [-1, 200, 207, 1 << 30, -(1 << 31)], [250, -7] + good]
+    for g in range(w.num_kv_heads):
+        l = lists[g % 2]
+        st.union_idx[g, :len(l)] = torch.tensor(l, dtype=torch.int32)
+        st.union_count[g] = len(l)
+    st.attend(q)
+    torch.cuda.synchronize()
+    out = st.out.cpu().float().numpy().astype(np.float64)
+    G = w.num_q_heads // w.num_kv_heads
+    for h in range(w.num_q_heads):
+        g = h // G
+        ref, rl = O.attention(synth.bits(w.q[0, h]), synth.bits(w.seq_k(0)[:, g]), synth.bits(w.seq_v(0)[:, g]), np.array(good))
+        ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
+        assert np.abs(out[0, h] - ref).max() <= MAX_ABS and np.linalg.norm(out[0, h] - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
+        assert abs(float(st.lse[0, h]) - rl) <= 1e-3 * max(1.0, abs(rl))
+
+
 def test_results_are_deterministic_run_to_run():
     w = synth.config(0, scale=0.25, seed=3)
     cache = build_cache(w)
