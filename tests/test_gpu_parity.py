@@ -601,6 +601,38 @@ def test_attention_ignores_list_entries_outside_the_sequence():
         assert abs(float(st.lse[0, h]) - rl) <= 1e-3 * max(1.0, abs(rl))
 
 
+def test_pruner_ignores_page_ids_outside_the_sequence():
+    """A caller-made page list with ids that do not exist (negative, beyond the last page): their slots
+    score -inf and are never kept; the valid pages behave as if the list held only them."""
+    T = _T()
+    w = synth.make_workload("badpage", [300], budget=64, p=0.9, heavy_frac=0.03, alpha_range=(1.0, 2.0), seed=59)
+    cache = build_cache(w)
+    dev = cache.device
+    q = w.q.to(dev)
+    st = T.DecodeStep(cache, max_sel=6, with_kept_idx=True)
+    good = [1, 4, 9, 18]                                     # 19 pages exist (300 tokens)
+    row = [-3, 1, 4, 9, 18, 25]
+    st.sel_pages[:] = torch.tensor(row, dtype=torch.int32)
+    st.sel_count[:] = len(row)
+    sc = torch.zeros(1, w.num_q_heads, 6 * 16, dtype=torch.float32, device=dev)
+    T.twilight_int4_score(cache.kv, q, st.sel_pages, st.sel_count, 6, sc, None)
+    st.prune(q, w.p)
+    torch.cuda.synchronize()
+    sc = sc.cpu().numpy()
+    assert np.all(np.isneginf(sc[0, :, :16])) and np.all(np.isneginf(sc[0, :, 80:]))
+    G = w.num_q_heads // w.num_kv_heads
+    cand = O.candidate_tokens(np.array(good, dtype=np.int32), 300)
+    for h in range(w.num_q_heads):
+        kb = synth.bits(w.seq_k(0)[:, h // G])
+        u, s_, z = O.quantize_k(kb)
+        qi, sq = O.quantize_q(synth.bits(w.q[0, h]))
+        s_hat = O.int4_scores(qi, sq, u[cand], s_[cand], z[cand])
+        tok = (np.array(good)[:, None] * 16 + np.arange(16)[None]).reshape(-1)
+        assert np.array_equal(sc[0, h, 16:80][tok < 300], s_hat) and np.all(np.isneginf(sc[0, h, 16:80][tok >= 300]))
+        kept = st.kept_idx[0, h, :int(st.kept_count[0, h])].cpu().numpy()
+        check_topp(kept, s_hat, cand, w.p)
+
+
 def test_results_are_deterministic_run_to_run():
     w = synth.config(0, scale=0.25, seed=3)
     cache = build_cache(w)
