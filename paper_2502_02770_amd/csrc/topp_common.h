@@ -24,12 +24,15 @@ struct PruneWs {
 PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full);
 
 #ifdef __HIPCC__
-// softmax numerator e in (0, 1] -> 2^-40 fixed point, from the float's own bits
+// softmax numerator e in [0, 1] -> floor(e * 2^40), exactly: the top 8 bits and the remaining 32
+// bits are taken by two float -> integer truncations (every step below is exact in fp32: scaling by
+// a power of two, the integer part of a value below 2^9, and the difference of the two)
 __device__ __forceinline__ unsigned long long hp_fix(float e) {
-  const uint32_t u = __float_as_uint(e);
-  const int sh = (int)(u >> 23) - 127 + 17;                  // mantissa * 2^(exponent - 23 + 40)
-  const unsigned long long mant = (u & 0x7FFFFFu) | 0x800000u;
-  return sh >= 0 ? mant << sh : (sh > -24 ? mant >> (-sh) : 0ull);
+  const float t = e * 256.0f;
+  const uint32_t hi = (uint32_t)t;
+  const float rem = t - (float)hi;
+  const uint32_t lo = (uint32_t)(rem * 4294967296.0f);
+  return ((unsigned long long)hi << 32) | lo;
 }
 // rank of a score: distance to the max logit in 2^-22 units; HP_NONE when the score is
 // invalid or more than 27.5 logits below the max (its 2^-40 fixed-point mass is at most one unit there)

@@ -19,6 +19,7 @@
 //                 the union of a KV head's query heads)
 // All sums are 64-bit fixed point and all atomics are integer adds / maxima,
 // so results do not depend on scheduling.
+#include <stdlib.h>
 #include "topp_common.h"
 
 namespace {
@@ -29,7 +30,6 @@ struct WideState {           // per head
 };
 constexpr uint32_t WF_DONE = 1, WF_EMPTY = 4, WF_TIER_ALL = 8;
 constexpr int W_SLOTS = 32;                    // candidate slots per thread
-constexpr int W_CHUNK = 1024 * W_SLOTS;        // per workgroup
 constexpr int W_CAP = 4096;                    // undecided scores that the resolve kernel takes
 constexpr int W_NB = 2048;                     // buckets per pass: pass 0 covers every rank (32 logits at 1/64)
 constexpr int W_BITS = 11;
@@ -79,14 +79,16 @@ __device__ __forceinline__ int wide_count(const WideArgs& a, int b, int bh) {
   return count;
 }
 
-// A workgroup covers W_CHUNK consecutive candidate slots; thread t owns 8 groups of 4 slots,
-// group v at chunk + v*4096 + 4t, so that every load instruction of a wave reads 1 KiB
-// contiguous.  Loaded unconditionally (clamped) and masked to -inf at and beyond N.
-__device__ __forceinline__ int wide_slot(int chunk0, int v, int tid) { return chunk0 + v * 4096 + tid * 4; }
+// A workgroup of NT threads covers NT * W_SLOTS consecutive candidate slots; thread t owns 8 groups
+// of 4 slots, group v at chunk + v * 4 * NT + 4t, so that every load instruction of a wave reads
+// 1 KiB contiguous.  Loaded unconditionally (clamped) and masked to -inf at and beyond N.
+template <int NT>
+__device__ __forceinline__ int wide_slot(int chunk0, int v, int tid) { return chunk0 + v * 4 * NT + tid * 4; }
+template <int NT>
 __device__ __forceinline__ void wide_load(const float* row, int chunk0, int tid, int N, int cand_stride, float* s) {
 #pragma unroll
   for (int v = 0; v < W_SLOTS / 4; ++v) {
-    const int c = wide_slot(chunk0, v, tid);
+    const int c = wide_slot<NT>(chunk0, v, tid);
     const float4 x = *(const float4*)(row + (c < cand_stride ? c : cand_stride - 4));
     s[4 * v] = c < N ? x.x : -__builtin_inff();     // N is a multiple of 16: a group is inside or outside
     s[4 * v + 1] = c < N ? x.y : -__builtin_inff();
@@ -95,7 +97,9 @@ __device__ __forceinline__ void wide_load(const float* row, int chunk0, int tid,
   }
 }
 
-__global__ __launch_bounds__(1024) void wide_hist_kernel(WideArgs a) {
+template <int NT>
+__global__ __launch_bounds__(NT) void wide_hist_kernel(WideArgs a) {
+  constexpr int W_CHUNK = NT * W_SLOTS;
   const int bh = blockIdx.y, b = bh / a.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const WideState st = a.state[bh];
   if (st.flags & WF_DONE) return;
@@ -108,9 +112,9 @@ __global__ __launch_bounds__(1024) void wide_hist_kernel(WideArgs a) {
 
   __shared__ unsigned long long histM[W_NB];
   __shared__ uint32_t histC[W_NB];
-  for (int i = tid; i < W_NB; i += 1024) { histM[i] = 0; histC[i] = 0; }
+  for (int i = tid; i < W_NB; i += NT) { histM[i] = 0; histC[i] = 0; }
   float s[W_SLOTS];
-  wide_load(a.scores + (long long)bh * a.cand_stride, chunk0, tid, N, a.cand_stride, s);
+  wide_load<NT>(a.scores + (long long)bh * a.cand_stride, chunk0, tid, N, a.cand_stride, s);
   __syncthreads();
 #pragma unroll
   for (int e = 0; e < W_SLOTS; ++e) {
@@ -124,7 +128,7 @@ __global__ __launch_bounds__(1024) void wide_hist_kernel(WideArgs a) {
     }
   }
   __syncthreads();
-  for (int i = tid; i < W_NB; i += 1024) {
+  for (int i = tid; i < W_NB; i += NT) {
     const uint32_t c = histC[i];
     if (c) { atomicAdd(&a.ghistM[(long long)bh * W_NB + i], histM[i]); atomicAdd(&a.ghistC[(long long)bh * W_NB + i], c); }
   }
@@ -182,7 +186,9 @@ __global__ __launch_bounds__(64) void wide_decide_kernel(WideArgs a) {
   if (lane == 0) a.state[bh] = st;
 }
 
-__global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
+template <int NT>
+__global__ __launch_bounds__(NT) void wide_emit_kernel(WideArgs a) {
+  constexpr int W_CHUNK = NT * W_SLOTS;
   const int bh = blockIdx.y, b = bh / a.Hq, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const WideState st = a.state[bh];
   if (!a.keep_all && st.mk == 0) return;          // no valid score: bitmap stays empty
@@ -195,13 +201,13 @@ __global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
   const bool tier = (st.flags & WF_TIER_ALL) || !(st.flags & WF_DONE);
   const uint32_t rhi = st.rlo + (st.shift >= 32 ? 0xFFFFFFFFu : (1u << st.shift)) - 1u;
   float s[W_SLOTS];
-  wide_load(a.scores + (long long)bh * a.cand_stride, chunk0, tid, N, a.cand_stride, s);
+  wide_load<NT>(a.scores + (long long)bh * a.cand_stride, chunk0, tid, N, a.cand_stride, s);
   int pg[W_SLOTS / 4];                            // logical page of each group of 4 slots (page lists only)
 #pragma unroll
   for (int v = 0; v < W_SLOTS / 4; ++v) {
     pg[v] = 0;
     if (a.sel_pages) {
-      const int pi = wide_slot(chunk0, v, tid) >> 4;
+      const int pi = wide_slot<NT>(chunk0, v, tid) >> 4;
       pg[v] = a.sel_pages[(long long)bh * a.max_sel + (pi < a.max_sel ? pi : a.max_sel - 1)];
     }
   }
@@ -233,7 +239,7 @@ __global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
       for (int e = 0; e < W_SLOTS; ++e) {
         if ((umask >> e) & 1u) {
           if (at < (uint32_t)W_CAP) {
-            const int slot = wide_slot(chunk0, e >> 2, tid) + (e & 3);
+            const int slot = wide_slot<NT>(chunk0, e >> 2, tid) + (e & 3);
             const int tok = a.sel_pages ? pg[e >> 2] * TW_PAGE + (slot & 15) : slot;
             a.ulist[(long long)bh * W_CAP + at] = make_uint2(tw_float_key(s[e]), (uint32_t)tok);
           }
@@ -247,7 +253,7 @@ __global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
   uint32_t* bm = a.bitmaps + (long long)bh * a.words_stride;
 #pragma unroll
   for (int v = 0; v < W_SLOTS / 4; ++v) {
-    const int c = wide_slot(chunk0, v, tid);
+    const int c = wide_slot<NT>(chunk0, v, tid);
     uint32_t x = ((mask >> (4 * v)) & 0xFu) << (4 * (lane & 7));
     x |= (uint32_t)tw_dpp_i<TW_DPP_XOR1>((int)x);
     x |= (uint32_t)tw_dpp_i<TW_DPP_XOR2>((int)x);
@@ -266,7 +272,7 @@ __global__ __launch_bounds__(1024) void wide_emit_kernel(WideArgs a) {
   __syncthreads();
   if (tid == 0) {
     uint32_t t = 0;
-    for (int w = 0; w < 16; ++w) t += wc[w];
+    for (int w = 0; w < NT / 64; ++w) t += wc[w];
     if (t) atomicAdd(&a.kdef[(long long)bh * TW_CTR], t);
   }
 }
@@ -508,14 +514,22 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
   a.Hq = d.Hq; a.max_pages = d.max_pages; a.max_sel = max_sel; a.cand_stride = cand_stride;
   a.words_stride = L.words_stride; a.keep_all = p >= 1.0f ? 1 : 0; a.p = p;
   const int nbh = d.batch * d.Hq;
-  const dim3 wide_grid((cand_stride + W_CHUNK - 1) / W_CHUNK, nbh);
+  // measured at 4 x 262144 tokens x 64 heads: histogram pass 72 / 77 / 83 us with 1024 / 512 / 256 threads (fewer
+  // flushes of the LDS histogram per score), emit pass 86 / 69 / 58 us (small workgroups overlap their load and
+  // compute phases; at 88 registers only one 1024-thread workgroup fits a CU)
+  constexpr int HIST_NT = 1024, EMIT_NT = 256;
+  static const int emit_nt = getenv("TW_WIDE_EMIT_NT") ? atoi(getenv("TW_WIDE_EMIT_NT")) : EMIT_NT;   // tuning switch
+  static const int hist_nt = getenv("TW_WIDE_HIST_NT") ? atoi(getenv("TW_WIDE_HIST_NT")) : HIST_NT;   // tuning switch
+  auto grid_for = [&](int nt) { return dim3((cand_stride + nt * W_SLOTS - 1) / (nt * W_SLOTS), nbh); };
   if (!a.keep_all) {
     // pass 0 locates the 1/64-logit bucket of the threshold; two 11-bit refinements at most follow
     // (a head stops as soon as <= 4096 scores are left, normally after pass 0; its later passes
     //  return at once)
     for (int pass = 0; pass < 3; ++pass) {
       tw_prof_before(TW_K_TOPP, s);
-      hipLaunchKernelGGL(wide_hist_kernel, wide_grid, dim3(1024), 0, s, a);
+      if (hist_nt == 256)      hipLaunchKernelGGL(wide_hist_kernel<256>, grid_for(256), dim3(256), 0, s, a);
+      else if (hist_nt == 512) hipLaunchKernelGGL(wide_hist_kernel<512>, grid_for(512), dim3(512), 0, s, a);
+      else                     hipLaunchKernelGGL(wide_hist_kernel<1024>, grid_for(1024), dim3(1024), 0, s, a);
       if (int e = tw_prof_after(s)) return e;
       tw_prof_before(TW_K_TOPP, s);
       hipLaunchKernelGGL(wide_decide_kernel, dim3(nbh), dim3(64), 0, s, a);
@@ -523,7 +537,10 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
     }
   }
   tw_prof_before(TW_K_TOPP, s);
-  hipLaunchKernelGGL(wide_emit_kernel, wide_grid, dim3(1024), 0, s, a);
+  if (emit_nt == 128)       hipLaunchKernelGGL(wide_emit_kernel<128>, grid_for(128), dim3(128), 0, s, a);
+  else if (emit_nt == 512)  hipLaunchKernelGGL(wide_emit_kernel<512>, grid_for(512), dim3(512), 0, s, a);
+  else if (emit_nt == 1024) hipLaunchKernelGGL(wide_emit_kernel<1024>, grid_for(1024), dim3(1024), 0, s, a);
+  else                      hipLaunchKernelGGL(wide_emit_kernel<256>, grid_for(256), dim3(256), 0, s, a);
   if (int e = tw_prof_after(s)) return e;
   tw_prof_before(TW_K_TOPP, s);
   hipLaunchKernelGGL(wide_resolve_kernel, dim3(nbh), dim3(1024), 0, s, a);
