@@ -773,7 +773,7 @@ PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full) {
   L.arrive = o;  o += al((size_t)d.batch * d.Hkv * TW_CTR * 4);
   L.bitmaps = o; o += al(bh * (size_t)L.words_stride * 4);
   if (head) {                                                // the long-row buffers are not needed
-    L.ghistM = L.ghistC = L.gtail = L.ucount = L.kdef = L.state = L.ulist = o;
+    L.ghistM = L.ghistC = L.gtail = L.ucount = L.kdef = L.state = L.ulist = L.segcnt = o;
     L.total = o;
     return L;
   }
@@ -784,6 +784,7 @@ PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full) {
   L.kdef = o;    o += al(bh * TW_CTR * 4);
   L.state = o;   o += al(bh * 48);                       // (... up to here)
   L.ulist = o;   o += al(bh * 4096 * 8);
+  L.segcnt = o;  o += al(bh * (size_t)((L.words_stride + 255) / 256) * 4);   // set bits per 256-word segment of a row's bitmap(s)
   L.total = o;
   return L;
 }

@@ -416,13 +416,32 @@ struct ListArgs {
   uint32_t* status;
   int rows_per_seq, maps_per_row, max_pages, words_stride, out_stride;
   uint32_t trunc_bit;
+  uint32_t* segcnt;           // [row][segs]: set bits per segment, filled by bitmap_count_kernel; nullptr = count in place
+  int segs;
 };
 
 // Row r: OR of NB consecutive bitmaps (r * maps_per_row ...) -> ascending positions.  One
-// workgroup per (segment of 256 words, row): it first counts the bits of the row's earlier
-// segments (its output offset), then stages its own positions in LDS and copies them out
-// coalesced.  The workgroup of the last segment also writes the count.
+// workgroup per (segment of 256 words, row): its output offset is the number of bits in the
+// row's earlier segments - read from the per-segment counts that bitmap_count_kernel left
+// (long rows), or counted in place (rows of a few segments); it then stages its own positions
+// in LDS and copies them out coalesced.  The workgroup of the last segment also writes the count.
 constexpr int BL_SEG = 256;
+template <int NB>
+__global__ __launch_bounds__(256) void bitmap_count_kernel(ListArgs a) {
+  const int row = blockIdx.y, seg = blockIdx.x, tid = threadIdx.x;
+  const uint32_t* bm = a.bitmaps + (long long)row * a.maps_per_row * a.words_stride;
+  const int wi = seg * BL_SEG + tid;
+  uint32_t w = 0;
+  if (wi < a.words_stride) {
+#pragma unroll
+    for (int hh = 0; hh < NB; ++hh) w |= bm[(long long)hh * a.words_stride + wi];
+  }
+  __shared__ uint32_t ws32[16];
+  uint32_t total;
+  tw_block_scan_u32(__popc(w), ws32, &total);
+  if (tid == 0) a.segcnt[(long long)row * a.segs + seg] = total;
+}
+
 template <int NB>
 __global__ __launch_bounds__(256) void bitmap_list_kernel(ListArgs a) {
   const int row = blockIdx.y, seg = blockIdx.x, b = row / a.rows_per_seq, tid = threadIdx.x;
@@ -439,6 +458,9 @@ __global__ __launch_bounds__(256) void bitmap_list_kernel(ListArgs a) {
   int32_t* out = a.idx_out + (long long)row * a.out_stride;
   // bits before this segment
   uint32_t before = 0;
+  if (a.segcnt) {
+    for (int s0 = tid; s0 < seg; s0 += 256) before += a.segcnt[(long long)row * a.segs + s0];
+  } else
   for (int s0 = 0; s0 < seg; s0 += 4) {             // 4 clamped loads in flight
     uint32_t x[4];
 #pragma unroll
@@ -478,10 +500,13 @@ __global__ __launch_bounds__(256) void bitmap_list_kernel(ListArgs a) {
 }
 
 template <int NB>
-void launch_list(const ListArgs& a, int rows, hipStream_t s) {
+void launch_list(ListArgs a, int rows, uint32_t* segcnt, hipStream_t s) {
   const int max_words = (a.max_pages + 1) / 2;
   int segs = (max_words + BL_SEG - 1) / BL_SEG;
   if (segs < 1) segs = 1;
+  a.segs = segs;
+  a.segcnt = segs > 4 ? segcnt : nullptr;           // few segments: counting the earlier ones in place is cheaper than a launch
+  if (a.segcnt) hipLaunchKernelGGL(bitmap_count_kernel<NB>, dim3(segs, rows), dim3(256), 0, s, a);
   hipLaunchKernelGGL(bitmap_list_kernel<NB>, dim3(segs, rows), dim3(256), 0, s, a);
 }
 
@@ -546,6 +571,7 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
   hipLaunchKernelGGL(wide_resolve_kernel, dim3(nbh), dim3(1024), 0, s, a);
   if (int e = tw_prof_after(s)) return e;
 
+  uint32_t* segcnt = (uint32_t*)(base + L.segcnt);
   ListArgs l;
   l.bitmaps = a.bitmaps; l.seq_lens = kv->seq_lens; l.status = status; l.max_pages = d.max_pages;
   l.words_stride = L.words_stride;
@@ -553,17 +579,17 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
     l.count_out = kept_count; l.idx_out = kept_idx; l.rows_per_seq = d.Hq; l.maps_per_row = 1; l.out_stride = kept_stride;
     l.trunc_bit = TW_STATUS_KEPT_TRUNCATED;
     tw_prof_before(TW_K_UNION, s);
-    launch_list<1>(l, nbh, s);
+    launch_list<1>(l, nbh, segcnt, s);
     if (int e = tw_prof_after(s)) return e;
   }
   l.count_out = union_count; l.idx_out = union_idx; l.rows_per_seq = d.Hkv; l.maps_per_row = d.G; l.out_stride = union_stride;
   l.trunc_bit = TW_STATUS_UNION_TRUNCATED;
   tw_prof_before(TW_K_UNION, s);
   switch (d.G) {
-    case 1: launch_list<1>(l, d.batch * d.Hkv, s); break;
-    case 2: launch_list<2>(l, d.batch * d.Hkv, s); break;
-    case 4: launch_list<4>(l, d.batch * d.Hkv, s); break;
-    default: launch_list<8>(l, d.batch * d.Hkv, s); break;
+    case 1: launch_list<1>(l, d.batch * d.Hkv, segcnt, s); break;
+    case 2: launch_list<2>(l, d.batch * d.Hkv, segcnt, s); break;
+    case 4: launch_list<4>(l, d.batch * d.Hkv, segcnt, s); break;
+    default: launch_list<8>(l, d.batch * d.Hkv, segcnt, s); break;
   }
   return tw_prof_after(s);
 }
