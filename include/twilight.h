@@ -273,8 +273,9 @@ int twilight_abi_version(void);
 /*
  * Per-kernel timing with HIP events recorded on the launch stream, for
  * benchmarks.  mode 0 = off (default), 1 = bracket every kernel, 2 = bracket
- * only the kernel id given to twilight_prof_select (two events per step
- * instead of two per kernel, so the step time is hardly disturbed).  While on,
+ * only the kernel id given to twilight_prof_select, at every `every`-th of
+ * its launches (an event pair holds the stream up for a few microseconds, so
+ * timing one kernel now and then hardly disturbs the step).  While on,
  * each launch adds one record {kernel id, start event, stop event} (at most
  * TW_PROF_MAX_RECORDS between two collects; further launches are not timed).
  * twilight_prof_collect synchronises the events, writes up to `cap` records
@@ -292,7 +293,7 @@ int twilight_abi_version(void);
 #define TW_K_COMBINE 7
 #define TW_K_COUNT 8
 int twilight_prof_enable(int mode);
-int twilight_prof_select(int kernel_id);
+int twilight_prof_select(int kernel_id, int every);
 int twilight_prof_collect(int32_t* kernel_ids /*host*/, float* ms /*host*/, int32_t cap);
 const char* twilight_kernel_name(int kernel_id);
 

@@ -59,7 +59,7 @@ def lib():
     L.twilight_strerror.restype = ctypes.c_char_p
     L.twilight_abi_version.restype = ctypes.c_int
     L.twilight_prof_enable.argtypes = [ctypes.c_int]
-    L.twilight_prof_select.argtypes = [ctypes.c_int]
+    L.twilight_prof_select.argtypes = [ctypes.c_int, ctypes.c_int]
     L.twilight_prof_collect.argtypes = [_vp, _vp, _i32]
     L.twilight_kernel_name.argtypes = [ctypes.c_int]
     L.twilight_kernel_name.restype = ctypes.c_char_p
@@ -162,8 +162,8 @@ def twilight_prof_enable(mode):
     _check(lib().twilight_prof_enable(int(mode)))
 
 
-def twilight_prof_select(kernel_name):
-    _check(lib().twilight_prof_select(KERNEL_NAMES.index(kernel_name)))
+def twilight_prof_select(kernel_name, every=1):
+    _check(lib().twilight_prof_select(KERNEL_NAMES.index(kernel_name), int(every)))
 
 
 def twilight_prof_collect(cap=65536):

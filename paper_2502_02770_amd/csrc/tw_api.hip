@@ -108,10 +108,14 @@ ProfRec g_rec[TW_PROF_MAX_RECORDS];
 int g_created = 0;   // events exist for records [0, g_created)
 }  // namespace
 
-int g_only = -1;     // mode 2: the one kernel id that is timed
+int g_only = -1;     // mode 2: the one kernel id that is timed ...
+int g_every = 1;     // ... at every g_every-th of its launches
+long long g_seen = 0;
 
-extern "C" int twilight_prof_select(int kernel_id) {
+extern "C" int twilight_prof_select(int kernel_id, int every) {
   g_only = kernel_id;
+  g_every = every > 0 ? every : 1;
+  g_seen = 0;
   return TW_OK;
 }
 
@@ -125,7 +129,7 @@ extern "C" int twilight_prof_enable(int mode) {
 void tw_prof_before(int kernel_id, hipStream_t s) {
   g_open = false;
   if (!g_mode || g_n >= TW_PROF_MAX_RECORDS) return;
-  if (g_mode == 2 && kernel_id != g_only) return;
+  if (g_mode == 2 && (kernel_id != g_only || (g_seen++ % g_every) != 0)) return;
   if (g_n >= g_created) {
     if (hipEventCreate(&g_rec[g_n].e0) != hipSuccess) return;
     if (hipEventCreate(&g_rec[g_n].e1) != hipSuccess) return;
