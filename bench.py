@@ -26,7 +26,7 @@ TRAFFIC_C2 = {"page_score": 33161 * 2048 + 2130 * 1024, "int4_score": 20598 * 20
               "page_select": 1076 * 2048 + 264 * 1024}
 
 # Median kernel durations (us) of the same C2 step under rocprofv3 --kernel-trace, from
-# profiles/c2_decode_step_kernel_trace.md: an event pair brackets dispatch latency too and reads ~2.5-3.5 us more.
+# profiles/c2_decode_step_kernel_trace.md, for comparison with the live figure.
 ROCPROF_US_C2 = {"page_score": 17.7, "int4_score": 14.4, "sparse_decode": 15.2, "topp": 12.0, "page_select": 8.6,
                  "combine": 3.7}
 
@@ -233,8 +233,8 @@ def main():
 
     # ---- timed region: K steps; HIP events (on the launch stream) around the dominant kernel only,
     # so the event pairs do not stretch the step the way bracketing all seven launches does
-    # (and only at every 4th of its launches: an event pair holds the stream up for ~3 us each time)
-    T.twilight_prof_select(dom, every=4)
+    # (and only at every 8th of its launches: a launch that carries events costs the stream ~10 us)
+    T.twilight_prof_select(dom, every=8)
     T.twilight_prof_enable(2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()

@@ -271,11 +271,12 @@ const char* twilight_strerror(int code);
 int twilight_abi_version(void);
 
 /*
- * Per-kernel timing with HIP events recorded on the launch stream, for
- * benchmarks.  mode 0 = off (default), 1 = bracket every kernel, 2 = bracket
- * only the kernel id given to twilight_prof_select, at every `every`-th of
- * its launches (an event pair holds the stream up for a few microseconds, so
- * timing one kernel now and then hardly disturbs the step).  While on,
+ * Per-kernel timing for benchmarks, with a HIP event pair attached to the
+ * kernel's own dispatch (hipExtLaunchKernelGGL: start and stop timestamps of
+ * the kernel, no extra packets on the stream).  mode 0 = off (default), 1 =
+ * every kernel, 2 = only the kernel id given to twilight_prof_select, at
+ * every `every`-th of its launches.  Timed launches are not meant to be
+ * captured into a graph.  While on,
  * each launch adds one record {kernel id, start event, stop event} (at most
  * TW_PROF_MAX_RECORDS between two collects; further launches are not timed).
  * twilight_prof_collect synchronises the events, writes up to `cap` records

@@ -141,8 +141,8 @@ extern "C" int twilight_kquant_append(const twilight_kv_t* kv, const void* k_new
   hipStream_t s = (hipStream_t)stream;
   tw_prof_before(TW_K_KQUANT_APPEND, s);
   const dim3 grid(pages, d.Hkv, d.batch);
-  if (d.bits == 4)      hipLaunchKernelGGL(kquant_append_kernel<4>, grid, dim3(256), 0, s, a);
-  else if (d.bits == 8) hipLaunchKernelGGL(kquant_append_kernel<8>, grid, dim3(256), 0, s, a);
-  else                  hipLaunchKernelGGL(kquant_append_kernel<2>, grid, dim3(256), 0, s, a);
+  if (d.bits == 4)      TW_LAUNCH(kquant_append_kernel<4>, grid, dim3(256), 0, s, a);
+  else if (d.bits == 8) TW_LAUNCH(kquant_append_kernel<8>, grid, dim3(256), 0, s, a);
+  else                  TW_LAUNCH(kquant_append_kernel<2>, grid, dim3(256), 0, s, a);
   return tw_prof_after(s);
 }

@@ -400,8 +400,8 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
 
 template <int G>
 void launch_score(const ScoreArgs& a, dim3 grid, bool append, hipStream_t s) {
-  if (append) hipLaunchKernelGGL((page_score_kernel<G, true>), grid, dim3(256), 0, s, a);
-  else        hipLaunchKernelGGL((page_score_kernel<G, false>), grid, dim3(256), 0, s, a);
+  if (append) TW_LAUNCH((page_score_kernel<G, true>), grid, dim3(256), 0, s, a);
+  else        TW_LAUNCH((page_score_kernel<G, false>), grid, dim3(256), 0, s, a);
 }
 
 }  // namespace
@@ -449,17 +449,17 @@ static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* bu
   if (d.max_pages > 2048 && d.max_pages <= SEL_LDS_PAGES && (long long)d.batch * d.Hq > 2ll * tw_num_cus()) {
     sa.p_upto = 2048;
     tw_prof_before(TW_K_PAGE_SELECT, s);
-    hipLaunchKernelGGL(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
     if (int e = tw_prof_after(s)) return e;
     sa.p_above = 2048; sa.p_upto = d.max_pages;
   }
   tw_prof_before(TW_K_PAGE_SELECT, s);
   if (d.max_pages <= 2048)
-    hipLaunchKernelGGL(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
   else if (d.max_pages <= SEL_LDS_PAGES)
-    hipLaunchKernelGGL(page_select_lds_kernel<1024>, dim3(d.Hq, d.batch), dim3(1024), 0, s, sa);
+    TW_LAUNCH(page_select_lds_kernel<1024>, dim3(d.Hq, d.batch), dim3(1024), 0, s, sa);
   else
-    hipLaunchKernelGGL(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+    TW_LAUNCH(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
   return tw_prof_after(s);
 }
 

@@ -411,7 +411,7 @@ void launch_decode(const DecodeArgs& a, long long max_items, size_t lds, hipStre
   long long grid = (long long)tw_num_cus() * decode_blocks_per_cu<G>(lds);
   if (grid > max_items) grid = max_items;
   if (grid < 1) grid = 1;
-  hipLaunchKernelGGL((sparse_decode_kernel<G>), dim3((unsigned)grid), dim3(256), lds, s, a);
+  TW_LAUNCH((sparse_decode_kernel<G>), dim3((unsigned)grid), dim3(256), lds, s, a);
 }
 
 }  // namespace
@@ -476,7 +476,7 @@ static int decode_impl(const twilight_kv_t* kv, const void* q, const int32_t* co
   c.ws_prefix = a.ws_prefix; c.ws_ml = a.ws_ml; c.ws_acc = (const float*)a.ws_acc;
   c.out = (uint16_t*)out; c.lse = lse; c.Hq = d.Hq; c.Hkv = LH; c.G = Gk;
   tw_prof_before(TW_K_COMBINE, s);
-  hipLaunchKernelGGL(combine_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, c);
+  TW_LAUNCH(combine_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, c);
   return tw_prof_after(s);
 }
 

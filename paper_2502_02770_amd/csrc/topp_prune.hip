@@ -696,15 +696,15 @@ template <int NH, bool FULL>
 void launch_score(const ScoreArgs& a, dim3 grid, bool dots, int bits, hipStream_t s) {
   // pages in flight per wave: 4, fewer when 8 heads share a page (register budget)
   if (bits == 2) {
-    if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2, 2>), grid, dim3(256), 0, s, a);
-    else      hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 2, 2>), grid, dim3(256), 0, s, a);
+    if (dots) TW_LAUNCH((int4_score_kernel<NH, FULL, true, 2, 2>), grid, dim3(256), 0, s, a);
+    else      TW_LAUNCH((int4_score_kernel<NH, FULL, false, 2, 2>), grid, dim3(256), 0, s, a);
   } else if (bits == 8) {
-    if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2, 8>), grid, dim3(256), 0, s, a);
-    else      hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 2, 8>), grid, dim3(256), 0, s, a);
+    if (dots) TW_LAUNCH((int4_score_kernel<NH, FULL, true, 2, 8>), grid, dim3(256), 0, s, a);
+    else      TW_LAUNCH((int4_score_kernel<NH, FULL, false, 2, 8>), grid, dim3(256), 0, s, a);
   }
-  else if (dots) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, true, 2>), grid, dim3(256), 0, s, a);
-  else if (NH < 8) hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 4>), grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((int4_score_kernel<NH, FULL, false, 2>), grid, dim3(256), 0, s, a);
+  else if (dots) TW_LAUNCH((int4_score_kernel<NH, FULL, true, 2>), grid, dim3(256), 0, s, a);
+  else if (NH < 8) TW_LAUNCH((int4_score_kernel<NH, FULL, false, 4>), grid, dim3(256), 0, s, a);
+  else TW_LAUNCH((int4_score_kernel<NH, FULL, false, 2>), grid, dim3(256), 0, s, a);
 }
 
 int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int32_t* sel_pages,
@@ -731,11 +731,11 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
   else if (d.G >= 4 && d.bits == 4 && !valu_only) {               // matrix-core kernel: 4 or 8 heads share every page
     // 8 pages in flight per wave (the kernel needs few registers, so 4 to 7 waves per SIMD stay resident)
     if (d.G == 4) {
-      if (dots) hipLaunchKernelGGL((int4_score_mfma_kernel<1, true, 4>), grid, dim3(256), 0, s, a);
-      else      hipLaunchKernelGGL((int4_score_mfma_kernel<1, false, 8>), grid, dim3(256), 0, s, a);
+      if (dots) TW_LAUNCH((int4_score_mfma_kernel<1, true, 4>), grid, dim3(256), 0, s, a);
+      else      TW_LAUNCH((int4_score_mfma_kernel<1, false, 8>), grid, dim3(256), 0, s, a);
     } else {
-      if (dots) hipLaunchKernelGGL((int4_score_mfma_kernel<2, true, 4>), grid, dim3(256), 0, s, a);
-      else      hipLaunchKernelGGL((int4_score_mfma_kernel<2, false, 8>), grid, dim3(256), 0, s, a);
+      if (dots) TW_LAUNCH((int4_score_mfma_kernel<2, true, 4>), grid, dim3(256), 0, s, a);
+      else      TW_LAUNCH((int4_score_mfma_kernel<2, false, 8>), grid, dim3(256), 0, s, a);
     }
   } else switch (d.G) {
     case 1: launch_score<1, true>(a, grid, dots != nullptr, d.bits, s); break;
@@ -856,25 +856,25 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
       f.n_upto = 4096;
       tw_prof_before(TW_K_TOPP, s);
       switch (d.G) {
-        case 1: hipLaunchKernelGGL((topp_head_kernel<512, 8, 1>), grid, dim3(512), 0, s, f); break;
-        case 2: hipLaunchKernelGGL((topp_head_kernel<512, 8, 2>), grid, dim3(512), 0, s, f); break;
-        case 4: hipLaunchKernelGGL((topp_head_kernel<512, 8, 4>), grid, dim3(512), 0, s, f); break;
-        default: hipLaunchKernelGGL((topp_head_kernel<512, 8, 8>), grid, dim3(512), 0, s, f); break;
+        case 1: TW_LAUNCH((topp_head_kernel<512, 8, 1>), grid, dim3(512), 0, s, f); break;
+        case 2: TW_LAUNCH((topp_head_kernel<512, 8, 2>), grid, dim3(512), 0, s, f); break;
+        case 4: TW_LAUNCH((topp_head_kernel<512, 8, 4>), grid, dim3(512), 0, s, f); break;
+        default: TW_LAUNCH((topp_head_kernel<512, 8, 8>), grid, dim3(512), 0, s, f); break;
       }
       if (int e = tw_prof_after(s)) return e;
       f.n_above = 4096; f.n_upto = cand_stride;
     }
     tw_prof_before(TW_K_TOPP, s);
     if (cand_stride <= 4096) switch (d.G) {
-      case 1: hipLaunchKernelGGL((topp_head_kernel<1024, 4, 1>), grid, dim3(1024), 0, s, f); break;
-      case 2: hipLaunchKernelGGL((topp_head_kernel<1024, 4, 2>), grid, dim3(1024), 0, s, f); break;
-      case 4: hipLaunchKernelGGL((topp_head_kernel<1024, 4, 4>), grid, dim3(1024), 0, s, f); break;
-      default: hipLaunchKernelGGL((topp_head_kernel<1024, 4, 8>), grid, dim3(1024), 0, s, f); break;
+      case 1: TW_LAUNCH((topp_head_kernel<1024, 4, 1>), grid, dim3(1024), 0, s, f); break;
+      case 2: TW_LAUNCH((topp_head_kernel<1024, 4, 2>), grid, dim3(1024), 0, s, f); break;
+      case 4: TW_LAUNCH((topp_head_kernel<1024, 4, 4>), grid, dim3(1024), 0, s, f); break;
+      default: TW_LAUNCH((topp_head_kernel<1024, 4, 8>), grid, dim3(1024), 0, s, f); break;
     } else switch (d.G) {
-      case 1: hipLaunchKernelGGL((topp_head_kernel<1024, 8, 1>), grid, dim3(1024), 0, s, f); break;
-      case 2: hipLaunchKernelGGL((topp_head_kernel<1024, 8, 2>), grid, dim3(1024), 0, s, f); break;
-      case 4: hipLaunchKernelGGL((topp_head_kernel<1024, 8, 4>), grid, dim3(1024), 0, s, f); break;
-      default: hipLaunchKernelGGL((topp_head_kernel<1024, 8, 8>), grid, dim3(1024), 0, s, f); break;
+      case 1: TW_LAUNCH((topp_head_kernel<1024, 8, 1>), grid, dim3(1024), 0, s, f); break;
+      case 2: TW_LAUNCH((topp_head_kernel<1024, 8, 2>), grid, dim3(1024), 0, s, f); break;
+      case 4: TW_LAUNCH((topp_head_kernel<1024, 8, 4>), grid, dim3(1024), 0, s, f); break;
+      default: TW_LAUNCH((topp_head_kernel<1024, 8, 8>), grid, dim3(1024), 0, s, f); break;
     }
     return tw_prof_after(s);
   }

@@ -500,14 +500,20 @@ __global__ __launch_bounds__(256) void bitmap_list_kernel(ListArgs a) {
 }
 
 template <int NB>
-void launch_list(ListArgs a, int rows, uint32_t* segcnt, hipStream_t s) {
+int launch_list(ListArgs a, int rows, uint32_t* segcnt, hipStream_t s) {
+  int err = TW_OK;
   const int max_words = (a.max_pages + 1) / 2;
   int segs = (max_words + BL_SEG - 1) / BL_SEG;
   if (segs < 1) segs = 1;
   a.segs = segs;
   a.segcnt = segs > 4 ? segcnt : nullptr;           // few segments: counting the earlier ones in place is cheaper than a launch
-  if (a.segcnt) hipLaunchKernelGGL(bitmap_count_kernel<NB>, dim3(segs, rows), dim3(256), 0, s, a);
-  hipLaunchKernelGGL(bitmap_list_kernel<NB>, dim3(segs, rows), dim3(256), 0, s, a);
+  if (a.segcnt) {                                    // a launch of its own: close the caller's bracket, open another
+    TW_LAUNCH(bitmap_count_kernel<NB>, dim3(segs, rows), dim3(256), 0, s, a);
+    err = tw_prof_after(s);
+    tw_prof_before(TW_K_UNION, s);
+  }
+  TW_LAUNCH(bitmap_list_kernel<NB>, dim3(segs, rows), dim3(256), 0, s, a);
+  return err;
 }
 
 }  // namespace
@@ -519,7 +525,7 @@ int tw_prune_wide_init(const TwDims& d, const PruneWs& L, void* ws, hipStream_t 
   const int nbh = d.batch * d.Hq;
   const size_t n = n16 > (size_t)nbh ? n16 : (size_t)nbh;
   tw_prof_before(TW_K_TOPP, s);
-  hipLaunchKernelGGL(wide_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
+  TW_LAUNCH(wide_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s,
                      (uint4*)((char*)ws + L.headmax), n16, (WideState*)((char*)ws + L.state), nbh);
   return tw_prof_after(s);
 }
@@ -552,23 +558,23 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
     //  return at once)
     for (int pass = 0; pass < 3; ++pass) {
       tw_prof_before(TW_K_TOPP, s);
-      if (hist_nt == 256)      hipLaunchKernelGGL(wide_hist_kernel<256>, grid_for(256), dim3(256), 0, s, a);
-      else if (hist_nt == 512) hipLaunchKernelGGL(wide_hist_kernel<512>, grid_for(512), dim3(512), 0, s, a);
-      else                     hipLaunchKernelGGL(wide_hist_kernel<1024>, grid_for(1024), dim3(1024), 0, s, a);
+      if (hist_nt == 256)      TW_LAUNCH(wide_hist_kernel<256>, grid_for(256), dim3(256), 0, s, a);
+      else if (hist_nt == 512) TW_LAUNCH(wide_hist_kernel<512>, grid_for(512), dim3(512), 0, s, a);
+      else                     TW_LAUNCH(wide_hist_kernel<1024>, grid_for(1024), dim3(1024), 0, s, a);
       if (int e = tw_prof_after(s)) return e;
       tw_prof_before(TW_K_TOPP, s);
-      hipLaunchKernelGGL(wide_decide_kernel, dim3(nbh), dim3(64), 0, s, a);
+      TW_LAUNCH(wide_decide_kernel, dim3(nbh), dim3(64), 0, s, a);
       if (int e = tw_prof_after(s)) return e;
     }
   }
   tw_prof_before(TW_K_TOPP, s);
-  if (emit_nt == 128)       hipLaunchKernelGGL(wide_emit_kernel<128>, grid_for(128), dim3(128), 0, s, a);
-  else if (emit_nt == 512)  hipLaunchKernelGGL(wide_emit_kernel<512>, grid_for(512), dim3(512), 0, s, a);
-  else if (emit_nt == 1024) hipLaunchKernelGGL(wide_emit_kernel<1024>, grid_for(1024), dim3(1024), 0, s, a);
-  else                      hipLaunchKernelGGL(wide_emit_kernel<256>, grid_for(256), dim3(256), 0, s, a);
+  if (emit_nt == 128)       TW_LAUNCH(wide_emit_kernel<128>, grid_for(128), dim3(128), 0, s, a);
+  else if (emit_nt == 512)  TW_LAUNCH(wide_emit_kernel<512>, grid_for(512), dim3(512), 0, s, a);
+  else if (emit_nt == 1024) TW_LAUNCH(wide_emit_kernel<1024>, grid_for(1024), dim3(1024), 0, s, a);
+  else                      TW_LAUNCH(wide_emit_kernel<256>, grid_for(256), dim3(256), 0, s, a);
   if (int e = tw_prof_after(s)) return e;
   tw_prof_before(TW_K_TOPP, s);
-  hipLaunchKernelGGL(wide_resolve_kernel, dim3(nbh), dim3(1024), 0, s, a);
+  TW_LAUNCH(wide_resolve_kernel, dim3(nbh), dim3(1024), 0, s, a);
   if (int e = tw_prof_after(s)) return e;
 
   uint32_t* segcnt = (uint32_t*)(base + L.segcnt);
@@ -579,17 +585,20 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
     l.count_out = kept_count; l.idx_out = kept_idx; l.rows_per_seq = d.Hq; l.maps_per_row = 1; l.out_stride = kept_stride;
     l.trunc_bit = TW_STATUS_KEPT_TRUNCATED;
     tw_prof_before(TW_K_UNION, s);
-    launch_list<1>(l, nbh, segcnt, s);
+    const int le = launch_list<1>(l, nbh, segcnt, s);
     if (int e = tw_prof_after(s)) return e;
+    if (le) return le;
   }
   l.count_out = union_count; l.idx_out = union_idx; l.rows_per_seq = d.Hkv; l.maps_per_row = d.G; l.out_stride = union_stride;
   l.trunc_bit = TW_STATUS_UNION_TRUNCATED;
   tw_prof_before(TW_K_UNION, s);
+  int le;
   switch (d.G) {
-    case 1: launch_list<1>(l, d.batch * d.Hkv, segcnt, s); break;
-    case 2: launch_list<2>(l, d.batch * d.Hkv, segcnt, s); break;
-    case 4: launch_list<4>(l, d.batch * d.Hkv, segcnt, s); break;
-    default: launch_list<8>(l, d.batch * d.Hkv, segcnt, s); break;
+    case 1: le = launch_list<1>(l, d.batch * d.Hkv, segcnt, s); break;
+    case 2: le = launch_list<2>(l, d.batch * d.Hkv, segcnt, s); break;
+    case 4: le = launch_list<4>(l, d.batch * d.Hkv, segcnt, s); break;
+    default: le = launch_list<8>(l, d.batch * d.Hkv, segcnt, s); break;
   }
-  return tw_prof_after(s);
+  if (int e = tw_prof_after(s)) return e;
+  return le;
 }

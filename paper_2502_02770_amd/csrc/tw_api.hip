@@ -136,12 +136,20 @@ void tw_prof_before(int kernel_id, hipStream_t s) {
     g_created = g_n + 1;
   }
   g_rec[g_n].id = kernel_id;
-  if (hipEventRecord(g_rec[g_n].e0, s) == hipSuccess) g_open = true;
+  g_open = true;
+  (void)s;
+}
+
+bool tw_prof_events(hipEvent_t* start, hipEvent_t* stop) {
+  if (!g_open) return false;
+  *start = g_rec[g_n].e0;
+  *stop = g_rec[g_n].e1;
+  return true;
 }
 
 int tw_prof_after(hipStream_t s) {
+  (void)s;
   if (g_open) {
-    hipEventRecord(g_rec[g_n].e1, s);
     ++g_n;
     g_open = false;
   }

@@ -18,10 +18,26 @@ struct TwDims {
 int tw_check_kv(const twilight_kv_t* kv, TwDims* d);   // TW_OK or TW_EINVAL
 int tw_num_cus();                                        // compute units of the current device
 
-// Launch bracket used by every entry point: optional event pair around the
-// kernel, then hipGetLastError -> TW_ELAUNCH.
+// Launch bracket used by every entry point: tw_prof_before opens a timing record when the
+// kernel is to be timed, TW_LAUNCH then launches with the record's event pair attached to the
+// dispatch itself (start / stop timestamps of the kernel, no extra packets on the stream; a plain
+// launch otherwise), tw_prof_after closes the record and turns hipGetLastError into TW_ELAUNCH.
+// One launch per bracket.
 void tw_prof_before(int kernel_id, hipStream_t s);
 int tw_prof_after(hipStream_t s);
+bool tw_prof_events(hipEvent_t* start, hipEvent_t* stop);   // the open record's events, false if none
+
+#ifdef __HIPCC__
+#include <hip/hip_ext.h>
+#define TW_LAUNCH(kernel, grid, block, lds, stream, ...)                                          \
+  do {                                                                                            \
+    hipEvent_t tw_e0_, tw_e1_;                                                                    \
+    if (tw_prof_events(&tw_e0_, &tw_e1_))                                                         \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, tw_e0_, tw_e1_, 0, __VA_ARGS__);    \
+    else                                                                                          \
+      hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                          \
+  } while (0)
+#endif
 
 // ---------------------------------------------------------------- device side
 #ifdef __HIPCC__
