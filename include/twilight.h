@@ -152,7 +152,8 @@ int twilight_select_pages(const twilight_kv_t* kv, const void* q, const int32_t*
  * INT4 codes, scale/zero, page bounds - bit for bit the same), then select
  * pages as twilight_select_pages does, the new token's page included.  Saves
  * the separate append launch of a decode step.  quant_bits must be 4.
- *   k_new, v_new   bf16 [batch][num_kv_heads][128] (v_new may be NULL)
+ *   k_new, v_new   bf16 [batch][num_kv_heads][128] (v_new may be NULL; kv->k_pool
+ *                  may be NULL as in twilight_kquant_append)
  *   new_pos        i32 [batch] position of the new token, < seq_lens[b]
  *                  (seq_lens already counts it); negative: nothing appended
  *                  for that sequence

@@ -32,7 +32,7 @@ struct ScoreArgs {
   const uint4* k_new;
   const uint4* v_new;         // or nullptr
   const int32_t* new_pos;     // [b] position of the new token, < 0: none
-  uint4* k_pool;
+  uint4* k_pool;              // or nullptr (no bf16 copy kept)
   uint4* v_pool;
   uint32_t* kq_pool;          // INT4 codes, 16 words per token
   uint32_t* kq_meta;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
           const long long row = (long long)b * a.Hkv + g;
           const uint4 raw = a.k_new[row * 16 + seg];
           const long long slot = (pool[it] * a.Hkv + g) * TW_PAGE + (sp & 15);
-          a.k_pool[slot * 16 + seg] = raw;
+          if (a.k_pool) a.k_pool[slot * 16 + seg] = raw;
           if (a.v_new) a.v_pool[slot * 16 + seg] = a.v_new[row * 16 + seg];
           float x[8];
           tw_unpack8(raw, x);

@@ -631,9 +631,11 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   const int gi = b * a.Hkv + h / G;
   // Ordering without cache-wide fences (a device-scope fence writes back / invalidates the whole
   // L2 and costs several microseconds here): the bitmap words are stored and loaded with
-  // device-scope atomics, which go through to the point where all CUs agree; the barrier below
-  // waits until this block's stores have completed; only then does thread 0 count the arrival.
-  // The last head of the group therefore finds every earlier head's words in place.
+  // device-scope atomics, which go through to the point where all CUs agree; every thread waits
+  // for the acknowledgement of its own stores (a workgroup barrier alone does not), the barrier
+  // then collects the block, and only after it does thread 0 count the arrival.  The last head
+  // of the group therefore finds every earlier head's words in place.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (tid == 0)
     sh_last = __hip_atomic_fetch_add(a.arrive + gi * TW_CTR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(G - 1) ? 1u : 0u;

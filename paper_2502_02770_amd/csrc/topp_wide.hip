@@ -259,7 +259,7 @@ __global__ __launch_bounds__(NT) void wide_emit_kernel(WideArgs a) {
     x |= (uint32_t)tw_dpp_i<TW_DPP_XOR2>((int)x);
     if (a.sel_pages) {                            // one 16-bit half word per selected page
       const uint32_t half = (x >> (16 * ((lane >> 2) & 1))) & 0xFFFFu;
-      if ((lane & 3) == 0 && (c >> 4) < count && (pg[v] >> 1) < a.words_stride)
+      if ((lane & 3) == 0 && (c >> 4) < count && pg[v] >= 0 && (pg[v] >> 1) < a.words_stride)   // ids outside the row: no bits, no store
         ((unsigned short*)bm)[pg[v]] = (unsigned short)half;
     } else {                                      // slots are token positions: one word per 8 lanes
       x |= (uint32_t)tw_dpp_i<TW_DPP_HALF_MIRROR>((int)x);

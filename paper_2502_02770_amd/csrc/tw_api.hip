@@ -106,11 +106,10 @@ int g_n = 0;
 bool g_open = false;
 ProfRec g_rec[TW_PROF_MAX_RECORDS];
 int g_created = 0;   // events exist for records [0, g_created)
-}  // namespace
-
 int g_only = -1;     // mode 2: the one kernel id that is timed ...
 int g_every = 1;     // ... at every g_every-th of its launches
 long long g_seen = 0;
+}  // namespace
 
 extern "C" int twilight_prof_select(int kernel_id, int every) {
   g_only = kernel_id;

@@ -601,25 +601,27 @@ def test_attention_ignores_list_entries_outside_the_sequence():
         assert abs(float(st.lse[0, h]) - rl) <= 1e-3 * max(1.0, abs(rl))
 
 
-def test_pruner_ignores_page_ids_outside_the_sequence():
+@pytest.mark.parametrize("max_sel", [6, 520], ids=["short_rows", "long_row_path"])
+def test_pruner_ignores_page_ids_outside_the_sequence(max_sel):
     """A caller-made page list with ids that do not exist (negative, beyond the last page): their slots
-    score -inf and are never kept; the valid pages behave as if the list held only them."""
+    score -inf and are never kept; the valid pages behave as if the list held only them.  A row bound of
+    520 pages (8320 candidates) sends the same list down the multi-workgroup path."""
     T = _T()
     w = synth.make_workload("badpage", [300], budget=64, p=0.9, heavy_frac=0.03, alpha_range=(1.0, 2.0), seed=59)
     cache = build_cache(w)
     dev = cache.device
     q = w.q.to(dev)
-    st = T.DecodeStep(cache, max_sel=6, with_kept_idx=True)
+    st = T.DecodeStep(cache, max_sel=max_sel, with_kept_idx=True)
     good = [1, 4, 9, 18]                                     # 19 pages exist (300 tokens)
     row = [-3, 1, 4, 9, 18, 25]
-    st.sel_pages[:] = torch.tensor(row, dtype=torch.int32)
+    st.sel_pages[:, :, :len(row)] = torch.tensor(row, dtype=torch.int32)
     st.sel_count[:] = len(row)
-    sc = torch.zeros(1, w.num_q_heads, 6 * 16, dtype=torch.float32, device=dev)
-    T.twilight_int4_score(cache.kv, q, st.sel_pages, st.sel_count, 6, sc, None)
+    sc = torch.zeros(1, w.num_q_heads, max_sel * 16, dtype=torch.float32, device=dev)
+    T.twilight_int4_score(cache.kv, q, st.sel_pages, st.sel_count, max_sel, sc, None)
     st.prune(q, w.p)
     torch.cuda.synchronize()
     sc = sc.cpu().numpy()
-    assert np.all(np.isneginf(sc[0, :, :16])) and np.all(np.isneginf(sc[0, :, 80:]))
+    assert np.all(np.isneginf(sc[0, :, :16])) and np.all(np.isneginf(sc[0, :, 80:96]))
     G = w.num_q_heads // w.num_kv_heads
     cand = O.candidate_tokens(np.array(good, dtype=np.int32), 300)
     for h in range(w.num_q_heads):
@@ -865,3 +867,68 @@ def test_long_row_path_is_deterministic():
         x, y = getattr(a, name), getattr(b, name)
         assert torch.equal(x.view(torch.int16) if x.dtype == torch.bfloat16 else x,
                            y.view(torch.int16) if y.dtype == torch.bfloat16 else y), name
+
+
+def test_append_select_without_a_bf16_k_pool():
+    """kv->k_pool may be NULL for the appending calls (no bf16 copy of K kept): the quantised copy and the
+    page bounds are written as usual and nothing else is touched."""
+    T = _T()
+    lens = [100, 33]
+    w = synth.make_workload("nokpool", lens, budget=64, p=0.9, seed=77)
+    dev = "cuda"
+    k, q, budget = w.k.to(dev), w.q.to(dev), w.budget.to(dev)
+    ref = build_cache(w)
+    c = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev, need_v=False)
+    kv = T.make_kv(c.batch, c.Hq, c.Hkv, c.max_pages, c.num_pool_pages, c.page_table, c.seq_lens, None, None,
+                   c.kq_pool, c.kq_meta, c.page_minmax)
+    start = torch.zeros(w.batch, dtype=torch.int32, device=dev)
+    offs = torch.tensor(w.seq_offsets[:-1], dtype=torch.int32, device=dev)
+    T.twilight_kquant_append(kv, k, None, start, c.seq_lens - 1, offs, max(lens) - 1)
+    last = torch.tensor([w.seq_offsets[b + 1] - 1 for b in range(w.batch)], dtype=torch.int64, device=dev)
+    pos = (torch.tensor(lens, dtype=torch.int32, device=dev) - 1).contiguous()
+    st = T.DecodeStep(c, max_sel=4)
+    T.twilight_append_select(kv, k[last].contiguous(), None, pos, q, budget, st.sel_pages, st.sel_count, 4, st.ws_select)
+    torch.cuda.synchronize()
+    for name in ("kq_pool", "kq_meta", "page_minmax"):
+        assert torch.equal(getattr(c, name).view(torch.uint8), getattr(ref, name).view(torch.uint8)), name
+    assert int(c.k_pool.view(torch.int16).abs().max()) == 0          # the pool this cache owns was not given to the call
+    rs = T.DecodeStep(ref, max_sel=4)
+    rs.select(q, budget)
+    torch.cuda.synchronize()
+    assert torch.equal(st.sel_pages, rs.sel_pages) and torch.equal(st.sel_count, rs.sel_count)
+
+
+def test_attention_at_the_list_count_limit():
+    """12000 (sequence, KV head) lists, the documented maximum of twilight_sparse_decode: the item map of all
+    lists sits in the workgroup's LDS.  Short sequences; dense and list form against the oracle on samples."""
+    T = _T()
+    batch, H = 1500, 8
+    rng = np.random.default_rng(5)
+    lens = rng.integers(1, 40, size=batch).tolist()
+    w = synth.make_workload("manylists", lens, num_q_heads=H, num_kv_heads=H, budget=16, p=0.9, seed=78)
+    cache = build_cache(w)
+    dev = cache.device
+    q = w.q.to(dev)
+    st = T.DecodeStep(cache, max_sel=1, union_stride=48)
+    cnt = torch.tensor([min(n, 3) for n in lens], dtype=torch.int32).repeat_interleave(H)
+    st.union_count[:] = cnt.to(dev)
+    st.union_idx[:, 0] = 0
+    st.union_idx[:, 1] = torch.tensor([n // 2 for n in lens], dtype=torch.int32).repeat_interleave(H).to(dev)
+    st.union_idx[:, 2] = torch.tensor([max(n - 1, 0) for n in lens], dtype=torch.int32).repeat_interleave(H).to(dev)
+    st.attend(q)
+    torch.cuda.synchronize()
+    out = st.out.cpu().float().numpy().astype(np.float64)
+    dense_out = torch.zeros_like(st.out)
+    st.dense(q, out=dense_out)
+    torch.cuda.synchronize()
+    dense_out = dense_out.cpu().float().numpy().astype(np.float64)
+    for b in (0, 1, 749, 1499):
+        n = lens[b]
+        for h in (0, 7):
+            kb, vb = synth.bits(w.seq_k(b)[:, h]), synth.bits(w.seq_v(b)[:, h])
+            idx = np.array([0, n // 2, n - 1][:min(n, 3)], dtype=np.int64)
+            for got, ids in ((out, idx), (dense_out, np.arange(n))):
+                ref, _ = O.attention(synth.bits(w.q[b, h]), kb, vb, ids)
+                ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
+                assert np.abs(got[b, h] - ref).max() <= MAX_ABS
+                assert np.linalg.norm(got[b, h] - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
