@@ -318,6 +318,42 @@ def main():
             res[name + "_us"] = sum(ms for k, ms in r) / 20 * 1e3            # decode + combine
         res["group_union_rows"] = int(sv.union_count.sum().item())
         res["per_head_rows"] = int(sv.kept_count.sum().item())
+        # "padded" (Appendix B.2, Figure 11): every head's list padded to the longest kept list of the batch with
+        # further candidates of its own, i.e. the uniform per-head budget a kernel without variable lengths needs.
+        # The lists are put together with torch ops here (set-up only); the attention is the per-head entry point.
+        dev = q.device
+        L = int(sv.kept_count.max().item())
+        slots = sv.max_sel * 16
+        cand = (sv.sel_pages.long().unsqueeze(-1) * 16 + torch.arange(16, device=dev)).reshape(w.batch, w.num_q_heads, slots)
+        sl = torch.arange(slots, device=dev)
+        ok = (sl[None, None, :] < sv.sel_count.long().unsqueeze(-1) * 16) & (cand < cache.seq_lens.long()[:, None, None])
+        is_kept = torch.zeros(w.batch, w.num_q_heads, cache.max_pages * 16 + 1, dtype=torch.bool, device=dev)
+        kidx = sv.kept_idx.long().clone()
+        kidx[torch.arange(kidx.shape[-1], device=dev)[None, None, :] >= sv.kept_count.long().unsqueeze(-1)] = cache.max_pages * 16
+        is_kept.scatter_(2, kidx, True)
+        prio = torch.gather(is_kept[..., :-1], 2, cand.clamp(0, cache.max_pages * 16 - 1)).int() * 2 + 1
+        prio[~ok] = 0
+        order = torch.argsort(prio, dim=2, descending=True, stable=True)[..., :L]
+        lists = torch.gather(cand, 2, order)
+        lcount = torch.minimum(ok.sum(2), torch.tensor(L, device=dev)).int()
+        lists[torch.arange(L, device=dev)[None, None, :] >= lcount.long().unsqueeze(-1)] = 1 << 30
+        lists = torch.sort(lists, dim=2).values.int().contiguous()
+        del is_kept, kidx, prio, order, cand, ok
+        ws_p = torch.empty(T.twilight_workspace_bytes(T.TW_WS_DECODE_PER_HEAD, cache.kv, 0, L), dtype=torch.uint8, device=dev)
+
+        def padded(qq):
+            T.twilight_sparse_decode_per_head(cache.kv, qq, lcount, lists, L, sv.out, None, ws_p)
+        for _ in range(3):
+            padded(q)
+        T.twilight_prof_enable(1)
+        for _ in range(20):
+            padded(q)
+        torch.cuda.synchronize()
+        r = T.twilight_prof_collect()
+        T.twilight_prof_enable(0)
+        res["padded_us"] = sum(ms for k, ms in r) / 20 * 1e3
+        res["padded_rows"] = int(lcount.sum().item())
+        res["padded_list_length"] = L
         variants = res
         del sv
 

@@ -18,7 +18,7 @@ constexpr int HM_SLOTS = 32;
 // Workspace of twilight_topp_prune (byte offsets).  Both paths use scores,
 // headmax, bitmaps, arrive; the rest belongs to the long-row path.
 struct PruneWs {
-  size_t scores, headmax, bitmaps, arrive, state, ghistM, ghistC, gtail, ulist, ucount, kdef, segcnt, total;
+  size_t scores, headmax, bitmaps, arrive, state, ghistM, ghistC, ulist, ucount, kdef, segcnt, total;
   int words_stride;       // bitmap words per head
 };
 PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full);

@@ -775,13 +775,12 @@ PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full) {
   L.arrive = o;  o += al((size_t)d.batch * d.Hkv * TW_CTR * 4);
   L.bitmaps = o; o += al(bh * (size_t)L.words_stride * 4);
   if (head) {                                                // the long-row buffers are not needed
-    L.ghistM = L.ghistC = L.gtail = L.ucount = L.kdef = L.state = L.ulist = L.segcnt = o;
+    L.ghistM = L.ghistC = L.ucount = L.kdef = L.state = L.ulist = L.segcnt = o;
     L.total = o;
     return L;
   }
   L.ghistM = o;  o += al(bh * 2048 * 8);
   L.ghistC = o;  o += al(bh * 2048 * 4);
-  L.gtail = o;
   L.ucount = o;  o += al(bh * TW_CTR * 4);
   L.kdef = o;    o += al(bh * TW_CTR * 4);
   L.state = o;   o += al(bh * 48);                       // (... up to here)
