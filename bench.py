@@ -352,6 +352,30 @@ def main():
         r = T.twilight_prof_collect()
         T.twilight_prof_enable(0)
         res["padded_us"] = sum(ms for k, ms in r) / 20 * 1e3
+        # the pruner behind a token-level selector (twilight_topp_prune_tokens): the same candidates handed over as
+        # token lists (gathered 80-byte pieces instead of whole 1280-byte pages), against the page-list form
+        if slots <= 8192 and cache.max_pages * 16 <= 196608:
+            tl = (sv.sel_pages.long().unsqueeze(-1) * 16 + torch.arange(16, device=dev)).reshape(w.batch, w.num_q_heads, slots).int().contiguous()
+            tc = (sv.sel_count * 16).int().contiguous()
+            ws_t = torch.empty(T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, cache.kv, slots), dtype=torch.uint8, device=dev)
+
+            def prune_tokens(qq):
+                T.twilight_topp_prune_tokens(cache.kv, qq, tl, tc, slots, w.p, sv.kept_count, None, 0, sv.union_count,
+                                             sv.union_idx, sv.union_stride, sv.status, ws_t)
+
+            def prune_pages(qq):
+                T.twilight_topp_prune(cache.kv, qq, sv.sel_pages, sv.sel_count, sv.max_sel, w.p, sv.kept_count, None, 0,
+                                      sv.union_count, sv.union_idx, sv.union_stride, sv.status, sv.ws_prune)
+            for name, fn in (("pruner_page_lists_us", prune_pages), ("pruner_token_lists_us", prune_tokens)):
+                for _ in range(3):
+                    fn(q)
+                T.twilight_prof_enable(1)
+                for _ in range(20):
+                    fn(q)
+                torch.cuda.synchronize()
+                r = T.twilight_prof_collect()
+                T.twilight_prof_enable(0)
+                res[name] = sum(ms for k, ms in r) / 20 * 1e3
         res["padded_rows"] = int(lcount.sum().item())
         res["padded_list_length"] = L
         variants = res

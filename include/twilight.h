@@ -26,7 +26,8 @@
  *   - Size limits (TW_EINVAL beyond them): batch * num_q_heads <= 65535;
  *     num_pool_pages * num_kv_heads * 16 < 2^31; at most 2^22 candidate
  *     tokens per query head in twilight_topp_prune (max_sel * 16, or
- *     max_pages_per_seq * 16 with sel_pages == NULL); batch * num_kv_heads
+ *     max_pages_per_seq * 16 with sel_pages == NULL), at most 8192 per row
+ *     of a token list (the *_tokens entry points); batch * num_kv_heads
  *     (batch * num_q_heads for the per-head variant) <= 12000 in
  *     twilight_sparse_decode.
  *   - Token indices are logical positions in their sequence (0 .. len-1);
@@ -212,6 +213,34 @@ int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const int32_t* s
                         uint32_t* status, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The pruner behind ANY token-level selector (Section 4.1: the base algorithm
+ * is a black box that hands over a token subset I_0; Section 4.2 then prunes
+ * it).  Same arithmetic and the same outputs as twilight_int4_score /
+ * twilight_topp_prune, but the candidates of a query head are a list of token
+ * positions instead of a list of pages: candidate slot c of head (b, h) is
+ * token cand_tokens[b][h][c].
+ *
+ *   cand_tokens    i32 [batch][num_q_heads][max_cand], ascending, distinct.
+ *                  Entries outside [0, seq_lens[b]) or on unmapped pages score
+ *                  -inf and are never kept.
+ *   cand_count     i32 [batch][num_q_heads], clamped to [0, max_cand]
+ *   max_cand       host: a multiple of 16, at most 8192; the sequences must
+ *                  not exceed 196608 tokens (max_pages_per_seq * 16)
+ *   scores         fp32 [batch][num_q_heads][max_cand]           out
+ *   dots           i32  [batch][num_q_heads][max_cand][4] or NULL out
+ *   ws             >= twilight_workspace_bytes(TW_WS_PRUNE_TOKENS, kv, max_cand, 0)
+ *   the rest       as twilight_topp_prune
+ */
+int twilight_int4_score_tokens(const twilight_kv_t* kv, const void* q, const int32_t* cand_tokens,
+                               const int32_t* cand_count, int32_t max_cand, float* scores, int32_t* dots,
+                               void* stream);
+int twilight_topp_prune_tokens(const twilight_kv_t* kv, const void* q, const int32_t* cand_tokens,
+                               const int32_t* cand_count, int32_t max_cand, float p,
+                               int32_t* kept_count, int32_t* kept_idx, int32_t kept_stride,
+                               int32_t* union_count, int32_t* union_idx, int32_t union_stride,
+                               uint32_t* status, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Sparse decode attention (stage 3; Definition 3.1 with the weights
  * renormalised over the attended set, Appendix B.2 group-wise varlen).
  * Every query head of KV head g attends over union_idx[b*Hkv+g][0..count):
@@ -252,7 +281,9 @@ int twilight_sparse_decode_per_head(const twilight_kv_t* kv, const void* q, cons
 #define TW_WS_PRUNE 1
 #define TW_WS_DECODE 2
 #define TW_WS_DECODE_PER_HEAD 3
-/*  max_sel: as passed to the call (0 with sel_pages == NULL);
+#define TW_WS_PRUNE_TOKENS 4
+/*  max_sel: as passed to the call (0 with sel_pages == NULL; max_cand for
+ *  TW_WS_PRUNE_TOKENS);
  *  union_stride: as passed to sparse_decode (0 for dense), kept_stride for
  *  TW_WS_DECODE_PER_HEAD. */
 size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, int32_t max_sel, int32_t union_stride);

@@ -13,7 +13,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("TWILIGHT_LIB") or os.path.join(_PKG, "libtwilight.so")   # override: tuning builds
 
-TW_WS_SELECT, TW_WS_PRUNE, TW_WS_DECODE, TW_WS_DECODE_PER_HEAD = 0, 1, 2, 3
+TW_WS_SELECT, TW_WS_PRUNE, TW_WS_DECODE, TW_WS_DECODE_PER_HEAD, TW_WS_PRUNE_TOKENS = 0, 1, 2, 3, 4
 TW_STATUS_UNION_TRUNCATED, TW_STATUS_KEPT_TRUNCATED = 1, 2
 KERNEL_NAMES = ["kquant_append", "page_score", "page_select", "int4_score", "topp", "union",
                 "sparse_decode", "combine"]
@@ -49,6 +49,8 @@ def lib():
     L.twilight_int4_score.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
     L.twilight_append_select.argtypes = [kvp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
     L.twilight_topp_prune.argtypes = [kvp, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
+    L.twilight_int4_score_tokens.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
+    L.twilight_topp_prune_tokens.argtypes = [kvp, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
     L.twilight_sparse_decode.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
     L.twilight_sparse_decode_per_head.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _sz, _vp]
     L.twilight_workspace_bytes.argtypes = [ctypes.c_int, kvp, _i32, _i32]
@@ -64,6 +66,7 @@ def lib():
     L.twilight_kernel_name.argtypes = [ctypes.c_int]
     L.twilight_kernel_name.restype = ctypes.c_char_p
     for f in ("twilight_kquant_append", "twilight_select_pages", "twilight_append_select", "twilight_int4_score", "twilight_topp_prune",
+              "twilight_int4_score_tokens", "twilight_topp_prune_tokens",
               "twilight_sparse_decode", "twilight_sparse_decode_per_head", "twilight_prof_enable", "twilight_prof_select", "twilight_prof_collect"):
         getattr(L, f).restype = ctypes.c_int
     _lib = L
@@ -144,6 +147,19 @@ def twilight_topp_prune(kv, q, sel_pages, sel_count, max_sel, p, kept_count, kep
                                      float(p), _ptr(kept_count), _ptr(kept_idx), int(kept_stride),
                                      _ptr(union_count), _ptr(union_idx), int(union_stride), _ptr(status),
                                      _ptr(ws), ws.numel() * ws.element_size(), _stream()))
+
+
+def twilight_int4_score_tokens(kv, q, cand_tokens, cand_count, max_cand, scores, dots=None):
+    _check(lib().twilight_int4_score_tokens(ctypes.byref(kv), _ptr(q), _ptr(cand_tokens), _ptr(cand_count), int(max_cand),
+                                            _ptr(scores), _ptr(dots), _stream()))
+
+
+def twilight_topp_prune_tokens(kv, q, cand_tokens, cand_count, max_cand, p, kept_count, kept_idx, kept_stride,
+                               union_count, union_idx, union_stride, status, ws):
+    _check(lib().twilight_topp_prune_tokens(ctypes.byref(kv), _ptr(q), _ptr(cand_tokens), _ptr(cand_count), int(max_cand),
+                                            float(p), _ptr(kept_count), _ptr(kept_idx), int(kept_stride),
+                                            _ptr(union_count), _ptr(union_idx), int(union_stride), _ptr(status),
+                                            _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def twilight_sparse_decode(kv, q, union_count, union_idx, union_stride, out, lse, ws):

@@ -22,6 +22,7 @@ struct PruneWs {
   int words_stride;       // bitmap words per head
 };
 PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full);
+PruneWs tw_prune_layout_tokens(const TwDims& d, int max_cand);   // token-list candidates (register-resident path only)
 
 #ifdef __HIPCC__
 // softmax numerator e in [0, 1] -> floor(e * 2^40), exactly: the top 8 bits and the remaining 32

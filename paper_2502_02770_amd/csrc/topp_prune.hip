@@ -214,6 +214,74 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   }
 }
 
+// ------------------------------------------------------------------ int4_score over token lists
+// The candidates of a head are token positions handed over by any token-level selector
+// (Section 4.1).  A quad of lanes owns one candidate (lane & 3 = group of 32 dims): 16 bytes of
+// codes and the group's (scale, zero) per lane, gathered from the token's slot in its page; a
+// workgroup covers 256 consecutive candidate slots, 64 per step, all steps' loads in flight
+// together.  Same integers and fp32 operations as the page-list kernel: bit-identical scores.
+template <bool DOTS, int BITS>
+__global__ __launch_bounds__(256) void int4_score_tokens_kernel(ScoreArgs a) {
+  constexpr int IT = 4;
+  const int tid = threadIdx.x, j = tid & 3;
+  const int b = blockIdx.y / a.Hq, h0 = blockIdx.y % a.Hq, g = h0 / (a.Hq / a.Hkv);
+  const int n = a.seq_lens[b];
+  const int ntok = n < a.max_pages * TW_PAGE ? n : a.max_pages * TW_PAGE;
+  int count = a.sel_count[b * a.Hq + h0];
+  if (count > a.max_sel) count = a.max_sel;
+  const int wg_first = blockIdx.x * 64 * IT;
+  if (a.arrive && blockIdx.x == 0 && tid == 0) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
+  if (wg_first >= count) return;
+
+  // token -> pool slot of every step first, so that the dependent loads overlap the query prologue
+  const long long row = ((long long)(b * a.Hq + h0)) * a.cand_stride;
+  long long slot4[IT];                              // (token slot in the pool) * 4 + group, or -1
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int c = wg_first + it * 64 + (tid >> 2);
+    const int tok = c < count ? a.sel_pages[row + c] : -1;
+    slot4[it] = -1;
+    if (tok >= 0 && tok < ntok) {
+      const int pp = a.page_table[(long long)b * a.max_pages + (tok >> 4)];
+      if (pp >= 0 && pp < a.pool_pages) slot4[it] = ((((long long)pp * a.Hkv + g) * TW_PAGE + (tok & 15)) << 2) + j;
+    }
+  }
+
+  __shared__ int qi_s[1][32];
+  __shared__ float red[4];
+  __shared__ float c_s[1];
+  tw_quantize_q<1>(a.q + ((long long)(b * a.Hq + h0)) * 128, qi_s, red, c_s);
+  int qw[8], qs = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    qw[k] = qi_s[0][8 * j + k];
+    qs = __builtin_amdgcn_sdot4(qw[k], 0x01010101, qs, false);
+  }
+  const float qsf = (float)qs, cc = c_s[0];
+  const int qs128 = BITS == 8 ? 128 * qs : 0;
+
+  int u[IT][8];
+  uint32_t meta[IT];
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {                 // unconditional loads (an invalid candidate reads slot 0, masked below)
+    const long long idx = slot4[it] >= 0 ? slot4[it] : (long long)j;
+    tw_load_codes<BITS>(a.kq_pool, idx, u[it]);
+    meta[it] = a.kq_meta[idx];
+  }
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int c = wg_first + it * 64 + (tid >> 2);
+    const bool valid = slot4[it] >= 0;
+    const int I = tw_group_dot(qw, u[it], qs128);
+    const float T = tw_token_sum(meta[it], I, qsf);   // all four lanes of the quad take part
+    const float sc = valid ? __fmul_rn(T, cc) : -__builtin_inff();
+    if (c < count) {
+      if (j == 0) a.scores[row + c] = sc;
+      if (DOTS) a.dots[(row + c) * 4 + j] = valid ? I : 0;
+    }
+  }
+}
+
 // ------------------------------------------------------------------ int4_score on the matrix cores
 // Every page a candidate and 4 or 8 query heads per KV head: per page the scores are a small dense
 // contraction, [heads x 128 dims] . [128 dims x 16 tokens], which on the vector ALU costs 8 dot4
@@ -390,7 +458,9 @@ struct HeadArgs {
 constexpr int HP_CAP = 64;                    // exact resolve handles up to this many scores
 constexpr int HP_BITMAP_WORDS = 6144;         // 196608 tokens
 
-template <int NT, int EPT, int G>
+// TOK: the candidates are token positions (sel_pages = the token lists, max_sel = their row length,
+// sel_count in tokens) instead of pages of 16 slots.
+template <int NT, int EPT, int G, bool TOK = false>
 __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   constexpr int NW = NT / 64;
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -403,7 +473,7 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   int count = a.sel_count[bh];
   if (count > a.max_sel) count = a.max_sel;
   if (count < 0) count = 0;
-  const int N = count * TW_PAGE;
+  const int N = TOK ? count : count * TW_PAGE;
   if (N <= a.n_above || N > a.n_upto) return;     // another launch's head (block-uniform)
   const float* row = a.scores + (long long)bh * a.cand_stride;
   const int c0 = tid * EPT;
@@ -421,7 +491,7 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   // ---- scores into registers; logical pages of the owned slots
   // (loads do not wait for the list length: anything inside the row is readable, slots at or
   //  beyond N are masked afterwards)
-  constexpr int NPG = (EPT + 15) / 16;             // pages a thread's slots fall into (a part of one if EPT < 16)
+  constexpr int NPG = TOK ? EPT : (EPT + 15) / 16; // pages a thread's slots fall into (a part of one if EPT < 16); TOK: one token per slot
   float s[EPT];
   int pg[NPG];
 #pragma unroll
@@ -430,10 +500,19 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
     const float4 x = *(const float4*)(row + cc);
     s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
   }
+  if (TOK) {
 #pragma unroll
-  for (int v = 0; v < NPG; ++v) {
-    const int pi = (c0 >> 4) + v < a.max_sel ? (c0 >> 4) + v : a.max_sel - 1;
-    pg[v] = a.sel_pages[(long long)bh * a.max_sel + pi];
+    for (int v = 0; v < EPT / 4; ++v) {
+      const int cc = c0 + 4 * v < a.max_sel ? c0 + 4 * v : a.max_sel - 4;
+      const int4 x = *(const int4*)(a.sel_pages + (long long)bh * a.max_sel + cc);
+      pg[(4 * v) % NPG] = x.x; pg[(4 * v + 1) % NPG] = x.y; pg[(4 * v + 2) % NPG] = x.z; pg[(4 * v + 3) % NPG] = x.w;
+    }
+  } else {
+#pragma unroll
+    for (int v = 0; v < NPG; ++v) {
+      const int pi = (c0 >> 4) + v < a.max_sel ? (c0 >> 4) + v : a.max_sel - 1;
+      pg[v] = a.sel_pages[(long long)bh * a.max_sel + pi];
+    }
   }
 #pragma unroll
   for (int e = 0; e < EPT; ++e) s[e] = (c0 + e < N) ? s[e] : -__builtin_inff();
@@ -601,6 +680,17 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
     const uint32_t wsumc = tw_wave_scan_u32(cnt);
     if (lane == 63 && wsumc) atomicAdd(&sh_kept, wsumc);
   }
+  if (TOK) {
+    int32_t* out = a.kept_idx ? a.kept_idx + (long long)bh * a.kept_stride : nullptr;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) {
+      if ((keep >> e) & 1u) {                       // kept => valid score => a token inside the sequence
+        const int tok = pg[e % NPG];
+        if (tok < HP_BITMAP_WORDS * 32) atomicOr(&bitmap[tok >> 5], 1u << (tok & 31));
+        if (out) { if (pos < (uint32_t)a.kept_stride) out[pos] = tok; ++pos; }
+      }
+    }
+  } else
 #pragma unroll
   for (int v = 0; v < NPG; ++v) {
     constexpr int PB = EPT < 16 ? EPT : 16;        // slots of this thread inside page v
@@ -879,4 +969,102 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
     }
     return tw_prof_after(s);
   }
+}
+
+// ------------------------------------------------------------------ token-list candidates
+static int tw_check_tokens(const TwDims& d, int32_t max_cand) {
+  if (max_cand <= 0 || (max_cand & 15) || max_cand > 1024 * 8) return TW_EINVAL;
+  if ((long long)d.max_pages * TW_PAGE > HP_BITMAP_WORDS * 32ll) return TW_EINVAL;
+  return TW_OK;
+}
+
+PruneWs tw_prune_layout_tokens(const TwDims& d, int max_cand) {
+  auto al = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  const size_t bh = (size_t)d.batch * d.Hq;
+  PruneWs L;
+  L.words_stride = (d.max_pages + 1) / 2;
+  size_t o = 0;
+  L.scores = o;  o += al(bh * (size_t)max_cand * 4);
+  L.headmax = o;
+  L.arrive = o;  o += al((size_t)d.batch * d.Hkv * TW_CTR * 4);
+  L.bitmaps = o; o += al(bh * (size_t)L.words_stride * 4);
+  L.ghistM = L.ghistC = L.ucount = L.kdef = L.state = L.ulist = L.segcnt = o;
+  L.total = o;
+  return L;
+}
+
+static int run_score_tokens(const twilight_kv_t* kv, const TwDims& d, const void* q, const int32_t* cand_tokens,
+                            const int32_t* cand_count, int32_t max_cand, float* scores, int32_t* dots,
+                            uint32_t* arrive, hipStream_t s) {
+  ScoreArgs a;
+  a.arrive = arrive; a.headmax = nullptr;
+  a.q = (const uint16_t*)q; a.sel_pages = cand_tokens; a.sel_count = cand_count;
+  a.page_table = kv->page_table; a.seq_lens = kv->seq_lens;
+  a.kq_pool = (const uint4*)kv->kq_pool; a.kq_meta = (const uint32_t*)kv->kq_meta;
+  a.scores = scores; a.dots = dots;
+  a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.max_sel = max_cand; a.cand_stride = max_cand; a.pw = 0;
+  a.pool_pages = d.pool_pages;
+  const dim3 grid((max_cand + 255) / 256, d.batch * d.Hq);
+  tw_prof_before(TW_K_INT4_SCORE, s);
+  if (d.bits == 2) {
+    if (dots) TW_LAUNCH((int4_score_tokens_kernel<true, 2>), grid, dim3(256), 0, s, a);
+    else      TW_LAUNCH((int4_score_tokens_kernel<false, 2>), grid, dim3(256), 0, s, a);
+  } else if (d.bits == 8) {
+    if (dots) TW_LAUNCH((int4_score_tokens_kernel<true, 8>), grid, dim3(256), 0, s, a);
+    else      TW_LAUNCH((int4_score_tokens_kernel<false, 8>), grid, dim3(256), 0, s, a);
+  } else {
+    if (dots) TW_LAUNCH((int4_score_tokens_kernel<true, 4>), grid, dim3(256), 0, s, a);
+    else      TW_LAUNCH((int4_score_tokens_kernel<false, 4>), grid, dim3(256), 0, s, a);
+  }
+  return tw_prof_after(s);
+}
+
+extern "C" int twilight_int4_score_tokens(const twilight_kv_t* kv, const void* q, const int32_t* cand_tokens,
+                                          const int32_t* cand_count, int32_t max_cand, float* scores, int32_t* dots,
+                                          void* stream) {
+  TwDims d;
+  if (int e = tw_check_kv(kv, &d)) return e;
+  if (!q || !scores || !cand_tokens || !cand_count || !kv->kq_pool || !kv->kq_meta) return TW_EINVAL;
+  if (int e = tw_check_tokens(d, max_cand)) return e;
+  return run_score_tokens(kv, d, q, cand_tokens, cand_count, max_cand, scores, dots, nullptr, (hipStream_t)stream);
+}
+
+extern "C" int twilight_topp_prune_tokens(const twilight_kv_t* kv, const void* q, const int32_t* cand_tokens,
+                                          const int32_t* cand_count, int32_t max_cand, float p,
+                                          int32_t* kept_count, int32_t* kept_idx, int32_t kept_stride,
+                                          int32_t* union_count, int32_t* union_idx, int32_t union_stride,
+                                          uint32_t* status, void* ws, size_t ws_bytes, void* stream) {
+  TwDims d;
+  if (int e = tw_check_kv(kv, &d)) return e;
+  if (!q || !cand_tokens || !cand_count || !kept_count || !union_count || !union_idx || !status || !kv->kq_pool || !kv->kq_meta)
+    return TW_EINVAL;
+  if (!(p > 0.f) || p > 1.f || union_stride <= 0 || (kept_idx && kept_stride <= 0)) return TW_EINVAL;
+  if (int e = tw_check_tokens(d, max_cand)) return e;
+  const PruneWs L = tw_prune_layout_tokens(d, max_cand);
+  if (!ws || ws_bytes < L.total) return TW_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  float* scores = (float*)((char*)ws + L.scores);
+  uint32_t* arrive = (uint32_t*)((char*)ws + L.arrive);
+  if (int e = run_score_tokens(kv, d, q, cand_tokens, cand_count, max_cand, scores, nullptr, arrive, s)) return e;
+  HeadArgs f;
+  f.scores = scores; f.sel_pages = cand_tokens; f.sel_count = cand_count; f.seq_lens = kv->seq_lens;
+  f.kept_count = kept_count; f.kept_idx = kept_idx; f.bitmaps = (uint32_t*)((char*)ws + L.bitmaps); f.arrive = arrive;
+  f.union_count = union_count; f.union_idx = union_idx; f.status = status;
+  f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_cand; f.cand_stride = max_cand;
+  f.kept_stride = kept_stride; f.words_stride = L.words_stride; f.union_stride = union_stride; f.p = p;
+  f.n_above = -1; f.n_upto = max_cand;
+  const dim3 grid(d.Hq, d.batch);
+  tw_prof_before(TW_K_TOPP, s);
+  if (max_cand <= 4096) switch (d.G) {
+    case 1: TW_LAUNCH((topp_head_kernel<1024, 4, 1, true>), grid, dim3(1024), 0, s, f); break;
+    case 2: TW_LAUNCH((topp_head_kernel<1024, 4, 2, true>), grid, dim3(1024), 0, s, f); break;
+    case 4: TW_LAUNCH((topp_head_kernel<1024, 4, 4, true>), grid, dim3(1024), 0, s, f); break;
+    default: TW_LAUNCH((topp_head_kernel<1024, 4, 8, true>), grid, dim3(1024), 0, s, f); break;
+  } else switch (d.G) {
+    case 1: TW_LAUNCH((topp_head_kernel<1024, 8, 1, true>), grid, dim3(1024), 0, s, f); break;
+    case 2: TW_LAUNCH((topp_head_kernel<1024, 8, 2, true>), grid, dim3(1024), 0, s, f); break;
+    case 4: TW_LAUNCH((topp_head_kernel<1024, 8, 4, true>), grid, dim3(1024), 0, s, f); break;
+    default: TW_LAUNCH((topp_head_kernel<1024, 8, 8, true>), grid, dim3(1024), 0, s, f); break;
+  }
+  return tw_prof_after(s);
 }

@@ -65,6 +65,9 @@ extern "C" size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, i
       const int bound = max_sel > 0 ? max_sel : d.max_pages;
       return tw_prune_layout(d, bound, max_sel <= 0).total;
     }
+    case TW_WS_PRUNE_TOKENS:
+      if (max_sel <= 0 || (max_sel & 15) || max_sel > 8192) return 0;
+      return tw_prune_layout_tokens(d, max_sel).total;
     case TW_WS_DECODE: {
       const bool dense = union_stride <= 0;
       const size_t items = (size_t)tw_decode_max_items(d, dense, union_stride);

@@ -93,6 +93,16 @@ def test_bad_arguments_are_rejected_on_the_host(T):
     long_row.kq_pool, long_row.kq_meta, long_row.page_minmax, long_row.k_pool, long_row.v_pool = 4096, 4096, 4096, 4096, 4096
     assert L.twilight_topp_prune(ctypes.byref(long_row), one, None, None, 0, ctypes.c_float(0.9), one, None, 0, one, one,
                                  64, one, one, 1 << 40, None) == -1                                # 2^24 candidates
+    # token-list candidates: row length a multiple of 16 and at most 8192, sequences of at most 196608 tokens
+    f09 = ctypes.c_float(0.9)
+    assert L.twilight_topp_prune_tokens(ctypes.byref(kv), one, one, one, 100, f09, one, None, 0, one, one, 64, one, one, 1 << 30, None) == -1
+    assert L.twilight_topp_prune_tokens(ctypes.byref(kv), one, one, one, 8208, f09, one, None, 0, one, one, 64, one, one, 1 << 30, None) == -1
+    assert L.twilight_topp_prune_tokens(ctypes.byref(kv), one, None, one, 64, f09, one, None, 0, one, one, 64, one, one, 1 << 30, None) == -1
+    assert L.twilight_topp_prune_tokens(ctypes.byref(kv), one, one, one, 64, f09, one, None, 0, one, one, 64, one, one, 8, None) == -2
+    assert L.twilight_int4_score_tokens(ctypes.byref(kv), one, one, one, 24, one, None, None) == -1
+    assert L.twilight_int4_score_tokens(ctypes.byref(long_row), one, one, one, 64, one, None, None) == -1
+    assert T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, kv, 64, 0) >= 32 * 64 * 4
+    assert T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, kv, 100, 0) == 0
     # pinned-pointer query: NULL arguments
     out = ctypes.c_void_p()
     assert L.twilight_pinned_device_pointer(None, ctypes.byref(out)) == -1

@@ -932,3 +932,137 @@ def test_attention_at_the_list_count_limit():
                 ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
                 assert np.abs(got[b, h] - ref).max() <= MAX_ABS
                 assert np.linalg.norm(got[b, h] - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
+
+
+def _token_candidates(w, max_cand, seed, bad_ids=False):
+    """Per (sequence, query head) an ascending list of distinct token positions of random length (some empty,
+    some full), as a token-level selector would hand over; optionally with ids outside the sequence."""
+    rng = np.random.default_rng(seed)
+    cand = np.zeros((w.batch, w.num_q_heads, max_cand), dtype=np.int32)
+    cnt = np.zeros((w.batch, w.num_q_heads), dtype=np.int32)
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        for h in range(w.num_q_heads):
+            c = int(rng.choice([0, 1, 17, min(n, max_cand), rng.integers(1, min(n, max_cand) + 1)]))
+            ids = np.sort(rng.choice(n, size=c, replace=False)).astype(np.int32)
+            if bad_ids and c >= 3:
+                ids[0] = -5
+                ids[-1] = n + 3
+            cand[b, h, :c] = ids
+            cnt[b, h] = c
+    return cand, cnt
+
+
+@pytest.mark.parametrize("bits", [4, 2, 8])
+def test_token_list_scores_bit_exact(bits):
+    """twilight_int4_score_tokens: scores and integer dot products of arbitrary token lists equal the
+    oracle's bit for bit; ids outside the sequence score -inf."""
+    T = _T()
+    w = synth.make_workload("tokcand", [1500, 333, 40], num_q_heads=8, num_kv_heads=2, budget=64, p=0.9,
+                            heavy_frac=0.02, alpha_range=(0.5, 3.0), shuffle_pool=True, extra_pool_pages=3, seed=90 + bits)
+    cache = build_cache(w, bits=bits)
+    dev = cache.device
+    q = w.q.to(dev)
+    max_cand = 1504
+    cand, cnt = _token_candidates(w, max_cand, seed=bits, bad_ids=True)
+    sc = torch.full((w.batch, w.num_q_heads, max_cand), 7.0, dtype=torch.float32, device=dev)
+    dots = torch.zeros(w.batch, w.num_q_heads, max_cand, 4, dtype=torch.int32, device=dev)
+    T.twilight_int4_score_tokens(cache.kv, q, torch.from_numpy(cand).to(dev), torch.from_numpy(cnt).to(dev), max_cand, sc, dots)
+    torch.cuda.synchronize()
+    sc, dots = sc.cpu().numpy(), dots.cpu().numpy()
+    G = w.num_q_heads // w.num_kv_heads
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        for h in range(w.num_q_heads):
+            c = int(cnt[b, h])
+            ids = cand[b, h, :c]
+            ok = (ids >= 0) & (ids < n)
+            u, s_, z = O.quantize_k(synth.bits(w.seq_k(b)[:, h // G]), bits)
+            qi, sq = O.quantize_q(synth.bits(w.q[b, h]))
+            v = ids[ok]
+            s_hat = O.int4_scores(qi, sq, u[v], s_[v], z[v])
+            I, _ = O.int4_dots(qi, u[v])
+            assert np.array_equal(sc[b, h, :c][ok].view(np.uint32), s_hat.view(np.uint32)), (b, h)
+            assert np.all(np.isneginf(sc[b, h, :c][~ok]))
+            assert np.array_equal(dots[b, h, :c][ok], I), (b, h)
+            assert np.all(sc[b, h, c:] == 7.0)                     # slots beyond the list are not written
+
+
+@pytest.mark.parametrize("max_cand", [1504, 4112], ids=["4_per_thread", "8_per_thread"])
+def test_pruner_on_token_lists_against_oracle(max_cand):
+    """twilight_topp_prune_tokens behind a token-level selector (Section 4.1): per head the top-p threshold
+    set of its own token list (Definition 3.3), the group's union, and attention over it."""
+    T = _T()
+    lens = [5000, 333, 40] if max_cand > 4096 else [1500, 333, 40]
+    w = synth.make_workload("tokprune", lens, num_q_heads=8, num_kv_heads=2, budget=64, p=0.9,
+                            heavy_frac=0.02, alpha_range=(0.5, 3.0), shuffle_pool=True, extra_pool_pages=3, seed=95)
+    cache = build_cache(w)
+    dev = cache.device
+    q = w.q.to(dev)
+    cand, cnt = _token_candidates(w, max_cand, seed=3, bad_ids=True)
+    st = T.DecodeStep(cache, max_sel=max_cand // 16, with_kept_idx=True)     # output buffers of the same shapes
+    ws = torch.empty(T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, cache.kv, max_cand), dtype=torch.uint8, device=dev)
+    for rep in range(2):                                                       # twice: the arrival counters must be reusable
+        T.twilight_topp_prune_tokens(cache.kv, q, torch.from_numpy(cand).to(dev), torch.from_numpy(cnt).to(dev), max_cand, w.p,
+                                     st.kept_count, st.kept_idx, st.kept_stride, st.union_count, st.union_idx,
+                                     st.union_stride, st.status, ws)
+        st.attend(q)
+        torch.cuda.synchronize()
+        assert int(st.status.item()) == 0
+        out = st.out.cpu().float().numpy().astype(np.float64)
+        G = w.num_q_heads // w.num_kv_heads
+        for b in range(w.batch):
+            n = int(w.seq_lens[b])
+            for g in range(w.num_kv_heads):
+                kb, vb = synth.bits(w.seq_k(b)[:, g]), synth.bits(w.seq_v(b)[:, g])
+                u, s_, z = O.quantize_k(kb)
+                kept_all = []
+                for h in range(g * G, g * G + G):
+                    ids = cand[b, h, :int(cnt[b, h])]
+                    v = ids[(ids >= 0) & (ids < n)]
+                    qi, sq = O.quantize_q(synth.bits(w.q[b, h]))
+                    s_hat = O.int4_scores(qi, sq, u[v], s_[v], z[v])
+                    kept = st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+                    if len(v):
+                        check_topp(kept, s_hat, v, w.p)
+                    else:
+                        assert len(kept) == 0
+                    kept_all.append(kept)
+                gi = b * w.num_kv_heads + g
+                un = st.union_idx[gi, :int(st.union_count[gi])].cpu().numpy()
+                assert un.tolist() == np.unique(np.concatenate(kept_all)).tolist()
+                for h in range(g * G, g * G + G):
+                    if len(un) == 0:
+                        assert np.all(out[b, h] == 0)
+                        continue
+                    ref, _ = O.attention(synth.bits(w.q[b, h]), kb, vb, un)
+                    ref = O.bf16_to_f32(O.f32_to_bf16(ref.astype(np.float32))).astype(np.float64)
+                    assert np.abs(out[b, h] - ref).max() <= MAX_ABS
+                    assert np.linalg.norm(out[b, h] - ref) <= REL_L2 * np.linalg.norm(ref) + 1e-6
+
+
+def test_token_lists_of_whole_pages_equal_the_page_list_pruner():
+    """The tokens of the selected pages handed over as token lists: scores, kept lists and unions are
+    bit-identical to twilight_topp_prune on the page lists."""
+    T = _T()
+    w = synth.config(0, scale=0.5, seed=11)
+    cache = build_cache(w)
+    dev = cache.device
+    q = w.q.to(dev)
+    st, _ = run_pipeline(w, cache)
+    max_cand = st.max_sel * 16
+    cand = (st.sel_pages.long().unsqueeze(-1) * 16 + torch.arange(16, device=dev)).reshape(w.batch, w.num_q_heads, max_cand).int().contiguous()
+    cnt = (st.sel_count * 16).int().contiguous()
+    st2 = T.DecodeStep(cache, max_sel=st.max_sel, with_kept_idx=True)
+    ws = torch.empty(T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, cache.kv, max_cand), dtype=torch.uint8, device=dev)
+    T.twilight_topp_prune_tokens(cache.kv, q, cand, cnt, max_cand, w.p, st2.kept_count, st2.kept_idx, st2.kept_stride,
+                                 st2.union_count, st2.union_idx, st2.union_stride, st2.status, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(st.kept_count, st2.kept_count) and torch.equal(st.union_count, st2.union_count)
+    for b in range(w.batch):
+        for h in range(w.num_q_heads):
+            c = int(st.kept_count[b, h])
+            assert torch.equal(st.kept_idx[b, h, :c], st2.kept_idx[b, h, :c])
+    for gi in range(w.batch * w.num_kv_heads):
+        c = int(st.union_count[gi])
+        assert torch.equal(st.union_idx[gi, :c], st2.union_idx[gi, :c])
