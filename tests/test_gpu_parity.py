@@ -709,6 +709,30 @@ def test_full_size_bench_config_sampled():
     check_sampled_groups(w, cache, st, q, ((0, 0), (3, 5), (7, 7)), pages_to_check=(0, 1000, 2047))
 
 
+def test_full_size_smallest_config_every_group():
+    """Benchmark config C1 at full size (1 x 4096, budget 1024, p 0.95): every head and group against the oracle."""
+    w = synth.config(0)
+    cache = build_cache(w)
+    check_cache(w, cache)
+    st, q = run_pipeline(w, cache)
+    assert int(st.status.item()) == 0
+    check_sets_and_output(w, cache, st)
+
+
+@pytest.mark.parametrize("p", [0.8, 0.9, 0.95, 0.99])
+def test_full_size_long_context_p_sweep_sampled(p):
+    """Benchmark config C3 at full size (1 x 131072, clustered heavy hitters, budget 8192) at each threshold
+    of its sweep; the oracle recomputes two sampled KV heads stage by stage."""
+    w = synth.config(2)
+    w.p = p
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache, with_kept=True)
+    assert int(st.status.item()) == 0
+    check_sampled_groups(w, cache, st, q, ((0, 1), (0, 6)), pages_to_check=(0, 4095, 8191))
+    del st, cache
+    torch.cuda.empty_cache()
+
+
 def test_full_size_pruner_stress_sampled():
     """Benchmark config C4 at full size (4 x 262144 tokens, 64 query / 8 KV heads, every token a candidate):
     matrix-core scoring and the multi-workgroup top-p at the size bench.py --config 3 times."""
