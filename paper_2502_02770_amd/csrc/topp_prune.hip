@@ -733,36 +733,46 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   if (!sh_last) return;
   TW_STAMP(14);
   if (tid == 0) __hip_atomic_store(a.arrive + gi * TW_CTR, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
-  constexpr int WMAX = (HP_BITMAP_WORDS + NT - 1) / NT;
-  const int wpt = (nwords + NT - 1) / NT;
-  const int w0 = tid * wpt;
+  // OR of the group's bitmaps into LDS (this block's own bitmap is no longer needed there): coalesced,
+  // four words per thread and bitmap in flight
   const uint32_t* bmg = a.bitmaps + ((long long)(b * a.Hq + (h / G) * G)) * a.words_stride;
-  uint32_t w[WMAX];
-  uint32_t ucnt = 0;
+  for (int base = 0; base < nwords; base += 4 * NT) {
+    uint32_t x[4];
 #pragma unroll
-  for (int i = 0; i < WMAX; ++i) {                 // clamped, unconditional loads; masked afterwards
-    const bool ok = i < wpt && w0 + i < nwords;
-    const int wi = ok ? w0 + i : 0;
-    uint32_t x = 0;
+    for (int k = 0; k < 4; ++k) {
+      x[k] = 0;
+      if (base + k * NT < nwords) {                  // block-uniform
+        const int i = base + k * NT + tid;
+        const int wi = i < nwords ? i : 0;
 #pragma unroll
-    for (int hh = 0; hh < G; ++hh)
-      x |= __hip_atomic_load(bmg + (long long)hh * a.words_stride + wi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    w[i] = ok ? x : 0u;
-    ucnt += __popc(w[i]);
+        for (int hh = 0; hh < G; ++hh)
+          x[k] |= __hip_atomic_load(bmg + (long long)hh * a.words_stride + wi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int i = base + k * NT + tid;
+      if (i < nwords) bitmap[i] = x[k];
+    }
   }
+  __syncthreads();
   TW_STAMP(15);
+  // thread t owns the contiguous words [t * wpt, (t + 1) * wpt): ascending output positions
+  const int wpt = (nwords + NT - 1) / NT;
+  const int w0 = tid * wpt, w1 = w0 + wpt < nwords ? w0 + wpt : nwords;
+  uint32_t ucnt = 0;
+  for (int i = w0; i < w1; ++i) ucnt += __popc(bitmap[i]);
   uint32_t utotal;
   const uint32_t uincl = tw_block_scan_u32(ucnt, ws32, &utotal);
   TW_STAMP(16);
   int32_t* uout = a.union_idx + (long long)gi * a.union_stride;
   uint32_t upos = uincl - ucnt;
-#pragma unroll
-  for (int i = 0; i < WMAX; ++i) {
-    uint32_t x = w[i];
+  for (int i = w0; i < w1; ++i) {
+    uint32_t x = bitmap[i];
     while (x) {
       const int bit = __ffs(x) - 1;
       x &= x - 1;
-      if (upos < (uint32_t)a.union_stride) uout[upos] = (w0 + i) * 32 + bit;
+      if (upos < (uint32_t)a.union_stride) uout[upos] = i * 32 + bit;
       ++upos;
     }
   }
