@@ -1090,3 +1090,47 @@ def test_token_lists_of_whole_pages_equal_the_page_list_pruner():
     for gi in range(w.batch * w.num_kv_heads):
         c = int(st.union_count[gi])
         assert torch.equal(st.union_idx[gi, :c], st2.union_idx[gi, :c])
+
+
+def test_token_lists_keep_all_at_p1_and_report_overflow():
+    """p = 1 keeps every candidate that lies inside its sequence; lists longer than their strides are cut and
+    the status word says so."""
+    T = _T()
+    w = synth.make_workload("tokp1", [700, 90], num_q_heads=4, num_kv_heads=2, budget=64, p=1.0, seed=97)
+    cache = build_cache(w)
+    dev = cache.device
+    q = w.q.to(dev)
+    max_cand = 704
+    cand, cnt = _token_candidates(w, max_cand, seed=9, bad_ids=True)
+    cnt[0, 0] = 0                                              # an empty list next to full ones
+    cand_d, cnt_d = torch.from_numpy(cand).to(dev), torch.from_numpy(cnt).to(dev)
+    st = T.DecodeStep(cache, max_sel=max_cand // 16, with_kept_idx=True)
+    ws = torch.empty(T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, cache.kv, max_cand), dtype=torch.uint8, device=dev)
+    T.twilight_topp_prune_tokens(cache.kv, q, cand_d, cnt_d, max_cand, 1.0, st.kept_count, st.kept_idx, st.kept_stride,
+                                 st.union_count, st.union_idx, st.union_stride, st.status, ws)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    G = 2
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        for h in range(w.num_q_heads):
+            ids = cand[b, h, :int(cnt[b, h])]
+            v = ids[(ids >= 0) & (ids < n)]
+            assert st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy().tolist() == v.tolist()
+        for g in range(w.num_kv_heads):
+            gi = b * w.num_kv_heads + g
+            parts = [cand[b, h, :int(cnt[b, h])] for h in range(g * G, g * G + G)]
+            allv = np.unique(np.concatenate(parts))
+            allv = allv[(allv >= 0) & (allv < n)]
+            assert st.union_idx[gi, :int(st.union_count[gi])].cpu().numpy().tolist() == allv.tolist()
+    # strides shorter than the lists: first entries kept, status bits set
+    small_k = torch.zeros(w.batch, w.num_q_heads, 5, dtype=torch.int32, device=dev)
+    small_u = torch.zeros(w.batch * w.num_kv_heads, 7, dtype=torch.int32, device=dev)
+    T.twilight_topp_prune_tokens(cache.kv, q, cand_d, cnt_d, max_cand, 1.0, st.kept_count, small_k, 5,
+                                 st.union_count, small_u, 7, st.status, ws)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == (T.binding.TW_STATUS_UNION_TRUNCATED | T.binding.TW_STATUS_KEPT_TRUNCATED)
+    assert int(st.kept_count.max()) <= 5 and int(st.union_count.max()) <= 7
+    ids = cand[0, 1, :int(cnt[0, 1])]
+    v = ids[(ids >= 0) & (ids < int(w.seq_lens[0]))]
+    assert small_k[0, 1, :int(st.kept_count[0, 1])].cpu().numpy().tolist() == v[:5].tolist()
