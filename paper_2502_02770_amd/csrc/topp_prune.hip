@@ -39,6 +39,7 @@ struct ScoreArgs {
   uint32_t* arrive;           // [b][Hkv] arrival counters of the top-p kernel that follows, or nullptr
   uint32_t* headmax;          // [b][Hq][HM_SLOTS] keys whose maximum is the head's largest score (atomicMax), or nullptr
   int Hq, Hkv, max_pages, max_sel, cand_stride, pw;   // pw: pages per wave (<= 64)
+  int rotate;                 // list mode with a grid a multiple of 8 wide: chunk = (column - group % 8) mod width
   long long pool_pages;
 };
 
@@ -125,13 +126,21 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   if (P > a.max_pages) P = a.max_pages;
   int count = P;
   if (!FULL) { count = a.sel_count[b * a.Hq + h0]; if (count > a.max_sel) count = a.max_sel; }
-  const int wg_first = blockIdx.x * 4 * a.pw;
+  // A workgroup takes the chunks of 4 * pw pages number blockIdx.x, blockIdx.x + gridDim.x, ... of its row
+  // (one chunk each when the grid covers the row bound; fewer, looping workgroups for batches of many heads,
+  // whose lists are often far shorter than the bound).
+  // Workgroups go to the 8 XCDs round robin in dispatch order, so with a grid a multiple of 8 wide column x runs on XCD x % 8
+  // and the heads of a KV head, which select largely the same pages, find each other's pages in that XCD's
+  // L2.  Rotating the chunks by the group's number keeps that and spreads the first chunks of short lists
+  // over all XCDs.
+  const int col = (!FULL && a.rotate) ? (int)((blockIdx.x + gridDim.x - ((unsigned)(b * a.Hkv + g) & 7u)) % gridDim.x) : (int)blockIdx.x;
+  int wg_first = col * 4 * a.pw;
   if (a.arrive && blockIdx.x == 0 && tid == 0) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
   if (wg_first >= count) return;
 
-  // ---- this wave's pages: lane k holds the k-th one (logical id, pool id).  Issued before the
-  //      query is quantised, so that the two dependent loads overlap that prologue.
-  const int first = wg_first + wave * a.pw;
+  // ---- this wave's pages: lane k holds the k-th one (logical id, pool id).  The first chunk's are
+  //      issued before the query is quantised, so that the two dependent loads overlap that prologue.
+  int first = wg_first + wave * a.pw;
   int my_lp = -1, my_pool = -1;
   if (lane < a.pw && first + lane < count) {
     my_lp = FULL ? first + lane : a.sel_pages[((long long)(b * a.Hq + h0)) * a.max_sel + first + lane];
@@ -168,6 +177,8 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
 #pragma unroll
   for (int h = 0; h < NH; ++h) hm[h] = -__builtin_inff();
 #pragma unroll 1
+  for (;;) {
+#pragma unroll 1
   for (int k0 = 0; k0 < npages; k0 += UNR) {
 #pragma unroll
    for (int kk = 0; kk < UNR; ++kk) {
@@ -196,6 +207,21 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
       }
     }
    }
+  }
+  // ---- next chunk of this workgroup, if any (block-uniform)
+  wg_first += gridDim.x * 4 * a.pw;
+  if (wg_first >= count) break;
+  first = wg_first + wave * a.pw;
+  my_lp = -1; my_pool = -1;
+  if (lane < a.pw && first + lane < count) {
+    my_lp = FULL ? first + lane : a.sel_pages[((long long)(b * a.Hq + h0)) * a.max_sel + first + lane];
+    if (my_lp >= 0 && my_lp < P) {
+      const int pp = a.page_table[(long long)b * a.max_pages + my_lp];
+      if (pp >= 0 && pp < a.pool_pages) my_pool = pp;
+    }
+  }
+  npages = count - first;
+  if (npages > a.pw) npages = a.pw;
   }
   if (a.headmax) {
     // one atomic per head and workgroup: waves reduce through LDS first
@@ -827,6 +853,23 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
   static const int pw_env = getenv("TW_INT4_PW") ? atoi(getenv("TW_INT4_PW")) : 0;   // tuning switch
   if (pw_env >= 4 && pw_env <= 64) a.pw = pw_env;
   dim3 grid((bound + 4 * a.pw - 1) / (4 * a.pw), d.batch * (full ? d.Hkv : d.Hq));
+  a.rotate = 0;
+  if (!full) {
+    // Per-head page lists: at most 8 pages per wave; rows of more than 8 chunks get a grid a multiple of 8 wide
+    // (one column per XCD, see the kernel) and at most about 16384 workgroups - batches of many heads have
+    // lists far shorter than the row bound, and their workgroups loop over the chunks beyond the grid
+    static const int x_env = getenv("TW_INT4_X") ? atoi(getenv("TW_INT4_X")) : 0;   // tuning switch
+    if (!(pw_env >= 4 && pw_env <= 64) && a.pw > 8) a.pw = 8;
+    int x = (bound + 4 * a.pw - 1) / (4 * a.pw);
+    if (x > 8) {
+      long long cap = 16384 / ((long long)d.batch * d.Hq);
+      if (cap > x) cap = x;
+      x = cap < 8 ? 8 : (int)(cap & ~7ll);
+    }
+    if (x_env > 0) x = x_env;
+    grid.x = x;
+    a.rotate = (x & 7) == 0 ? 1 : 0;
+  }
   tw_prof_before(TW_K_INT4_SCORE, s);
   static const bool valu_only = getenv("TW_INT4_VALU") != nullptr;   // tuning switch: vector-ALU kernel for every G
   if (!full) launch_score<1, false>(a, grid, dots != nullptr, d.bits, s);
@@ -966,7 +1009,14 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
       f.n_above = 4096; f.n_upto = cand_stride;
     }
     tw_prof_before(TW_K_TOPP, s);
-    if (cand_stride <= 4096) switch (d.G) {
+    // More heads than CUs and rows of at most 4096 candidates: 512-thread workgroups, two to a CU (a 1024-thread
+    // workgroup has a CU to itself at this register count: 8 x 32 x 4 = 1024 heads took 35.8 us that way)
+    if (cand_stride <= 4096 && (long long)d.batch * d.Hq > tw_num_cus()) switch (d.G) {
+      case 1: TW_LAUNCH((topp_head_kernel<512, 8, 1>), grid, dim3(512), 0, s, f); break;
+      case 2: TW_LAUNCH((topp_head_kernel<512, 8, 2>), grid, dim3(512), 0, s, f); break;
+      case 4: TW_LAUNCH((topp_head_kernel<512, 8, 4>), grid, dim3(512), 0, s, f); break;
+      default: TW_LAUNCH((topp_head_kernel<512, 8, 8>), grid, dim3(512), 0, s, f); break;
+    } else if (cand_stride <= 4096) switch (d.G) {
       case 1: TW_LAUNCH((topp_head_kernel<1024, 4, 1>), grid, dim3(1024), 0, s, f); break;
       case 2: TW_LAUNCH((topp_head_kernel<1024, 4, 2>), grid, dim3(1024), 0, s, f); break;
       case 4: TW_LAUNCH((topp_head_kernel<1024, 4, 4>), grid, dim3(1024), 0, s, f); break;
@@ -1012,7 +1062,7 @@ static int run_score_tokens(const twilight_kv_t* kv, const TwDims& d, const void
   a.page_table = kv->page_table; a.seq_lens = kv->seq_lens;
   a.kq_pool = (const uint4*)kv->kq_pool; a.kq_meta = (const uint32_t*)kv->kq_meta;
   a.scores = scores; a.dots = dots;
-  a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.max_sel = max_cand; a.cand_stride = max_cand; a.pw = 0;
+  a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.max_sel = max_cand; a.cand_stride = max_cand; a.pw = 0; a.rotate = 0;
   a.pool_pages = d.pool_pages;
   const dim3 grid((max_cand + 255) / 256, d.batch * d.Hq);
   tw_prof_before(TW_K_INT4_SCORE, s);
