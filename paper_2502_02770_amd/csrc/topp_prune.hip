@@ -255,23 +255,28 @@ __global__ __launch_bounds__(256) void int4_score_tokens_kernel(ScoreArgs a) {
   const int ntok = n < a.max_pages * TW_PAGE ? n : a.max_pages * TW_PAGE;
   int count = a.sel_count[b * a.Hq + h0];
   if (count > a.max_sel) count = a.max_sel;
-  const int wg_first = blockIdx.x * 64 * IT;
+  // chunk columns as in the page-list kernel: a grid a multiple of 8 wide is rotated by the KV group's number
+  const int col = a.rotate ? (int)((blockIdx.x + gridDim.x - ((unsigned)(b * a.Hkv + g) & 7u)) % gridDim.x) : (int)blockIdx.x;
+  int wg_first = col * 64 * IT;
   if (a.arrive && blockIdx.x == 0 && tid == 0) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
   if (wg_first >= count) return;
 
   // token -> pool slot of every step first, so that the dependent loads overlap the query prologue
   const long long row = ((long long)(b * a.Hq + h0)) * a.cand_stride;
   long long slot4[IT];                              // (token slot in the pool) * 4 + group, or -1
+  auto translate = [&]() {
 #pragma unroll
-  for (int it = 0; it < IT; ++it) {
-    const int c = wg_first + it * 64 + (tid >> 2);
-    const int tok = c < count ? a.sel_pages[row + c] : -1;
-    slot4[it] = -1;
-    if (tok >= 0 && tok < ntok) {
-      const int pp = a.page_table[(long long)b * a.max_pages + (tok >> 4)];
-      if (pp >= 0 && pp < a.pool_pages) slot4[it] = ((((long long)pp * a.Hkv + g) * TW_PAGE + (tok & 15)) << 2) + j;
+    for (int it = 0; it < IT; ++it) {
+      const int c = wg_first + it * 64 + (tid >> 2);
+      const int tok = c < count ? a.sel_pages[row + c] : -1;
+      slot4[it] = -1;
+      if (tok >= 0 && tok < ntok) {
+        const int pp = a.page_table[(long long)b * a.max_pages + (tok >> 4)];
+        if (pp >= 0 && pp < a.pool_pages) slot4[it] = ((((long long)pp * a.Hkv + g) * TW_PAGE + (tok & 15)) << 2) + j;
+      }
     }
-  }
+  };
+  translate();
 
   __shared__ int qi_s[1][32];
   __shared__ float red[4];
@@ -286,25 +291,31 @@ __global__ __launch_bounds__(256) void int4_score_tokens_kernel(ScoreArgs a) {
   const float qsf = (float)qs, cc = c_s[0];
   const int qs128 = BITS == 8 ? 128 * qs : 0;
 
-  int u[IT][8];
-  uint32_t meta[IT];
+#pragma unroll 1
+  for (;;) {
+    int u[IT][8];
+    uint32_t meta[IT];
 #pragma unroll
-  for (int it = 0; it < IT; ++it) {                 // unconditional loads (an invalid candidate reads slot 0, masked below)
-    const long long idx = slot4[it] >= 0 ? slot4[it] : (long long)j;
-    tw_load_codes<BITS>(a.kq_pool, idx, u[it]);
-    meta[it] = a.kq_meta[idx];
-  }
-#pragma unroll
-  for (int it = 0; it < IT; ++it) {
-    const int c = wg_first + it * 64 + (tid >> 2);
-    const bool valid = slot4[it] >= 0;
-    const int I = tw_group_dot(qw, u[it], qs128);
-    const float T = tw_token_sum(meta[it], I, qsf);   // all four lanes of the quad take part
-    const float sc = valid ? __fmul_rn(T, cc) : -__builtin_inff();
-    if (c < count) {
-      if (j == 0) a.scores[row + c] = sc;
-      if (DOTS) a.dots[(row + c) * 4 + j] = valid ? I : 0;
+    for (int it = 0; it < IT; ++it) {               // unconditional loads (an invalid candidate reads slot 0, masked below)
+      const long long idx = slot4[it] >= 0 ? slot4[it] : (long long)j;
+      tw_load_codes<BITS>(a.kq_pool, idx, u[it]);
+      meta[it] = a.kq_meta[idx];
     }
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int c = wg_first + it * 64 + (tid >> 2);
+      const bool valid = slot4[it] >= 0;
+      const int I = tw_group_dot(qw, u[it], qs128);
+      const float T = tw_token_sum(meta[it], I, qsf);   // all four lanes of the quad take part
+      const float sc = valid ? __fmul_rn(T, cc) : -__builtin_inff();
+      if (c < count) {
+        if (j == 0) a.scores[row + c] = sc;
+        if (DOTS) a.dots[(row + c) * 4 + j] = valid ? I : 0;
+      }
+    }
+    wg_first += gridDim.x * 64 * IT;                // next chunk of this workgroup, if any (block-uniform)
+    if (wg_first >= count) break;
+    translate();
   }
 }
 
@@ -891,6 +902,42 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
   return tw_prof_after(s);
 }
 
+
+template <int NT, int EPT, bool TOK>
+void launch_topp_one(const HeadArgs& f, int G, dim3 grid, hipStream_t s) {
+  switch (G) {
+    case 1: TW_LAUNCH((topp_head_kernel<NT, EPT, 1, TOK>), grid, dim3(NT), 0, s, f); break;
+    case 2: TW_LAUNCH((topp_head_kernel<NT, EPT, 2, TOK>), grid, dim3(NT), 0, s, f); break;
+    case 4: TW_LAUNCH((topp_head_kernel<NT, EPT, 4, TOK>), grid, dim3(NT), 0, s, f); break;
+    default: TW_LAUNCH((topp_head_kernel<NT, EPT, 8, TOK>), grid, dim3(NT), 0, s, f); break;
+  }
+}
+
+// Register-resident top-p over rows of at most 8192 candidates (cand_stride = row bound).
+//  - few heads: one 1024-thread workgroup per head (4 or 8 candidates per thread);
+//  - more heads than CUs and rows of at most 4096 candidates: 512-thread workgroups, two to a CU (a 1024-thread
+//    workgroup has a CU to itself at this register count: 8 x 32 x 4 = 1024 heads took 35.8 us that way, 22.9 us so);
+//  - many heads with a bound above 4096 candidates (ragged batches): heads of at most 4096 candidates go to a
+//    512-thread launch of their own, the longer ones to the 1024-thread launch.
+template <bool TOK>
+int launch_topp(HeadArgs f, const TwDims& d, int cand_stride, hipStream_t s) {
+  const dim3 grid(d.Hq, d.batch);
+  const long long heads = (long long)d.batch * d.Hq;
+  f.n_above = -1; f.n_upto = cand_stride;
+  if (cand_stride > 4096 && heads > 2ll * tw_num_cus()) {
+    f.n_upto = 4096;
+    tw_prof_before(TW_K_TOPP, s);
+    launch_topp_one<512, 8, TOK>(f, d.G, grid, s);
+    if (int e = tw_prof_after(s)) return e;
+    f.n_above = 4096; f.n_upto = cand_stride;
+  }
+  tw_prof_before(TW_K_TOPP, s);
+  if (cand_stride <= 4096 && heads > tw_num_cus()) launch_topp_one<512, 8, TOK>(f, d.G, grid, s);
+  else if (cand_stride <= 4096) launch_topp_one<1024, 4, TOK>(f, d.G, grid, s);
+  else launch_topp_one<1024, 8, TOK>(f, d.G, grid, s);
+  return tw_prof_after(s);
+}
+
 }  // namespace
 
 
@@ -990,44 +1037,7 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
     f.union_count = union_count; f.union_idx = union_idx; f.status = status;
     f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_sel; f.cand_stride = cand_stride;
     f.kept_stride = kept_stride; f.words_stride = words_stride; f.union_stride = union_stride; f.p = p;
-    const dim3 grid(d.Hq, d.batch);
-    f.n_above = -1; f.n_upto = cand_stride;
-    // Many heads with a bound above 4096 candidates (ragged batches): the 1024-thread kernel leaves
-    // room for one workgroup per CU.  Heads of at most 4096 candidates then go to a 512-thread
-    // launch of their own (two per CU), the longer ones to the 1024-thread launch.
-    const bool split = cand_stride > 4096 && (long long)d.batch * d.Hq > 2ll * tw_num_cus();
-    if (split) {
-      f.n_upto = 4096;
-      tw_prof_before(TW_K_TOPP, s);
-      switch (d.G) {
-        case 1: TW_LAUNCH((topp_head_kernel<512, 8, 1>), grid, dim3(512), 0, s, f); break;
-        case 2: TW_LAUNCH((topp_head_kernel<512, 8, 2>), grid, dim3(512), 0, s, f); break;
-        case 4: TW_LAUNCH((topp_head_kernel<512, 8, 4>), grid, dim3(512), 0, s, f); break;
-        default: TW_LAUNCH((topp_head_kernel<512, 8, 8>), grid, dim3(512), 0, s, f); break;
-      }
-      if (int e = tw_prof_after(s)) return e;
-      f.n_above = 4096; f.n_upto = cand_stride;
-    }
-    tw_prof_before(TW_K_TOPP, s);
-    // More heads than CUs and rows of at most 4096 candidates: 512-thread workgroups, two to a CU (a 1024-thread
-    // workgroup has a CU to itself at this register count: 8 x 32 x 4 = 1024 heads took 35.8 us that way)
-    if (cand_stride <= 4096 && (long long)d.batch * d.Hq > tw_num_cus()) switch (d.G) {
-      case 1: TW_LAUNCH((topp_head_kernel<512, 8, 1>), grid, dim3(512), 0, s, f); break;
-      case 2: TW_LAUNCH((topp_head_kernel<512, 8, 2>), grid, dim3(512), 0, s, f); break;
-      case 4: TW_LAUNCH((topp_head_kernel<512, 8, 4>), grid, dim3(512), 0, s, f); break;
-      default: TW_LAUNCH((topp_head_kernel<512, 8, 8>), grid, dim3(512), 0, s, f); break;
-    } else if (cand_stride <= 4096) switch (d.G) {
-      case 1: TW_LAUNCH((topp_head_kernel<1024, 4, 1>), grid, dim3(1024), 0, s, f); break;
-      case 2: TW_LAUNCH((topp_head_kernel<1024, 4, 2>), grid, dim3(1024), 0, s, f); break;
-      case 4: TW_LAUNCH((topp_head_kernel<1024, 4, 4>), grid, dim3(1024), 0, s, f); break;
-      default: TW_LAUNCH((topp_head_kernel<1024, 4, 8>), grid, dim3(1024), 0, s, f); break;
-    } else switch (d.G) {
-      case 1: TW_LAUNCH((topp_head_kernel<1024, 8, 1>), grid, dim3(1024), 0, s, f); break;
-      case 2: TW_LAUNCH((topp_head_kernel<1024, 8, 2>), grid, dim3(1024), 0, s, f); break;
-      case 4: TW_LAUNCH((topp_head_kernel<1024, 8, 4>), grid, dim3(1024), 0, s, f); break;
-      default: TW_LAUNCH((topp_head_kernel<1024, 8, 8>), grid, dim3(1024), 0, s, f); break;
-    }
-    return tw_prof_after(s);
+    return launch_topp<false>(f, d, cand_stride, s);
   }
 }
 
@@ -1064,7 +1074,16 @@ static int run_score_tokens(const twilight_kv_t* kv, const TwDims& d, const void
   a.scores = scores; a.dots = dots;
   a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.max_sel = max_cand; a.cand_stride = max_cand; a.pw = 0; a.rotate = 0;
   a.pool_pages = d.pool_pages;
-  const dim3 grid((max_cand + 255) / 256, d.batch * d.Hq);
+  // grid as for page lists: rows of more than 8 chunks get a width that is a multiple of 8, cut so that the
+  // launch stays near 16384 workgroups; the workgroups loop over the chunks beyond it
+  int x = (max_cand + 255) / 256;
+  if (x > 8) {
+    long long cap = 16384 / ((long long)d.batch * d.Hq);
+    if (cap > x) cap = x;
+    x = cap < 8 ? 8 : (int)(cap & ~7ll);
+  }
+  a.rotate = (x & 7) == 0 ? 1 : 0;
+  const dim3 grid(x, d.batch * d.Hq);
   tw_prof_before(TW_K_INT4_SCORE, s);
   if (d.bits == 2) {
     if (dots) TW_LAUNCH((int4_score_tokens_kernel<true, 2>), grid, dim3(256), 0, s, a);
@@ -1112,19 +1131,5 @@ extern "C" int twilight_topp_prune_tokens(const twilight_kv_t* kv, const void* q
   f.union_count = union_count; f.union_idx = union_idx; f.status = status;
   f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_cand; f.cand_stride = max_cand;
   f.kept_stride = kept_stride; f.words_stride = L.words_stride; f.union_stride = union_stride; f.p = p;
-  f.n_above = -1; f.n_upto = max_cand;
-  const dim3 grid(d.Hq, d.batch);
-  tw_prof_before(TW_K_TOPP, s);
-  if (max_cand <= 4096) switch (d.G) {
-    case 1: TW_LAUNCH((topp_head_kernel<1024, 4, 1, true>), grid, dim3(1024), 0, s, f); break;
-    case 2: TW_LAUNCH((topp_head_kernel<1024, 4, 2, true>), grid, dim3(1024), 0, s, f); break;
-    case 4: TW_LAUNCH((topp_head_kernel<1024, 4, 4, true>), grid, dim3(1024), 0, s, f); break;
-    default: TW_LAUNCH((topp_head_kernel<1024, 4, 8, true>), grid, dim3(1024), 0, s, f); break;
-  } else switch (d.G) {
-    case 1: TW_LAUNCH((topp_head_kernel<1024, 8, 1, true>), grid, dim3(1024), 0, s, f); break;
-    case 2: TW_LAUNCH((topp_head_kernel<1024, 8, 2, true>), grid, dim3(1024), 0, s, f); break;
-    case 4: TW_LAUNCH((topp_head_kernel<1024, 8, 4, true>), grid, dim3(1024), 0, s, f); break;
-    default: TW_LAUNCH((topp_head_kernel<1024, 8, 8, true>), grid, dim3(1024), 0, s, f); break;
-  }
-  return tw_prof_after(s);
+  return launch_topp<true>(f, d, max_cand, s);
 }
