@@ -1134,3 +1134,16 @@ def test_token_lists_keep_all_at_p1_and_report_overflow():
     ids = cand[0, 1, :int(cnt[0, 1])]
     v = ids[(ids >= 0) & (ids < int(w.seq_lens[0]))]
     assert small_k[0, 1, :int(st.kept_count[0, 1])].cpu().numpy().tolist() == v[:5].tolist()
+
+
+def test_more_heads_than_cus_short_rows():
+    """More (sequence, query head) rows than CUs with rows of at most 4096 candidates: top-p runs in
+    512-thread workgroups, two to a CU."""
+    lens = [900 + 211 * i for i in range(10)]                              # 10 sequences x 32 heads = 320 rows
+    w = synth.make_workload("manyshort", lens, budget=512, p=0.9, heavy_frac=0.01, alpha_range=(0.0, 3.0),
+                            shuffle_pool=True, seed=33)
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache)
+    assert int(st.status.item()) == 0
+    assert st.max_sel * 16 <= 4096 and w.batch * w.num_q_heads > 256
+    check_sets_and_output(w, cache, st)
