@@ -494,6 +494,7 @@ struct HeadArgs {
 
 constexpr int HP_CAP = 64;                    // exact resolve handles up to this many scores
 constexpr int HP_BITMAP_WORDS = 6144;         // 196608 tokens
+constexpr int HP_USTAGE = 2048;               // union lists up to this length leave through LDS
 
 // TOK: the candidates are token positions (sel_pages = the token lists, max_sel = their row length,
 // sel_count in tokens) instead of pages of 16 slots.
@@ -524,6 +525,7 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   __shared__ uint32_t ws32[16];
   __shared__ float redf[NW];
   __shared__ uint32_t sh_n, sh_kept, sh_T, sh_last;
+  __shared__ int32_t ustage[HP_USTAGE];            // the group's union list on its way out
 
   // ---- scores into registers; logical pages of the owned slots
   // (loads do not wait for the list length: anything inside the row is readable, slots at or
@@ -804,13 +806,29 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   TW_STAMP(16);
   int32_t* uout = a.union_idx + (long long)gi * a.union_stride;
   uint32_t upos = uincl - ucnt;
-  for (int i = w0; i < w1; ++i) {
-    uint32_t x = bitmap[i];
-    while (x) {
-      const int bit = __ffs(x) - 1;
-      x &= x - 1;
-      if (upos < (uint32_t)a.union_stride) uout[upos] = i * 32 + bit;
-      ++upos;
+  if (utotal <= (uint32_t)HP_USTAGE) {               // block-uniform; the usual case
+    // positions staged in LDS, then copied out coalesced: a dense word costs its thread 32 scattered
+    // stores otherwise, one store instruction of the whole wave each (1.5 us of the kernel's tail)
+    for (int i = w0; i < w1; ++i) {
+      uint32_t x = bitmap[i];
+      while (x) {
+        const int bit = __ffs(x) - 1;
+        x &= x - 1;
+        ustage[upos++] = i * 32 + bit;
+      }
+    }
+    __syncthreads();
+    const uint32_t lim = utotal < (uint32_t)a.union_stride ? utotal : (uint32_t)a.union_stride;
+    for (uint32_t i = tid; i < lim; i += NT) uout[i] = ustage[i];
+  } else {
+    for (int i = w0; i < w1; ++i) {
+      uint32_t x = bitmap[i];
+      while (x) {
+        const int bit = __ffs(x) - 1;
+        x &= x - 1;
+        if (upos < (uint32_t)a.union_stride) uout[upos] = i * 32 + bit;
+        ++upos;
+      }
     }
   }
   if (tid == 0) {
