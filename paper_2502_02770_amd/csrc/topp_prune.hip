@@ -499,7 +499,7 @@ constexpr int HP_USTAGE = 2048;               // union lists up to this length l
 // TOK: the candidates are token positions (sel_pages = the token lists, max_sel = their row length,
 // sel_count in tokens) instead of pages of 16 slots.
 template <int NT, int EPT, int G, bool TOK = false>
-__global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
+__global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadArgs a) {
   constexpr int NW = NT / 64;
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int bh = b * a.Hq + h;
@@ -577,13 +577,18 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
   else searching = true;
 
   if (searching) {                                 // block-uniform
-    // rank and numerator of every score, computed once
-    uint32_t rk[EPT];
-    float ef[EPT];
+    // rank and numerator of every score: computed once and kept, or (512-thread workgroups, which are there
+    // to fit more of them on a CU) recomputed from the score where needed - a few instructions that save
+    // 2 * EPT registers
+    constexpr bool RECOMP = NT <= 512;
+    uint32_t rk[RECOMP ? 1 : EPT];
+    float ef[RECOMP ? 1 : EPT];
+    if (!RECOMP) {
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) {
-      rk[e] = hp_rank(m, s[e], &ef[e]);
+      for (int e = 0; e < EPT; ++e) rk[RECOMP ? 0 : e] = hp_rank(m, s[e], &ef[RECOMP ? 0 : e]);
     }
+    auto rank_of = [&](int e) -> uint32_t { return RECOMP ? hp_rank_only(m, s[e]) : rk[RECOMP ? 0 : e]; };
+    auto numer_of = [&](int e) -> float { return RECOMP ? hp_numer(m, s[e]) : ef[RECOMP ? 0 : e]; };
     uint32_t rlo = 0, pop = 0;
     int shift = 16, pass = 0;
     unsigned long long A = 0, target = 0;
@@ -596,9 +601,10 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
       unsigned long long below = 0;                // mass past the end of the interval (pass 0 only)
 #pragma unroll
       for (int e = 0; e < EPT; ++e) {
-        if (rk[e] != HP_NONE && rk[e] >= rlo) {
-          const uint32_t bk = (rk[e] - rlo) >> shift;
-          const unsigned long long w = hp_fix(ef[e]);
+        const uint32_t r = rank_of(e);
+        if (r != HP_NONE && r >= rlo) {
+          const uint32_t bk = (r - rlo) >> shift;
+          const unsigned long long w = hp_fix(numer_of(e));
           if (bk < HP_NB) { atomicAdd(&histM[bk], w); atomicAdd(&histC[bk], 1u); }
           else below += w;
         }
@@ -659,12 +665,13 @@ __global__ __launch_bounds__(NT) void topp_head_kernel(HeadArgs a) {
     uint32_t kmin = 0xFFFFFFFFu;
 #pragma unroll
     for (int e = 0; e < EPT; ++e) {
-      if (rk[e] != HP_NONE && rk[e] >= rlo && rk[e] <= rhi) {
+      const uint32_t r = rank_of(e);
+      if (r != HP_NONE && r >= rlo && r <= rhi) {
         const uint32_t k = tw_float_key(s[e]);
         kmin = k < kmin ? k : kmin;
         if (small) {
           const uint32_t at = atomicAdd(&sh_n, 1u);
-          if (at < HP_CAP) { cand_key[at] = k; cand_mass[at] = hp_fix(ef[e]); }
+          if (at < HP_CAP) { cand_key[at] = k; cand_mass[at] = hp_fix(numer_of(e)); }
         }
       }
     }
