@@ -522,3 +522,21 @@ def test_workload_generator_is_deterministic_and_shaped():
     r = synth.config(4, scale=1 / 32, batch=5)
     assert r.batch == 5 and all(64 <= int(n) <= 2048 for n in r.seq_lens)
     assert [int(x) for x in r.budget] == [max(16, int(n) // 8) for n in r.seq_lens]
+
+
+def test_attention_tolerance_rule_accepts_only_rounding_ties():
+    """The GPU parity tests compare attention outputs with the oracle's result rounded to bf16; an element
+    whose exact value sits on the midpoint of two bf16 neighbours (within fp32 error) may round either way.
+    The helper accepts exactly that, and still rejects a one-ulp error anywhere else."""
+    from tests.gpu_util import assert_attention, bf16_round
+    rng = np.random.default_rng(0)
+    x = rng.normal(size=128) * 0.01
+    assert_attention(bf16_round(x), x)
+    x[3] = 0.583984218                          # 1.6e-7 below the midpoint of 0.58203125 and 0.5859375
+    g = bf16_round(x)
+    assert g[3] == 0.58203125
+    g[3] = 0.5859375                            # the other neighbour: 0.4 % of the dominant element
+    assert_attention(g, x)
+    x[3] = 0.5825                               # well inside the lower half: the same output is now wrong
+    with pytest.raises(AssertionError):
+        assert_attention(g, x)
