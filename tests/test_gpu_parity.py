@@ -943,6 +943,38 @@ def test_attention_at_the_list_count_limit():
                 assert_attention(got[b, h], ref)
 
 
+def check_token_list_results(w, st, cand, cnt, bits=4):
+    """Kept sets, unions and attention outputs of the token-list pruner against the oracle."""
+    out = st.out.cpu().float().numpy().astype(np.float64)
+    G = w.num_q_heads // w.num_kv_heads
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        for g in range(w.num_kv_heads):
+            kb, vb = synth.bits(w.seq_k(b)[:, g]), synth.bits(w.seq_v(b)[:, g])
+            u, s_, z = O.quantize_k(kb, bits)
+            kept_all = []
+            for h in range(g * G, g * G + G):
+                ids = cand[b, h, :int(cnt[b, h])]
+                v = ids[(ids >= 0) & (ids < n)]
+                qi, sq = O.quantize_q(synth.bits(w.q[b, h]))
+                s_hat = O.int4_scores(qi, sq, u[v], s_[v], z[v])
+                kept = st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+                if len(v):
+                    check_topp(kept, s_hat, v, w.p)
+                else:
+                    assert len(kept) == 0
+                kept_all.append(kept)
+            gi = b * w.num_kv_heads + g
+            un = st.union_idx[gi, :int(st.union_count[gi])].cpu().numpy()
+            assert un.tolist() == np.unique(np.concatenate(kept_all)).tolist()
+            for h in range(g * G, g * G + G):
+                if len(un) == 0:
+                    assert np.all(out[b, h] == 0)
+                    continue
+                ref, _ = O.attention(synth.bits(w.q[b, h]), kb, vb, un)
+                assert_attention(out[b, h], ref)
+
+
 def _token_candidates(w, max_cand, seed, bad_ids=False):
     """Per (sequence, query head) an ascending list of distinct token positions of random length (some empty,
     some full), as a token-level selector would hand over; optionally with ids outside the sequence."""
@@ -952,7 +984,8 @@ def _token_candidates(w, max_cand, seed, bad_ids=False):
     for b in range(w.batch):
         n = int(w.seq_lens[b])
         for h in range(w.num_q_heads):
-            c = int(rng.choice([0, 1, 17, min(n, max_cand), rng.integers(1, min(n, max_cand) + 1)]))
+            top = min(n, max_cand)
+            c = min(top, int(rng.choice([0, 1, 17, top, rng.integers(1, top + 1)])))
             ids = np.sort(rng.choice(n, size=c, replace=False)).astype(np.int32)
             if bad_ids and c >= 3:
                 ids[0] = -5
@@ -1018,34 +1051,7 @@ def test_pruner_on_token_lists_against_oracle(max_cand):
         st.attend(q)
         torch.cuda.synchronize()
         assert int(st.status.item()) == 0
-        out = st.out.cpu().float().numpy().astype(np.float64)
-        G = w.num_q_heads // w.num_kv_heads
-        for b in range(w.batch):
-            n = int(w.seq_lens[b])
-            for g in range(w.num_kv_heads):
-                kb, vb = synth.bits(w.seq_k(b)[:, g]), synth.bits(w.seq_v(b)[:, g])
-                u, s_, z = O.quantize_k(kb)
-                kept_all = []
-                for h in range(g * G, g * G + G):
-                    ids = cand[b, h, :int(cnt[b, h])]
-                    v = ids[(ids >= 0) & (ids < n)]
-                    qi, sq = O.quantize_q(synth.bits(w.q[b, h]))
-                    s_hat = O.int4_scores(qi, sq, u[v], s_[v], z[v])
-                    kept = st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
-                    if len(v):
-                        check_topp(kept, s_hat, v, w.p)
-                    else:
-                        assert len(kept) == 0
-                    kept_all.append(kept)
-                gi = b * w.num_kv_heads + g
-                un = st.union_idx[gi, :int(st.union_count[gi])].cpu().numpy()
-                assert un.tolist() == np.unique(np.concatenate(kept_all)).tolist()
-                for h in range(g * G, g * G + G):
-                    if len(un) == 0:
-                        assert np.all(out[b, h] == 0)
-                        continue
-                    ref, _ = O.attention(synth.bits(w.q[b, h]), kb, vb, un)
-                    assert_attention(out[b, h], ref)
+        check_token_list_results(w, st, cand, cnt)
 
 
 def test_token_lists_of_whole_pages_equal_the_page_list_pruner():
@@ -1166,3 +1172,49 @@ def test_random_small_workloads_against_oracle():
     for i in range(150):
         w, bits = _random_workload(rng, i)
         pipeline_against_oracle(w, bits)
+
+
+def test_random_small_workloads_other_entry_points():
+    """90 seeded random workloads through the other forms of the path: no selector (every token a candidate:
+    multi-workgroup top-p and bitmap lists), the pruner on token lists, and head-wise attention."""
+    T = _T()
+    rng = np.random.default_rng(4048)
+    for i in range(90):
+        w, bits = _random_workload(rng, i)
+        if i % 3 == 0:
+            w.full_selector = True
+            cache = build_cache(w)
+            st, q = run_pipeline(w, cache)
+            assert int(st.status.item()) == 0
+            check_sets_and_output(w, cache, st, exact_floor=0.0)
+        elif i % 3 == 1:
+            cache = build_cache(w, bits=bits)
+            dev = cache.device
+            q = w.q.to(dev)
+            max_cand = int(rng.choice([16, 64, 1504, 4096, 4112, 8192]))
+            cand, cnt = _token_candidates(w, max_cand, seed=int(rng.integers(1 << 30)), bad_ids=bool(rng.integers(2)))
+            st = T.DecodeStep(cache, max_sel=max_cand // 16, with_kept_idx=True)
+            ws = torch.empty(T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, cache.kv, max_cand), dtype=torch.uint8, device=dev)
+            T.twilight_topp_prune_tokens(cache.kv, q, torch.from_numpy(cand).to(dev), torch.from_numpy(cnt).to(dev), max_cand,
+                                         w.p, st.kept_count, st.kept_idx, st.kept_stride, st.union_count, st.union_idx,
+                                         st.union_stride, st.status, ws)
+            st.attend(q)
+            torch.cuda.synchronize()
+            assert int(st.status.item()) == 0
+            check_token_list_results(w, st, cand, cnt, bits)
+        else:
+            cache = build_cache(w, bits=bits)
+            st, q = run_pipeline(w, cache)
+            st.attend_per_head(q)
+            torch.cuda.synchronize()
+            out = st.out.cpu().float().numpy().astype(np.float64)
+            G = w.num_q_heads // w.num_kv_heads
+            for b in range(w.batch):
+                for h in range(w.num_q_heads):
+                    kept = st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+                    if len(kept) == 0:
+                        assert np.all(out[b, h] == 0)
+                        continue
+                    ref, _ = O.attention(synth.bits(w.q[b, h]), synth.bits(w.seq_k(b)[:, h // G]),
+                                         synth.bits(w.seq_v(b)[:, h // G]), kept)
+                    assert_attention(out[b, h], ref)
