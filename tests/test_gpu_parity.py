@@ -1218,3 +1218,33 @@ def test_random_small_workloads_other_entry_points():
                     ref, _ = O.attention(synth.bits(w.q[b, h]), synth.bits(w.seq_k(b)[:, h // G]),
                                          synth.bits(w.seq_v(b)[:, h // G]), kept)
                     assert_attention(out[b, h], ref)
+
+
+def test_two_streams_with_their_own_buffers_do_not_interfere():
+    """The library keeps no state between calls: two decode steps on two streams, each with its own cache,
+    outputs and workspaces, give the results of the same steps run one after the other."""
+    T = _T()
+    ws_ = [synth.config(0, scale=0.5, seed=21), synth.make_workload("s2", [1800, 700], budget=512, p=0.9, shuffle_pool=True, seed=22)]
+    caches = [build_cache(w) for w in ws_]
+    ref = []
+    for w, c in zip(ws_, caches):
+        st, _ = run_pipeline(w, c)
+        ref.append((st.out.clone(), st.kept_count.clone(), st.union_count.clone(), st.union_idx.clone()))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    steps, qs, bud = [], [], []
+    for w, c in zip(ws_, caches):
+        max_sel = min(int(max(-(-int(b) // 16) for b in w.budget)), c.max_pages)
+        steps.append(T.DecodeStep(c, max_sel=max_sel, with_kept_idx=True))
+        qs.append(w.q.to(c.device)); bud.append(w.budget.to(c.device))
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for i in (0, 1):
+            with torch.cuda.stream(streams[i]):
+                steps[i].run(qs[i], bud[i], ws_[i].p)
+    torch.cuda.synchronize()
+    for i in (0, 1):
+        o, kc, uc, ui = ref[i]
+        assert torch.equal(steps[i].out.view(torch.int16), o.view(torch.int16))
+        assert torch.equal(steps[i].kept_count, kc) and torch.equal(steps[i].union_count, uc)
+        for gi in range(uc.numel()):
+            assert torch.equal(steps[i].union_idx[gi, :int(uc[gi])], ui[gi, :int(uc[gi])])
