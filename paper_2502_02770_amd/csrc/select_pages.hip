@@ -46,9 +46,18 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
   const int b = blockIdx.z, g = blockIdx.x;
   const int tid = threadIdx.x, seg = tid & 15, grp = tid >> 4;   // grp: 0..15 page slot in the WG
   const int n = a.seq_lens[b];
+  const int base = blockIdx.y * PS_PAGES_PER_WG;
+  // page-table entries of this lane's 4 pages: issued before the sequence length is known (any entry of
+  // the row may be read; entries beyond the last page are ignored below), so that the two loads overlap
+  constexpr int IT = PS_PAGES_PER_WG / 16;
+  long long pool[IT];
+#pragma unroll
+  for (int it = 0; it < IT; ++it) {
+    const int lp = base + it * 16 + grp;
+    pool[it] = a.page_table[(long long)b * a.max_pages + (lp < a.max_pages ? lp : a.max_pages - 1)];
+  }
   int P = (n + TW_PAGE - 1) / TW_PAGE;
   if (P > a.max_pages) P = a.max_pages;
-  const int base = blockIdx.y * PS_PAGES_PER_WG;
   if (base >= P) return;
 
   // q of the G heads, the 8 dims of this lane; the sign decides which corner
@@ -60,17 +69,11 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
     tw_unpack8(r, q[h]);
   }
 
-  // page-table entries of this lane's 4 pages first, then all 8 bound loads (clamped addresses,
-  // unconditional) so that they are in flight together; unmapped pages are masked afterwards
-  constexpr int IT = PS_PAGES_PER_WG / 16;
-  long long pool[IT];
+  // then all 8 bound loads (clamped addresses, unconditional) so that they are in flight together;
+  // unmapped pages are masked afterwards
   bool live[IT], ok[IT];
 #pragma unroll
-  for (int it = 0; it < IT; ++it) {
-    const int lp = base + it * 16 + grp;
-    live[it] = lp < P;
-    pool[it] = a.page_table[(long long)b * a.max_pages + (live[it] ? lp : P - 1)];
-  }
+  for (int it = 0; it < IT; ++it) live[it] = base + it * 16 + grp < P;
   uint4 rmn[IT], rmx[IT];
 #pragma unroll
   for (int it = 0; it < IT; ++it) {
