@@ -1248,3 +1248,47 @@ def test_two_streams_with_their_own_buffers_do_not_interfere():
         assert torch.equal(steps[i].kept_count, kc) and torch.equal(steps[i].union_count, uc)
         for gi in range(uc.numel()):
             assert torch.equal(steps[i].union_idx[gi, :int(uc[gi])], ui[gi, :int(uc[gi])])
+
+
+def test_random_append_schedules_build_the_same_cache():
+    """40 seeded random ways of building a cache - bulk chunks of random sizes, single tokens through
+    twilight_kquant_append or through twilight_append_select, sequences idle for some rounds - all end in the
+    cache the oracle describes (codes, scale / zero, bounds, bf16 rows), for every estimator width."""
+    T = _T()
+    rng = np.random.default_rng(777)
+    dev = "cuda"
+    for trial in range(40):
+        batch = int(rng.integers(1, 5))
+        lens = [int(rng.integers(1, 400)) for _ in range(batch)]
+        Hq, Hkv = [(4, 4), (8, 2), (32, 8), (8, 1)][rng.integers(4)]
+        bits = int(rng.choice([4, 4, 2, 8]))
+        w = synth.make_workload("appr%d" % trial, lens, num_q_heads=Hq, num_kv_heads=Hkv, budget=64, p=0.9,
+                                shuffle_pool=bool(rng.integers(2)), extra_pool_pages=int(rng.integers(0, 4)),
+                                seed=int(rng.integers(1 << 30)))
+        cache = T.PagedKV(Hq, Hkv, w.page_table, w.seq_lens, w.num_pool_pages, dev, quant_bits=bits)
+        k, v, q = w.k.to(dev), w.v.to(dev), w.q.to(dev)
+        st = T.DecodeStep(cache, max_sel=4)
+        budget = w.budget.to(dev)
+        full_lens = cache.seq_lens.clone()
+        done = [0] * batch
+        while any(done[b] < lens[b] for b in range(batch)):
+            step = []
+            for b in range(batch):
+                left = lens[b] - done[b]
+                step.append(0 if left == 0 or rng.random() < 0.2 else int(min(left, rng.choice([1, 1, 2, 15, 16, 17, 40, 400]))))
+            if not any(step):
+                continue
+            offs = torch.tensor([w.seq_offsets[b] + done[b] for b in range(batch)], dtype=torch.int32, device=dev)
+            start = torch.tensor(done, dtype=torch.int32, device=dev)
+            if bits == 4 and max(step) == 1 and rng.random() < 0.7:
+                # one token per sequence through the selector's launch; sequences without one get position -1
+                rows = torch.tensor([w.seq_offsets[b] + done[b] if step[b] else 0 for b in range(batch)], dtype=torch.int64, device=dev)
+                pos = torch.tensor([done[b] if step[b] else -1 for b in range(batch)], dtype=torch.int32, device=dev)
+                cache.seq_lens.copy_(torch.tensor([done[b] + step[b] for b in range(batch)], dtype=torch.int32))
+                st.append_select(k[rows].contiguous(), v[rows].contiguous(), pos, q, budget)
+            else:
+                cache.append(k, v, start, torch.tensor(step, dtype=torch.int32, device=dev), offs, max(step))
+            done = [done[b] + step[b] for b in range(batch)]
+        cache.seq_lens.copy_(full_lens)
+        torch.cuda.synchronize()
+        check_cache(w, cache, bits)
