@@ -233,8 +233,8 @@ def main():
 
     # ---- timed region: K steps; HIP events (on the launch stream) around the dominant kernel only,
     # so the event pairs do not stretch the step the way bracketing all seven launches does
-    # (and only at every 16th of its launches: a launch that carries events costs the stream ~10 us)
-    T.twilight_prof_select(dom, every=16 if a.steps >= 64 else 4)
+    # (and only at every 32nd of its launches: a launch that carries events delays the stream by some 20-30 us)
+    T.twilight_prof_select(dom, every=32 if a.steps >= 128 else 4)
     T.twilight_prof_enable(2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
