@@ -1292,3 +1292,30 @@ def test_random_append_schedules_build_the_same_cache():
         cache.seq_lens.copy_(full_lens)
         torch.cuda.synchronize()
         check_cache(w, cache, bits)
+
+
+@pytest.mark.parametrize("lens", [[1500, 320], [40000], [140000]], ids=["lds_256", "lds_1024", "radix"])
+def test_select_is_cut_at_max_sel(lens):
+    """A page list shorter than the budget asks for: the max_sel pages with the largest bounds, ascending -
+    what the oracle selects for a budget of max_sel pages (all three selection kernels)."""
+    T = _T()
+    Hq, Hkv = (8, 2) if lens[0] < 100000 else (2, 1)
+    w = synth.make_workload("cutsel", lens, num_q_heads=Hq, num_kv_heads=Hkv, budget=[n // 2 for n in lens], p=0.9,
+                            need_v=False, seed=61)
+    cache = build_cache(w)
+    dev = cache.device
+    q = w.q.to(dev)
+    max_sel = 7
+    st = T.DecodeStep(cache, max_sel=max_sel)
+    st.select(q, w.budget.to(dev))
+    torch.cuda.synchronize()
+    G = Hq // Hkv
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        for g in range(Hkv):
+            mn, mx = O.page_minmax(synth.bits(w.seq_k(b)[:, g]))
+            for h in range(g * G, g * G + G):
+                U = O.page_upper_bounds(synth.bits(w.q[b, h]), mn, mx)
+                want = O.select_pages(U, max_sel * 16, n)
+                assert int(st.sel_count[b, h]) == len(want) == max_sel
+                assert st.sel_pages[b, h].cpu().numpy().tolist() == want.tolist(), (b, h)
