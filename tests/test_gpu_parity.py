@@ -1319,3 +1319,35 @@ def test_select_is_cut_at_max_sel(lens):
                 want = O.select_pages(U, max_sel * 16, n)
                 assert int(st.sel_count[b, h]) == len(want) == max_sel
                 assert st.sel_pages[b, h].cpu().numpy().tolist() == want.tolist(), (b, h)
+
+
+@pytest.mark.parametrize("n", [3000, 48000, 144000], ids=["lds_256", "lds_1024", "radix"])
+def test_page_ties_go_to_the_lower_page_id(n):
+    """Every page holds 16 copies of one of three key rows, so a head's page bounds take three values and
+    almost every page ties with a thousand others at the cut: the selected set must be the oracle's
+    (ties to the lower page id), in each of the three selection kernels."""
+    T = _T()
+    Hq, Hkv = (4, 2) if n < 100000 else (2, 1)
+    w = synth.make_workload("ties", [n], num_q_heads=Hq, num_kv_heads=Hkv, budget=n // 3, p=0.9, need_v=False, seed=62)
+    P = (n + 15) // 16
+    gen = torch.Generator().manual_seed(5)
+    proto = torch.randn(3, Hkv, 128, generator=gen).to(torch.bfloat16)
+    which = torch.randint(0, 3, (P,), generator=gen)
+    w.k[:] = proto[which.repeat_interleave(16)[:n]]
+    cache = build_cache(w)
+    dev = cache.device
+    q = w.q.to(dev)
+    max_sel = -(-int(w.budget[0]) // 16)
+    st = T.DecodeStep(cache, max_sel=max_sel)
+    st.select(q, w.budget.to(dev))
+    torch.cuda.synchronize()
+    G = Hq // Hkv
+    for g in range(Hkv):
+        mn, mx = O.page_minmax(synth.bits(w.seq_k(0)[:, g]))
+        for h in range(g * G, g * G + G):
+            U = O.page_upper_bounds(synth.bits(w.q[0, h]), mn, mx)
+            assert len(np.unique(U)) <= 4                      # three rows (+ the partial last page)
+            want = O.select_pages(U, int(w.budget[0]), n)
+            cnt = int(st.sel_count[0, h])
+            assert cnt == len(want)
+            assert st.sel_pages[0, h, :cnt].cpu().numpy().tolist() == want.tolist(), h
