@@ -1351,3 +1351,31 @@ def test_page_ties_go_to_the_lower_page_id(n):
             cnt = int(st.sel_count[0, h])
             assert cnt == len(want)
             assert st.sel_pages[0, h, :cnt].cpu().numpy().tolist() == want.tolist(), h
+
+
+@pytest.mark.parametrize("n,budget,full", [(4096, 4096, False), (8192, 8192, False), (30000, None, True)],
+                         ids=["4_per_thread", "8_per_thread", "long_rows"])
+@pytest.mark.parametrize("p", [0.3, 0.9])
+def test_score_ties_by_the_thousand_at_the_threshold(n, budget, full, p):
+    """Every key is one of two rows, so a head's scores take two values, thousands of candidates each: the
+    threshold falls inside one of the two tiers and the whole tier is kept (Definition 3.3's set as Algorithm 1
+    returns it: all ties at the cut), on the register-resident and on the multi-workgroup path."""
+    T = _T()
+    w = synth.make_workload("tiers", [n], num_q_heads=4, num_kv_heads=2, budget=budget if budget else n, p=p,
+                            full_selector=full, need_v=False, seed=63)
+    gen = torch.Generator().manual_seed(9)
+    proto = torch.randn(2, 2, 128, generator=gen).to(torch.bfloat16)
+    which = torch.randint(0, 2, (n,), generator=gen)
+    w.k[:] = proto[which]
+    cache = build_cache(w)
+    st, q = run_pipeline(w, cache)
+    assert int(st.status.item()) == 0
+    r = oracle_seq(w, 0)
+    for h in range(w.num_q_heads):
+        assert len(np.unique(r["s_hat"][h])) == 2
+        kept = st.kept_idx[0, h, :int(st.kept_count[0, h])].cpu().numpy()
+        assert kept.tolist() == r["kept"][h].tolist(), h
+        assert len(kept) > 1000
+    for g in range(w.num_kv_heads):
+        un = st.union_idx[g, :int(st.union_count[g])].cpu().numpy()
+        assert un.tolist() == r["union"][g].tolist()
