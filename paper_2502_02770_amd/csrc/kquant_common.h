@@ -10,6 +10,17 @@
 // every fp32 operation rounded on its own.  Returns the lane's packed codes (layouts: twilight_kv_t;
 // word2 only for 8 bits; for 2 bits the even lane of a pair gets the pair's word) and the group's
 // (scale | zero << 16).
+// fp32 -> fp16, round to nearest even everywhere.  The hardware conversion rounds an exact tie in the
+// fp16-subnormal range away from zero on this part (4.5 * 2^-24 -> 5 * 2^-24); below 2^-14 the result is an integer
+// number of 2^-24 steps, taken here with rintf (x * 2^24 is exact, at most 1024, and 1024 is the smallest normal).
+__device__ __forceinline__ __half tw_f32_to_f16_rne(float x) {
+  if (fabsf(x) < 6.103515625e-05f) {
+    const uint32_t steps = (uint32_t)rintf(fabsf(x) * 16777216.0f);
+    return __ushort_as_half((unsigned short)(steps | ((__float_as_uint(x) >> 16) & 0x8000u)));
+  }
+  return __float2half_rn(x);
+}
+
 template <int BITS>
 __device__ __forceinline__ void tw_quantize_lane8(const float (&x)[8], int seg, uint32_t* word_out, uint32_t* word2_out,
                                                   uint32_t* meta_out) {
@@ -21,8 +32,8 @@ __device__ __forceinline__ void tw_quantize_lane8(const float (&x)[8], int seg, 
   for (int i = 1; i < 8; ++i) { lmn = fminf(lmn, x[i]); lmx = fmaxf(lmx, x[i]); }
   const float gmn = tw_quad_min(lmn), gmx = tw_quad_max(lmx);
 
-  const __half hs = __float2half_rn(__fmul_rn(__fsub_rn(gmx, gmn), kInvLevels));
-  const __half hz = __float2half_rn(gmn);
+  const __half hs = tw_f32_to_f16_rne(__fmul_rn(__fsub_rn(gmx, gmn), kInvLevels));
+  const __half hz = tw_f32_to_f16_rne(gmn);
   const float sf = __half2float(hs), zf = __half2float(hz);
   uint32_t u[8];
 #pragma unroll

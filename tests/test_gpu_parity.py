@@ -1379,3 +1379,16 @@ def test_score_ties_by_the_thousand_at_the_threshold(n, budget, full, p):
     for g in range(w.num_kv_heads):
         un = st.union_idx[g, :int(st.union_count[g])].cpu().numpy()
         assert un.tolist() == r["union"][g].tolist()
+
+
+@pytest.mark.parametrize("scale", [1e-6, 1e-4, 30.0, 2000.0], ids=["subnormal_scale", "tiny", "large", "near_fp16_limit"])
+def test_key_magnitudes_at_the_ends_of_the_fp16_range(scale):
+    """Keys scaled so that the fp16 (scale, zero) of the quantised copy are subnormal, tiny, large or close to
+    the documented |x| < 3e4 limit: codes, scale / zero bits, bounds, scores and sets stay equal to the oracle's."""
+    w = synth.make_workload("mag", [700, 90], num_q_heads=8, num_kv_heads=2, budget=256, p=0.9, heavy_frac=0.02,
+                            alpha_range=(0.0, 2.0), shuffle_pool=True, seed=64)
+    w.k[:] = (w.k.float() * scale).to(torch.bfloat16)
+    assert float(w.k.float().abs().max()) < 3e4
+    cache = build_cache(w)
+    check_cache(w, cache)
+    pipeline_against_oracle(w, 4, cache)
