@@ -540,3 +540,21 @@ def test_attention_tolerance_rule_accepts_only_rounding_ties():
     x[3] = 0.5825                               # well inside the lower half: the same output is now wrong
     with pytest.raises(AssertionError):
         assert_attention(g, x)
+
+
+def test_scale_ties_round_to_even_in_the_fp16_subnormal_range():
+    """Appendix B.1 keeps scale and zero in fp16.  A group spanning [-33, 34.5] * 2^-24 has
+    (max - min) * fl(1/15) = 4.5 * 2^-24 exactly in fp32 (67.5 * 0.0666666701 = 4.50000023, below the fp32 midpoint
+    4.50000024), a tie between the fp16 subnormals 4 and 5 steps: round to nearest EVEN gives 0x0004.  (The GPU's
+    own conversion instruction returns 5 here, which is how this case was found.)"""
+    x = np.full(128, -33 * 2.0 ** -24, dtype=np.float32)
+    x[1::2] = 34.5 * 2.0 ** -24
+    bits = O.f32_to_bf16(x)
+    assert np.array_equal(O.bf16_to_f32(bits), x)                 # both values are bf16-exact
+    r = np.float32(x.max() - x.min()) * np.float32(1.0 / 15.0)
+    assert float(r) * 2.0 ** 24 == 4.5
+    u, s, z = O.quantize_k(bits[None, :])
+    assert s.view(np.uint16).tolist() == [[4, 4, 4, 4]]
+    assert z.view(np.uint16).tolist() == [[0x8021] * 4]          # -33 steps
+    # codes follow from the rounded scale: (34.5 + 33) / 4 = 16.875 -> clamped to 15; the minimum maps to 0
+    assert set(u[0].tolist()) == {0, 15}
