@@ -158,7 +158,7 @@ def cpu_baseline(w, max_seconds=25.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="benchmark configuration 0..4 = C1..C5 (default 1 = C2)")
     ap.add_argument("--scale", type=float, default=1.0)
@@ -233,8 +233,10 @@ def main():
 
     # ---- timed region: K steps; HIP events (on the launch stream) around the dominant kernel only,
     # so the event pairs do not stretch the step the way bracketing all seven launches does
-    # (and only at every 32nd of its launches: a launch that carries events delays the stream by some 20-30 us)
-    T.twilight_prof_select(dom, every=32 if a.steps >= 128 else 4)
+    # (and only at every 41st of its launches: a launch that carries events delays the stream by some 40 us; an
+    # odd period because every 128th step - some periodic work of the runtime - runs this kernel 6 us slower, and a
+    # period that divides 128 would sample those steps far too often)
+    T.twilight_prof_select(dom, every=41 if a.steps >= 256 else (19 if a.steps >= 128 else 3))
     T.twilight_prof_enable(2)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
