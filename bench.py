@@ -149,7 +149,7 @@ def cpu_baseline(w, max_seconds=25.0):
     dt = time.time() - t0
     tok = sum(int(w.seq_lens[b]) for b in range(done))
     per_layer_us = dt / tok * int(w.seq_lens.sum()) * 1e6     # scaled to the whole batch by tokens
-    return {"value": per_layer_us, "unit": "us/layer", "cores": 1, "kind": "oracle",
+    return {"value": per_layer_us, "unit": "\u00b5s/layer", "cores": 1, "kind": "oracle",
             "sample": "%d of %d sequences (%d tokens), all stages incl. quantising the whole cache, %.1f s; "
                       "scaled to the batch by token count; numpy, single-threaded apart from BLAS calls"
                       % (done, w.batch, tok, dt)}
@@ -404,8 +404,8 @@ def main():
 
     cpu = None if a.no_cpu_baseline else cpu_baseline(w)
     line = {
-        "metric": "sparse decode-attention us/layer and achieved HBM GB/s vs peak (1 MI355X)",
-        "value": ms_per_step * 1e3, "unit": "us/layer", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "metric": "sparse decode-attention \u00b5s/layer and achieved HBM GB/s vs peak (1 MI355X)",
+        "value": ms_per_step * 1e3, "unit": "\u00b5s/layer", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 KV, int%d K estimate, fp32 accumulate" % a.bits, "data": "synthetic",
         "config": {"workload": "%s: batch %d, %d q / %d kv heads, head_dim 128, context %s, page 16, budget %s, p=%g%s"
