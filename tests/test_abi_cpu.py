@@ -109,3 +109,11 @@ def test_bad_arguments_are_rejected_on_the_host(T):
     assert L.twilight_pinned_device_pointer(one, None) == -1
     with pytest.raises(T.TwilightError):
         T.binding._check(-3)
+
+
+def test_bench_reports_the_named_metric():
+    """bench.py's JSON line carries the metric of the benchmark spec, spelled the same way."""
+    import json
+    src = open(os.path.join(ROOT, "bench.py"), encoding="utf-8").read()
+    metric = re.search(r'"metric": "([^"]+)"', src).group(1).encode().decode("unicode_escape")
+    assert metric == json.load(open(os.path.join(ROOT, "BASELINE.json"), encoding="utf-8"))["metric"]
