@@ -79,8 +79,8 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
   for (int it = 0; it < IT; ++it) {
     ok[it] = live[it] && pool[it] >= 0 && pool[it] < a.pool_pages;
     const uint4* pm = a.page_minmax + ((ok[it] ? pool[it] : 0) * a.Hkv + g) * 32;
-    rmn[it] = pm[seg];
-    rmx[it] = pm[16 + seg];
+    rmn[it] = tw_ld_stream(pm + seg);
+    rmx[it] = tw_ld_stream(pm + 16 + seg);
   }
   if (APPEND) {
     // the page of the new token, if it lies in this workgroup's 64 pages: its 16 owner lanes append

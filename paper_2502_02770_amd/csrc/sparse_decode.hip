@@ -173,8 +173,8 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
       for (int t = 0; t < 4; ++t) {
         rr[t] = rows[sb * 64 + t * 16 + rg];
         if (rr[t] >= 0) {
-          kr[t] = a.k_pool[(long long)rr[t] * 16 + seg];
-          vr[t] = a.v_pool[(long long)rr[t] * 16 + seg];
+          kr[t] = tw_ld_stream(a.k_pool + (long long)rr[t] * 16 + seg);
+          vr[t] = tw_ld_stream(a.v_pool + (long long)rr[t] * 16 + seg);
         } else {
           kr[t] = make_uint4(0, 0, 0, 0);
           vr[t] = make_uint4(0, 0, 0, 0);

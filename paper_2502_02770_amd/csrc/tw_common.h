@@ -82,6 +82,20 @@ __device__ __forceinline__ float tw_quad_max(float v) {
   return fmaxf(v, tw_dpp_f<TW_DPP_XOR2>(v));
 }
 
+// Loads of data that is read once (key bounds, K/V rows): marked non-temporal, so that the stream does not push
+// out of the caches what the step reads again - page tables, lists, scores, the INT4 pages the heads of a group
+// share (batch 32: page_score 61.0 -> 55.3 us, decode 43.2 -> 40.4 us; C2: step 72.9 -> 67.8 us).
+typedef unsigned int tw_u32x4 __attribute__((ext_vector_type(4)));
+typedef float tw_f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 tw_ld_stream(const uint4* p) {
+  const tw_u32x4 r = __builtin_nontemporal_load((const tw_u32x4*)p);
+  return make_uint4(r.x, r.y, r.z, r.w);
+}
+__device__ __forceinline__ float4 tw_ld_stream(const float4* p) {
+  const tw_f32x4 r = __builtin_nontemporal_load((const tw_f32x4*)p);
+  return make_float4(r.x, r.y, r.z, r.w);
+}
+
 // bf16 pair in a 32-bit word -> two fp32 (exact).
 __device__ __forceinline__ float tw_bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float tw_bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
