@@ -75,10 +75,12 @@ __device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32]
 
 // One lane's group of 32 codes of slot (token, group) `idx` of the pool, as 8 dot4 operands
 // (4 dims each, in the order of the query words); 8-bit codes come out as code - 128.
-template <int BITS>
+// STREAM: the codes are read once (every page a candidate, all heads of the group in one workgroup) and loaded
+// non-temporally; with per-head page lists they stay cached for the other heads of the group.
+template <int BITS, bool STREAM = false>
 __device__ __forceinline__ void tw_load_codes(const uint4* kq_pool, long long idx, int (&u)[8]) {
   if (BITS == 4) {
-    const uint4 nib = kq_pool[idx];
+    const uint4 nib = STREAM ? tw_ld_stream(kq_pool + idx) : kq_pool[idx];
     u[0] = nib.x & 0x0F0F0F0F; u[1] = (nib.x >> 4) & 0x0F0F0F0F;
     u[2] = nib.y & 0x0F0F0F0F; u[3] = (nib.y >> 4) & 0x0F0F0F0F;
     u[4] = nib.z & 0x0F0F0F0F; u[5] = (nib.z >> 4) & 0x0F0F0F0F;
@@ -189,8 +191,8 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
     // four pages of an unrolled step are in flight together
     const long long blk = ((long long)(pool >= 0 ? pool : 0) * a.Hkv + g) * 64;
     int u[8];
-    tw_load_codes<BITS>(a.kq_pool, blk + lane, u);
-    const uint32_t meta = a.kq_meta[blk + lane];
+    tw_load_codes<BITS, FULL>(a.kq_pool, blk + lane, u);
+    const uint32_t meta = FULL ? __builtin_nontemporal_load(a.kq_meta + blk + lane) : a.kq_meta[blk + lane];
     const int tok = lp * TW_PAGE + (lane >> 2);
     const bool valid = pool >= 0 && tok < n;
     const long long slot = (long long)(first + k) * TW_PAGE + (lane >> 2);
@@ -404,8 +406,9 @@ __global__ __launch_bounds__(256) void int4_score_mfma_kernel(ScoreArgs a) {
       const int pool = k < npages ? __builtin_amdgcn_readlane(my_pool, k & 63) : -1;
       okv[kk] = pool >= 0;
       const long long blk = ((long long)(pool >= 0 ? pool : 0) * a.Hkv + g) * 64;
-      nib[kk] = a.kq_pool[blk + t * 4 + kb];                   // group kb of token t: 32 codes
-      mt[kk] = ((const uint4*)a.kq_meta)[(blk >> 2) + t];      // token t: 4 x (scale | zero << 16)
+      // every page is read once here (all heads of the group in this workgroup): non-temporal loads
+      nib[kk] = tw_ld_stream(a.kq_pool + blk + t * 4 + kb);                // group kb of token t: 32 codes
+      mt[kk] = tw_ld_stream((const uint4*)a.kq_meta + (blk >> 2) + t);     // token t: 4 x (scale | zero << 16)
     }
 #pragma unroll
     for (int kk = 0; kk < UNR; ++kk) {
