@@ -47,9 +47,10 @@ __global__ __launch_bounds__(256) void kquant_append_kernel(AppendArgs a) {
   uint4 raw = make_uint4(0, 0, 0, 0);
   if (is_new) {
     const long long row = ((long long)a.new_offsets[b] + (tok - start)) * a.Hkv + g;
-    raw = a.k_new[row * 16 + seg];
-    if (a.k_pool) a.k_pool[slot * 16 + seg] = raw;
-    if (a.v_new) a.v_pool[slot * 16 + seg] = a.v_new[row * 16 + seg];
+    // the bf16 rows pass through once (a bulk build moves gigabytes of them): non-temporal both ways
+    raw = tw_ld_stream(a.k_new + row * 16 + seg);
+    if (a.k_pool) tw_st_stream(a.k_pool + slot * 16 + seg, raw);
+    if (a.v_new) tw_st_stream(a.v_pool + slot * 16 + seg, tw_ld_stream(a.v_new + row * 16 + seg));
   }
   tw_unpack8(raw, x);
 

@@ -96,6 +96,11 @@ __device__ __forceinline__ float4 tw_ld_stream(const float4* p) {
   return make_float4(r.x, r.y, r.z, r.w);
 }
 
+__device__ __forceinline__ void tw_st_stream(uint4* p, const uint4& v) {
+  tw_u32x4 r; r.x = v.x; r.y = v.y; r.z = v.z; r.w = v.w;
+  __builtin_nontemporal_store(r, (tw_u32x4*)p);
+}
+
 // bf16 pair in a 32-bit word -> two fp32 (exact).
 __device__ __forceinline__ float tw_bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float tw_bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
