@@ -558,3 +558,22 @@ def test_scale_ties_round_to_even_in_the_fp16_subnormal_range():
     assert z.view(np.uint16).tolist() == [[0x8021] * 4]          # -33 steps
     # codes follow from the rounded scale: (34.5 + 33) / 4 = 16.875 -> clamped to 15; the minimum maps to 0
     assert set(u[0].tolist()) == {0, 15}
+
+
+def test_set_check_accepts_a_mass_on_the_threshold_only_within_1e6():
+    """The parity tests accept a GPU set that differs from the oracle's by a token far from tau* only when the
+    cumulative mass itself sits on p (within 1e-6): the set must lie between the oracle's sets for p -/+ 1e-6."""
+    from tests.test_gpu_parity import check_topp
+    # four weights 0.5 + 1e-9, 0.3, 0.15, 0.05 - 1e-9 (as logits): at p = 0.5 the first token alone just suffices
+    W = np.array([0.5 + 1e-9, 0.3, 0.15, 0.05 - 1e-9])
+    s = np.log(W).astype(np.float64)
+    cand = np.arange(4)
+    mask, _ = O.topp_set(s, 0.5)
+    assert mask.tolist() == [True, False, False, False]
+    check_topp(np.array([0]), s, cand, 0.5)
+    check_topp(np.array([0, 1]), s, cand, 0.5)            # one more token: the mass was 1e-9 over p
+    with pytest.raises(AssertionError):
+        check_topp(np.array([0, 1, 2]), s, cand, 0.5)     # two more: not explained by the mass arithmetic
+    W2 = np.array([0.5 + 1e-4, 0.3, 0.15, 0.05 - 1e-4])    # mass clearly over p: the extra token is an error
+    with pytest.raises(AssertionError):
+        check_topp(np.array([0, 1]), np.log(W2), cand, 0.5)
