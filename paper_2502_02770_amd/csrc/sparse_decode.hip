@@ -55,8 +55,14 @@ __device__ __forceinline__ float tw_row_bcast(float v) {
 #define TW_DPP_ROR4 0x124
 #define TW_DPP_ROR8 0x128
 
+typedef __bf16 tw_bf16x2 __attribute__((ext_vector_type(2)));
+// a.lo * b.lo + a.hi * b.hi + c on bf16 pairs (v_dot2c_f32_bf16)
+__device__ __forceinline__ float tw_dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(tw_bf16x2, a), __builtin_bit_cast(tw_bf16x2, b), c, false);
+}
+
 template <int G>
-__global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(DecodeArgs a) {
   constexpr int R = (G + 3) / 4;                 // score values a lane ends up owning per sub-block
   constexpr int HB = G < 4 ? G : 4;              // heads merged through LDS at a time
   extern __shared__ int32_t prefix[];            // [NG + 1]
@@ -144,15 +150,10 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
       }
       rows[i] = r;
     }
-    // q of the G heads, pre-scaled so that scores are base-2 logits
-    float q[G][8];
+    // q of the G heads, this lane's 8 dims, as loaded (bf16 pairs)
+    uint4 q[G];
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const uint4 r = a.q[((long long)(b * a.Hq + l * G + h)) * 16 + seg];
-      tw_unpack8(r, q[h]);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) q[h][i] *= kLog2eRsqrtD;
-    }
+    for (int h = 0; h < G; ++h) q[h] = a.q[((long long)(b * a.Hq + l * G + h)) * 16 + seg];
     float acc[G][8], M[G], Mmine[R], lacc[R];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
@@ -188,15 +189,10 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
         for (int r = 0; r < R; ++r) val[c][r] = 0.f;
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        float kf[8];
-        tw_unpack8(kr[t], kf);
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-          float d = 0.f;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) d = __builtin_fmaf(q[h][i], kf[i], d);
-          val[t * 4 + (h & 3)][h >> 2] = d;
-        }
+        for (int h = 0; h < G; ++h)              // bf16 pair dot products, fp32 accumulation
+          val[t * 4 + (h & 3)][h >> 2] =
+              tw_dot2_bf16(q[h].w, kr[t].w, tw_dot2_bf16(q[h].z, kr[t].z, tw_dot2_bf16(q[h].y, kr[t].y, tw_dot2_bf16(q[h].x, kr[t].x, 0.f))));
       }
       // ---- transposing reduction over the 16 lanes of the row: each step a lane keeps the half
       //      of the values selected by one bit of its lane id and adds the partner's copy of it;
@@ -221,7 +217,7 @@ __global__ __launch_bounds__(256) void sparse_decode_kernel(DecodeArgs a) {
           a2[j] = keep + tw_dpp_f<TW_DPP_XOR2>(send);
         }
         const float keep = b0 ? a2[1] : a2[0], send = b0 ? a2[0] : a2[1];
-        s_mine[r] = keep + tw_dpp_f<TW_DPP_XOR1>(send);
+        s_mine[r] = (keep + tw_dpp_f<TW_DPP_XOR1>(send)) * kLog2eRsqrtD;   // base-2 logit
       }
       const bool valid = rows[sb * 64 + my_t * 16 + rg] >= 0;
       // ---- maximum per head over the sub-block: over t inside the row, the 4 rows of the wave, the 4 waves
