@@ -27,7 +27,7 @@ TRAFFIC_C2 = {"page_score": 33161 * 2048 + 2130 * 1024, "int4_score": 20219 * 20
 
 # Median kernel durations (us) of the same C2 step under rocprofv3 --kernel-trace, from
 # profiles/c2_decode_step_kernel_trace.md, for comparison with the live figure.
-ROCPROF_US_C2 = {"page_score": 17.6, "int4_score": 13.5, "sparse_decode": 15.4, "topp": 11.9, "page_select": 6.7,
+ROCPROF_US_C2 = {"page_score": 17.6, "int4_score": 13.7, "sparse_decode": 16.0, "topp": 12.0, "page_select": 6.8,
                  "combine": 4.0}
 
 # Paper context (another machine: one A100, FP16 KV, LongBench-derived prompts) - not a target.
