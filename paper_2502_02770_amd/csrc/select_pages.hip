@@ -18,7 +18,7 @@
 
 namespace {
 
-constexpr int PS_PAGES_PER_WG = 64;   // 4 waves x 4 pages x 4 iterations
+constexpr int PS_PAGES_PER_WG = 32;   // 4 waves x 4 pages x 2 iterations
 
 struct ScoreArgs {
   const uint32_t* q;          // bf16 pairs [b][Hq][64]
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
     rmx[it] = tw_ld_stream(pm + 16 + seg);
   }
   if (APPEND) {
-    // the page of the new token, if it lies in this workgroup's 64 pages: its 16 owner lanes append
+    // the page of the new token, if it lies in this workgroup's pages: its 16 owner lanes append
     const int sp = a.new_pos[b];
     const int off = (sp >> 4) - base;
     if (sp >= 0 && sp < n && off >= 0 && off < PS_PAGES_PER_WG && (off & 15) == grp) {
