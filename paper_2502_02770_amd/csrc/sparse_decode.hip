@@ -25,6 +25,7 @@ constexpr float kLog2eRsqrtD = 0x1.0527dcp-3f;   // fp32(log2(e) / sqrt(128))
 constexpr float kLn2 = 0x1.62e43p-1f;
 constexpr float kNegBig = -1.0e30f;              // finite stand-in for -inf in running maxima
 constexpr int DEC_MAX_CHUNK = 512;
+constexpr unsigned DEC_ITEMS_PER_WG = 3;         // measured: 64-entry items at 1.2 per workgroup, 128 at 2.5, 256 at 2 were the best choices
 
 struct DecodeArgs {
   const uint4* q;             // bf16 [b][Hq][16 x uint4]
@@ -77,8 +78,9 @@ __global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(Deco
   const bool b3 = seg & 8, b2 = seg & 4, b1 = seg & 2, b0 = seg & 1;
   const int my_t = seg >> 2, my_hc = seg & 3;
 
-  // ---- chunk length: the shortest of {c0, 2c0, 4c0} (<= 512) whose item count fits the grid,
-  //      so that short lists are spread over all workgroups and long ones amortise the merge
+  // ---- chunk length: the shortest of {c0, 2c0, 4c0} (<= 512) that leaves a workgroup at most
+  //      DEC_ITEMS_PER_WG items, so that short lists are spread over all workgroups (whose phases then
+  //      interleave) and long ones amortise the per-item set-up and merge
   uint32_t n0 = 0, n1 = 0, n2 = 0;
   const int c0 = a.chunk;
   for (int gi = tid; gi < a.NG; gi += 256) {
@@ -94,9 +96,9 @@ __global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(Deco
   n0 = red3[0][0] + red3[0][1] + red3[0][2] + red3[0][3];
   n1 = red3[1][0] + red3[1][1] + red3[1][2] + red3[1][3];
   int chunk = c0;
-  if (!a.fix_chunk && n0 > gridDim.x && 2 * c0 <= DEC_MAX_CHUNK) {
+  if (!a.fix_chunk && n0 > DEC_ITEMS_PER_WG * gridDim.x && 2 * c0 <= DEC_MAX_CHUNK) {
     chunk = 2 * c0;
-    if (n1 > gridDim.x && 4 * c0 <= DEC_MAX_CHUNK) chunk = 4 * c0;
+    if (n1 > DEC_ITEMS_PER_WG * gridDim.x && 4 * c0 <= DEC_MAX_CHUNK) chunk = 4 * c0;
   }
 
   // ---- item map: exclusive prefix of per-group chunk counts
