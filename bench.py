@@ -22,12 +22,12 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch at config C2 from rocprofv3 --pmc FETCH_SIZE (x2.0, calibrated against a
 # plain copy) + WRITE_SIZE, see profiles/c2_decode_step_hbm_traffic.md.  Not measurable live.
 TRAFFIC_C2 = {"page_score": 33125 * 2048 + 2118 * 1024, "int4_score": 20219 * 2048 + 4172 * 1024,
-              "sparse_decode": 19722 * 2048 + 1282 * 1024, "topp": 2784 * 2048 + 1343 * 1024,
+              "sparse_decode": 19771 * 2048 + 2497 * 1024, "topp": 2784 * 2048 + 1343 * 1024,
               "page_select": 1078 * 2048 + 264 * 1024}
 
 # Median kernel durations (us) of the same C2 step under rocprofv3 --kernel-trace, from
 # profiles/c2_decode_step_kernel_trace.md, for comparison with the live figure.
-ROCPROF_US_C2 = {"page_score": 16.9, "int4_score": 13.7, "sparse_decode": 16.0, "topp": 12.0, "page_select": 6.8,
+ROCPROF_US_C2 = {"page_score": 16.9, "int4_score": 13.5, "sparse_decode": 14.4, "topp": 12.0, "page_select": 6.8,
                  "combine": 4.0}
 
 # Paper context (another machine: one A100, FP16 KV, LongBench-derived prompts) - not a target.
