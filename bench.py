@@ -36,7 +36,7 @@ PAPER_CONTEXT = {"quest_twi_vs_fa2_attention_speedup": 15.8, "quest_twi_vs_quest
 
 
 def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_selector=False, offload=False,
-                separate_append=False):
+                separate_append=False, kv_heads=None):
     """`layers` independent copies of the layer's cache (same contents, different memory).  Successive steps
     rotate over them, as the layers of a model do, so that a step finds its pools in HBM and not in the
     256 MB memory-side cache left warm by the previous step over the very same addresses."""
@@ -44,7 +44,7 @@ def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_select
     import paper_2502_02770_amd as T
     from workloads import synth
     t0 = time.time()
-    w = synth.config(cfg_idx, scale=scale, seed=seed, batch=batch)
+    w = synth.config(cfg_idx, scale=scale, seed=seed, batch=batch, kv_heads=kv_heads)
     if p is not None:
         w.p = float(p)
     if full_selector:
@@ -164,6 +164,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--kv-heads", type=int, default=None,
+                    help="KV heads of the C2 shape (default 8; 32 = multi-head attention, one query head per KV head)")
     ap.add_argument("--layers", type=int, default=4,
                     help="independent copies of the cache that successive steps rotate over (1 = same memory every step)")
     ap.add_argument("--bits", type=int, default=4, choices=[2, 4, 8],
@@ -189,7 +191,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
-    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits, a.p, a.full_selector, a.offload, a.separate_append)
+    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits, a.p, a.full_selector, a.offload, a.separate_append, a.kv_heads)
     if a.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
@@ -384,7 +386,7 @@ def main():
         del sv
 
     ach = nbytes[dom] / (dom_avg * dom_calls * 1e-3) / 1e9
-    default_cfg = (a.config == 1 and a.scale == 1.0 and a.batch is None and a.seed == 0 and a.bits == 4 and a.p is None
+    default_cfg = (a.config == 1 and a.scale == 1.0 and a.batch is None and a.seed == 0 and a.bits == 4 and a.p is None and a.kv_heads is None
                    and not a.full_selector and not a.offload)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS,

@@ -399,7 +399,7 @@ int decode_blocks_per_cu(size_t lds) {
     int n = 0;
     occ_lds = lds;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, sparse_decode_kernel<G>, 256, lds) != hipSuccess || n < 1) n = 1;
-    occ = n > 4 ? 4 : n;
+    occ = n > 6 ? 6 : n;
   }
   return occ;
 }

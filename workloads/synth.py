@@ -168,7 +168,7 @@ def ragged_lengths(count, lo, hi, seed=0):
 
 # The five benchmark configurations C1..C5, and `scale`d
 # variants: scale < 1 shrinks contexts and budgets by that factor for tests.
-def config(idx, scale=1.0, seed=0, batch=None):
+def config(idx, scale=1.0, seed=0, batch=None, kv_heads=None):
     def sc(x, lo=PAGE):
         return max(lo, int(round(x * scale)))
     if idx == 0:
@@ -176,8 +176,9 @@ def config(idx, scale=1.0, seed=0, batch=None):
                              alpha_range=(0.5, 3.0), seed=seed)
     if idx == 1:
         b = 8 if batch is None else batch
+        extra = {} if kv_heads is None else {"num_kv_heads": int(kv_heads)}   # 32 = the multi-head (G = 1) shape
         return make_workload("C2", [sc(32768)] * b, budget=sc(4096), p=0.9, heavy_frac=0.005,
-                             alpha_range=(0.0, 4.0), shuffle_pool=True, seed=seed)
+                             alpha_range=(0.0, 4.0), shuffle_pool=True, seed=seed, **extra)
     if idx == 2:
         return make_workload("C3", [sc(131072)], budget=sc(8192), p=0.9, spans=(8, 64),
                              alpha_range=(1.0, 4.0), seed=seed)
