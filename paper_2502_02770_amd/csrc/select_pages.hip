@@ -46,7 +46,9 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
   const int b = blockIdx.z, g = blockIdx.x;
   const int tid = threadIdx.x, seg = tid & 15, grp = tid >> 4;   // grp: 0..15 page slot in the WG
   const int n = a.seq_lens[b];
-  const int base = blockIdx.y * PS_PAGES_PER_WG;
+  // last pages first: the workgroup that appends the step's new token (the sequence's last page) has the longest
+  // chain of dependent accesses and should not be the one that starts last
+  const int base = (int)(gridDim.y - 1 - blockIdx.y) * PS_PAGES_PER_WG;
   // page-table entries of this lane's 4 pages: issued before the sequence length is known (any entry of
   // the row may be read; entries beyond the last page are ignored below), so that the two loads overlap
   constexpr int IT = PS_PAGES_PER_WG / 16;
