@@ -55,7 +55,8 @@ extern "C" {
 #define TW_OK 0
 #define TW_EINVAL (-1)     /* NULL pointer, unsupported shape or parameter */
 #define TW_EWORKSPACE (-2) /* workspace smaller than twilight_workspace_bytes */
-#define TW_ELAUNCH (-3)    /* HIP reported an error at launch */
+#define TW_ELAUNCH (-3)    /* HIP reported an error (kernel launch, device or symbol query) */
+#define TW_ELIMIT (-4)     /* problem larger than the fixed scratch of twilight_select_pages_static */
 
 /* status bits (device word) */
 #define TW_STATUS_UNION_TRUNCATED 1u /* a group's union exceeded union_stride */
@@ -146,6 +147,26 @@ int twilight_kquant_append(const twilight_kv_t* kv, const void* k_new, const voi
 int twilight_select_pages(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
                           int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
                           void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * twilight_select_pages for callers that cannot allocate device memory or hand
+ * over a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same kernels, same results bit for bit;
+ * the fp32 bound scores (batch * num_q_heads * max_pages_per_seq * 4 bytes) go
+ * to a fixed array of TW_STATIC_SELECT_WS_BYTES of device memory that is part
+ * of the library's code object (each GPU the library runs on holds its copy
+ * until the process ends).  The call allocates and frees nothing (no hipMalloc /
+ * hipFree, no allocating library routine; per-kernel timing must be off).
+ * TW_ELIMIT when the scores do not fit; TW_ELAUNCH when the array's device
+ * address cannot be obtained.  All calls on one GPU share the array, which
+ * keeps the previous call's contents (every score that is read is written
+ * first, so nothing needs clearing): calls that overlap on one GPU - on
+ * different streams or from different threads - race and must be serialised
+ * by the caller.
+ */
+#define TW_STATIC_SELECT_WS_BYTES (8u << 20)
+int twilight_select_pages_static(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
+                                 int32_t* sel_pages, int32_t* sel_count, int32_t max_sel, void* stream);
 
 /*
  * The decode step's form of stages 4 + 1 in one launch: append ONE new token

@@ -13,6 +13,7 @@
 // page_score<G, true> also appends the decode step's one new token per sequence on its way
 // (twilight_append_select): the 16 lanes that own the page the token falls into store its K/V
 // rows, quantise K, and fold it into the page's bounds before scoring them.
+#include <atomic>
 #include "tw_common.h"
 #include "kquant_common.h"
 
@@ -475,6 +476,42 @@ extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, con
                                      int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
                                      void* ws, size_t ws_bytes, void* stream) {
   return select_impl(kv, q, budget_tokens, sel_pages, sel_count, max_sel, ws, ws_bytes, stream, false, nullptr, nullptr, nullptr);
+}
+
+// ---- the selector for callers that must not allocate: same kernels, the bound scores go to a
+// fixed array of device memory that the library's code object carries.  The array's name is only a
+// host-side handle; its address on the current device comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[TW_STATIC_SELECT_WS_BYTES];
+
+static int static_scratch_ptr(void** out) {
+  static std::atomic<void*> ptrs[TW_MAX_DEVICES];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= TW_MAX_DEVICES) return TW_ELAUNCH;
+  void* p = ptrs[dev].load(std::memory_order_acquire);
+  if (!p) {
+    // every GPU holds its own copy of the array at its own address; racing first calls look up the same value
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return TW_ELAUNCH;
+    }
+    ptrs[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return TW_OK;
+}
+
+extern "C" int twilight_select_pages_static(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
+                                            int32_t* sel_pages, int32_t* sel_count, int32_t max_sel, void* stream) {
+  TwDims d;
+  if (int e = tw_check_kv(kv, &d)) return e;
+  if (max_sel <= 0) return TW_EINVAL;
+  const size_t need = twilight_workspace_bytes(TW_WS_SELECT, kv, max_sel, 0);
+  if (need == 0) return TW_EINVAL;
+  if (need > (size_t)TW_STATIC_SELECT_WS_BYTES) return TW_ELIMIT;
+  void* ws = nullptr;
+  if (int e = static_scratch_ptr(&ws)) return e;
+  // every score the select kernels read is written by page_score in this call: nothing has to start at zero
+  return select_impl(kv, q, budget_tokens, sel_pages, sel_count, max_sel, ws, need, stream, false, nullptr, nullptr, nullptr);
 }
 
 extern "C" int twilight_append_select(const twilight_kv_t* kv, const void* k_new, const void* v_new, const int32_t* new_pos,

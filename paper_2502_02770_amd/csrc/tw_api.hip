@@ -24,9 +24,9 @@ int tw_check_kv(const twilight_kv_t* kv, TwDims* d) {
 }
 
 int tw_num_cus() {
-  static int cus[64] = {0};
+  static int cus[TW_MAX_DEVICES] = {0};
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= TW_MAX_DEVICES) return 256;
   if (cus[dev] == 0) {
     int n = 0;
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
@@ -88,7 +88,8 @@ extern "C" const char* twilight_strerror(int code) {
     case TW_OK: return "ok";
     case TW_EINVAL: return "invalid argument (NULL pointer, unsupported shape or parameter)";
     case TW_EWORKSPACE: return "workspace missing or smaller than twilight_workspace_bytes";
-    case TW_ELAUNCH: return "HIP reported an error at kernel launch";
+    case TW_ELAUNCH: return "HIP reported an error (kernel launch, device or symbol query)";
+    case TW_ELIMIT: return "problem exceeds the fixed scratch array of the entry point that allocates nothing";
     default: return "unknown error code";
   }
 }

@@ -8,6 +8,7 @@
 #define TW_HEAD_DIM 128
 #define TW_PAGE 16
 #define TW_QGROUP 32
+#define TW_MAX_DEVICES 64   // per-device host-side caches are indexed by the HIP device ordinal
 
 // ---------------------------------------------------------------- host side
 struct TwDims {
