@@ -19,7 +19,11 @@
  *     `stream` is a hipStream_t passed as void* (NULL = default stream).
  *   - The caller owns every buffer.  The library allocates nothing, frees
  *     nothing, copies nothing between host and device and never synchronises;
- *     all work is enqueued on `stream`.
+ *     all work is enqueued on `stream`.  It keeps no state between calls
+ *     beyond cached device properties (compute-unit count, occupancy of its
+ *     own kernels) and reads no environment variables; entry points may be
+ *     called from several threads.  The one exception is the opt-in per-kernel
+ *     timing of twilight_prof.h, which is process-global (off by default).
  *   - head_dim must be 128, page_size 16, quant_group 32, quant_bits 0/4, 2 or 8,
  *     num_q_heads / num_kv_heads one of 1, 2, 4, 8.
  *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
@@ -322,34 +326,6 @@ int twilight_pinned_device_pointer(void* host_ptr, void** device_ptr /* host, ou
 
 const char* twilight_strerror(int code);
 int twilight_abi_version(void);
-
-/*
- * Per-kernel timing for benchmarks, with a HIP event pair attached to the
- * kernel's own dispatch (hipExtLaunchKernelGGL: start and stop timestamps of
- * the kernel, no extra packets on the stream).  mode 0 = off (default), 1 =
- * every kernel, 2 = only the kernel id given to twilight_prof_select, at
- * every `every`-th of its launches.  Timed launches are not meant to be
- * captured into a graph.  While on,
- * each launch adds one record {kernel id, start event, stop event} (at most
- * TW_PROF_MAX_RECORDS between two collects; further launches are not timed).
- * twilight_prof_collect synchronises the events, writes up to `cap` records
- * (kernel id, milliseconds) to the HOST arrays and clears the list; returns
- * the number written.  Not thread-safe; one stream at a time.
- */
-#define TW_PROF_MAX_RECORDS 65536
-#define TW_K_KQUANT_APPEND 0
-#define TW_K_PAGE_SCORE 1
-#define TW_K_PAGE_SELECT 2
-#define TW_K_INT4_SCORE 3
-#define TW_K_TOPP 4
-#define TW_K_UNION 5
-#define TW_K_DECODE 6
-#define TW_K_COMBINE 7
-#define TW_K_COUNT 8
-int twilight_prof_enable(int mode);
-int twilight_prof_select(int kernel_id, int every);
-int twilight_prof_collect(int32_t* kernel_ids /*host*/, float* ms /*host*/, int32_t cap);
-const char* twilight_kernel_name(int kernel_id);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,48 @@
+/*
+ * twilight_prof.h - opt-in per-kernel timing of the library's launches, for
+ * benchmarks.  This is the library's only process-global mutable state: one
+ * list of event pairs shared by all threads and streams (calls are serialised
+ * by a lock; while timing is on, use one stream at a time).  Off by default;
+ * nothing here is needed to use the entry points of twilight.h.
+ */
+#ifndef TWILIGHT_PROF_H
+#define TWILIGHT_PROF_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * A HIP event pair is attached to the
+ * kernel's own dispatch (hipExtLaunchKernelGGL: start and stop timestamps of
+ * the kernel, no extra packets on the stream).  mode 0 = off (default), 1 =
+ * every kernel, 2 = only the kernel id given to twilight_prof_select, at
+ * every `every`-th of its launches.  Timed launches are not meant to be
+ * captured into a graph.  While on,
+ * each launch adds one record {kernel id, start event, stop event} (at most
+ * TW_PROF_MAX_RECORDS between two collects; further launches are not timed).
+ * twilight_prof_collect synchronises the events, writes up to `cap` records
+ * (kernel id, milliseconds) to the HOST arrays and clears the list; returns
+ * the number written.
+ */
+#define TW_PROF_MAX_RECORDS 65536
+#define TW_K_KQUANT_APPEND 0
+#define TW_K_PAGE_SCORE 1
+#define TW_K_PAGE_SELECT 2
+#define TW_K_INT4_SCORE 3
+#define TW_K_TOPP 4
+#define TW_K_UNION 5
+#define TW_K_DECODE 6
+#define TW_K_COMBINE 7
+#define TW_K_COUNT 8
+int twilight_prof_enable(int mode);
+int twilight_prof_select(int kernel_id, int every);
+int twilight_prof_collect(int32_t* kernel_ids /*host*/, float* ms /*host*/, int32_t cap);
+const char* twilight_kernel_name(int kernel_id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TWILIGHT_PROF_H */

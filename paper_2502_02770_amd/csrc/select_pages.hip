@@ -46,6 +46,7 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
   // and the workgroups that read them start next to each other
   const int b = blockIdx.z, g = blockIdx.x;
   const int tid = threadIdx.x, seg = tid & 15, grp = tid >> 4;   // grp: 0..15 page slot in the WG
+  TW_STAMP(0);
   const int n = a.seq_lens[b];
   // last pages first: the workgroup that appends the step's new token (the sequence's last page) has the longest
   // chain of dependent accesses and should not be the one that starts last
@@ -270,6 +271,7 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
     for (int i = tid; i < P; i += NT) out[i] = i;
     return;
   }
+  TW_STAMP(10);
 
   __shared__ uint32_t key_s[NT == 256 ? 2048 : SEL_LDS_PAGES];   // the 256-thread variant serves rows of at most 2048 pages
   __shared__ uint32_t hist[SEL_NB];
@@ -305,21 +307,30 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
   for (int w = 1; w < NW; ++w) { klo = red_lo[w] < klo ? red_lo[w] : klo; khi = red_hi[w] > khi ? red_hi[w] : khi; }
 
   uint32_t need = (uint32_t)Kp, T = 0, need_eq = 0;
+  TW_STAMP(11);
 #pragma unroll 1
   for (int pass = 0;; ++pass) {
-    // every pass drops the live minimum or maximum, so 64 passes are never reached
-    if (klo == khi || pass == 64) { T = klo; need_eq = need; break; }      // everything left ties
+    if (pass < 6) TW_STAMP(12 + pass);
+    if (klo == khi) { T = klo; need_eq = need; break; }                    // everything left ties
     const float smn = tw_key_to_float(klo), smx = tw_key_to_float(khi);
     const float scale = (float)SEL_NB / (smx - smn);
+    // Buckets are linear in the bound's value while that works: a finite scale over a normal span, and only
+    // for the first passes.  Otherwise (spans in the subnormal range, infinite bounds, rows that keep falling
+    // into one bucket) they are linear in the order-preserving key, which splits any span of at least 2048
+    // keys 2048 ways and resolves a shorter one exactly, so every pass narrows the interval.
+    const bool by_key = !(scale <= 3.0e38f) || !(smx - smn >= 1.1754944e-38f) || pass >= 3;
+    const uint32_t span = khi - klo;
+    const int kshift = span < (uint32_t)SEL_NB ? 0 : 32 - __clz(span) - 11;
+    auto bucket_of = [&](uint32_t k) -> int {
+      if (by_key) return (int)((k - klo) >> kshift);
+      const int bk = (int)((tw_key_to_float(k) - smn) * scale);
+      return bk > SEL_NB - 1 ? SEL_NB - 1 : (bk < 0 ? 0 : bk);
+    };
     for (int i = tid; i < SEL_NB; i += NT) hist[i] = 0;
     __syncthreads();
     for (int i = tid; i < P; i += NT) {
       const uint32_t k = key_s[i];
-      if (k >= klo && k <= khi) {
-        int bk = (int)((tw_key_to_float(k) - smn) * scale);
-        bk = bk > SEL_NB - 1 ? SEL_NB - 1 : (bk < 0 ? 0 : bk);
-        atomicAdd(&hist[bk], 1u);
-      }
+      if (k >= klo && k <= khi) atomicAdd(&hist[bucket_of(k)], 1u);
     }
     __syncthreads();
     // thread t owns the BPT buckets below 2047 - BPT*t, walked downwards
@@ -346,9 +357,7 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
     for (int i = tid; i < P; i += NT) {
       const uint32_t k = key_s[i];
       if (k >= klo && k <= khi) {
-        int bk = (int)((tw_key_to_float(k) - smn) * scale);
-        bk = bk > SEL_NB - 1 ? SEL_NB - 1 : (bk < 0 ? 0 : bk);
-        if (bk == bkt) {
+        if (bucket_of(k) == bkt) {
           nlo = k < nlo ? k : nlo;
           nhi = k > nhi ? k : nhi;
           if (small) { const uint32_t at = atomicAdd(&sh_n, 1u); if (at < SEL_CAP) { ck[at] = k; ci[at] = i; } }
@@ -385,6 +394,7 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
     __syncthreads();                              // red_* and hist are rewritten by the next pass
   }
 
+  TW_STAMP(20);
   // ---- ordered emit: thread t owns the contiguous pages [t*E, (t+1)*E)
   const int E = (P + NT - 1) / NT;
   const int i0 = tid * E, i1 = (i0 + E < P) ? i0 + E : P;
@@ -402,6 +412,7 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
     gt_before += k > T ? 1u : 0u;
     eq_before += k == T ? 1u : 0u;
   }
+  TW_STAMP(21);
 }
 
 template <int G>
@@ -411,6 +422,12 @@ void launch_score(const ScoreArgs& a, dim3 grid, bool append, hipStream_t s) {
 }
 
 }  // namespace
+
+#ifdef TW_PHASE_TIMING
+extern "C" int twilight_debug_stamps_select(unsigned long long* host_out) {
+  return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(tw_dbg_stamps), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : -1;
+}
+#endif
 
 static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
                        int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,

@@ -17,6 +17,7 @@
 // The same kernel serves the per-head variant (the head-wise form of Appendix
 // B.2): one list per query head, G = 1, list l reads KV head l / group size.
 #include <stdlib.h>
+#include <atomic>
 #include "tw_common.h"
 
 namespace {
@@ -77,6 +78,7 @@ __global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(Deco
   const bool dense = a.union_idx == nullptr;
   const bool b3 = seg & 8, b2 = seg & 4, b1 = seg & 2, b0 = seg & 1;
   const int my_t = seg >> 2, my_hc = seg & 3;
+  TW_STAMP(0);
 
   // ---- chunk length: the shortest of {c0, 2c0, 4c0} (<= 512) that leaves a workgroup at most
   //      DEC_ITEMS_PER_WG items, so that short lists are spread over all workgroups (whose phases then
@@ -121,6 +123,7 @@ __global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(Deco
   if (tid == 0) prefix[a.NG] = (int32_t)run;
   __syncthreads();
   const int total_items = (int)run;
+  TW_STAMP(1);
   if (blockIdx.x == 0)
     for (int i = tid; i <= a.NG; i += 256) a.ws_prefix[i] = prefix[i];
 
@@ -152,6 +155,7 @@ __global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(Deco
       }
       rows[i] = r;
     }
+    if (item == 0) TW_STAMP(2);
     // q of the G heads, this lane's 8 dims, as loaded (bf16 pairs)
     uint4 q[G];
 #pragma unroll
@@ -183,6 +187,9 @@ __global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(Deco
           vr[t] = make_uint4(0, 0, 0, 0);
         }
       }
+#ifdef TW_PHASE_TIMING
+      if (item == 0 && sb == 0) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); TW_STAMP(3); }
+#endif
       // ---- partial dot products of this lane's 8 dims: val[t*4 + h%4][h/4]
       float val[16][R];
 #pragma unroll
@@ -283,6 +290,7 @@ __global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(Deco
       }
     }
 
+    if (item == 0) TW_STAMP(4);
     // ---- merge the 16 rows of the workgroup: all share the running maxima, so plain sums
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -322,7 +330,9 @@ __global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(Deco
       }
       __syncthreads();                          // macc / rows / ml_s are reused
     }
+    if (item == 0) TW_STAMP(5);
   }
+  if (blockIdx.x == 0) TW_STAMP(6);
 }
 
 struct CombineArgs {
@@ -393,15 +403,15 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a) {
 // earlier one has finished all of its own.
 template <int G>
 int decode_blocks_per_cu(size_t lds) {
-  static int occ = 0;
-  static size_t occ_lds = 0;
-  if (occ == 0 || occ_lds != lds) {
-    int n = 0;
-    occ_lds = lds;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, sparse_decode_kernel<G>, 256, lds) != hipSuccess || n < 1) n = 1;
-    occ = n > 6 ? 6 : n;
-  }
-  return occ;
+  // read-only property of the kernel, cached for the LDS size last asked for (racing threads compute the same value)
+  static std::atomic<unsigned long long> cache{0};               // (lds << 8) | occupancy
+  const unsigned long long c = cache.load(std::memory_order_relaxed);
+  if ((c & 0xFF) != 0 && (c >> 8) == lds) return (int)(c & 0xFF);
+  int n = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, sparse_decode_kernel<G>, 256, lds) != hipSuccess || n < 1) n = 1;
+  n = n > 6 ? 6 : n;
+  cache.store(((unsigned long long)lds << 8) | (unsigned)n, std::memory_order_relaxed);
+  return n;
 }
 
 template <int G>
@@ -414,11 +424,19 @@ void launch_decode(const DecodeArgs& a, long long max_items, size_t lds, hipStre
 
 }  // namespace
 
+#ifdef TW_PHASE_TIMING
+extern "C" int twilight_debug_stamps_decode(unsigned long long* host_out) {
+  return hipMemcpyFromSymbol(host_out, HIP_SYMBOL(tw_dbg_stamps), sizeof(unsigned long long) * 64) == hipSuccess ? 0 : -1;
+}
+#endif
+
 // Items are `chunk` list entries: short for sparse lists (many small items keep
 // all CUs busy on short, latency-bound gathers), longer for the dense sweep.
 int tw_decode_chunk(bool dense) {
-  static const int c0 = getenv("TW_DECODE_C0") ? atoi(getenv("TW_DECODE_C0")) : 0;   // tuning switch
+#ifdef TW_TUNING                                 // tuning builds only: the shipped library reads no environment
+  static const int c0 = getenv("TW_DECODE_C0") ? atoi(getenv("TW_DECODE_C0")) : 0;
   if (!dense && (c0 == 64 || c0 == 128 || c0 == 256 || c0 == 512)) return c0;
+#endif
   return dense ? 256 : 64;
 }
 
@@ -458,8 +476,11 @@ static int decode_impl(const twilight_kv_t* kv, const void* q, const int32_t* co
   a.Hq = d.Hq; a.Hkv = d.Hkv; a.max_pages = d.max_pages; a.union_stride = stride;
   a.LH = LH; a.kv_div = per_head ? d.G : 1;
   a.NG = NG; a.chunk = tw_decode_chunk(dense); a.pool_pages = d.pool_pages;
-  static const bool fixed_c0 = getenv("TW_DECODE_C0") != nullptr;   // tuning switch: chunk length as given
+  a.fix_chunk = 0;
+#ifdef TW_TUNING
+  static const bool fixed_c0 = getenv("TW_DECODE_C0") != nullptr;   // chunk length as given
   a.fix_chunk = (!dense && fixed_c0) ? 1 : 0;
+#endif
   const size_t lds = (size_t)(NG + 1) * 4;
   tw_prof_before(TW_K_DECODE, s);
   switch (Gk) {

@@ -518,6 +518,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
   if (N <= a.n_above || N > a.n_upto) return;     // another launch's head (block-uniform)
   const float* row = a.scores + (long long)bh * a.cand_stride;
   const int c0 = tid * EPT;
+  TW_STAMP(0);
 
   __shared__ unsigned long long histM[HP_NB];
   __shared__ uint32_t histC[HP_NB];
@@ -889,7 +890,14 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
   const int bound = full ? d.max_pages : max_sel;
   a.cand_stride = bound * TW_PAGE;
   a.pw = pages_per_wave((long long)bound * d.batch * (full ? d.Hkv : d.Hq), bound);
-  static const int pw_env = getenv("TW_INT4_PW") ? atoi(getenv("TW_INT4_PW")) : 0;   // tuning switch
+#ifdef TW_TUNING                                 // tuning builds only: the shipped library reads no environment
+  static const int pw_env = getenv("TW_INT4_PW") ? atoi(getenv("TW_INT4_PW")) : 0;
+  static const int x_env = getenv("TW_INT4_X") ? atoi(getenv("TW_INT4_X")) : 0;
+  static const bool valu_only = getenv("TW_INT4_VALU") != nullptr;   // vector-ALU kernel for every G
+#else
+  constexpr int pw_env = 0, x_env = 0;
+  constexpr bool valu_only = false;
+#endif
   if (pw_env >= 4 && pw_env <= 64) a.pw = pw_env;
   dim3 grid((bound + 4 * a.pw - 1) / (4 * a.pw), d.batch * (full ? d.Hkv : d.Hq));
   a.rotate = 0;
@@ -897,7 +905,6 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
     // Per-head page lists: at most 8 pages per wave; rows of more than 8 chunks get a grid a multiple of 8 wide
     // (one column per XCD, see the kernel) and at most about 16384 workgroups - batches of many heads have
     // lists far shorter than the row bound, and their workgroups loop over the chunks beyond the grid
-    static const int x_env = getenv("TW_INT4_X") ? atoi(getenv("TW_INT4_X")) : 0;   // tuning switch
     if (!(pw_env >= 4 && pw_env <= 64) && a.pw > 8) a.pw = 8;
     int x = (bound + 4 * a.pw - 1) / (4 * a.pw);
     if (x > 8) {
@@ -910,7 +917,6 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
     a.rotate = (x & 7) == 0 ? 1 : 0;
   }
   tw_prof_before(TW_K_INT4_SCORE, s);
-  static const bool valu_only = getenv("TW_INT4_VALU") != nullptr;   // tuning switch: vector-ALU kernel for every G
   if (!full) launch_score<1, false>(a, grid, dots != nullptr, d.bits, s);
   else if (d.G >= 4 && d.bits == 4 && !valu_only) {               // matrix-core kernel: 4 or 8 heads share every page
     // 8 pages in flight per wave (the kernel needs few registers, so 4 to 7 waves per SIMD stay resident)

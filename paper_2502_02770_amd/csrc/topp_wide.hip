@@ -549,8 +549,12 @@ int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv
   // flushes of the LDS histogram per score), emit pass 86 / 69 / 58 us (small workgroups overlap their load and
   // compute phases; at 88 registers only one 1024-thread workgroup fits a CU)
   constexpr int HIST_NT = 1024, EMIT_NT = 256;
-  static const int emit_nt = getenv("TW_WIDE_EMIT_NT") ? atoi(getenv("TW_WIDE_EMIT_NT")) : EMIT_NT;   // tuning switch
-  static const int hist_nt = getenv("TW_WIDE_HIST_NT") ? atoi(getenv("TW_WIDE_HIST_NT")) : HIST_NT;   // tuning switch
+#ifdef TW_TUNING                                 // tuning builds only: the shipped library reads no environment
+  static const int emit_nt = getenv("TW_WIDE_EMIT_NT") ? atoi(getenv("TW_WIDE_EMIT_NT")) : EMIT_NT;
+  static const int hist_nt = getenv("TW_WIDE_HIST_NT") ? atoi(getenv("TW_WIDE_HIST_NT")) : HIST_NT;
+#else
+  constexpr int emit_nt = EMIT_NT, hist_nt = HIST_NT;
+#endif
   auto grid_for = [&](int nt) { return dim3((cand_stride + nt * W_SLOTS - 1) / (nt * W_SLOTS), nbh); };
   if (!a.keep_all) {
     // pass 0 locates the 1/64-logit bucket of the threshold; two 11-bit refinements at most follow

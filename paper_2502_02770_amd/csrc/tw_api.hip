@@ -1,5 +1,7 @@
 // Host-side pieces shared by the entry points: argument checks, workspace
 // sizes, error strings, and the optional per-kernel event timing.
+#include <atomic>
+#include <mutex>
 #include "topp_common.h"
 
 int tw_decode_chunk(bool dense);
@@ -24,15 +26,15 @@ int tw_check_kv(const twilight_kv_t* kv, TwDims* d) {
 }
 
 int tw_num_cus() {
-  static int cus[TW_MAX_DEVICES] = {0};
+  static std::atomic<int> cus[TW_MAX_DEVICES];    // read-only device property, cached per device
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= TW_MAX_DEVICES) return 256;
-  if (cus[dev] == 0) {
-    int n = 0;
+  int n = cus[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
     if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-    cus[dev] = n;
+    cus[dev].store(n, std::memory_order_relaxed);
   }
-  return cus[dev];
+  return n;
 }
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -103,11 +105,15 @@ extern "C" const char* twilight_kernel_name(int id) {
 }
 
 // ---------------------------------------------------------------- profiling
+// The record list is the library's only process-global mutable state.  g_lock serialises every access;
+// it is held from tw_prof_before to tw_prof_after of a timed launch (an open record), so launches of other
+// threads wait for that one launch while timing is on.  With timing off no lock is taken.
 namespace {
 struct ProfRec { int id; hipEvent_t e0, e1; };
+std::mutex g_lock;
+std::atomic<int> g_on{0};   // == g_mode != 0, readable without the lock
 int g_mode = 0;
 int g_n = 0;
-bool g_open = false;
 ProfRec g_rec[TW_PROF_MAX_RECORDS];
 int g_created = 0;   // events exist for records [0, g_created)
 int g_only = -1;     // mode 2: the one kernel id that is timed ...
@@ -116,6 +122,7 @@ long long g_seen = 0;
 }  // namespace
 
 extern "C" int twilight_prof_select(int kernel_id, int every) {
+  std::lock_guard<std::mutex> lk(g_lock);
   g_only = kernel_id;
   g_every = every > 0 ? every : 1;
   g_seen = 0;
@@ -123,28 +130,35 @@ extern "C" int twilight_prof_select(int kernel_id, int every) {
 }
 
 extern "C" int twilight_prof_enable(int mode) {
+  std::lock_guard<std::mutex> lk(g_lock);
   g_mode = mode < 0 || mode > 2 ? 1 : mode;
+  g_on.store(g_mode != 0, std::memory_order_release);
   g_n = 0;
-  g_open = false;
   return TW_OK;
 }
 
+// the calling thread's open record (the lock is held while it is open)
+static thread_local bool t_open = false;
+
 void tw_prof_before(int kernel_id, hipStream_t s) {
-  g_open = false;
-  if (!g_mode || g_n >= TW_PROF_MAX_RECORDS) return;
-  if (g_mode == 2 && (kernel_id != g_only || (g_seen++ % g_every) != 0)) return;
-  if (g_n >= g_created) {
-    if (hipEventCreate(&g_rec[g_n].e0) != hipSuccess) return;
-    if (hipEventCreate(&g_rec[g_n].e1) != hipSuccess) return;
-    g_created = g_n + 1;
-  }
-  g_rec[g_n].id = kernel_id;
-  g_open = true;
   (void)s;
+  t_open = false;
+  if (!g_on.load(std::memory_order_acquire)) return;
+  g_lock.lock();
+  bool take = g_mode != 0 && g_n < TW_PROF_MAX_RECORDS;
+  if (take && g_mode == 2 && (kernel_id != g_only || (g_seen++ % g_every) != 0)) take = false;
+  if (take && g_n >= g_created) {
+    if (hipEventCreate(&g_rec[g_n].e0) != hipSuccess) take = false;
+    else if (hipEventCreate(&g_rec[g_n].e1) != hipSuccess) { (void)hipEventDestroy(g_rec[g_n].e0); take = false; }
+    else g_created = g_n + 1;
+  }
+  if (!take) { g_lock.unlock(); return; }
+  g_rec[g_n].id = kernel_id;
+  t_open = true;                                  // g_lock stays held until tw_prof_after
 }
 
 bool tw_prof_events(hipEvent_t* start, hipEvent_t* stop) {
-  if (!g_open) return false;
+  if (!t_open) return false;
   *start = g_rec[g_n].e0;
   *stop = g_rec[g_n].e1;
   return true;
@@ -152,14 +166,16 @@ bool tw_prof_events(hipEvent_t* start, hipEvent_t* stop) {
 
 int tw_prof_after(hipStream_t s) {
   (void)s;
-  if (g_open) {
+  if (t_open) {
     ++g_n;
-    g_open = false;
+    t_open = false;
+    g_lock.unlock();
   }
   return hipGetLastError() == hipSuccess ? TW_OK : TW_ELAUNCH;
 }
 
 extern "C" int twilight_prof_collect(int32_t* kernel_ids, float* ms, int32_t cap) {
+  std::lock_guard<std::mutex> lk(g_lock);
   int w = 0;
   for (int i = 0; i < g_n; ++i) {
     if (hipEventSynchronize(g_rec[i].e1) != hipSuccess) break;

@@ -4,6 +4,7 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 #include "twilight.h"
+#include "twilight_prof.h"
 
 #define TW_HEAD_DIM 128
 #define TW_PAGE 16

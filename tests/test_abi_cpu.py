@@ -19,7 +19,8 @@ def T():
 
 
 def test_exports_every_declared_symbol(T):
-    hdr = open(os.path.join(ROOT, "include", "twilight.h")).read()
+    hdr = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include")))
+                  if f.endswith(".h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(twilight_[a-z0-9_]+)\s*\(", hdr))
     assert {"twilight_kquant_append", "twilight_select_pages", "twilight_topp_prune",
@@ -117,3 +118,10 @@ def test_bench_reports_the_named_metric():
     src = open(os.path.join(ROOT, "bench.py"), encoding="utf-8").read()
     metric = re.search(r'"metric": "([^"]+)"', src).group(1).encode().decode("unicode_escape")
     assert metric == json.load(open(os.path.join(ROOT, "BASELINE.json"), encoding="utf-8"))["metric"]
+
+
+def test_shipped_library_reads_no_environment(T):
+    """Tuning switches exist only in -DTW_TUNING builds: the library as built by build() does not import getenv."""
+    import subprocess
+    syms = subprocess.run(["nm", "-D", "--undefined-only", T.binding.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    assert "getenv" not in syms

@@ -706,7 +706,8 @@ def test_full_size_bench_config_sampled():
     cache = build_cache(w)
     st, q = run_pipeline(w, cache, with_kept=True)
     assert int(st.status.item()) == 0
-    check_sampled_groups(w, cache, st, q, ((0, 0), (3, 5), (7, 7)), pages_to_check=(0, 1000, 2047))
+    every = [(b, g) for b in range(w.batch) for g in range(w.num_kv_heads)]       # all 64 groups: a few seconds of oracle
+    check_sampled_groups(w, cache, st, q, every, pages_to_check=(0, 1000, 2047))
 
 
 def test_full_size_smallest_config_every_group():
@@ -753,8 +754,9 @@ def test_full_size_ragged_batch_sampled():
     st, q = run_pipeline(w, cache, with_kept=True)
     assert int(st.status.item()) == 0
     lens = w.seq_lens.tolist()
-    longest, shortest = int(np.argmax(lens)), int(np.argmin(lens))
-    check_sampled_groups(w, cache, st, q, ((longest, 2), (shortest, 7), (len(lens) // 2, 0)), pages_to_check=(0, 77))
+    order = np.argsort(lens)                       # 16 sequences spread over the length range, shortest and longest included
+    picks = [int(order[round(i * (len(lens) - 1) / 15)]) for i in range(16)]
+    check_sampled_groups(w, cache, st, q, [(b, (3 * i) % w.num_kv_heads) for i, b in enumerate(picks)], pages_to_check=(0, 77))
     del st, cache
     torch.cuda.empty_cache()
 
@@ -1197,7 +1199,7 @@ def test_random_small_workloads_other_entry_points():
             cache = build_cache(w)
             st, q = run_pipeline(w, cache)
             assert int(st.status.item()) == 0
-            check_sets_and_output(w, cache, st, exact_floor=0.0)
+            check_sets_and_output(w, cache, st, exact_floor=0.95)
         elif i % 3 == 1:
             cache = build_cache(w, bits=bits)
             dev = cache.device
@@ -1364,6 +1366,34 @@ def test_page_ties_go_to_the_lower_page_id(n):
             assert st.sel_pages[0, h, :cnt].cpu().numpy().tolist() == want.tolist(), h
 
 
+@pytest.mark.parametrize("n", [3000, 40000], ids=["lds_256", "lds_1024"])
+@pytest.mark.parametrize("qs,ks", [(1e-19, 1e-19), (1.0, 2.0 ** -124), (0.125, 2.0 ** -131)],
+                         ids=["span_1e-37", "span_1e-36", "subnormal_bounds"])
+def test_page_bounds_that_differ_by_subnormal_amounts(n, qs, ks):
+    """Queries and keys so small that a head's page bounds lie within 1e-37 of each other, or are subnormal: a
+    bucket width computed as 2048 / (largest - smallest bound) overflows there.  The selected sets must still be
+    the oracle's (the selection then buckets on the bounds' bit patterns)."""
+    T = _T()
+    w = synth.make_workload("tinyb", [n], num_q_heads=4, num_kv_heads=2, budget=n // 4, p=0.9, need_v=False, seed=65)
+    w.q[:] = (w.q.float() * qs).to(torch.bfloat16)
+    w.k[:] = (w.k.float() * ks).to(torch.bfloat16)
+    cache = build_cache(w)
+    dev = cache.device
+    max_sel = -(-int(w.budget[0]) // 16)
+    st = T.DecodeStep(cache, max_sel=max_sel)
+    st.select(w.q.to(dev), w.budget.to(dev))
+    torch.cuda.synchronize()
+    for g in range(2):
+        mn, mx = O.page_minmax(synth.bits(w.seq_k(0)[:, g]))
+        for h in range(2 * g, 2 * g + 2):
+            U = O.page_upper_bounds(synth.bits(w.q[0, h]), mn, mx)
+            assert len(np.unique(U)) > 100 and float(np.abs(U).max()) < 1e-30
+            want = O.select_pages(U, int(w.budget[0]), n)
+            cnt = int(st.sel_count[0, h])
+            assert cnt == len(want)
+            assert st.sel_pages[0, h, :cnt].cpu().numpy().tolist() == want.tolist(), h
+
+
 @pytest.mark.parametrize("n,budget,full", [(4096, 4096, False), (8192, 8192, False), (30000, None, True)],
                          ids=["4_per_thread", "8_per_thread", "long_rows"])
 @pytest.mark.parametrize("p", [0.3, 0.9])
@@ -1425,3 +1455,147 @@ def test_random_key_magnitudes_and_degenerate_groups():
         cache = build_cache(w, bits=bits)
         check_cache(w, cache, bits)
         pipeline_against_oracle(w, bits, cache)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Canaries: nothing outside what an entry point is documented to write may change.
+
+_GUARD = 4096
+
+
+class _Guarded:
+    """Device buffers with a 4 KiB canary in front of and behind each one."""
+
+    def __init__(self, dev):
+        self.dev, self.raw = dev, []
+
+    def buf(self, shape, dtype, fill=None):
+        n = int(np.prod(shape)) * torch.empty(0, dtype=dtype).element_size()
+        pad = (-n) % 256
+        raw = torch.full((n + pad + 2 * _GUARD,), 0xA5, dtype=torch.uint8, device=self.dev)
+        self.raw.append((raw, n))
+        t = raw[_GUARD:_GUARD + n].view(dtype).reshape(shape)
+        if fill is not None:
+            t.fill_(fill)
+        return t
+
+    def check(self, what):
+        torch.cuda.synchronize()
+        for raw, n in self.raw:
+            assert bool((raw[:_GUARD] == 0xA5).all()) and bool((raw[_GUARD + n:] == 0xA5).all()), "canary overwritten: " + what
+
+
+def _unused_pool_pages(w):
+    used = set(int(x) for x in w.page_table.reshape(-1).tolist() if x >= 0)
+    return torch.tensor([pp for pp in range(w.num_pool_pages) if pp not in used], dtype=torch.long)
+
+
+@pytest.mark.parametrize("kind", ["page_lists", "all_tokens", "many_pages"])
+def test_canaries_pool_pages_workspace_tails_and_list_tails(kind):
+    """Every entry point on buffers with canaries: pool pages that no page table names, the bytes in front of and
+    behind every output, list and workspace (sized exactly by twilight_workspace_bytes), and list entries past
+    their count must come out unchanged."""
+    T = _T()
+    lens = {"page_lists": [1500, 333, 2049], "all_tokens": [9000, 700], "many_pages": [140000]}[kind]
+    Hq, Hkv = (8, 2) if kind != "many_pages" else (2, 1)
+    w = synth.make_workload("canary_" + kind, lens, num_q_heads=Hq, num_kv_heads=Hkv, budget=[max(64, n // 6) for n in lens],
+                            p=0.9, heavy_frac=0.01, alpha_range=(0.0, 3.0), shuffle_pool=True, extra_pool_pages=5,
+                            full_selector=(kind == "all_tokens"), seed=77)
+    dev = "cuda:0"
+    cache = T.PagedKV(Hq, Hkv, w.page_table, w.seq_lens, w.num_pool_pages, dev)
+    spare = _unused_pool_pages(w).to(dev)
+    assert spare.numel() == 5
+    pools = {"k": cache.k_pool, "v": cache.v_pool, "kq": cache.kq_pool, "meta": cache.kq_meta, "mm": cache.page_minmax}
+    marks = {}
+    for name, pool in pools.items():                   # mark the spare pages of every pool
+        raw = pool.view(torch.uint8).reshape(w.num_pool_pages, -1)
+        raw[spare] = 0x5A
+        marks[name] = raw[spare].clone()
+    G_ = _Guarded(dev)
+    b_, total = w.batch, int(w.seq_lens.sum())
+    i32 = torch.int32
+    # prefill all but the last token of every sequence, then the last one through the fused append + select
+    k, v = w.k.to(dev), w.v.to(dev)
+    start = torch.zeros(b_, dtype=i32, device=dev)
+    offs = torch.tensor(w.seq_offsets[:-1], dtype=i32, device=dev)
+    cache.append(k, v, start, cache.seq_lens - 1, offs, int(w.seq_lens.max()) - 1)
+    last = torch.tensor([w.seq_offsets[i + 1] - 1 for i in range(b_)], dtype=torch.long, device=dev)
+    k_last, v_last = k[last].contiguous(), v[last].contiguous()
+    pos = (cache.seq_lens - 1).contiguous()
+    q, budget = w.q.to(dev), w.budget.to(dev)
+    full = w.full_selector
+    max_sel = 0 if full else min(int(max(-(-int(x) // 16) for x in w.budget)), cache.max_pages)
+    cand = (cache.max_pages if full else max_sel) * 16
+    sel_pages = sel_count = None
+    if not full:
+        sel_pages = G_.buf((b_, Hq, max_sel), i32, -7)
+        sel_count = G_.buf((b_, Hq), i32, -7)
+        ws_sel = G_.buf((T.twilight_workspace_bytes(T.TW_WS_SELECT, cache.kv, max_sel),), torch.uint8)
+        T.twilight_append_select(cache.kv, k_last, v_last, pos, q, budget, sel_pages, sel_count, max_sel, ws_sel)
+        G_.check("append_select")
+        sp2, sc2 = G_.buf((b_, Hq, max_sel), i32, -7), G_.buf((b_, Hq), i32, -7)
+        T.twilight_select_pages(cache.kv, q, budget, sp2, sc2, max_sel, ws_sel)
+        G_.check("select_pages")
+        assert torch.equal(sp2, sel_pages) and torch.equal(sc2, sel_count)
+        if T.twilight_workspace_bytes(T.TW_WS_SELECT, cache.kv, max_sel) <= T.binding.TW_STATIC_SELECT_WS_BYTES:
+            sp3, sc3 = G_.buf((b_, Hq, max_sel), i32, -7), G_.buf((b_, Hq), i32, -7)
+            T.twilight_select_pages_static(cache.kv, q, budget, sp3, sc3, max_sel)
+            G_.check("select_pages_static")
+            assert torch.equal(sp3, sel_pages)
+        for bb in range(b_):                           # list entries past the count keep their fill
+            for h in range(Hq):
+                assert bool((sel_pages[bb, h, int(sel_count[bb, h]):] == -7).all())
+        scores = G_.buf((b_, Hq, cand), torch.float32, 7.0)
+        dots = G_.buf((b_, Hq, cand, 4), i32, -7)
+        T.twilight_int4_score(cache.kv, q, sel_pages, sel_count, max_sel, scores, dots)
+        G_.check("int4_score")
+    else:
+        one = torch.ones(b_, dtype=i32, device=dev)
+        rows = torch.arange(b_, dtype=i32, device=dev)
+        cache.append(k_last, v_last, pos, one, rows, 1)
+        scores = G_.buf((b_, Hq, cand), torch.float32, 7.0)
+        T.twilight_int4_score(cache.kv, q, None, None, 0, scores, None)
+        G_.check("int4_score (all tokens)")
+    check_cache(w, cache)                              # and the cache itself is the oracle's
+    union_stride = min((Hq // Hkv) * cand, cache.max_pages * 16)
+    kept_count = G_.buf((b_, Hq), i32, -7)
+    kept_idx = G_.buf((b_, Hq, cand), i32, -7)
+    union_count = G_.buf((b_ * Hkv,), i32, -7)
+    union_idx = G_.buf((b_ * Hkv, union_stride), i32, -7)
+    status = G_.buf((1,), i32, 0)
+    ws_prune = G_.buf((T.twilight_workspace_bytes(T.TW_WS_PRUNE, cache.kv, max_sel),), torch.uint8)
+    T.twilight_topp_prune(cache.kv, q, sel_pages, sel_count, max_sel, w.p, kept_count, kept_idx, cand, union_count,
+                          union_idx, union_stride, status, ws_prune)
+    G_.check("topp_prune")
+    assert int(status.item()) == 0
+    for bb in range(b_):
+        for h in range(Hq):
+            assert bool((kept_idx[bb, h, int(kept_count[bb, h]):] == -7).all())
+    for gi in range(b_ * Hkv):
+        assert bool((union_idx[gi, int(union_count[gi]):] == -7).all())
+    out = G_.buf((b_, Hq, 128), torch.bfloat16)
+    lse = G_.buf((b_, Hq), torch.float32)
+    ws_dec = G_.buf((T.twilight_workspace_bytes(T.TW_WS_DECODE, cache.kv, 0, union_stride),), torch.uint8)
+    T.twilight_sparse_decode(cache.kv, q, union_count, union_idx, union_stride, out, lse, ws_dec)
+    G_.check("sparse_decode")
+    ws_ph = G_.buf((T.twilight_workspace_bytes(T.TW_WS_DECODE_PER_HEAD, cache.kv, 0, cand),), torch.uint8)
+    T.twilight_sparse_decode_per_head(cache.kv, q, kept_count, kept_idx, cand, out, lse, ws_ph)
+    G_.check("sparse_decode_per_head")
+    ws_dense = G_.buf((T.twilight_workspace_bytes(T.TW_WS_DECODE, cache.kv, 0, 0),), torch.uint8)
+    T.twilight_sparse_decode(cache.kv, q, None, None, 0, out, lse, ws_dense)
+    G_.check("sparse_decode (dense)")
+    if cand <= 8192 and cache.max_pages * 16 <= 196608 and not full:   # the same candidates handed over as token lists
+        tl = (sel_pages.long().clamp(min=0).unsqueeze(-1) * 16 + torch.arange(16, device=dev)).reshape(b_, Hq, cand).int().contiguous()
+        tc = (sel_count * 16).int().contiguous()
+        sc_t = G_.buf((b_, Hq, cand), torch.float32, 7.0)
+        T.twilight_int4_score_tokens(cache.kv, q, tl, tc, cand, sc_t, None)
+        G_.check("int4_score_tokens")
+        ws_t = G_.buf((T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, cache.kv, cand),), torch.uint8)
+        kc2, ki2 = G_.buf((b_, Hq), i32, -7), G_.buf((b_, Hq, cand), i32, -7)
+        uc2, ui2 = G_.buf((b_ * Hkv,), i32, -7), G_.buf((b_ * Hkv, union_stride), i32, -7)
+        T.twilight_topp_prune_tokens(cache.kv, q, tl, tc, cand, w.p, kc2, ki2, cand, uc2, ui2, union_stride, status, ws_t)
+        G_.check("topp_prune_tokens")
+        assert torch.equal(kc2, kept_count) and torch.equal(uc2, union_count) and torch.equal(ui2, union_idx)
+    for name, pool in pools.items():                   # spare pool pages untouched by all of the above
+        raw = pool.view(torch.uint8).reshape(w.num_pool_pages, -1)
+        assert torch.equal(raw[spare], marks[name]), "spare pool page written: " + name
