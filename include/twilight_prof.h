@@ -14,6 +14,8 @@
 extern "C" {
 #endif
 
+struct twilight_kv;   /* twilight.h */
+
 /*
  * A HIP event pair is attached to the
  * kernel's own dispatch (hipExtLaunchKernelGGL: start and stop timestamps of
@@ -41,6 +43,18 @@ int twilight_prof_enable(int mode);
 int twilight_prof_select(int kernel_id, int every);
 int twilight_prof_collect(int32_t* kernel_ids /*host*/, float* ms /*host*/, int32_t cap);
 const char* twilight_kernel_name(int kernel_id);
+
+/*
+ * Launch shape of the attention kernel for a cache shape (host only; only
+ * kv's shape fields are read): the persistent grid before it is cut to the
+ * number of work items, the shortest chunk of list entries per work item
+ * (dense != 0: the all-tokens sweep), and the number of items per workgroup
+ * beyond which the kernel doubles the chunk (up to 4 x chunk0, at most 512).
+ * which = TW_WS_DECODE or TW_WS_DECODE_PER_HEAD.  For reports on how evenly
+ * ragged lists spread over the workgroups (Section 4.2, load balancing).
+ */
+int twilight_decode_plan(const struct twilight_kv* kv, int which, int32_t dense, int32_t* grid /*host, out*/,
+                         int32_t* chunk0 /*host, out*/, int32_t* items_per_wg /*host, out*/);
 
 #ifdef __cplusplus
 }

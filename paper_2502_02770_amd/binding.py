@@ -66,6 +66,8 @@ def lib():
     L.twilight_prof_select.argtypes = [ctypes.c_int, ctypes.c_int]
     L.twilight_prof_collect.argtypes = [_vp, _vp, _i32]
     L.twilight_kernel_name.argtypes = [ctypes.c_int]
+    L.twilight_decode_plan.argtypes = [kvp, ctypes.c_int, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+    L.twilight_decode_plan.restype = ctypes.c_int
     L.twilight_kernel_name.restype = ctypes.c_char_p
     for f in ("twilight_kquant_append", "twilight_select_pages", "twilight_select_pages_static", "twilight_append_select", "twilight_int4_score", "twilight_topp_prune",
               "twilight_int4_score_tokens", "twilight_topp_prune_tokens",
@@ -180,6 +182,13 @@ def twilight_sparse_decode_per_head(kv, q, kept_count, kept_idx, kept_stride, ou
     _check(lib().twilight_sparse_decode_per_head(ctypes.byref(kv), _ptr(q), _ptr(kept_count), _ptr(kept_idx),
                                                  int(kept_stride), _ptr(out), _ptr(lse), _ptr(ws),
                                                  ws.numel() * ws.element_size(), _stream()))
+
+
+def twilight_decode_plan(kv, which=TW_WS_DECODE, dense=False):
+    """-> (grid, chunk0, items_per_wg) of the attention kernel's launch for this cache shape."""
+    g, c, i = _i32(), _i32(), _i32()
+    _check(lib().twilight_decode_plan(ctypes.byref(kv), int(which), int(bool(dense)), ctypes.byref(g), ctypes.byref(c), ctypes.byref(i)))
+    return g.value, c.value, i.value
 
 
 def twilight_prof_enable(mode):

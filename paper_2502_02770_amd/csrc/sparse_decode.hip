@@ -499,6 +499,34 @@ static int decode_impl(const twilight_kv_t* kv, const void* q, const int32_t* co
   return tw_prof_after(s);
 }
 
+// Launch shape of the decode kernel for this cache shape (host only): workgroups of the persistent grid (before
+// it is cut to the number of work items), the shortest chunk, and how many items a workgroup may take before
+// the kernel doubles the chunk.  For benchmarks that report the balance of the work list.
+extern "C" int twilight_decode_plan(const twilight_kv_t* kv, int which, int32_t dense, int32_t* grid, int32_t* chunk0,
+                                    int32_t* items_per_wg) {
+  TwDims d;
+  twilight_kv_t tmp;
+  if (!kv || !grid || !chunk0 || !items_per_wg) return TW_EINVAL;
+  tmp = *kv;                                     // the pointers are not needed here: check the shape fields only
+  int dummy = 0;
+  tmp.page_table = &dummy; tmp.seq_lens = &dummy;
+  if (int e = tw_check_kv(&tmp, &d)) return e;
+  if (which != TW_WS_DECODE && which != TW_WS_DECODE_PER_HEAD) return TW_EINVAL;
+  const int LH = which == TW_WS_DECODE_PER_HEAD ? d.Hq : d.Hkv, Gk = which == TW_WS_DECODE_PER_HEAD ? 1 : d.G;
+  const size_t lds = (size_t)(d.batch * LH + 1) * 4;
+  int occ = 1;
+  switch (Gk) {
+    case 1: occ = decode_blocks_per_cu<1>(lds); break;
+    case 2: occ = decode_blocks_per_cu<2>(lds); break;
+    case 4: occ = decode_blocks_per_cu<4>(lds); break;
+    default: occ = decode_blocks_per_cu<8>(lds); break;
+  }
+  *grid = tw_num_cus() * occ;
+  *chunk0 = tw_decode_chunk(dense != 0);
+  *items_per_wg = (int32_t)DEC_ITEMS_PER_WG;
+  return TW_OK;
+}
+
 extern "C" int twilight_sparse_decode(const twilight_kv_t* kv, const void* q, const int32_t* union_count,
                                       const int32_t* union_idx, int32_t union_stride, void* out, float* lse,
                                       void* ws, size_t ws_bytes, void* stream) {

@@ -758,6 +758,22 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
   }
   __syncthreads();
   uint32_t* bm = a.bitmaps + (long long)bh * a.words_stride;
+#ifdef TW_FORMAL_ORDER
+  // Measurement build: the hand-off written with the memory model's own pair - plain stores, a workgroup
+  // barrier, one agent-scope acq_rel read-modify-write by thread 0 (release: everything the block wrote is
+  // made visible to the agent first; acquire: nothing the reader loads afterwards may be stale).
+  for (int i = tid; i < nwords; i += NT) bm[i] = bitmap[i];
+  if (tid == 0) {
+    uint32_t kc = sh_kept;
+    if (a.kept_idx && kc > (uint32_t)a.kept_stride) { atomicOr(a.status, TW_STATUS_KEPT_TRUNCATED); kc = a.kept_stride; }
+    a.kept_count[bh] = (int32_t)kc;
+  }
+  const int gi = b * a.Hkv + h / G;
+  __syncthreads();
+  if (tid == 0)
+    sh_last = __hip_atomic_fetch_add(a.arrive + gi * TW_CTR, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(G - 1) ? 1u : 0u;
+  __syncthreads();
+#else
   // device-scope (write-through) stores: the group's last head reads these words from another CU
   for (int i = tid; i < nwords; i += NT) __hip_atomic_store(bm + i, bitmap[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (tid == 0) {
@@ -769,17 +785,18 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
 
   // ---- the last head of the KV head's group to get here turns the G bitmaps into the sorted union
   const int gi = b * a.Hkv + h / G;
-  // Ordering without cache-wide fences (a device-scope fence writes back / invalidates the whole
-  // L2 and costs several microseconds here): the bitmap words are stored and loaded with
-  // device-scope atomics, which go through to the point where all CUs agree; every thread waits
-  // for the acknowledgement of its own stores (a workgroup barrier alone does not), the barrier
-  // then collects the block, and only after it does thread 0 count the arrival.  The last head
-  // of the group therefore finds every earlier head's words in place.
+  // Ordering without cache-wide fences: the bitmap words are stored and loaded with agent-scope atomics
+  // (write-through stores, loads that bypass the caches that are not shared by all compute units), every
+  // thread waits for the acknowledgement of its own stores (a workgroup barrier alone does not), the barrier
+  // then collects the block, and only after it does thread 0 count the arrival.  The last head of the group
+  // therefore finds every earlier head's words in place.  (The memory model's own form of this hand-off - plain
+  // stores and an acq_rel counter, -DTW_FORMAL_ORDER - writes back and invalidates the whole L2 at every arrival.)
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   if (tid == 0)
     sh_last = __hip_atomic_fetch_add(a.arrive + gi * TW_CTR, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)(G - 1) ? 1u : 0u;
   __syncthreads();
+#endif
   if (!sh_last) return;
   TW_STAMP(14);
   if (tid == 0) __hip_atomic_store(a.arrive + gi * TW_CTR, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
@@ -796,7 +813,11 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
         const int wi = i < nwords ? i : 0;
 #pragma unroll
         for (int hh = 0; hh < G; ++hh)
+#ifdef TW_FORMAL_ORDER
+          x[k] |= bmg[(long long)hh * a.words_stride + wi];
+#else
           x[k] |= __hip_atomic_load(bmg + (long long)hh * a.words_stride + wi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#endif
       }
     }
 #pragma unroll
