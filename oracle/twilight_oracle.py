@@ -22,6 +22,9 @@ works in float64.
 
 Parity pins: every function here is pinned by tests/test_oracle_*.py against
 closed forms, brute force, library routines or invariants; none is unpinned.
+(ds_scores / ds_select, the channel-sparse token selector, are pinned the
+same way, but the paper gives no definition or value for that selector:
+their reading is ours, "parity unpinned by paper values".)
 The paper prints no worked numeric example for this path that can be
 reproduced without model weights (its p=0.8 -> 97 tokens example is a real
 attention head), so no pin uses a value printed by the paper except the cost
@@ -202,6 +205,36 @@ def int4_scores(qi, sq, u, scale, zero):
 
 
 # --------------------------------------------------------------------------
+# Another token selector in front of the pruner (Section 4.1: the base
+# algorithm is a black box that hands over a token subset; Sections 4.3 and 5
+# name a Double-Sparsity-style one, which ranks tokens by an estimate taken
+# from a few channels of a 4-bit copy of K).  The paper defines it only by
+# citation and prints no values for it: PARITY UNPINNED BY PAPER VALUES.
+# Reading taken: a fixed set of channels per KV head (found offline; an input
+# here), the estimate is the INT4 score above with the query's other channels
+# set to zero, and the B tokens with the largest estimate are handed over.
+# --------------------------------------------------------------------------
+def ds_scores(qi, sq, u, scale, zero, channels):
+    """Channel-sparse estimate: int4_scores with qi kept only on `channels`
+    (dims 0..127 of the KV head's channel set); sq is the full query's."""
+    keep = np.zeros(HEAD_DIM, bool)
+    keep[np.asarray(channels, dtype=np.int64)] = True
+    return int4_scores(np.where(keep, qi, 0).astype(np.int8), sq, u, scale, zero)
+
+
+def ds_select(s_ds, budget_tokens, n):
+    """Positions (ascending) of the min(B, n) tokens with the largest
+    estimate; among equal estimates the lower position wins."""
+    s_ds = np.asarray(s_ds, dtype=np.float32)
+    assert s_ds.shape[0] == n
+    K = min(int(budget_tokens), n)
+    if K <= 0:
+        return np.zeros(0, np.int32)
+    order = np.lexsort((np.arange(n), -s_ds.astype(np.float64)))  # by -estimate, then position
+    return np.sort(order[:K]).astype(np.int32)
+
+
+# --------------------------------------------------------------------------
 # Stage 2b/c: softmax over the candidates and the top-p set
 # (Definition 3.3; Algorithm 1 returns the threshold set {W >= l}).
 # --------------------------------------------------------------------------
@@ -236,15 +269,12 @@ def topp_set(s, p):
 
 
 def topp_binary_search(W, p, eps):
-    """Algorithm 1 taken step by step on one weight vector: bisect a weight
-    threshold m in [0, max W]; l stays feasible (sum of W >= l is >= p), r
-    infeasible; stop once every weight still undecided (l < W <= r) lies
-    within eps of the others; return the mask W >= l.
-
-    Reading of the printed listing: its exit test is taken as "<= eps" (as
-    printed, ">= eps", it holds before the first halving), and the midpoint
-    is recomputed in every iteration.
-    """
+    """The threshold search of Algorithm 1 on one weight vector: bisect a
+    weight threshold between 0 and the largest weight, keeping the lower end
+    feasible (the weights at or above it sum to at least p) and the upper end
+    infeasible, until all weights still undecided (above the lower end, at or
+    below the upper one) lie within eps of each other; the result is the set
+    of weights at or above the lower end.  With eps = 0 this is topp_set."""
     W = np.asarray(W, dtype=np.float64)
     l, r = 0.0, float(W.max())
     for _ in range(4096):

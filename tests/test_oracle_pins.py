@@ -577,3 +577,55 @@ def test_set_check_accepts_a_mass_on_the_threshold_only_within_1e6():
     W2 = np.array([0.5 + 1e-4, 0.3, 0.15, 0.05 - 1e-4])    # mass clearly over p: the extra token is an error
     with pytest.raises(AssertionError):
         check_topp(np.array([0, 1]), np.log(W2), cand, 0.5)
+
+
+# ------------------------------------------------------------------ channel-sparse token selector
+def test_ds_scores_full_channel_set_is_the_int4_score_and_masking_hits_the_right_dims(rng):
+    """All 128 channels: the estimate IS the INT4 score (bit for bit).  A subset: it equals, in float64, the dot
+    product of the quantised query with the dequantised keys over exactly those channels."""
+    k = _bf16_bits(rng.standard_normal((300, 128)))
+    u, sc, ze = O.quantize_k(k)
+    qi, sq = O.quantize_q(_bf16_bits(rng.standard_normal(128)))
+    assert np.array_equal(O.ds_scores(qi, sq, u, sc, ze, np.arange(128)), O.int4_scores(qi, sq, u, sc, ze))
+    for r in (1, 8, 16, 40):
+        ch = np.sort(rng.choice(128, size=r, replace=False))
+        got = O.ds_scores(qi, sq, u, sc, ze, ch).astype(np.float64)
+        xhat = O.dequantize_k(u, sc, ze).astype(np.float64)
+        want = (xhat[:, ch] * qi[ch].astype(np.float64)).sum(1) * float(sq) / math.sqrt(128.0)
+        assert np.allclose(got, want, rtol=1e-5, atol=1e-6 * np.abs(want).max())
+        other = np.setdiff1d(np.arange(128), ch)                 # the two halves add up to the full score
+        rest = O.ds_scores(qi, sq, u, sc, ze, other).astype(np.float64)
+        assert np.allclose(got + rest, O.int4_scores(qi, sq, u, sc, ze), rtol=1e-5, atol=1e-5)
+
+
+def test_ds_scores_hand_example():
+    """One channel (dim 5), codes 0..15 over 16 tokens, scale 0.5 and zero -1 in group 0: with q = 127 on that
+    channel (sq = 1) the estimate of token t is (0.5 * 127 t - 127) / sqrt(128)."""
+    u = np.zeros((16, 128), np.uint8)
+    u[:, 5] = np.arange(16)
+    sc = np.zeros((16, 4), np.float16); sc[:, 0] = 0.5
+    ze = np.zeros((16, 4), np.float16); ze[:, 0] = -1.0
+    qi = np.zeros(128, np.int8); qi[5] = 127; qi[70] = -50
+    got = O.ds_scores(qi, np.float32(1.0), u, sc, ze, [5])
+    want = (0.5 * 127.0 * np.arange(16) - 127.0) / math.sqrt(128.0)
+    assert np.allclose(got, want, rtol=1e-6)
+    assert np.all(O.ds_scores(qi, np.float32(1.0), u, sc, ze, []) == 0)      # no channels: every estimate is zero
+
+
+def test_ds_select_brute_force_ties_and_budgets(rng):
+    for n, B in ((1, 1), (7, 3), (50, 50), (50, 80), (200, 37), (64, 0)):
+        s = rng.integers(0, 6, n).astype(np.float32)             # few distinct values: many ties
+        got = O.ds_select(s, B, n)
+        order = sorted(range(n), key=lambda i: (-float(s[i]), i))        # pure-Python sort, ties to the lower position
+        want = sorted(order[:min(B, n)])
+        assert got.tolist() == want
+    s = np.zeros(40, np.float32)
+    assert O.ds_select(s, 12, 40).tolist() == list(range(12))            # all equal: the first B positions
+    # a heavy token is found from the channels its key was pushed along
+    k = rng.standard_normal((500, 128)).astype(np.float32)
+    q = rng.standard_normal(128).astype(np.float32)
+    ch = np.argsort(-np.abs(q))[:16]
+    k[123, ch] += 8.0 * np.sign(q[ch])
+    u, sc, ze = O.quantize_k(_bf16_bits(k))
+    qi, sq = O.quantize_q(_bf16_bits(q))
+    assert 123 in O.ds_select(O.ds_scores(qi, sq, u, sc, ze, ch), 5, 500).tolist()
