@@ -385,6 +385,47 @@ def attention_variants(T, w, cache, st, q):
     return res
 
 
+def channel_sparse_selector(T, w, cache, st, q, r=16):
+    """The other token selector in front of the same pruner (Section 4.1): a channel-sparse one (r of 128 channels
+    of the INT4 copy, twilight_ds_select_tokens) with the page selector's budget, then the pruner on its token lists
+    and attention; per-kernel times with HIP events and the attention mass the result captures."""
+    import torch
+    from workloads import synth
+    dev = q.device
+    max_cand = st.max_sel * 16
+    if max_cand > 8192 or cache.max_pages * 16 > 196608:
+        return None
+    _, masks = synth.calibrated_channels(w, r)
+    masks = masks.to(dev)
+    budget = w.budget.to(dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    cand = torch.zeros(w.batch, w.num_q_heads, max_cand, **i32)
+    cnt = torch.zeros(w.batch, w.num_q_heads, **i32)
+    ws_ds = torch.empty(T.twilight_workspace_bytes(T.TW_WS_DS_SELECT, cache.kv, max_cand), dtype=torch.uint8, device=dev)
+    ws_t = torch.empty(T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, cache.kv, max_cand), dtype=torch.uint8, device=dev)
+    sv = T.DecodeStep(cache, max_sel=st.max_sel, with_kept_idx=False, with_lse=True)
+
+    def step():
+        T.twilight_ds_select_tokens(cache.kv, q, masks, budget, cand, cnt, max_cand, ws_ds)
+        T.twilight_topp_prune_tokens(cache.kv, q, cand, cnt, max_cand, w.p, sv.kept_count, None, 0, sv.union_count,
+                                     sv.union_idx, sv.union_stride, sv.status, ws_t)
+        sv.attend(q)
+    for _ in range(3):
+        step()
+    kern = kernel_pass(T, step, 20)
+    us = {k: sum(v) / 20 * 1e3 for k, v in kern.items()}
+    lse_d = torch.zeros(w.batch, w.num_q_heads, dtype=torch.float32, device=dev)
+    sv.dense(q, out=torch.empty_like(sv.out), lse=lse_d)
+    step()
+    torch.cuda.synchronize()
+    m = torch.exp(sv.lse - lse_d).cpu()
+    tokens = int(w.seq_lens.sum())
+    return {"channels": r, "per_kernel_us": us, "step_us_sum_of_kernels": sum(us.values()),
+            "int4_bytes_read": tokens * w.num_kv_heads * 80, "kept_per_head": float(sv.kept_count.float().mean()),
+            "union_per_group": float(sv.union_count.float().mean()),
+            "attention_mass_captured": {"mean": float(m.mean()), "min": float(m.min())}}
+
+
 def mass_within_candidates(T, w, cache, st, q):
     """Per query head, the softmax mass of its kept set within its candidate set: as the pruner estimates it (INT4
     scores; top-p keeps this at or above p) and exactly (bf16 logits: log-sum-exp over the kept list minus that over
@@ -562,6 +603,7 @@ def main():
     variants = None
     if w.v.numel() and not st.full and not a.step_only:
         variants = attention_variants(T, w, cache, st, q)
+        variants["channel_sparse_selector"] = channel_sparse_selector(T, w, cache, st, q)
 
     ach = nbytes[dom] / (dom_avg * dom_calls * 1e-3) / 1e9
     default_cfg = (a.config == 1 and a.scale == 1.0 and a.batch is None and a.seed == 0 and a.bits == 4 and a.p is None and a.kv_heads is None

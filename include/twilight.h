@@ -266,6 +266,32 @@ int twilight_topp_prune_tokens(const twilight_kv_t* kv, const void* q, const int
                                uint32_t* status, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * A second token selector for the front of the pruner, of the channel-sparse
+ * kind (Section 4.1: the base algorithm is a black box; Sections 4.3 and 5
+ * name a Double-Sparsity-style selector, which ranks tokens by an estimate
+ * taken from a few channels of a 4-bit copy of K - the copy this cache
+ * already holds).  The paper does not define that selector; the form built
+ * here: per KV head a fixed set of channels (found offline by the caller),
+ * per (sequence, query head) the estimate of EVERY token of the sequence,
+ *   s_ds = the s_hat of twilight_int4_score with the int8 query set to 0
+ *          outside the channel set (sq stays that of the whole query),
+ * and the min(budget, length, max_cand) tokens with the largest estimate are
+ * handed over; equal estimates: lower position first.  The lists feed
+ * twilight_topp_prune_tokens (max_cand <= 8192 there).
+ *
+ *   channel_mask   u32 [num_kv_heads][4]: bit (d % 32) of word d / 32 set =
+ *                  channel d of that KV head takes part
+ *   budget_tokens  i32 [batch]
+ *   cand_tokens    i32 [batch][num_q_heads][max_cand]  out, ascending positions
+ *   cand_count     i32 [batch][num_q_heads]            out
+ *   ws             >= twilight_workspace_bytes(TW_WS_DS_SELECT, kv, max_cand, 0)
+ *                  (one fp32 estimate per token and query head)
+ */
+int twilight_ds_select_tokens(const twilight_kv_t* kv, const void* q, const uint32_t* channel_mask,
+                              const int32_t* budget_tokens, int32_t* cand_tokens, int32_t* cand_count,
+                              int32_t max_cand, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Sparse decode attention (stage 3; Definition 3.1 with the weights
  * renormalised over the attended set, Appendix B.2 group-wise varlen).
  * Every query head of KV head g attends over union_idx[b*Hkv+g][0..count):
@@ -307,6 +333,7 @@ int twilight_sparse_decode_per_head(const twilight_kv_t* kv, const void* q, cons
 #define TW_WS_DECODE 2
 #define TW_WS_DECODE_PER_HEAD 3
 #define TW_WS_PRUNE_TOKENS 4
+#define TW_WS_DS_SELECT 5
 /*  max_sel: as passed to the call (0 with sel_pages == NULL; max_cand for
  *  TW_WS_PRUNE_TOKENS);
  *  union_stride: as passed to sparse_decode (0 for dense), kept_stride for

@@ -13,7 +13,7 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("TWILIGHT_LIB") or os.path.join(_PKG, "libtwilight.so")   # override: tuning builds
 
-TW_WS_SELECT, TW_WS_PRUNE, TW_WS_DECODE, TW_WS_DECODE_PER_HEAD, TW_WS_PRUNE_TOKENS = 0, 1, 2, 3, 4
+TW_WS_SELECT, TW_WS_PRUNE, TW_WS_DECODE, TW_WS_DECODE_PER_HEAD, TW_WS_PRUNE_TOKENS, TW_WS_DS_SELECT = 0, 1, 2, 3, 4, 5
 TW_STATUS_UNION_TRUNCATED, TW_STATUS_KEPT_TRUNCATED = 1, 2
 TW_STATIC_SELECT_WS_BYTES = 8 << 20
 KERNEL_NAMES = ["kquant_append", "page_score", "page_select", "int4_score", "topp", "union",
@@ -49,6 +49,7 @@ def lib():
     L.twilight_select_pages.argtypes = [kvp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
     L.twilight_select_pages_static.argtypes = [kvp, _vp, _vp, _vp, _vp, _i32, _vp]
     L.twilight_int4_score.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
+    L.twilight_ds_select_tokens.argtypes = [kvp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
     L.twilight_append_select.argtypes = [kvp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
     L.twilight_topp_prune.argtypes = [kvp, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
     L.twilight_int4_score_tokens.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
@@ -69,7 +70,7 @@ def lib():
     L.twilight_decode_plan.argtypes = [kvp, ctypes.c_int, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
     L.twilight_decode_plan.restype = ctypes.c_int
     L.twilight_kernel_name.restype = ctypes.c_char_p
-    for f in ("twilight_kquant_append", "twilight_select_pages", "twilight_select_pages_static", "twilight_append_select", "twilight_int4_score", "twilight_topp_prune",
+    for f in ("twilight_ds_select_tokens", "twilight_kquant_append", "twilight_select_pages", "twilight_select_pages_static", "twilight_append_select", "twilight_int4_score", "twilight_topp_prune",
               "twilight_int4_score_tokens", "twilight_topp_prune_tokens",
               "twilight_sparse_decode", "twilight_sparse_decode_per_head", "twilight_prof_enable", "twilight_prof_select", "twilight_prof_collect"):
         getattr(L, f).restype = ctypes.c_int
@@ -138,6 +139,12 @@ def twilight_select_pages_static(kv, q, budget_tokens, sel_pages, sel_count, max
     """The selector without a caller workspace and without any allocation (fixed scratch inside the library)."""
     _check(lib().twilight_select_pages_static(ctypes.byref(kv), _ptr(q), _ptr(budget_tokens), _ptr(sel_pages),
                                               _ptr(sel_count), int(max_sel), _stream()))
+
+
+def twilight_ds_select_tokens(kv, q, channel_mask, budget_tokens, cand_tokens, cand_count, max_cand, ws):
+    _check(lib().twilight_ds_select_tokens(ctypes.byref(kv), _ptr(q), _ptr(channel_mask), _ptr(budget_tokens),
+                                           _ptr(cand_tokens), _ptr(cand_count), int(max_cand), _ptr(ws),
+                                           ws.numel() * ws.element_size(), _stream()))
 
 
 def twilight_append_select(kv, k_new, v_new, new_pos, q, budget_tokens, sel_pages, sel_count, max_sel, ws):

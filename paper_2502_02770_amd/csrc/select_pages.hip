@@ -16,6 +16,7 @@
 #include <atomic>
 #include "tw_common.h"
 #include "kquant_common.h"
+#include "topp_common.h"
 
 namespace {
 
@@ -165,18 +166,25 @@ struct SelectArgs {
   int32_t* sel_count;
   int Hq, max_pages, max_sel;
   int p_above, p_upto;        // the LDS kernel takes the heads with p_above < pages <= p_upto
+  int unit;                   // tokens per row entry: 16 = pages (budget and lengths are in tokens), 1 = the rows hold
+                              // one score per token (channel-sparse token selector; max_pages is then the row length)
 };
+
+// entries of a sequence's row and how many of them the budget asks for
+__device__ __forceinline__ void tw_select_sizes(const SelectArgs& a, int n, int B, int* P_out, int* K_out) {
+  int P = n > 0 ? (n + a.unit - 1) / a.unit : 0;
+  if (P > a.max_pages) P = a.max_pages;
+  long long kp = B > 0 ? ((long long)B + a.unit - 1) / a.unit : 0;
+  if (kp > P) kp = P;
+  if (kp > a.max_sel) kp = a.max_sel;
+  *P_out = P;
+  *K_out = (int)kp;
+}
 
 __global__ __launch_bounds__(256) void page_select_kernel(SelectArgs a) {
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
-  const int n = a.seq_lens[b];
-  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
-  if (P > a.max_pages) P = a.max_pages;
-  const int B = a.budget[b];
-  long long kp = B > 0 ? ((long long)B + TW_PAGE - 1) / TW_PAGE : 0;
-  if (kp > P) kp = P;
-  if (kp > a.max_sel) kp = a.max_sel;
-  const int Kp = (int)kp;
+  int P, Kp;
+  tw_select_sizes(a, a.seq_lens[b], a.budget[b], &P, &Kp);
   const float* sc = a.scores + ((long long)(b * a.Hq + h)) * a.max_pages;
   int32_t* out = a.sel_pages + ((long long)(b * a.Hq + h)) * a.max_sel;
   if (tid == 0) a.sel_count[b * a.Hq + h] = Kp;
@@ -254,15 +262,9 @@ template <int NT>
 __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
   constexpr int NW = NT / 64, BPT = SEL_NB / NT;      // waves; histogram buckets per thread
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = a.seq_lens[b];
-  int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
-  if (P > a.max_pages) P = a.max_pages;
+  int P, Kp;
+  tw_select_sizes(a, a.seq_lens[b], a.budget[b], &P, &Kp);
   if (P <= a.p_above || P > a.p_upto) return;     // another launch's head (block-uniform)
-  const int B = a.budget[b];
-  long long kp = B > 0 ? ((long long)B + TW_PAGE - 1) / TW_PAGE : 0;
-  if (kp > P) kp = P;
-  if (kp > a.max_sel) kp = a.max_sel;
-  const int Kp = (int)kp;
   const float* sc = a.scores + ((long long)(b * a.Hq + h)) * a.max_pages;
   int32_t* out = a.sel_pages + ((long long)(b * a.Hq + h)) * a.max_sel;
   if (tid == 0) a.sel_count[b * a.Hq + h] = Kp;
@@ -429,6 +431,32 @@ extern "C" int twilight_debug_stamps_select(unsigned long long* host_out) {
 }
 #endif
 
+// The selection kernels by row length (entries per row = sa.max_pages) and number of heads.
+static int launch_select(SelectArgs sa, const TwDims& d, hipStream_t s) {
+  const int L = sa.max_pages;
+  sa.p_above = -1; sa.p_upto = L;
+  // Many heads and rows of up to 8192 entries (ragged batches): the 1024-thread kernel fits two
+  // workgroups per CU; rows of at most 2048 entries go to a 256-thread launch of their own.
+  if (L > 2048 && L <= SEL_LDS_PAGES && (long long)d.batch * d.Hq > 2ll * tw_num_cus()) {
+    sa.p_upto = 2048;
+    tw_prof_before(TW_K_PAGE_SELECT, s);
+    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+    if (int e = tw_prof_after(s)) return e;
+    sa.p_above = 2048; sa.p_upto = L;
+  }
+  tw_prof_before(TW_K_PAGE_SELECT, s);
+  // rows of 513..2048 entries: with few heads (at most two workgroups per CU) the 1024-thread variant is the
+  // quicker one (6.7 against 8.4 us at 8 x 32 heads x 2048 pages); many heads are better served by small workgroups
+  const bool few_heads = (long long)d.batch * d.Hq <= 2ll * tw_num_cus();
+  if (L <= 512 || (L <= 2048 && !few_heads))
+    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+  else if (L <= SEL_LDS_PAGES)
+    TW_LAUNCH(page_select_lds_kernel<1024>, dim3(d.Hq, d.batch), dim3(1024), 0, s, sa);
+  else
+    TW_LAUNCH(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+  return tw_prof_after(s);
+}
+
 static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
                        int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
                        void* ws, size_t ws_bytes, void* stream,
@@ -465,28 +493,30 @@ static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* bu
   SelectArgs sa;
   sa.scores = (const float*)ws; sa.seq_lens = kv->seq_lens; sa.budget = budget_tokens;
   sa.sel_pages = sel_pages; sa.sel_count = sel_count;
-  sa.Hq = d.Hq; sa.max_pages = d.max_pages; sa.max_sel = max_sel;
-  sa.p_above = -1; sa.p_upto = d.max_pages;
-  // Many heads and rows of up to 8192 pages (ragged batches): the 1024-thread kernel fits two
-  // workgroups per CU; rows of at most 2048 pages go to a 256-thread launch of their own.
-  if (d.max_pages > 2048 && d.max_pages <= SEL_LDS_PAGES && (long long)d.batch * d.Hq > 2ll * tw_num_cus()) {
-    sa.p_upto = 2048;
-    tw_prof_before(TW_K_PAGE_SELECT, s);
-    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
-    if (int e = tw_prof_after(s)) return e;
-    sa.p_above = 2048; sa.p_upto = d.max_pages;
-  }
-  tw_prof_before(TW_K_PAGE_SELECT, s);
-  // rows of 513..2048 pages: with few heads (at most two workgroups per CU) the 1024-thread variant is the
-  // quicker one (6.7 against 8.4 us at 8 x 32 heads x 2048 pages); many heads are better served by small workgroups
-  const bool few_heads = (long long)d.batch * d.Hq <= 2ll * tw_num_cus();
-  if (d.max_pages <= 512 || (d.max_pages <= 2048 && !few_heads))
-    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
-  else if (d.max_pages <= SEL_LDS_PAGES)
-    TW_LAUNCH(page_select_lds_kernel<1024>, dim3(d.Hq, d.batch), dim3(1024), 0, s, sa);
-  else
-    TW_LAUNCH(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
-  return tw_prof_after(s);
+  sa.Hq = d.Hq; sa.max_pages = d.max_pages; sa.max_sel = max_sel; sa.unit = TW_PAGE;
+  return launch_select(sa, d, s);
+}
+
+// Channel-sparse token selector (a Double-Sparsity-style base algorithm in front of the pruner; Section 4.1's
+// black-box token selector, Sections 4.3 / 5): every token of a sequence is scored from the INT4 copy of K with the
+// query restricted to the KV head's channel set, and the budget's worth of tokens with the largest estimate is handed
+// over as a token list (ties to the lower position, ascending).
+extern "C" int twilight_ds_select_tokens(const twilight_kv_t* kv, const void* q, const uint32_t* channel_mask,
+                                         const int32_t* budget_tokens, int32_t* cand_tokens, int32_t* cand_count,
+                                         int32_t max_cand, void* ws, size_t ws_bytes, void* stream) {
+  TwDims d;
+  if (int e = tw_check_kv(kv, &d)) return e;
+  if (!q || !channel_mask || !budget_tokens || !cand_tokens || !cand_count || max_cand <= 0 || !kv->kq_pool || !kv->kq_meta)
+    return TW_EINVAL;
+  if ((long long)d.max_pages * TW_PAGE > 0x7FFFFFFFll / 4) return TW_EINVAL;
+  if (!ws || ws_bytes < twilight_workspace_bytes(TW_WS_DS_SELECT, kv, max_cand, 0)) return TW_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  if (int e = tw_score_all_tokens_masked(kv, d, q, channel_mask, (float*)ws, s)) return e;
+  SelectArgs sa;
+  sa.scores = (const float*)ws; sa.seq_lens = kv->seq_lens; sa.budget = budget_tokens;
+  sa.sel_pages = cand_tokens; sa.sel_count = cand_count;
+  sa.Hq = d.Hq; sa.max_pages = d.max_pages * TW_PAGE; sa.max_sel = max_cand; sa.unit = 1;
+  return launch_select(sa, d, s);
 }
 
 extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,

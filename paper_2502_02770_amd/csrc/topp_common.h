@@ -24,6 +24,9 @@ struct PruneWs {
 PruneWs tw_prune_layout(const TwDims& d, int bound_pages, bool full);
 PruneWs tw_prune_layout_tokens(const TwDims& d, int max_cand);   // token-list candidates (register-resident path only)
 
+int tw_score_all_tokens_masked(const twilight_kv_t* kv, const TwDims& d, const void* q, const uint32_t* chmask, float* scores,
+                               hipStream_t s);
+
 #ifdef __HIPCC__
 // softmax numerator e in [0, 1] -> floor(e * 2^40), exactly: the top 8 bits and the remaining 32
 // bits are taken by two float -> integer truncations (every step below is exact in fp32: scaling by

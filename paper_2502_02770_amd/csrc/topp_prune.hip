@@ -38,6 +38,7 @@ struct ScoreArgs {
   int32_t* dots;              // [b][Hq][cand_stride][4] or nullptr
   uint32_t* arrive;           // [b][Hkv] arrival counters of the top-p kernel that follows, or nullptr
   uint32_t* headmax;          // [b][Hq][HM_SLOTS] keys whose maximum is the head's largest score (atomicMax), or nullptr
+  const uint32_t* chmask;     // [Hkv][4] channels of the query that take part (bit d % 32 of word d / 32), or nullptr = all
   int Hq, Hkv, max_pages, max_sel, cand_stride, pw;   // pw: pages per wave (<= 64)
   int rotate;                 // list mode with a grid a multiple of 8 wide: chunk = (column - group % 8) mod width
   long long pool_pages;
@@ -45,8 +46,11 @@ struct ScoreArgs {
 
 // q of NH consecutive heads -> int8 (symmetric per head: sq = max|q| * (1/127), round half even),
 // 4 values per word, and c = sq / sqrt(128) per head.  Called by all threads of the block (>= 128).
+// chmask: 4 words of the KV head's channel set, or nullptr - channels outside it get the int8 value 0 (the scale sq
+// is that of the whole query), which restricts the estimate to the set (channel-sparse token selector).
 template <int NH>
-__device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32], float* red, float* c_s) {
+__device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32], float* red, float* c_s,
+                                              const uint32_t* chmask = nullptr) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 #pragma unroll 1
   for (int h = 0; h < NH; ++h) {
@@ -66,6 +70,7 @@ __device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32]
         t = fminf(fmaxf(t, -127.f), 127.f);
         qi = (int)t;
       }
+      if (chmask && !((chmask[tid >> 5] >> (tid & 31)) & 1u)) qi = 0;
       ((int8_t*)qi_s[h])[tid] = (int8_t)qi;
     }
     if (tid == 0) c_s[h] = __fmul_rn(sq, kRsqrtD);
@@ -158,7 +163,7 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   __shared__ int qi_s[NH][32];
   __shared__ float red[4];
   __shared__ float c_s[NH];
-  tw_quantize_q<NH>(a.q + ((long long)(b * a.Hq + h0)) * 128, qi_s, red, c_s);
+  tw_quantize_q<NH>(a.q + ((long long)(b * a.Hq + h0)) * 128, qi_s, red, c_s, a.chmask ? a.chmask + g * 4 : nullptr);
   const int j = lane & 3;                       // this lane's group of 32 dims
   int qw[NH][8], qs128[NH];
   float qsf[NH], cc[NH];
@@ -361,7 +366,7 @@ __global__ __launch_bounds__(256) void int4_score_mfma_kernel(ScoreArgs a) {
   __shared__ int qi_s[NH][32];
   __shared__ float red[4];
   __shared__ float c_s[NH];
-  tw_quantize_q<NH>(a.q + ((long long)(b * a.Hq + h0)) * 128, qi_s, red, c_s);
+  tw_quantize_q<NH>(a.q + ((long long)(b * a.Hq + h0)) * 128, qi_s, red, c_s, a.chmask ? a.chmask + g * 4 : nullptr);
 
   const int kb = lane >> 4, t = lane & 15;       // B operand / result: k-block (= group of dims) or head, token
   // A operand: row m = lane & 15 = 4 * head + group; this lane's k-block only meets its own group
@@ -898,9 +903,9 @@ void launch_score(const ScoreArgs& a, dim3 grid, bool dots, int bits, hipStream_
 
 int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int32_t* sel_pages,
               const int32_t* sel_count, int32_t max_sel, float* scores, int32_t* dots, uint32_t* arrive,
-              uint32_t* headmax, hipStream_t s) {
+              uint32_t* headmax, hipStream_t s, const uint32_t* chmask = nullptr) {
   ScoreArgs a;
-  a.arrive = arrive; a.headmax = headmax;
+  a.arrive = arrive; a.headmax = headmax; a.chmask = chmask;
   a.q = (const uint16_t*)q; a.sel_pages = sel_pages; a.sel_count = sel_count;
   a.page_table = kv->page_table; a.seq_lens = kv->seq_lens;
   a.kq_pool = (const uint4*)kv->kq_pool; a.kq_meta = (const uint32_t*)kv->kq_meta;
@@ -995,6 +1000,13 @@ int launch_topp(HeadArgs f, const TwDims& d, int cand_stride, hipStream_t s) {
 
 }  // namespace
 
+
+// Channel-sparse estimate of every token of every sequence (the scoring half of the channel-sparse token selector):
+// scores [b][Hq][max_pages * 16], tokens at or beyond the sequence's end -inf.
+int tw_score_all_tokens_masked(const twilight_kv_t* kv, const TwDims& d, const void* q, const uint32_t* chmask, float* scores,
+                               hipStream_t s) {
+  return run_score(kv, d, q, nullptr, nullptr, 0, scores, nullptr, nullptr, nullptr, s, chmask);
+}
 
 int tw_prune_wide_init(const TwDims& d, const PruneWs& L, void* ws, hipStream_t s);
 int tw_prune_wide(const TwDims& d, const PruneWs& L, void* ws, const twilight_kv_t* kv, const int32_t* sel_pages,
@@ -1122,7 +1134,7 @@ static int run_score_tokens(const twilight_kv_t* kv, const TwDims& d, const void
                             const int32_t* cand_count, int32_t max_cand, float* scores, int32_t* dots,
                             uint32_t* arrive, hipStream_t s) {
   ScoreArgs a;
-  a.arrive = arrive; a.headmax = nullptr;
+  a.arrive = arrive; a.headmax = nullptr; a.chmask = nullptr;
   a.q = (const uint16_t*)q; a.sel_pages = cand_tokens; a.sel_count = cand_count;
   a.page_table = kv->page_table; a.seq_lens = kv->seq_lens;
   a.kq_pool = (const uint4*)kv->kq_pool; a.kq_meta = (const uint32_t*)kv->kq_meta;

@@ -63,6 +63,8 @@ extern "C" size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, i
   switch (which) {
     case TW_WS_SELECT:
       return align256(bh * d.max_pages * 4);
+    case TW_WS_DS_SELECT:
+      return align256(bh * d.max_pages * TW_PAGE * 4);
     case TW_WS_PRUNE: {
       const int bound = max_sel > 0 ? max_sel : d.max_pages;
       return tw_prune_layout(d, bound, max_sel <= 0).total;

@@ -1596,6 +1596,108 @@ def test_canaries_pool_pages_workspace_tails_and_list_tails(kind):
         T.twilight_topp_prune_tokens(cache.kv, q, tl, tc, cand, w.p, kc2, ki2, cand, uc2, ui2, union_stride, status, ws_t)
         G_.check("topp_prune_tokens")
         assert torch.equal(kc2, kept_count) and torch.equal(uc2, union_count) and torch.equal(ui2, union_idx)
+    if cache.max_pages * 16 <= 196608:                 # the channel-sparse token selector
+        _, masks = synth.calibrated_channels(w, 16)
+        mc = 512
+        ct, cc = G_.buf((b_, Hq, mc), i32, -7), G_.buf((b_, Hq), i32, -7)
+        ws_ds = G_.buf((T.twilight_workspace_bytes(T.TW_WS_DS_SELECT, cache.kv, mc),), torch.uint8)
+        T.twilight_ds_select_tokens(cache.kv, q, masks.to(dev), budget, ct, cc, mc, ws_ds)
+        G_.check("ds_select_tokens")
+        for bb in range(b_):
+            for h in range(Hq):
+                assert bool((ct[bb, h, int(cc[bb, h]):] == -7).all())
     for name, pool in pools.items():                   # spare pool pages untouched by all of the above
         raw = pool.view(torch.uint8).reshape(w.num_pool_pages, -1)
         assert torch.equal(raw[spare], marks[name]), "spare pool page written: " + name
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Channel-sparse token selector in front of the pruner (twilight_ds_select_tokens).  The paper names such a selector
+# only by citation and gives no values for it: parity is against the oracle's reading of it (ds_scores, ds_select),
+# "unpinned by paper values".
+
+def _ds_select(T, w, cache, r, max_cand, budget=None):
+    dev = cache.device
+    lists, masks = synth.calibrated_channels(w, r)
+    q = w.q.to(dev)
+    bud = (w.budget if budget is None else torch.tensor(budget, dtype=torch.int32)).to(dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    cand = torch.full((w.batch, w.num_q_heads, max_cand), -7, **i32)
+    cnt = torch.full((w.batch, w.num_q_heads), -7, **i32)
+    ws = torch.empty(T.twilight_workspace_bytes(T.TW_WS_DS_SELECT, cache.kv, max_cand), dtype=torch.uint8, device=dev)
+    T.twilight_ds_select_tokens(cache.kv, q, masks.to(dev), bud, cand, cnt, max_cand, ws)
+    torch.cuda.synchronize()
+    return lists, cand.cpu().numpy(), cnt.cpu().numpy(), bud.cpu().numpy()
+
+
+def _check_ds_lists(w, lists, cand, cnt, bud, max_cand, bits=4):
+    G = w.num_q_heads // w.num_kv_heads
+    for b in range(w.batch):
+        n = int(w.seq_lens[b])
+        for g in range(w.num_kv_heads):
+            u, s_, z = O.quantize_k(synth.bits(w.seq_k(b)[:, g]), bits)
+            for h in range(g * G, g * G + G):
+                qi, sq = O.quantize_q(synth.bits(w.q[b, h]))
+                want = O.ds_select(O.ds_scores(qi, sq, u, s_, z, lists[g]), min(int(bud[b]), max_cand), n)
+                c = int(cnt[b, h])
+                assert c == len(want), (b, h)
+                assert cand[b, h, :c].tolist() == want.tolist(), (b, h)       # token sets bit for bit
+                assert np.all(cand[b, h, c:] == -7)                            # nothing past the count
+
+
+@pytest.mark.parametrize("lens,r,Hq,Hkv", [([1500, 333, 16], 16, 8, 2), ([7000, 2100], 8, 8, 2), ([40000], 32, 4, 1),
+                                           ([900, 4000], 128, 16, 2), ([3000], 16, 2, 2)],
+                         ids=["rows_2048", "rows_8192", "radix_rows", "all_channels_gqa8", "mha"])
+def test_channel_sparse_selector_token_sets_bit_exact(lens, r, Hq, Hkv):
+    """Token lists of the channel-sparse selector against the oracle (each of the three selection kernels by row
+    length; 4 and 8 query heads per KV head go through the matrix-core scoring kernel, 1 and 2 through the vector one).
+    With all 128 channels the lists are the top-B tokens by the pruner's own INT4 score."""
+    T = _T()
+    w = synth.make_workload("ds", lens, num_q_heads=Hq, num_kv_heads=Hkv, budget=[max(16, n // 5) for n in lens], p=0.9,
+                            heavy_frac=0.01, alpha_range=(0.5, 3.0), shuffle_pool=True, seed=88)
+    cache = build_cache(w)
+    max_cand = min(8192, (max(int(b) for b in w.budget) + 15) // 16 * 16)
+    lists, cand, cnt, bud = _ds_select(T, w, cache, r, max_cand)
+    _check_ds_lists(w, lists, cand, cnt, bud, max_cand)
+    # a list shorter than the budget asks for, and a zero budget
+    lists, cand, cnt, bud = _ds_select(T, w, cache, r, 48, budget=[0 if i == 0 else 10 ** 6 for i in range(w.batch)])
+    _check_ds_lists(w, lists, cand, cnt, bud, 48)
+
+
+def test_channel_sparse_selector_ties_go_to_the_lower_position():
+    """Keys drawn from three rows: every estimate takes one of three values and thousands of tokens tie at the cut."""
+    T = _T()
+    n = 6000
+    w = synth.make_workload("dsties", [n], num_q_heads=4, num_kv_heads=2, budget=n // 3, p=0.9, seed=89)
+    gen = torch.Generator().manual_seed(3)
+    proto = torch.randn(3, 2, 128, generator=gen).to(torch.bfloat16)
+    w.k[:] = proto[torch.randint(0, 3, (n,), generator=gen)]
+    cache = build_cache(w)
+    lists, cand, cnt, bud = _ds_select(T, w, cache, 16, 2000)
+    _check_ds_lists(w, lists, cand, cnt, bud, 2000)
+
+
+def test_channel_sparse_selector_in_front_of_the_pruner():
+    """Select (channel-sparse) -> prune (token lists) -> attend, every stage against the oracle on the same lists."""
+    T = _T()
+    w = synth.make_workload("dspipe", [5000, 1200, 260], budget=[1024, 512, 4096], p=0.9, heavy_frac=0.01,
+                            alpha_range=(0.5, 3.0), shuffle_pool=True, seed=90)
+    cache = build_cache(w)
+    dev = cache.device
+    max_cand = 1024
+    lists, cand, cnt, bud = _ds_select(T, w, cache, 16, max_cand)
+    _check_ds_lists(w, lists, cand, cnt, bud, max_cand)
+    q = w.q.to(dev)
+    st = T.DecodeStep(cache, max_sel=max_cand // 16, with_kept_idx=True)
+    ws = torch.empty(T.twilight_workspace_bytes(T.TW_WS_PRUNE_TOKENS, cache.kv, max_cand), dtype=torch.uint8, device=dev)
+    T.twilight_topp_prune_tokens(cache.kv, q, torch.from_numpy(cand).to(dev), torch.from_numpy(cnt).to(dev), max_cand, w.p,
+                                 st.kept_count, st.kept_idx, st.kept_stride, st.union_count, st.union_idx, st.union_stride,
+                                 st.status, ws)
+    st.attend(q)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    check_token_list_results(w, st, cand, cnt)
+    # the heavy tokens of a peaked head are found through 16 of its 128 channels
+    hs = w.info["heavy_sets"]
+    found = [len(np.intersect1d(cand[0, h, :cnt[0, h]], hs[(0, h)])) / len(hs[(0, h)]) for h in range(w.num_q_heads) if float(w.alpha[0, h]) > 2.0]
+    assert found and min(found) > 0.5

@@ -194,3 +194,19 @@ def config(idx, scale=1.0, seed=0, batch=None, kv_heads=None):
                              heavy_frac_range=(0.001, 0.05), alpha_range=(0.0, 4.0),
                              shuffle_pool=True, seed=seed)
     raise ValueError("config index 0..4")
+
+
+def calibrated_channels(w, r):
+    """Channel sets for a channel-sparse token selector: per KV head the r of its 128 channels that an offline
+    calibration pass would keep - stood in for here by the channels with the largest mean |K| x mean |q| over the
+    workload's own tokens and heads.  Returns (lists [Hkv][r] ascending, bit masks uint32 [Hkv, 4] as int32 tensor)."""
+    G = w.num_q_heads // w.num_kv_heads
+    kmag = w.k.float().abs().mean(dim=0)                                  # [Hkv, 128]
+    qmag = w.q.float().abs().mean(dim=0).reshape(w.num_kv_heads, G, HEAD_DIM).mean(dim=1)
+    lists, masks = [], np.zeros((w.num_kv_heads, 4), dtype=np.uint32)
+    for g in range(w.num_kv_heads):
+        ch = np.sort(torch.argsort(-(kmag[g] * qmag[g]), stable=True)[:r].numpy())
+        lists.append(ch)
+        for d in ch:
+            masks[g, d // 32] |= np.uint32(1) << np.uint32(d % 32)
+    return lists, torch.from_numpy(masks.view(np.int32).copy())
