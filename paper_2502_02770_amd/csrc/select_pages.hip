@@ -253,7 +253,8 @@ __global__ __launch_bounds__(256) void page_select_kernel(SelectArgs a) {
 // linearly into 2048 buckets (one pass when the bounds are spread out),
 // narrowing to the bucket that holds it, and finishing with an exact rank
 // computation once at most 256 candidates remain.
-constexpr int SEL_LDS_PAGES = 8192;
+constexpr int SEL_LDS_PAGES = 8192;      // rows up to here run two workgroups per CU
+constexpr int SEL_LDS_MAX = 32768;       // longest row whose keys fit in LDS (128 KiB of the CU's 160)
 constexpr int SEL_NB = 2048;
 constexpr int SEL_CAP = 256;
 
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
   }
   TW_STAMP(10);
 
-  __shared__ uint32_t key_s[NT == 256 ? 2048 : SEL_LDS_PAGES];   // the 256-thread variant serves rows of at most 2048 pages
+  extern __shared__ uint32_t key_s[];             // one key per row entry (the launch sizes it to the row bound)
   __shared__ uint32_t hist[SEL_NB];
   __shared__ uint32_t wsum[16];
   __shared__ uint32_t red_lo[NW], red_hi[NW];
@@ -431,6 +432,22 @@ extern "C" int twilight_debug_stamps_select(unsigned long long* host_out) {
 }
 #endif
 
+// Rows of more than 12288 entries need more dynamic LDS than a launch may ask for by default: raised once per device.
+static bool select_lds_big_ok() {
+  static std::atomic<int> done[TW_MAX_DEVICES];   // 0 = not tried, 1 = ok, 2 = refused
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= TW_MAX_DEVICES) return false;
+  int st = done[dev].load(std::memory_order_relaxed);
+  if (st == 0) {
+    const hipError_t e = hipFuncSetAttribute((const void*)page_select_lds_kernel<1024>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             SEL_LDS_MAX * 4);
+    if (e != hipSuccess) (void)hipGetLastError();
+    st = e == hipSuccess ? 1 : 2;
+    done[dev].store(st, std::memory_order_relaxed);
+  }
+  return st == 1;
+}
+
 // The selection kernels by row length (entries per row = sa.max_pages) and number of heads.
 static int launch_select(SelectArgs sa, const TwDims& d, hipStream_t s) {
   const int L = sa.max_pages;
@@ -440,7 +457,7 @@ static int launch_select(SelectArgs sa, const TwDims& d, hipStream_t s) {
   if (L > 2048 && L <= SEL_LDS_PAGES && (long long)d.batch * d.Hq > 2ll * tw_num_cus()) {
     sa.p_upto = 2048;
     tw_prof_before(TW_K_PAGE_SELECT, s);
-    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 2048 * 4, s, sa);
     if (int e = tw_prof_after(s)) return e;
     sa.p_above = 2048; sa.p_upto = L;
   }
@@ -449,9 +466,9 @@ static int launch_select(SelectArgs sa, const TwDims& d, hipStream_t s) {
   // quicker one (6.7 against 8.4 us at 8 x 32 heads x 2048 pages); many heads are better served by small workgroups
   const bool few_heads = (long long)d.batch * d.Hq <= 2ll * tw_num_cus();
   if (L <= 512 || (L <= 2048 && !few_heads))
-    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
-  else if (L <= SEL_LDS_PAGES)
-    TW_LAUNCH(page_select_lds_kernel<1024>, dim3(d.Hq, d.batch), dim3(1024), 0, s, sa);
+    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), (size_t)L * 4, s, sa);
+  else if (L <= SEL_LDS_MAX && ((size_t)L * 4 <= 48 * 1024 || select_lds_big_ok()))
+    TW_LAUNCH(page_select_lds_kernel<1024>, dim3(d.Hq, d.batch), dim3(1024), (size_t)L * 4, s, sa);
   else
     TW_LAUNCH(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
   return tw_prof_after(s);

@@ -112,6 +112,11 @@ def gpu_scores(cache, st, q):
     return sc.cpu().numpy().reshape(-1)
 
 
+# how the kept sets compared over the whole run (printed at the end by conftest.py): equal to the oracle's, different
+# only in tokens whose weight lies within 1e-6 of the threshold, or inside the band on the cumulative mass
+TOPP_STATS = {"heads": 0, "equal": 0, "weight_band": 0, "mass_band": 0}
+
+
 def check_topp(kept_gpu, s_hat, cand, p):
     """GPU kept set vs the oracle's, tolerant inside the 1e-6 band around tau*.  The C ABI takes p as a
     float: the oracle decides with that same value."""
@@ -121,6 +126,8 @@ def check_topp(kept_gpu, s_hat, cand, p):
     gm = np.isin(cand, kept_gpu)
     assert set(kept_gpu) <= set(cand.tolist())
     diff = gm != mask
+    TOPP_STATS["heads"] += 1
+    TOPP_STATS["equal" if not diff.any() else ("weight_band" if np.all(np.abs(W[diff] - tau) <= 1e-6) else "mass_band")] += 1
     if not np.all(np.abs(W[diff] - tau) <= 1e-6):
         # Not a weight on the threshold: then the MASS is on it.  Threshold sets are nested in p; when the
         # cumulative mass of the oracle's set passes p by less than the kernels' mass arithmetic resolves (fp32
@@ -1307,7 +1314,7 @@ def test_random_append_schedules_build_the_same_cache():
         check_cache(w, cache, bits)
 
 
-@pytest.mark.parametrize("lens", [[1500, 320], [40000], [140000]], ids=["lds_256", "lds_1024", "radix"])
+@pytest.mark.parametrize("lens", [[1500, 320], [40000], [140000], [530000]], ids=["lds_256", "lds_1024", "lds_big", "radix"])
 def test_select_is_cut_at_max_sel(lens):
     """A page list shorter than the budget asks for: the max_sel pages with the largest bounds, ascending -
     what the oracle selects for a budget of max_sel pages (all three selection kernels)."""
@@ -1334,7 +1341,7 @@ def test_select_is_cut_at_max_sel(lens):
                 assert st.sel_pages[b, h].cpu().numpy().tolist() == want.tolist(), (b, h)
 
 
-@pytest.mark.parametrize("n", [3000, 48000, 144000], ids=["lds_256", "lds_1024", "radix"])
+@pytest.mark.parametrize("n", [3000, 48000, 144000, 530000], ids=["lds_256", "lds_1024", "lds_big", "radix"])
 def test_page_ties_go_to_the_lower_page_id(n):
     """Every page holds 16 copies of one of three key rows, so a head's page bounds take three values and
     almost every page ties with a thousand others at the cut: the selected set must be the oracle's
@@ -1646,10 +1653,10 @@ def _check_ds_lists(w, lists, cand, cnt, bud, max_cand, bits=4):
 
 
 @pytest.mark.parametrize("lens,r,Hq,Hkv", [([1500, 333, 16], 16, 8, 2), ([7000, 2100], 8, 8, 2), ([40000], 32, 4, 1),
-                                           ([900, 4000], 128, 16, 2), ([3000], 16, 2, 2)],
-                         ids=["rows_2048", "rows_8192", "radix_rows", "all_channels_gqa8", "mha"])
+                                           ([900, 4000], 128, 16, 2), ([3000], 16, 2, 2), ([30000, 9000], 16, 4, 1)],
+                         ids=["rows_2048", "rows_8192", "radix_rows", "all_channels_gqa8", "mha", "rows_32768"])
 def test_channel_sparse_selector_token_sets_bit_exact(lens, r, Hq, Hkv):
-    """Token lists of the channel-sparse selector against the oracle (each of the three selection kernels by row
+    """Token lists of the channel-sparse selector against the oracle (each of the selection kernels by row
     length; 4 and 8 query heads per KV head go through the matrix-core scoring kernel, 1 and 2 through the vector one).
     With all 128 channels the lists are the top-B tokens by the pruner's own INT4 score."""
     T = _T()
