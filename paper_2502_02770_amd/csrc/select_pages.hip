@@ -166,25 +166,27 @@ struct SelectArgs {
   int32_t* sel_count;
   int Hq, max_pages, max_sel;
   int p_above, p_upto;        // the LDS kernel takes the heads with p_above < pages <= p_upto
-  int unit;                   // tokens per row entry: 16 = pages (budget and lengths are in tokens), 1 = the rows hold
-                              // one score per token (channel-sparse token selector; max_pages is then the row length)
 };
+// The kernels' UNIT parameter = tokens per row entry: 16 = pages (budget and lengths are in tokens), 1 = the rows hold one
+// score per token (channel-sparse token selector; max_pages is then the row length in tokens).
 
-// entries of a sequence's row and how many of them the budget asks for
+// entries of a sequence's row and how many of them the budget asks for (UNIT = tokens per entry: 16 or 1)
+template <int UNIT>
 __device__ __forceinline__ void tw_select_sizes(const SelectArgs& a, int n, int B, int* P_out, int* K_out) {
-  int P = n > 0 ? (n + a.unit - 1) / a.unit : 0;
+  int P = n > 0 ? (n + UNIT - 1) / UNIT : 0;
   if (P > a.max_pages) P = a.max_pages;
-  long long kp = B > 0 ? ((long long)B + a.unit - 1) / a.unit : 0;
+  long long kp = B > 0 ? ((long long)B + UNIT - 1) / UNIT : 0;
   if (kp > P) kp = P;
   if (kp > a.max_sel) kp = a.max_sel;
   *P_out = P;
   *K_out = (int)kp;
 }
 
+template <int UNIT>
 __global__ __launch_bounds__(256) void page_select_kernel(SelectArgs a) {
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
   int P, Kp;
-  tw_select_sizes(a, a.seq_lens[b], a.budget[b], &P, &Kp);
+  tw_select_sizes<UNIT>(a, a.seq_lens[b], a.budget[b], &P, &Kp);
   const float* sc = a.scores + ((long long)(b * a.Hq + h)) * a.max_pages;
   int32_t* out = a.sel_pages + ((long long)(b * a.Hq + h)) * a.max_sel;
   if (tid == 0) a.sel_count[b * a.Hq + h] = Kp;
@@ -259,12 +261,12 @@ constexpr int SEL_NB = 2048;
 constexpr int SEL_CAP = 256;
 
 
-template <int NT>
+template <int NT, int UNIT>
 __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
   constexpr int NW = NT / 64, BPT = SEL_NB / NT;      // waves; histogram buckets per thread
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int P, Kp;
-  tw_select_sizes(a, a.seq_lens[b], a.budget[b], &P, &Kp);
+  tw_select_sizes<UNIT>(a, a.seq_lens[b], a.budget[b], &P, &Kp);
   if (P <= a.p_above || P > a.p_upto) return;     // another launch's head (block-uniform)
   const float* sc = a.scores + ((long long)(b * a.Hq + h)) * a.max_pages;
   int32_t* out = a.sel_pages + ((long long)(b * a.Hq + h)) * a.max_sel;
@@ -433,13 +435,14 @@ extern "C" int twilight_debug_stamps_select(unsigned long long* host_out) {
 #endif
 
 // Rows of more than 12288 entries need more dynamic LDS than a launch may ask for by default: raised once per device.
+template <int UNIT>
 static bool select_lds_big_ok() {
   static std::atomic<int> done[TW_MAX_DEVICES];   // 0 = not tried, 1 = ok, 2 = refused
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= TW_MAX_DEVICES) return false;
   int st = done[dev].load(std::memory_order_relaxed);
   if (st == 0) {
-    const hipError_t e = hipFuncSetAttribute((const void*)page_select_lds_kernel<1024>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    const hipError_t e = hipFuncSetAttribute((const void*)page_select_lds_kernel<1024, UNIT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                              SEL_LDS_MAX * 4);
     if (e != hipSuccess) (void)hipGetLastError();
     st = e == hipSuccess ? 1 : 2;
@@ -449,6 +452,7 @@ static bool select_lds_big_ok() {
 }
 
 // The selection kernels by row length (entries per row = sa.max_pages) and number of heads.
+template <int UNIT>
 static int launch_select(SelectArgs sa, const TwDims& d, hipStream_t s) {
   const int L = sa.max_pages;
   sa.p_above = -1; sa.p_upto = L;
@@ -457,7 +461,7 @@ static int launch_select(SelectArgs sa, const TwDims& d, hipStream_t s) {
   if (L > 2048 && L <= SEL_LDS_PAGES && (long long)d.batch * d.Hq > 2ll * tw_num_cus()) {
     sa.p_upto = 2048;
     tw_prof_before(TW_K_PAGE_SELECT, s);
-    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), 2048 * 4, s, sa);
+    TW_LAUNCH((page_select_lds_kernel<256, UNIT>), dim3(d.Hq, d.batch), dim3(256), 2048 * 4, s, sa);
     if (int e = tw_prof_after(s)) return e;
     sa.p_above = 2048; sa.p_upto = L;
   }
@@ -466,11 +470,11 @@ static int launch_select(SelectArgs sa, const TwDims& d, hipStream_t s) {
   // quicker one (6.7 against 8.4 us at 8 x 32 heads x 2048 pages); many heads are better served by small workgroups
   const bool few_heads = (long long)d.batch * d.Hq <= 2ll * tw_num_cus();
   if (L <= 512 || (L <= 2048 && !few_heads))
-    TW_LAUNCH(page_select_lds_kernel<256>, dim3(d.Hq, d.batch), dim3(256), (size_t)L * 4, s, sa);
-  else if (L <= SEL_LDS_MAX && ((size_t)L * 4 <= 48 * 1024 || select_lds_big_ok()))
-    TW_LAUNCH(page_select_lds_kernel<1024>, dim3(d.Hq, d.batch), dim3(1024), (size_t)L * 4, s, sa);
+    TW_LAUNCH((page_select_lds_kernel<256, UNIT>), dim3(d.Hq, d.batch), dim3(256), (size_t)L * 4, s, sa);
+  else if (L <= SEL_LDS_MAX && ((size_t)L * 4 <= 48 * 1024 || select_lds_big_ok<UNIT>()))
+    TW_LAUNCH((page_select_lds_kernel<1024, UNIT>), dim3(d.Hq, d.batch), dim3(1024), (size_t)L * 4, s, sa);
   else
-    TW_LAUNCH(page_select_kernel, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
+    TW_LAUNCH(page_select_kernel<UNIT>, dim3(d.Hq, d.batch), dim3(256), 0, s, sa);
   return tw_prof_after(s);
 }
 
@@ -510,8 +514,8 @@ static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* bu
   SelectArgs sa;
   sa.scores = (const float*)ws; sa.seq_lens = kv->seq_lens; sa.budget = budget_tokens;
   sa.sel_pages = sel_pages; sa.sel_count = sel_count;
-  sa.Hq = d.Hq; sa.max_pages = d.max_pages; sa.max_sel = max_sel; sa.unit = TW_PAGE;
-  return launch_select(sa, d, s);
+  sa.Hq = d.Hq; sa.max_pages = d.max_pages; sa.max_sel = max_sel;
+  return launch_select<TW_PAGE>(sa, d, s);
 }
 
 // Channel-sparse token selector (a Double-Sparsity-style base algorithm in front of the pruner; Section 4.1's
@@ -532,8 +536,8 @@ extern "C" int twilight_ds_select_tokens(const twilight_kv_t* kv, const void* q,
   SelectArgs sa;
   sa.scores = (const float*)ws; sa.seq_lens = kv->seq_lens; sa.budget = budget_tokens;
   sa.sel_pages = cand_tokens; sa.sel_count = cand_count;
-  sa.Hq = d.Hq; sa.max_pages = d.max_pages * TW_PAGE; sa.max_sel = max_cand; sa.unit = 1;
-  return launch_select(sa, d, s);
+  sa.Hq = d.Hq; sa.max_pages = d.max_pages * TW_PAGE; sa.max_sel = max_cand;
+  return launch_select<1>(sa, d, s);
 }
 
 extern "C" int twilight_select_pages(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
