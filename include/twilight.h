@@ -26,6 +26,11 @@
  *     timing of twilight_prof.h, which is process-global (off by default).
  *   - head_dim must be 128, page_size 16, quant_group 32, quant_bits 0/4, 2 or 8,
  *     num_q_heads / num_kv_heads one of 1, 2, 4, 8.
+ *     (The kernels are compiled per group size: the heads of a group share
+ *     every loaded bound, code page and K/V row in registers; at 16 heads per
+ *     KV head the accumulators no longer fit a workgroup's registers, and a
+ *     split into two passes of 8 would change the shape of the per-KV-head
+ *     union lists.  Larger ratios are refused with TW_EINVAL.)
  *   - Query head h reads KV head h / (num_q_heads / num_kv_heads).
  *   - Size limits (TW_EINVAL beyond them): batch * num_q_heads <= 65535;
  *     num_pool_pages * num_kv_heads * 16 < 2^31; at most 2^22 candidate

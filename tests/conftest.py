@@ -25,3 +25,5 @@ def pytest_terminal_summary(terminalreporter):
     if st and st["heads"]:
         terminalreporter.write_line("top-p sets compared: %(heads)d heads; equal to the oracle's %(equal)d, differing only within 1e-6 "
                                     "of the threshold weight %(weight_band)d, inside the 1e-6 band on the cumulative mass %(mass_band)d" % st)
+        for line in st["where"][:20]:
+            terminalreporter.write_line("  not equal: " + line)

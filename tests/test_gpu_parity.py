@@ -4,6 +4,8 @@ equal outside a 1e-6 band around the threshold weight; attention outputs
 within max-abs 2e-2 and rel-L2 1e-3 of the bf16-rounded oracle."""
 import math
 
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -114,7 +116,7 @@ def gpu_scores(cache, st, q):
 
 # how the kept sets compared over the whole run (printed at the end by conftest.py): equal to the oracle's, different
 # only in tokens whose weight lies within 1e-6 of the threshold, or inside the band on the cumulative mass
-TOPP_STATS = {"heads": 0, "equal": 0, "weight_band": 0, "mass_band": 0}
+TOPP_STATS = {"heads": 0, "equal": 0, "weight_band": 0, "mass_band": 0, "where": []}
 
 
 def check_topp(kept_gpu, s_hat, cand, p):
@@ -128,6 +130,9 @@ def check_topp(kept_gpu, s_hat, cand, p):
     diff = gm != mask
     TOPP_STATS["heads"] += 1
     TOPP_STATS["equal" if not diff.any() else ("weight_band" if np.all(np.abs(W[diff] - tau) <= 1e-6) else "mass_band")] += 1
+    if diff.any():
+        TOPP_STATS["where"].append("%s: %d of %d candidates differ, |W - tau| <= %.3g, tau = %.3g"
+                                   % (os.environ.get("PYTEST_CURRENT_TEST", "?"), int(diff.sum()), len(cand), float(np.abs(W[diff] - tau).max()), tau))
     if not np.all(np.abs(W[diff] - tau) <= 1e-6):
         # Not a weight on the threshold: then the MASS is on it.  Threshold sets are nested in p; when the
         # cumulative mass of the oracle's set passes p by less than the kernels' mass arithmetic resolves (fp32
