@@ -833,38 +833,106 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
   }
   __syncthreads();
   TW_STAMP(15);
-  // thread t owns the contiguous words [t * wpt, (t + 1) * wpt): ascending output positions
-  const int wpt = (nwords + NT - 1) / NT;
-  const int w0 = tid * wpt, w1 = w0 + wpt < nwords ? w0 + wpt : nwords;
-  uint32_t ucnt = 0;
-  for (int i = w0; i < w1; ++i) ucnt += __popc(bitmap[i]);
-  uint32_t utotal;
-  const uint32_t uincl = tw_block_scan_u32(ucnt, ws32, &utotal);
-  TW_STAMP(16);
   int32_t* uout = a.union_idx + (long long)gi * a.union_stride;
-  uint32_t upos = uincl - ucnt;
-  if (utotal <= (uint32_t)HP_USTAGE) {               // block-uniform; the usual case
-    // positions staged in LDS, then copied out coalesced: a dense word costs its thread 32 scattered
-    // stores otherwise, one store instruction of the whole wave each (1.5 us of the kernel's tail)
-    for (int i = w0; i < w1; ++i) {
-      uint32_t x = bitmap[i];
-      while (x) {
-        const int bit = __ffs(x) - 1;
-        x &= x - 1;
-        ustage[upos++] = i * 32 + bit;
+  uint32_t utotal;
+  // (block-uniform choice: long sequences - more than two bitmap words per thread - take the wave-cooperative
+  //  listing; with fewer words per thread the plain per-thread walk is as quick and needs fewer registers, which
+  //  is what the 512-thread workgroups are short of)
+  if (NT >= 1024 && nwords > 2 * NT) {
+    // Wave w owns the contiguous words [w * wpw, (w + 1) * wpw) and takes them 64 at a time, one word per lane.  The
+    // set bits of a round are listed either by every lane walking its own word (scattered kept tokens: few bits per
+    // word) or, when fewer words are non-empty than the fullest word has bits (clustered heavy hitters: a few words
+    // of 32), word by word with one lane per bit - two words at a time, one per half wave.
+    const int wpw = (((nwords + NW - 1) / NW) + 63) & ~63;
+    const int wbase = wave * wpw;
+    uint32_t ucnt = 0;
+    for (int r = 0; r < wpw; r += 64) {
+      const int i = wbase + r + lane;
+      ucnt += i < nwords ? __popc(bitmap[i]) : 0;
+    }
+    ucnt = tw_wave_scan_u32(ucnt);
+    if (lane == 63) ws32[wave] = ucnt;
+    __syncthreads();
+    uint32_t run = 0;
+    utotal = 0;
+  #pragma unroll
+    for (int w = 0; w < NW; ++w) { const uint32_t t = ws32[w]; run += w < wave ? t : 0u; utotal += t; }
+    TW_STAMP(16);
+    // positions staged in LDS and copied out coalesced when they fit (the usual case; block-uniform), else stored directly
+    const bool staged = utotal <= (uint32_t)HP_USTAGE;
+    auto put = [&](uint32_t pos, int tok) {
+      if (staged) ustage[pos] = tok;
+      else if (pos < (uint32_t)a.union_stride) uout[pos] = tok;
+    };
+    for (int r = 0; r < wpw; r += 64) {               // wave-uniform trip count
+      const int i = wbase + r + lane;
+      uint32_t x = i < nwords ? bitmap[i] : 0u;
+      const uint32_t c = __popc(x);
+      const uint32_t incl = tw_wave_scan_u32(c);
+      const uint32_t upos0 = run + incl - c;
+      run += __shfl(incl, 63, 64);
+      unsigned long long nz = __ballot(x != 0);
+      if (nz == 0) continue;                           // wave-uniform
+      const uint32_t maxc = tw_wave_max_u32(c);
+      if ((uint32_t)__popcll(nz) * 2 >= maxc) {        // every lane its own word
+        uint32_t upos = upos0;
+        while (x) {
+          const int bit = __ffs(x) - 1;
+          x &= x - 1;
+          put(upos++, i * 32 + bit);
+        }
+      } else {                                         // two non-empty words per step, one lane per bit
+        const int half = lane >> 5, bit = lane & 31;
+        while (nz) {                                   // wave-uniform
+          const int s0 = __ffsll((long long)nz) - 1;
+          nz &= nz - 1;
+          int s1 = -1;
+          if (nz) { s1 = __ffsll((long long)nz) - 1; nz &= nz - 1; }
+          const int src = half ? s1 : s0;
+          const uint32_t xw = (uint32_t)__shfl((int)x, src < 0 ? 0 : src, 64);
+          const uint32_t ow = (uint32_t)__shfl((int)upos0, src < 0 ? 0 : src, 64);
+          if (src >= 0 && ((xw >> bit) & 1u))
+            put(ow + __popc(xw & ((1u << bit) - 1u)), (wbase + r + src) * 32 + bit);
+        }
       }
     }
-    __syncthreads();
-    const uint32_t lim = utotal < (uint32_t)a.union_stride ? utotal : (uint32_t)a.union_stride;
-    for (uint32_t i = tid; i < lim; i += NT) uout[i] = ustage[i];
+    if (staged) {
+      __syncthreads();
+      const uint32_t lim = utotal < (uint32_t)a.union_stride ? utotal : (uint32_t)a.union_stride;
+      for (uint32_t i = tid; i < lim; i += NT) uout[i] = ustage[i];
+    }
   } else {
-    for (int i = w0; i < w1; ++i) {
-      uint32_t x = bitmap[i];
-      while (x) {
-        const int bit = __ffs(x) - 1;
-        x &= x - 1;
-        if (upos < (uint32_t)a.union_stride) uout[upos] = i * 32 + bit;
-        ++upos;
+    // thread t owns the contiguous words [t * wpt, (t + 1) * wpt): ascending output positions
+    const int wpt = (nwords + NT - 1) / NT;
+    const int w0 = tid * wpt, w1 = w0 + wpt < nwords ? w0 + wpt : nwords;
+    uint32_t ucnt = 0;
+    for (int i = w0; i < w1; ++i) ucnt += __popc(bitmap[i]);
+    const uint32_t uincl = tw_block_scan_u32(ucnt, ws32, &utotal);
+    TW_STAMP(16);
+    uint32_t upos = uincl - ucnt;
+    if (utotal <= (uint32_t)HP_USTAGE) {               // block-uniform; the usual case
+      // positions staged in LDS, then copied out coalesced: a dense word costs its thread 32 scattered
+      // stores otherwise, one store instruction of the whole wave each (1.5 us of the kernel's tail)
+      for (int i = w0; i < w1; ++i) {
+        uint32_t x = bitmap[i];
+        while (x) {
+          const int bit = __ffs(x) - 1;
+          x &= x - 1;
+          ustage[upos++] = i * 32 + bit;
+        }
+      }
+      __syncthreads();
+      const uint32_t lim = utotal < (uint32_t)a.union_stride ? utotal : (uint32_t)a.union_stride;
+      for (uint32_t i = tid; i < lim; i += NT) uout[i] = ustage[i];
+    } else {
+      for (int i = w0; i < w1; ++i) {
+        uint32_t x = bitmap[i];
+        while (x) {
+          const int bit = __ffs(x) - 1;
+          x &= x - 1;
+          if (upos < (uint32_t)a.union_stride) uout[upos] = i * 32 + bit;
+          ++upos;
+        }
       }
     }
   }
