@@ -1713,3 +1713,40 @@ def test_channel_sparse_selector_in_front_of_the_pruner():
     hs = w.info["heavy_sets"]
     found = [len(np.intersect1d(cand[0, h, :cnt[0, h]], hs[(0, h)])) / len(hs[(0, h)]) for h in range(w.num_q_heads) if float(w.alpha[0, h]) > 2.0]
     assert found and min(found) > 0.5
+
+
+def test_selector_and_pruner_at_the_head_count_limit():
+    """batch * num_q_heads = 65520, 15 below the documented limit of the selector and the pruner (their grids carry one
+    workgroup per head in y): 2047 short sequences x 32 query heads; sampled heads against the oracle, and one more
+    sequence is refused on the host."""
+    T = _T()
+    batch = 2047
+    rng = np.random.default_rng(6)
+    lens = rng.integers(17, 120, size=batch).tolist()
+    w = synth.make_workload("manyheads", lens, budget=48, p=0.9, heavy_frac=0.05, alpha_range=(0.5, 3.0), need_v=False, seed=79)
+    cache = build_cache(w)
+    dev = cache.device
+    q = w.q.to(dev)
+    st = T.DecodeStep(cache, max_sel=3, with_kept_idx=True)
+    st.select(q, w.budget.to(dev))
+    st.prune(q, w.p)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    G = w.num_q_heads // w.num_kv_heads
+    for b in (0, 1, 1023, 2046):
+        r = oracle_seq(w, b)
+        for h in range(w.num_q_heads):
+            cnt = int(st.sel_count[b, h])
+            assert st.sel_pages[b, h, :cnt].cpu().numpy().tolist() == r["pages"][h].tolist(), (b, h)
+            kept = st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy()
+            check_topp(kept, r["s_hat"][h], r["cand"][h], w.p)
+        for g in range(w.num_kv_heads):
+            gi = b * w.num_kv_heads + g
+            un = st.union_idx[gi, :int(st.union_count[gi])].cpu().numpy()
+            mine = np.unique(np.concatenate([st.kept_idx[b, h, :int(st.kept_count[b, h])].cpu().numpy() for h in range(g * G, g * G + G)]))
+            assert un.tolist() == mine.tolist()
+    kv = T.make_kv(2048, 32, 8, cache.max_pages, cache.num_pool_pages, cache.page_table, cache.seq_lens, cache.k_pool, None,
+                   cache.kq_pool, cache.kq_meta, cache.page_minmax)
+    assert T.twilight_workspace_bytes(T.TW_WS_SELECT, kv, 3) == 0          # 65536 heads: over the limit
+    with pytest.raises(T.TwilightError):
+        T.twilight_select_pages(kv, q, w.budget.to(dev), st.sel_pages, st.sel_count, 3, st.ws_select)
