@@ -628,6 +628,7 @@ def main():
     if setup.get("append_bulk"):
         per_kernel["kquant_append_bulk"] = setup["append_bulk"]
     if a.breakdown:
+        sys.stderr.write("timed launches of %s (us): %s\n" % (dom, " ".join("%.2f" % (x * 1e3) for x in dom_ms)))
         for k, v in per_kernel.items():
             if "calls_per_step" in v:
                 sys.stderr.write("%-16s %9.2f us x %-4.3g %12s B  %8.1f GB/s\n" % (k, v["us"], v["calls_per_step"], v["bytes"], v["GBps"] or 0))

@@ -140,6 +140,7 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
     float mn[8], mx[8];
     tw_unpack8(rmn[it], mn);
     tw_unpack8(rmx[it], mx);
+    float part[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       float acc = 0.f;
@@ -150,10 +151,38 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
         const float v = q[h][i] > 0.f ? mx[i] : mn[i];
         acc = __builtin_fmaf(q[h][i], v, acc);
       }
-      acc = tw_row16_sum(acc);
-      if (seg == 0 && live[it])
-        a.scores[((long long)(b * a.Hq + g * G + h)) * a.max_pages + lp] =
-            ok[it] ? __fadd_rn(acc, 0.0f) : -3.402823466e38f;   // unmapped page: ranks last
+      part[h] = acc;
+    }
+    if constexpr (G >= 4) {
+      // The pairwise tree over the 16 lanes (l^1, l^2, l^4, l^8) for four heads at once: at the first two levels a
+      // lane keeps the half of its values that one bit of its lane id selects and adds the partner's copy of them
+      // (the same two operands as the plain tree adds, so the same sums), which leaves lane l with the quad sum of
+      // head 2 * (l & 1) + ((l >> 1) & 1); the last two levels rotate the row by 4 and by 8 (a lane reads lane
+      // l - 4, then l - 8, modulo 16), which for lanes 4..7 are exactly l ^ 4 and l ^ 8 of the same head.  Lanes 4..7
+      // end with the four totals: 5 additions and 6 selects per four heads instead of 16 additions.
+      const bool b0 = seg & 1, b1 = seg & 2;
+#pragma unroll
+      for (int h4 = 0; h4 < G; h4 += 4) {
+        const float k0 = b0 ? part[h4 + 2] : part[h4 + 0], s0 = b0 ? part[h4 + 0] : part[h4 + 2];
+        const float k1 = b0 ? part[h4 + 3] : part[h4 + 1], s1 = b0 ? part[h4 + 1] : part[h4 + 3];
+        const float a0 = __fadd_rn(k0, tw_dpp_f<TW_DPP_XOR1>(s0));     // head h4 + 2 * b0
+        const float a1 = __fadd_rn(k1, tw_dpp_f<TW_DPP_XOR1>(s1));     // head h4 + 2 * b0 + 1
+        const float kk = b1 ? a1 : a0, ss = b1 ? a0 : a1;
+        float t = __fadd_rn(kk, tw_dpp_f<TW_DPP_XOR2>(ss));            // head h4 + 2 * b0 + b1, summed over the quad
+        t = __fadd_rn(t, tw_dpp_f<0x124>(t));                          // row_ror:4 - lanes 4..7 and 12..15 read l ^ 4
+        t = __fadd_rn(t, tw_dpp_f<0x128>(t));                          // row_ror:8 - every lane reads l ^ 8
+        if ((seg >> 2) == 1 && live[it])
+          a.scores[((long long)(b * a.Hq + g * G + h4 + 2 * (seg & 1) + ((seg >> 1) & 1))) * a.max_pages + lp] =
+              ok[it] ? __fadd_rn(t, 0.0f) : -3.402823466e38f;          // unmapped page: ranks last
+      }
+    } else {
+#pragma unroll
+      for (int h = 0; h < G; ++h) {
+        const float acc = tw_row16_sum(part[h]);
+        if (seg == 0 && live[it])
+          a.scores[((long long)(b * a.Hq + g * G + h)) * a.max_pages + lp] =
+              ok[it] ? __fadd_rn(acc, 0.0f) : -3.402823466e38f;   // unmapped page: ranks last
+      }
     }
   }
 }
