@@ -83,7 +83,7 @@ def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_select
     pos = (caches[0].seq_lens - 1).contiguous()
     rows = torch.arange(w.batch, dtype=torch.int32, device=dev)
     turn = [0]
-    fused_append = bits == 4 and not separate_append
+    fused_append = not separate_append
 
     def step():
         i = turn[0] % layers
@@ -657,7 +657,7 @@ def main():
         "config": {"workload": describe(w, a.scale),
                    "config_index": a.config, "seed": a.seed, "layers_rotated": max(1, a.layers),
                    "kv_offloaded_to_host": bool(a.offload),
-                   "append": "separate launch" if (a.separate_append or a.bits != 4 or w.full_selector) else "inside page_score"},
+                   "append": "separate launch" if (a.separate_append or w.full_selector) else "inside page_score"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "us_per_layer_events_off": ms_plain * 1e3,

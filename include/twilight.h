@@ -182,7 +182,7 @@ int twilight_select_pages_static(const twilight_kv_t* kv, const void* q, const i
  * per sequence (as twilight_kquant_append with n_new = 1 would: bf16 K/V rows,
  * INT4 codes, scale/zero, page bounds - bit for bit the same), then select
  * pages as twilight_select_pages does, the new token's page included.  Saves
- * the separate append launch of a decode step.  quant_bits must be 4.
+ * the separate append launch of a decode step (any quant_bits).
  *   k_new, v_new   bf16 [batch][num_kv_heads][128] (v_new may be NULL; kv->k_pool
  *                  may be NULL as in twilight_kquant_append)
  *   new_pos        i32 [batch] position of the new token, < seq_lens[b]

@@ -81,7 +81,7 @@ class DecodeStep:
         B.twilight_select_pages(self.cache.kv, q, budget, self.sel_pages, self.sel_count, self.max_sel, self.ws_select)
 
     def append_select(self, k_new, v_new, new_pos, q, budget):
-        """One new token per sequence appended and the pages selected in one launch (4-bit copy only)."""
+        """One new token per sequence appended and the pages selected in one launch."""
         B.twilight_append_select(self.cache.kv, k_new, v_new, new_pos, q, budget, self.sel_pages, self.sel_count,
                                  self.max_sel, self.ws_select)
 

@@ -41,7 +41,7 @@ struct ScoreArgs {
   uint4* page_minmax_w;
 };
 
-template <int G, bool APPEND>
+template <int G, bool APPEND, int BITS = 4>
 __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
   // KV head fastest in dispatch order: the 8 heads' bounds of a pool page are 4 KiB contiguous,
   // and the workgroups that read them start next to each other
@@ -103,8 +103,10 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
           float x[8];
           tw_unpack8(raw, x);
           uint32_t word, word2, meta;
-          tw_quantize_lane8<4>(x, seg, &word, &word2, &meta);
-          a.kq_pool[slot * 16 + seg] = word;
+          tw_quantize_lane8<BITS>(x, seg, &word, &word2, &meta);
+          if (BITS == 4) a.kq_pool[slot * 16 + seg] = word;
+          else if (BITS == 8) ((uint2*)a.kq_pool)[slot * 16 + seg] = make_uint2(word, word2);
+          else if ((seg & 1) == 0) a.kq_pool[slot * 8 + (seg >> 1)] = word;
           if ((seg & 3) == 0) a.kq_meta[slot * 4 + (seg >> 2)] = meta;
           // bounds: the token alone if it opens the page, else folded into the page's older tokens
           float mn[8], mx[8];
@@ -450,9 +452,11 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
 }
 
 template <int G>
-void launch_score(const ScoreArgs& a, dim3 grid, bool append, hipStream_t s) {
-  if (append) TW_LAUNCH((page_score_kernel<G, true>), grid, dim3(256), 0, s, a);
-  else        TW_LAUNCH((page_score_kernel<G, false>), grid, dim3(256), 0, s, a);
+void launch_score(const ScoreArgs& a, dim3 grid, bool append, int bits, hipStream_t s) {
+  if (!append)        TW_LAUNCH((page_score_kernel<G, false>), grid, dim3(256), 0, s, a);
+  else if (bits == 4) TW_LAUNCH((page_score_kernel<G, true, 4>), grid, dim3(256), 0, s, a);
+  else if (bits == 8) TW_LAUNCH((page_score_kernel<G, true, 8>), grid, dim3(256), 0, s, a);
+  else                TW_LAUNCH((page_score_kernel<G, true, 2>), grid, dim3(256), 0, s, a);
 }
 
 }  // namespace
@@ -517,7 +521,6 @@ static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* bu
   if (append) {
     if (!k_new || !new_pos || !kv->kq_pool || !kv->kq_meta) return TW_EINVAL;
     if (v_new && !kv->v_pool) return TW_EINVAL;
-    if (d.bits != 4) return TW_EINVAL;            // the fused append writes the 4-bit copy only
   }
   if (!ws || ws_bytes < twilight_workspace_bytes(TW_WS_SELECT, kv, max_sel, 0)) return TW_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -533,10 +536,10 @@ static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* bu
   dim3 grid(d.Hkv, (d.max_pages + PS_PAGES_PER_WG - 1) / PS_PAGES_PER_WG, d.batch);
   tw_prof_before(TW_K_PAGE_SCORE, s);
   switch (d.G) {
-    case 1: launch_score<1>(a, grid, append, s); break;
-    case 2: launch_score<2>(a, grid, append, s); break;
-    case 4: launch_score<4>(a, grid, append, s); break;
-    default: launch_score<8>(a, grid, append, s); break;
+    case 1: launch_score<1>(a, grid, append, d.bits, s); break;
+    case 2: launch_score<2>(a, grid, append, d.bits, s); break;
+    case 4: launch_score<4>(a, grid, append, d.bits, s); break;
+    default: launch_score<8>(a, grid, append, d.bits, s); break;
   }
   if (int e = tw_prof_after(s)) return e;
 

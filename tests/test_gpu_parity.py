@@ -416,7 +416,8 @@ def test_step_replays_from_a_hip_graph():
         del scratch
 
 
-def test_append_select_equals_append_then_select():
+@pytest.mark.parametrize("bits", [4, 2, 8])
+def test_append_select_equals_append_then_select(bits):
     """twilight_append_select (one new token per sequence appended on the selector's way) leaves the cache
     and the page sets exactly as twilight_kquant_append followed by twilight_select_pages do; new tokens
     that open a page, sit inside one, end one; a sequence without a new token; then against the oracle."""
@@ -435,7 +436,7 @@ def test_append_select_equals_append_then_select():
     max_sel = int(max(-(-int(b) // 16) for b in w.budget))
 
     def prefilled():
-        c = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev)
+        c = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev, quant_bits=bits)
         c.append(k, v, start, c.seq_lens - 1, offs, max(lens) - 1)      # everything but the last token
         return c
 
@@ -458,7 +459,7 @@ def test_append_select_equals_append_then_select():
             o = (bi * w.num_q_heads + h) * a.max_pages
             P = (lens[bi] + 15) // 16
             assert torch.equal(pa[o:o + P], pb[o:o + P]), (bi, h)
-    check_cache(w, b_)
+    check_cache(w, b_, bits)
     # a sequence without a new token keeps its cache (its last token is then simply missing)
     c = prefilled()
     sc = T.DecodeStep(c, max_sel=max_sel)
@@ -469,8 +470,7 @@ def test_append_select_equals_append_then_select():
     pg = int(w.page_table[3, (lens[3] - 1) // 16])
     assert torch.equal(c.kq_pool[pg], ref.kq_pool[pg]) and torch.equal(c.page_minmax[pg].view(torch.int16), ref.page_minmax[pg].view(torch.int16))
     # the rest of the step on the fused cache, against the oracle
-    sb2, _ = run_pipeline(w, b_)
-    check_sets_and_output(w, b_, sb2)
+    pipeline_against_oracle(w, bits, b_)
 
 
 def test_p1_full_budget_reproduces_dense_attention():
