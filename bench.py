@@ -642,8 +642,8 @@ def main():
         del cache, st, step, dense
         torch.cuda.empty_cache()
         others = []
-        for idx, k in ((0, 200), (2, 200), (4, 100)):
-            others.append(other_config(T, idx, k, 10, max(1, a.layers) if idx != 4 else 2))
+        for idx, k in ((0, 200), (2, 200), (3, 20), (4, 100)):
+            others.append(other_config(T, idx, k, 10 if idx != 3 else 3, max(1, a.layers) if idx not in (3, 4) else 2))
         # the headline shape at four times the batch: a launch then moves 277 MB of bounds and the fixed cost per
         # launch no longer sets the fraction of peak
         others.append(other_config(T, 1, 100, 10, 2, batch=32))
