@@ -26,7 +26,7 @@ PAPER_CONTEXT = {"quest_twi_vs_fa2_attention_speedup": 15.8, "quest_twi_vs_quest
 
 
 def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_selector=False, offload=False,
-                separate_append=False, kv_heads=None):
+                separate_append=False, kv_heads=None, separate_prune=False):
     """`layers` independent copies of the layer's cache (same contents, different memory).  Successive steps
     rotate over them, as the layers of a model do, so that a step finds its pools in HBM and not in the
     256 MB memory-side cache left warm by the previous step over the very same addresses."""
@@ -89,6 +89,13 @@ def build_state(cfg_idx, scale, seed, batch, layers, bits=4, p=None, full_select
         i = turn[0] % layers
         turn[0] += 1
         cache, st = caches[i], steps[i]
+        if fused_append and not st.full and not separate_prune:
+            # stages 4 + 1 + 2 in one call: the bounds (new token appended on the way), then selection, scoring, top-p
+            # and the union in one launch per head where the lists are short enough (else the separate launches)
+            st.select_prune(k_last, v_last, pos, q, budget, w.p)
+            if v_last is not None:
+                st.attend(q)
+            return
         if fused_append and not st.full:
             st.append_select(k_last, v_last, pos, q, budget)       # stages 4 + 1 in one launch
         else:

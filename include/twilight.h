@@ -196,6 +196,28 @@ int twilight_append_select(const twilight_kv_t* kv, const void* k_new, const voi
                            void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Selector and pruner of a decode step in one call (Section 4.1: the token
+ * selector's subset handed straight to the pruner; Section 4.2, Algorithm 1):
+ * what twilight_append_select (k_new given) or twilight_select_pages (k_new,
+ * v_new, new_pos all NULL) followed by twilight_topp_prune over the selected
+ * pages computes - the same page lists, kept sets and unions bit for bit - in
+ * two launches instead of four: the bounds of all pages, then one workgroup
+ * per query head that picks the head's pages, scores their tokens from the
+ * quantised K copy, runs top-p and, as the last head of its group, lists the
+ * union.  For quant_bits = 4 and max_sel <= 512 pages on sequences of at most
+ * 196608 tokens (TW_EINVAL otherwise: use the separate calls).
+ *   sel_pages, sel_count   out, as twilight_select_pages
+ *   kept_count ... status  out, as twilight_topp_prune
+ *   ws             >= twilight_workspace_bytes(TW_WS_SELECT_PRUNE, kv, max_sel, 0)
+ */
+int twilight_select_prune(const twilight_kv_t* kv, const void* k_new, const void* v_new, const int32_t* new_pos,
+                          const void* q, const int32_t* budget_tokens, float p,
+                          int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
+                          int32_t* kept_count, int32_t* kept_idx, int32_t kept_stride,
+                          int32_t* union_count, int32_t* union_idx, int32_t union_stride,
+                          uint32_t* status, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Estimated scores alone (first half of stage 2; Section 4.2: the sparse
  * matrix-vector product over the quantised K copy; Appendix B.1).  q is quantised per head to int8 (sq = max|q| * (1/127),
  * qi = clamp(rint(q / sq), -127, 127)); per token and group j of 32 dims
@@ -339,6 +361,7 @@ int twilight_sparse_decode_per_head(const twilight_kv_t* kv, const void* q, cons
 #define TW_WS_DECODE_PER_HEAD 3
 #define TW_WS_PRUNE_TOKENS 4
 #define TW_WS_DS_SELECT 5
+#define TW_WS_SELECT_PRUNE 6
 /*  max_sel: as passed to the call (0 with sel_pages == NULL; max_cand for
  *  TW_WS_PRUNE_TOKENS);
  *  union_stride: as passed to sparse_decode (0 for dense), kept_stride for

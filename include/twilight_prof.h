@@ -38,7 +38,9 @@ struct twilight_kv;   /* twilight.h */
 #define TW_K_UNION 5
 #define TW_K_DECODE 6
 #define TW_K_COMBINE 7
-#define TW_K_COUNT 8
+#define TW_K_SCORE_TOPP 8         /* scoring + top-p + union in one launch (twilight_select_prune) */
+#define TW_K_SELECT_SCORE_TOPP 9  /* page selection as well */
+#define TW_K_COUNT 10
 int twilight_prof_enable(int mode);
 int twilight_prof_select(int kernel_id, int every);
 int twilight_prof_collect(int32_t* kernel_ids /*host*/, float* ms /*host*/, int32_t cap);

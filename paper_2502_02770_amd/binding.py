@@ -13,11 +13,11 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("TWILIGHT_LIB") or os.path.join(_PKG, "libtwilight.so")   # override: tuning builds
 
-TW_WS_SELECT, TW_WS_PRUNE, TW_WS_DECODE, TW_WS_DECODE_PER_HEAD, TW_WS_PRUNE_TOKENS, TW_WS_DS_SELECT = 0, 1, 2, 3, 4, 5
+TW_WS_SELECT, TW_WS_PRUNE, TW_WS_DECODE, TW_WS_DECODE_PER_HEAD, TW_WS_PRUNE_TOKENS, TW_WS_DS_SELECT, TW_WS_SELECT_PRUNE = 0, 1, 2, 3, 4, 5, 6
 TW_STATUS_UNION_TRUNCATED, TW_STATUS_KEPT_TRUNCATED = 1, 2
 TW_STATIC_SELECT_WS_BYTES = 8 << 20
 KERNEL_NAMES = ["kquant_append", "page_score", "page_select", "int4_score", "topp", "union",
-                "sparse_decode", "combine"]
+                "sparse_decode", "combine", "score_topp", "select_score_topp"]
 
 _vp, _i32, _i64, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
 
@@ -51,6 +51,7 @@ def lib():
     L.twilight_int4_score.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
     L.twilight_ds_select_tokens.argtypes = [kvp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
     L.twilight_append_select.argtypes = [kvp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
+    L.twilight_select_prune.argtypes = [kvp, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
     L.twilight_topp_prune.argtypes = [kvp, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
     L.twilight_int4_score_tokens.argtypes = [kvp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]
     L.twilight_topp_prune_tokens.argtypes = [kvp, _vp, _vp, _vp, _i32, _f32, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _sz, _vp]
@@ -70,7 +71,7 @@ def lib():
     L.twilight_decode_plan.argtypes = [kvp, ctypes.c_int, _i32, ctypes.POINTER(_i32), ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
     L.twilight_decode_plan.restype = ctypes.c_int
     L.twilight_kernel_name.restype = ctypes.c_char_p
-    for f in ("twilight_ds_select_tokens", "twilight_kquant_append", "twilight_select_pages", "twilight_select_pages_static", "twilight_append_select", "twilight_int4_score", "twilight_topp_prune",
+    for f in ("twilight_select_prune", "twilight_ds_select_tokens", "twilight_kquant_append", "twilight_select_pages", "twilight_select_pages_static", "twilight_append_select", "twilight_int4_score", "twilight_topp_prune",
               "twilight_int4_score_tokens", "twilight_topp_prune_tokens",
               "twilight_sparse_decode", "twilight_sparse_decode_per_head", "twilight_prof_enable", "twilight_prof_select", "twilight_prof_collect"):
         getattr(L, f).restype = ctypes.c_int
@@ -151,6 +152,14 @@ def twilight_append_select(kv, k_new, v_new, new_pos, q, budget_tokens, sel_page
     _check(lib().twilight_append_select(ctypes.byref(kv), _ptr(k_new), _ptr(v_new), _ptr(new_pos), _ptr(q),
                                         _ptr(budget_tokens), _ptr(sel_pages), _ptr(sel_count), int(max_sel), _ptr(ws),
                                         ws.numel() * ws.element_size(), _stream()))
+
+
+def twilight_select_prune(kv, k_new, v_new, new_pos, q, budget_tokens, p, sel_pages, sel_count, max_sel, kept_count, kept_idx,
+                          kept_stride, union_count, union_idx, union_stride, status, ws):
+    _check(lib().twilight_select_prune(ctypes.byref(kv), _ptr(k_new), _ptr(v_new), _ptr(new_pos), _ptr(q), _ptr(budget_tokens),
+                                       float(p), _ptr(sel_pages), _ptr(sel_count), int(max_sel), _ptr(kept_count),
+                                       _ptr(kept_idx), int(kept_stride), _ptr(union_count), _ptr(union_idx),
+                                       int(union_stride), _ptr(status), _ptr(ws), ws.numel() * ws.element_size(), _stream()))
 
 
 def twilight_int4_score(kv, q, sel_pages, sel_count, max_sel, scores, dots=None):

@@ -61,7 +61,13 @@ class DecodeStep:
         if not self.full:
             self.sel_pages = torch.zeros(c.batch, c.Hq, self.max_sel, **i32)
             self.sel_count = torch.zeros(c.batch, c.Hq, **i32)
-            self.ws_select = torch.empty(B.twilight_workspace_bytes(B.TW_WS_SELECT, c.kv, self.max_sel), dtype=torch.uint8, device=dev)
+            # one allocation for the selector's and the pruner's workspaces, laid out as twilight_select_prune wants
+            # them; the separate calls get its two parts
+            nsel = B.twilight_workspace_bytes(B.TW_WS_SELECT, c.kv, self.max_sel)
+            self._ws_select_prune = torch.empty(B.twilight_workspace_bytes(B.TW_WS_SELECT_PRUNE, c.kv, self.max_sel),
+                                                dtype=torch.uint8, device=dev)
+            self.ws_select = self._ws_select_prune[:nsel]
+            self.ws_prune = self._ws_select_prune[nsel:]
         else:
             self.sel_pages = self.sel_count = None
         self.kept_count = torch.zeros(c.batch, c.Hq, **i32)
@@ -70,7 +76,8 @@ class DecodeStep:
         self.union_count = torch.zeros(c.batch * c.Hkv, **i32)
         self.union_idx = torch.zeros(c.batch * c.Hkv, self.union_stride, **i32)
         self.status = torch.zeros(1, **i32)
-        self.ws_prune = torch.empty(B.twilight_workspace_bytes(B.TW_WS_PRUNE, c.kv, self.max_sel), dtype=torch.uint8, device=dev)
+        if self.full:
+            self.ws_prune = torch.empty(B.twilight_workspace_bytes(B.TW_WS_PRUNE, c.kv, self.max_sel), dtype=torch.uint8, device=dev)
         self.ws_decode = torch.empty(B.twilight_workspace_bytes(B.TW_WS_DECODE, c.kv, 0, self.union_stride), dtype=torch.uint8, device=dev)
         self.out = torch.zeros(c.batch, c.Hq, 128, dtype=torch.bfloat16, device=dev)
         self.lse = torch.zeros(c.batch, c.Hq, dtype=torch.float32, device=dev) if with_lse else None
@@ -84,6 +91,12 @@ class DecodeStep:
         """One new token per sequence appended and the pages selected in one launch."""
         B.twilight_append_select(self.cache.kv, k_new, v_new, new_pos, q, budget, self.sel_pages, self.sel_count,
                                  self.max_sel, self.ws_select)
+
+    def select_prune(self, k_new, v_new, new_pos, q, budget, p):
+        """Selector (with the step's new token appended when k_new is given) and pruner in two launches."""
+        B.twilight_select_prune(self.cache.kv, k_new, v_new, new_pos, q, budget, p, self.sel_pages, self.sel_count,
+                                self.max_sel, self.kept_count, self.kept_idx, self.kept_stride, self.union_count,
+                                self.union_idx, self.union_stride, self.status, self._ws_select_prune)
 
     def prune(self, q, p):
         B.twilight_topp_prune(self.cache.kv, q, self.sel_pages, self.sel_count, self.max_sel, p, self.kept_count,
@@ -104,10 +117,16 @@ class DecodeStep:
         B.twilight_sparse_decode_per_head(self.cache.kv, q, self.kept_count, self.kept_idx, self.kept_stride,
                                           self.out, self.lse, self._ws_per_head)
 
-    def run(self, q, budget, p):
-        if not self.full:
+    def run(self, q, budget, p, separate=False):
+        """Selector, pruner, attention.  With a page selector the first two are one call (twilight_select_prune);
+        separate=True takes twilight_select_pages and twilight_topp_prune instead (same results bit for bit)."""
+        if self.full:
+            self.prune(q, p)
+        elif separate:
             self.select(q, budget)
-        self.prune(q, p)
+            self.prune(q, p)
+        else:
+            self.select_prune(None, None, None, q, budget, p)
         self.attend(q)
         return self.out
 

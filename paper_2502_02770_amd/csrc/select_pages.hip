@@ -14,9 +14,11 @@
 // (twilight_append_select): the 16 lanes that own the page the token falls into store its K/V
 // rows, quantise K, and fold it into the page's bounds before scoring them.
 #include <atomic>
+#include <stdlib.h>
 #include "tw_common.h"
 #include "kquant_common.h"
 #include "topp_common.h"
+#include "select_body.h"
 
 namespace {
 
@@ -39,6 +41,7 @@ struct ScoreArgs {
   uint32_t* kq_pool;          // INT4 codes, 16 words per token
   uint32_t* kq_meta;
   uint4* page_minmax_w;
+  uint32_t* arrive;           // [b][Hkv] arrival counters of a top-p launch that follows, cleared here, or nullptr
 };
 
 template <int G, bool APPEND, int BITS = 4>
@@ -48,6 +51,7 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
   const int b = blockIdx.z, g = blockIdx.x;
   const int tid = threadIdx.x, seg = tid & 15, grp = tid >> 4;   // grp: 0..15 page slot in the WG
   TW_STAMP(0);
+  if (a.arrive && blockIdx.y == 0 && tid == 0) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
   const int n = a.seq_lens[b];
   // last pages first: the workgroup that appends the step's new token (the sequence's last page) has the longest
   // chain of dependent accesses and should not be the one that starts last
@@ -201,16 +205,9 @@ struct SelectArgs {
 // The kernels' UNIT parameter = tokens per row entry: 16 = pages (budget and lengths are in tokens), 1 = the rows hold one
 // score per token (channel-sparse token selector; max_pages is then the row length in tokens).
 
-// entries of a sequence's row and how many of them the budget asks for (UNIT = tokens per entry: 16 or 1)
 template <int UNIT>
 __device__ __forceinline__ void tw_select_sizes(const SelectArgs& a, int n, int B, int* P_out, int* K_out) {
-  int P = n > 0 ? (n + UNIT - 1) / UNIT : 0;
-  if (P > a.max_pages) P = a.max_pages;
-  long long kp = B > 0 ? ((long long)B + UNIT - 1) / UNIT : 0;
-  if (kp > P) kp = P;
-  if (kp > a.max_sel) kp = a.max_sel;
-  *P_out = P;
-  *K_out = (int)kp;
+  ::tw_select_sizes<UNIT>(n, B, a.max_pages, a.max_sel, P_out, K_out);
 }
 
 template <int UNIT>
@@ -281,21 +278,9 @@ __global__ __launch_bounds__(256) void page_select_kernel(SelectArgs a) {
 }
 
 
-// ---- page_select for sequences of up to 8192 pages: bounds staged in LDS.
-// The Kp-th largest bound is located by bucketing the live key interval
-// linearly into 2048 buckets (one pass when the bounds are spread out),
-// narrowing to the bucket that holds it, and finishing with an exact rank
-// computation once at most 256 candidates remain.
-constexpr int SEL_LDS_PAGES = 8192;      // rows up to here run two workgroups per CU
-constexpr int SEL_LDS_MAX = 32768;       // longest row whose keys fit in LDS (128 KiB of the CU's 160)
-constexpr int SEL_NB = 2048;
-constexpr int SEL_CAP = 256;
-
-
 template <int NT, int UNIT>
 __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
-  constexpr int NW = NT / 64, BPT = SEL_NB / NT;      // waves; histogram buckets per thread
-  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
   int P, Kp;
   tw_select_sizes<UNIT>(a, a.seq_lens[b], a.budget[b], &P, &Kp);
   if (P <= a.p_above || P > a.p_upto) return;     // another launch's head (block-uniform)
@@ -307,148 +292,11 @@ __global__ __launch_bounds__(NT) void page_select_lds_kernel(SelectArgs a) {
     for (int i = tid; i < P; i += NT) out[i] = i;
     return;
   }
-  TW_STAMP(10);
-
   extern __shared__ uint32_t key_s[];             // one key per row entry (the launch sizes it to the row bound)
   __shared__ uint32_t hist[SEL_NB];
-  __shared__ uint32_t wsum[16];
-  __shared__ uint32_t red_lo[NW], red_hi[NW];
-  __shared__ uint32_t sh_bkt, sh_need, sh_pop, sh_n, sh_T, sh_need_eq;
   __shared__ uint32_t ck[SEL_CAP];
   __shared__ int32_t ci[SEL_CAP];
-
-  uint32_t lo = 0xFFFFFFFFu, hi = 0u;
-  for (int base = 0; base < P; base += 8 * NT) {    // 8 clamped loads in flight per thread
-    float v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { const int i = base + j * NT + tid; v[j] = sc[i < P ? i : P - 1]; }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int i = base + j * NT + tid;
-      if (i < P) {
-        const uint32_t k = tw_float_key(v[j]);
-        key_s[i] = k;
-        lo = k < lo ? k : lo;
-        hi = k > hi ? k : hi;
-      }
-    }
-  }
-  lo = ~tw_wave_max_u32(~lo);
-  hi = tw_wave_max_u32(hi);
-  if (lane == 0) { red_lo[wave] = lo; red_hi[wave] = hi; }
-  if (tid == 0) sh_n = 0;
-  __syncthreads();
-  uint32_t klo = red_lo[0], khi = red_hi[0];
-#pragma unroll
-  for (int w = 1; w < NW; ++w) { klo = red_lo[w] < klo ? red_lo[w] : klo; khi = red_hi[w] > khi ? red_hi[w] : khi; }
-
-  uint32_t need = (uint32_t)Kp, T = 0, need_eq = 0;
-  TW_STAMP(11);
-#pragma unroll 1
-  for (int pass = 0;; ++pass) {
-    if (pass < 6) TW_STAMP(12 + pass);
-    if (klo == khi) { T = klo; need_eq = need; break; }                    // everything left ties
-    const float smn = tw_key_to_float(klo), smx = tw_key_to_float(khi);
-    const float scale = (float)SEL_NB / (smx - smn);
-    // Buckets are linear in the bound's value while that works: a finite scale over a normal span, and only
-    // for the first passes.  Otherwise (spans in the subnormal range, infinite bounds, rows that keep falling
-    // into one bucket) they are linear in the order-preserving key, which splits any span of at least 2048
-    // keys 2048 ways and resolves a shorter one exactly, so every pass narrows the interval.
-    const bool by_key = !(scale <= 3.0e38f) || !(smx - smn >= 1.1754944e-38f) || pass >= 3;
-    const uint32_t span = khi - klo;
-    const int kshift = span < (uint32_t)SEL_NB ? 0 : 32 - __clz(span) - 11;
-    auto bucket_of = [&](uint32_t k) -> int {
-      if (by_key) return (int)((k - klo) >> kshift);
-      const int bk = (int)((tw_key_to_float(k) - smn) * scale);
-      return bk > SEL_NB - 1 ? SEL_NB - 1 : (bk < 0 ? 0 : bk);
-    };
-    for (int i = tid; i < SEL_NB; i += NT) hist[i] = 0;
-    __syncthreads();
-    for (int i = tid; i < P; i += NT) {
-      const uint32_t k = key_s[i];
-      if (k >= klo && k <= khi) atomicAdd(&hist[bucket_of(k)], 1u);
-    }
-    __syncthreads();
-    // thread t owns the BPT buckets below 2047 - BPT*t, walked downwards
-    uint32_t c[BPT], mine = 0;
-#pragma unroll
-    for (int j = 0; j < BPT; ++j) { c[j] = hist[SEL_NB - 1 - (BPT * tid + j)]; mine += c[j]; }
-    uint32_t total;
-    const uint32_t incl = tw_block_scan_u32(mine, wsum, &total);
-    uint32_t above = incl - mine;
-    if (above < need && incl >= need) {
-#pragma unroll
-      for (int j = 0; j < BPT; ++j) {
-        if (above < need && above + c[j] >= need) { sh_bkt = SEL_NB - 1 - (BPT * tid + j); sh_need = need - above; sh_pop = c[j]; }
-        above += c[j];
-      }
-    }
-    __syncthreads();
-    const int bkt = (int)sh_bkt;
-    need = sh_need;
-    const uint32_t pop = sh_pop;
-    // narrow to the keys of that bucket; collect them when few enough for the exact finish
-    const bool small = pop <= SEL_CAP && pop != need;
-    uint32_t nlo = 0xFFFFFFFFu, nhi = 0u;
-    for (int i = tid; i < P; i += NT) {
-      const uint32_t k = key_s[i];
-      if (k >= klo && k <= khi) {
-        if (bucket_of(k) == bkt) {
-          nlo = k < nlo ? k : nlo;
-          nhi = k > nhi ? k : nhi;
-          if (small) { const uint32_t at = atomicAdd(&sh_n, 1u); if (at < SEL_CAP) { ck[at] = k; ci[at] = i; } }
-        }
-      }
-    }
-    nlo = ~tw_wave_max_u32(~nlo);
-    nhi = tw_wave_max_u32(nhi);
-    if (lane == 0) { red_lo[wave] = nlo; red_hi[wave] = nhi; }
-    __syncthreads();
-    klo = red_lo[0]; khi = red_hi[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) { klo = red_lo[w] < klo ? red_lo[w] : klo; khi = red_hi[w] > khi ? red_hi[w] : khi; }
-    if (pop == need) { T = klo; need_eq = 0xFFFFFFFFu; break; }   // the whole bucket is taken
-    if (small) {
-      // exact: the candidate of rank need-1 (by bound, then by lower page id) is the last one taken
-      if (tid < (int)pop) {
-        const uint32_t kx = ck[tid];
-        const int ix = ci[tid];
-        uint32_t rank = 0, eq_lower = 0;
-        for (uint32_t j = 0; j < pop; ++j) {
-          const uint32_t kj = ck[j];
-          const int ij = ci[j];
-          rank += (kj > kx || (kj == kx && ij < ix)) ? 1u : 0u;
-          eq_lower += (kj == kx && ij < ix) ? 1u : 0u;
-        }
-        if (rank == need - 1) { sh_T = kx; sh_need_eq = eq_lower + 1; }
-      }
-      __syncthreads();
-      T = sh_T;
-      need_eq = sh_need_eq;
-      break;
-    }
-    __syncthreads();                              // red_* and hist are rewritten by the next pass
-  }
-
-  TW_STAMP(20);
-  // ---- ordered emit: thread t owns the contiguous pages [t*E, (t+1)*E)
-  const int E = (P + NT - 1) / NT;
-  const int i0 = tid * E, i1 = (i0 + E < P) ? i0 + E : P;
-  uint32_t gt = 0, eq = 0;
-  for (int i = i0; i < i1; ++i) { const uint32_t k = key_s[i]; gt += k > T ? 1u : 0u; eq += k == T ? 1u : 0u; }
-  uint32_t total;
-  const uint32_t incl = tw_block_scan_u32(gt | (eq << 16), wsum, &total);
-  uint32_t gt_before = (incl & 0xFFFFu) - gt, eq_before = (incl >> 16) - eq;
-  for (int i = i0; i < i1; ++i) {
-    const uint32_t k = key_s[i];
-    if (k > T || (k == T && eq_before < need_eq)) {
-      const uint32_t pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
-      if (pos < (uint32_t)a.max_sel) out[pos] = i;
-    }
-    gt_before += k > T ? 1u : 0u;
-    eq_before += k == T ? 1u : 0u;
-  }
-  TW_STAMP(21);
+  tw_select_row<NT, 10>(sc, P, Kp, a.max_sel, out, nullptr, key_s, hist, ck, ci);
 }
 
 template <int G>
@@ -514,7 +362,8 @@ static int launch_select(SelectArgs sa, const TwDims& d, hipStream_t s) {
 static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* budget_tokens,
                        int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
                        void* ws, size_t ws_bytes, void* stream,
-                       bool append, const void* k_new, const void* v_new, const int32_t* new_pos) {
+                       bool append, const void* k_new, const void* v_new, const int32_t* new_pos,
+                       uint32_t* arrive = nullptr, bool bounds_only = false) {
   TwDims d;
   if (int e = tw_check_kv(kv, &d)) return e;
   if (!q || !budget_tokens || !sel_pages || !sel_count || max_sel <= 0 || !kv->page_minmax) return TW_EINVAL;
@@ -533,6 +382,7 @@ static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* bu
   a.k_pool = (uint4*)kv->k_pool; a.v_pool = (uint4*)kv->v_pool;
   a.kq_pool = (uint32_t*)kv->kq_pool; a.kq_meta = (uint32_t*)kv->kq_meta;
   a.page_minmax_w = (uint4*)kv->page_minmax;
+  a.arrive = arrive;
   dim3 grid(d.Hkv, (d.max_pages + PS_PAGES_PER_WG - 1) / PS_PAGES_PER_WG, d.batch);
   tw_prof_before(TW_K_PAGE_SCORE, s);
   switch (d.G) {
@@ -542,6 +392,7 @@ static int select_impl(const twilight_kv_t* kv, const void* q, const int32_t* bu
     default: launch_score<8>(a, grid, append, d.bits, s); break;
   }
   if (int e = tw_prof_after(s)) return e;
+  if (bounds_only) return TW_OK;
 
   SelectArgs sa;
   sa.scores = (const float*)ws; sa.seq_lens = kv->seq_lens; sa.budget = budget_tokens;
@@ -619,4 +470,48 @@ extern "C" int twilight_append_select(const twilight_kv_t* kv, const void* k_new
                                       int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
                                       void* ws, size_t ws_bytes, void* stream) {
   return select_impl(kv, q, budget_tokens, sel_pages, sel_count, max_sel, ws, ws_bytes, stream, true, k_new, v_new, new_pos);
+}
+
+// Selector and pruner in one call (Section 4.1's pipeline up to the pruned index sets): page bounds (with the step's
+// new token appended on the way when k_new is given), then - where the lists are short enough for one workgroup per
+// head - a single launch that picks each head's pages, scores their tokens from the 4-bit copy of K, runs top-p and
+// builds the group's union; otherwise the launches of twilight_select_pages and twilight_topp_prune.
+extern "C" int twilight_select_prune(const twilight_kv_t* kv, const void* k_new, const void* v_new, const int32_t* new_pos,
+                                     const void* q, const int32_t* budget_tokens, float p,
+                                     int32_t* sel_pages, int32_t* sel_count, int32_t max_sel,
+                                     int32_t* kept_count, int32_t* kept_idx, int32_t kept_stride,
+                                     int32_t* union_count, int32_t* union_idx, int32_t union_stride,
+                                     uint32_t* status, void* ws, size_t ws_bytes, void* stream) {
+  TwDims d;
+  if (int e = tw_check_kv(kv, &d)) return e;
+  if (!q || !budget_tokens || !sel_pages || !sel_count || !kept_count || !union_count || !union_idx || !status ||
+      !kv->kq_pool || !kv->kq_meta || max_sel <= 0) return TW_EINVAL;
+  if (!(p > 0.f) || p > 1.f || union_stride <= 0 || (kept_idx && kept_stride <= 0)) return TW_EINVAL;
+  if ((long long)max_sel * TW_PAGE > (1ll << 22)) return TW_EINVAL;
+  const size_t sel_bytes = twilight_workspace_bytes(TW_WS_SELECT, kv, max_sel, 0);
+  const size_t need = twilight_workspace_bytes(TW_WS_SELECT_PRUNE, kv, max_sel, 0);
+  if (!ws || need == 0 || ws_bytes < need) return TW_EWORKSPACE;
+  void* ws_prune = (char*)ws + sel_bytes;
+  const bool append = k_new != nullptr;
+  // 2: selection and scoring inside the top-p kernel, 1: scoring only, 0: the separate launches
+  const int can = tw_prune_fused_ok(d, max_sel, true) ? 2 : (tw_prune_fused_ok(d, max_sel, false) ? 1 : 0);
+  int mode = can;
+  // few heads with long lists (a single long sequence): one workgroup per head cannot pull its list fast enough, the
+  // scoring launch's many workgroups can (32 heads x 8192 candidates: 51.8 us per step separately, 56.0 us fused)
+  if (max_sel * TW_PAGE > 4096 && (long long)d.batch * d.Hq < tw_num_cus()) mode = 0;
+#ifdef TW_TUNING
+  if (const char* e = getenv("TW_FUSE")) { const int m = atoi(e); mode = m < can ? m : can; }
+#endif
+  if (mode == 0) {
+    if (int e = select_impl(kv, q, budget_tokens, sel_pages, sel_count, max_sel, ws, sel_bytes, stream, append, k_new, v_new,
+                            new_pos)) return e;
+    return twilight_topp_prune(kv, q, sel_pages, sel_count, max_sel, p, kept_count, kept_idx, kept_stride, union_count,
+                               union_idx, union_stride, status, ws_prune, ws_bytes - sel_bytes, stream);
+  }
+  uint32_t* arrive = (uint32_t*)((char*)ws_prune + tw_prune_layout(d, max_sel, false).arrive);
+  if (int e = select_impl(kv, q, budget_tokens, sel_pages, sel_count, max_sel, ws, sel_bytes, stream, append, k_new, v_new,
+                          new_pos, arrive, mode == 2)) return e;
+  return tw_prune_fused(kv, d, q, mode == 2 ? (const float*)ws : nullptr, budget_tokens, sel_pages, sel_count, max_sel, p,
+                        kept_count, kept_idx, kept_stride, union_count, union_idx, union_stride, status, ws_prune,
+                        (hipStream_t)stream);
 }

@@ -27,6 +27,16 @@ PruneWs tw_prune_layout_tokens(const TwDims& d, int max_cand);   // token-list c
 int tw_score_all_tokens_masked(const twilight_kv_t* kv, const TwDims& d, const void* q, const uint32_t* chmask, float* scores,
                                hipStream_t s);
 
+// The pruner with the scoring - and, with `bounds`, the page selection - inside the per-head top-p kernel (per-head
+// page lists, 4-bit codes, rows short enough for registers: tw_prune_fused_ok).  ws = a TW_WS_PRUNE workspace for
+// this max_sel whose arrival counters (tw_prune_layout(d, max_sel, false).arrive, batch * Hkv * TW_CTR words) a
+// kernel earlier on the stream has cleared.
+bool tw_prune_fused_ok(const TwDims& d, int max_sel, bool with_select);
+int tw_prune_fused(const twilight_kv_t* kv, const TwDims& d, const void* q, const float* bounds, const int32_t* budget,
+                   int32_t* sel_pages, int32_t* sel_count, int32_t max_sel, float p, int32_t* kept_count, int32_t* kept_idx,
+                   int32_t kept_stride, int32_t* union_count, int32_t* union_idx, int32_t union_stride,
+                   uint32_t* status, void* ws, hipStream_t s);
+
 #ifdef __HIPCC__
 // softmax numerator e in [0, 1] -> floor(e * 2^40), exactly: the top 8 bits and the remaining 32
 // bits are taken by two float -> integer truncations (every step below is exact in fp32: scaling by

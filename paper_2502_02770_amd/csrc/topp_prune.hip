@@ -19,6 +19,7 @@
 // Rows too long for registers take the multi-workgroup path in topp_wide.hip.
 #include <stdlib.h>
 #include "topp_common.h"
+#include "select_body.h"
 
 namespace {
 
@@ -78,6 +79,28 @@ __device__ __forceinline__ void tw_quantize_q(const uint16_t* q, int (*qi_s)[32]
   }
 }
 
+// The same for one head whose 128 values the threads 0..127 already hold (v; others pass 0).
+__device__ __forceinline__ void tw_quantize_q1(float v, int (*qi_s)[32], float* red, float* c_s) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float av = fabsf(v);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) av = fmaxf(av, __shfl_xor(av, o, 64));
+  if (lane == 0 && wave < 2) red[wave] = av;
+  __syncthreads();
+  const float sq = __fmul_rn(fmaxf(red[0], red[1]), kInv127);
+  if (tid < 128) {
+    int qi = 0;
+    if (sq > 0.f) {
+      float t = rintf(__fdiv_rn(v, sq));
+      t = fminf(fmaxf(t, -127.f), 127.f);
+      qi = (int)t;
+    }
+    ((int8_t*)qi_s[0])[tid] = (int8_t)qi;
+  }
+  if (tid == 0) c_s[0] = __fmul_rn(sq, kRsqrtD);
+  __syncthreads();
+}
+
 // One lane's group of 32 codes of slot (token, group) `idx` of the pool, as 8 dot4 operands
 // (4 dims each, in the order of the query words); 8-bit codes come out as code - 128.
 // STREAM: the codes are read once (every page a candidate, all heads of the group in one workgroup) and loaded
@@ -98,6 +121,29 @@ __device__ __forceinline__ void tw_load_codes(const uint4* kq_pool, long long id
     const uint4 c0 = kq_pool[idx * 2], c1 = kq_pool[idx * 2 + 1];
     u[0] = c0.x ^ 0x80808080; u[1] = c0.y ^ 0x80808080; u[2] = c0.z ^ 0x80808080; u[3] = c0.w ^ 0x80808080;
     u[4] = c1.x ^ 0x80808080; u[5] = c1.y ^ 0x80808080; u[6] = c1.z ^ 0x80808080; u[7] = c1.w ^ 0x80808080;
+  }
+}
+// The same in two steps, so that a kernel can ask for several slots' codes before it unpacks the first.
+template <int BITS, bool STREAM = false>
+__device__ __forceinline__ void tw_load_raw(const uint4* kq_pool, long long idx, uint4 (&r)[BITS == 8 ? 2 : 1]) {
+  if (BITS == 4) r[0] = STREAM ? tw_ld_stream(kq_pool + idx) : kq_pool[idx];
+  else if (BITS == 2) { const uint2 c = ((const uint2*)kq_pool)[idx]; r[0] = make_uint4(c.x, c.y, 0u, 0u); }
+  else { r[0] = kq_pool[idx * 2]; r[BITS == 8 ? 1 : 0] = kq_pool[idx * 2 + 1]; }
+}
+template <int BITS>
+__device__ __forceinline__ void tw_unpack_codes(const uint4 (&r)[BITS == 8 ? 2 : 1], int (&u)[8]) {
+  if (BITS == 4) {
+    u[0] = r[0].x & 0x0F0F0F0F; u[1] = (r[0].x >> 4) & 0x0F0F0F0F;
+    u[2] = r[0].y & 0x0F0F0F0F; u[3] = (r[0].y >> 4) & 0x0F0F0F0F;
+    u[4] = r[0].z & 0x0F0F0F0F; u[5] = (r[0].z >> 4) & 0x0F0F0F0F;
+    u[6] = r[0].w & 0x0F0F0F0F; u[7] = (r[0].w >> 4) & 0x0F0F0F0F;
+  } else if (BITS == 2) {
+    u[0] = r[0].x & 0x03030303; u[1] = (r[0].x >> 2) & 0x03030303; u[2] = (r[0].x >> 4) & 0x03030303; u[3] = (r[0].x >> 6) & 0x03030303;
+    u[4] = r[0].y & 0x03030303; u[5] = (r[0].y >> 2) & 0x03030303; u[6] = (r[0].y >> 4) & 0x03030303; u[7] = (r[0].y >> 6) & 0x03030303;
+  } else {
+    constexpr int H = BITS == 8 ? 1 : 0;
+    u[0] = r[0].x ^ 0x80808080; u[1] = r[0].y ^ 0x80808080; u[2] = r[0].z ^ 0x80808080; u[3] = r[0].w ^ 0x80808080;
+    u[4] = r[H].x ^ 0x80808080; u[5] = r[H].y ^ 0x80808080; u[6] = r[H].z ^ 0x80808080; u[7] = r[H].w ^ 0x80808080;
   }
 }
 // I = sum over the group's 32 dims of q * code (i0 = 128 * sum q for 8-bit codes, else 0)
@@ -187,17 +233,28 @@ __global__ __launch_bounds__(256) void int4_score_kernel(ScoreArgs a) {
   for (;;) {
 #pragma unroll 1
   for (int k0 = 0; k0 < npages; k0 += UNR) {
+   // UNR pages per round: first all their loads (unconditional: an unmapped page or one past the wave's last reads
+   // pool page 0 and is masked below), so that they are in flight together, then the arithmetic
+   uint4 raw[UNR][BITS == 8 ? 2 : 1];
+   uint32_t metas[UNR];
+   int lps[UNR], pools[UNR];
 #pragma unroll
    for (int kk = 0; kk < UNR; ++kk) {
-    const int k = k0 + kk;                     // wave-uniform; pages past the end act as invalid
-    const int lp = __builtin_amdgcn_readlane(my_lp, k & 63);
-    const int pool = k < npages ? __builtin_amdgcn_readlane(my_pool, k & 63) : -1;
-    // unconditional loads (an unmapped page reads pool page 0 and is masked below), so that the
-    // four pages of an unrolled step are in flight together
-    const long long blk = ((long long)(pool >= 0 ? pool : 0) * a.Hkv + g) * 64;
+    const int k = k0 + kk;                     // wave-uniform
+    lps[kk] = __builtin_amdgcn_readlane(my_lp, k & 63);
+    const int pl = __builtin_amdgcn_readlane(my_pool, k & 63);
+    pools[kk] = k < npages ? pl : -1;
+    const long long blk = ((long long)(pools[kk] >= 0 ? pools[kk] : 0) * a.Hkv + g) * 64;
+    tw_load_raw<BITS, FULL>(a.kq_pool, blk + lane, raw[kk]);
+    metas[kk] = FULL ? __builtin_nontemporal_load(a.kq_meta + blk + lane) : a.kq_meta[blk + lane];
+   }
+#pragma unroll
+   for (int kk = 0; kk < UNR; ++kk) {
+    const int k = k0 + kk;
+    const int lp = lps[kk], pool = pools[kk];
     int u[8];
-    tw_load_codes<BITS, FULL>(a.kq_pool, blk + lane, u);
-    const uint32_t meta = FULL ? __builtin_nontemporal_load(a.kq_meta + blk + lane) : a.kq_meta[blk + lane];
+    tw_unpack_codes<BITS>(raw[kk], u);
+    const uint32_t meta = metas[kk];
     const int tok = lp * TW_PAGE + (lane >> 2);
     const bool valid = pool >= 0 && tok < n;
     const long long slot = (long long)(first + k) * TW_PAGE + (lane >> 2);
@@ -498,6 +555,19 @@ struct HeadArgs {
   int Hq, Hkv, max_pages, max_sel, cand_stride, kept_stride, words_stride, union_stride;
   int n_above, n_upto;        // this launch takes the heads with n_above < candidates <= n_upto
   float p;
+  // scoring inside the kernel (FUSE): the query, the quantised copy of K and the page table
+  const uint16_t* q;
+  const int32_t* page_table;
+  const uint4* kq_pool;
+  const uint32_t* kq_meta;
+  long long pool_pages;
+  int remap;                  // FUSE: workgroup -> head mapping that keeps the heads of a KV head on one XCD
+  // page selection inside the kernel as well (FUSE == 2): the bounds of all pages and the budgets; the lists go
+  // to sel_pages_w / sel_count_w
+  const float* bounds;        // [b][Hq][max_pages]
+  const int32_t* budget;      // [b] tokens
+  int32_t* sel_pages_w;
+  int32_t* sel_count_w;
 };
 
 constexpr int HP_CAP = 64;                    // exact resolve handles up to this many scores
@@ -506,19 +576,39 @@ constexpr int HP_USTAGE = 2048;               // union lists up to this length l
 
 // TOK: the candidates are token positions (sel_pages = the token lists, max_sel = their row length,
 // sel_count in tokens) instead of pages of 16 slots.
-template <int NT, int EPT, int G, bool TOK = false>
+// FUSE >= 1: the estimated scores are computed here, from the head's page list, instead of being read from the row a
+// scoring launch wrote: the workgroup's waves share the list (one page of 64 (token, group) lanes per wave and step,
+// the arithmetic of int4_score_kernel), the scores cross to their owner threads through LDS.
+// FUSE == 2: the page list too is made here, from the bounds of all pages (the selection of page_select_lds_kernel).
+template <int NT, int EPT, int G, bool TOK = false, int FUSE = 0>
 __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadArgs a) {
   constexpr int NW = NT / 64;
-  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int b_ = blockIdx.y, h_ = blockIdx.x;
+  if (FUSE && a.remap) {
+    // Workgroups go to the 8 XCDs round robin in dispatch order.  The G heads of a KV head select largely the
+    // same pages: they take G consecutive workgroups of one XCD, so that each finds the others' pages in its L2.
+    const unsigned L = blockIdx.y * gridDim.x + blockIdx.x, xcd = L & 7u, r = L >> 3;
+    const unsigned grp = (r / G) * 8u + xcd;             // (sequence, KV head), batch * Hkv a multiple of 8
+    b_ = (int)(grp / (unsigned)a.Hkv);
+    h_ = (int)(grp % (unsigned)a.Hkv) * G + (int)(r % G);
+  }
+  const int b = b_, h = h_;
   const int bh = b * a.Hq + h;
   const int n = a.seq_lens[b];
   int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
   if (P > a.max_pages) P = a.max_pages;
   const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
   const int nwords = (ntok + 31) >> 5;
-  int count = a.sel_count[bh];
-  if (count > a.max_sel) count = a.max_sel;
-  if (count < 0) count = 0;
+  int count;
+  if (FUSE == 2) {
+    int P2;
+    tw_select_sizes<TW_PAGE>(n, a.budget[b], a.max_pages, a.max_sel, &P2, &count);
+  } else {
+    count = a.sel_count[bh];
+    if (count > a.max_sel) count = a.max_sel;
+    if (count < 0) count = 0;
+  }
   const int N = TOK ? count : count * TW_PAGE;
   if (N <= a.n_above || N > a.n_upto) return;     // another launch's head (block-uniform)
   const float* row = a.scores + (long long)bh * a.cand_stride;
@@ -529,12 +619,37 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
   __shared__ uint32_t histC[HP_NB];
   __shared__ unsigned long long cand_mass[HP_CAP];
   __shared__ uint32_t cand_key[HP_CAP];
-  __shared__ uint32_t bitmap[HP_BITMAP_WORDS];
+  __shared__ uint32_t big_s[HP_BITMAP_WORDS + HP_USTAGE];   // position bitmap, then the union list on its way out
+  uint32_t* const bitmap = big_s;                            // (FUSE: first the scores on their way to their owners)
+  int32_t* const ustage = (int32_t*)(big_s + HP_BITMAP_WORDS);
   __shared__ unsigned long long tail_s[NW];
   __shared__ uint32_t ws32[16];
   __shared__ float redf[NW];
   __shared__ uint32_t sh_n, sh_kept, sh_T, sh_last;
-  __shared__ int32_t ustage[HP_USTAGE];            // the group's union list on its way out
+
+  __shared__ int32_t pages_s[FUSE == 2 ? 512 : 1];   // FUSE == 2: the head's page list ...
+  __shared__ int32_t pool_s[FUSE == 2 ? 512 : 1];    // ... and the pages' places in the pool
+  float qv = 0.f;                                    // FUSE: this thread's element of the query, asked for early
+  if (FUSE && tid < 128) qv = __uint_as_float((uint32_t)a.q[(long long)bh * 128 + tid] << 16);
+  if (FUSE == 2) {
+    static_assert(4096 + SEL_NB + 2 * SEL_CAP <= HP_BITMAP_WORDS + HP_USTAGE, "the selection's arrays lie in big_s");
+    int32_t* const out = a.sel_pages_w + (long long)bh * a.max_sel;
+    const int32_t* const ptab = a.page_table + (long long)b * a.max_pages;
+    if (tid == 0) a.sel_count_w[bh] = count;
+    if (count == P) {                               // the budget covers the sequence (block-uniform)
+      for (int i = tid; i < P; i += NT) { out[i] = i; pages_s[i] = i; pool_s[i] = ptab[i]; }
+    } else if (count > 0) {
+      // page-table entries of the pages this thread will list, in flight while the threshold is found
+      constexpr int EMAX = 4096 / NT;
+      const int E = (P + NT - 1) / NT;
+      int32_t pt[EMAX];
+#pragma unroll
+      for (int e = 0; e < EMAX; ++e) { const int i = tid * E + e; pt[e] = ptab[i < P ? i : P - 1]; }
+      tw_select_row<NT, 30, EMAX>(a.bounds + (long long)bh * a.max_pages, P, count, a.max_sel, out, pages_s, big_s, big_s + 4096,
+                                  big_s + 4096 + SEL_NB, (int32_t*)(big_s + 4096 + SEL_NB + SEL_CAP), pt, pool_s);
+    }
+    __syncthreads();                                // list complete; big_s free for the scores
+  }
 
   // ---- scores into registers; logical pages of the owned slots
   // (loads do not wait for the list length: anything inside the row is readable, slots at or
@@ -542,6 +657,72 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
   constexpr int NPG = TOK ? EPT : (EPT + 15) / 16; // pages a thread's slots fall into (a part of one if EPT < 16); TOK: one token per slot
   float s[EPT];
   int pg[NPG];
+  if (FUSE) {
+    static_assert(NT * EPT <= (HP_BITMAP_WORDS + HP_USTAGE), "scores of a row must fit the staging array");
+    float* const sc_s = (float*)big_s;
+    __shared__ int qi_s[1][32];
+    __shared__ float qred[4];
+    __shared__ float qc_s[1];
+    // this wave's share of the list: lane k holds its k-th page (at most EPT * 4 <= 32 of them)
+    constexpr int UF = NT >= 1024 ? 8 : 4;            // pages in flight per wave (register budget)
+    const int ppw = ((count + NW - 1) / NW + UF - 1) & ~(UF - 1);
+    const int first = __builtin_amdgcn_readfirstlane(wave) * ppw;   // (scalar: the loop below is wave-uniform)
+    int my_lp = -1, my_pool = -1;
+    if (lane < ppw && first + lane < count) {
+      my_lp = FUSE == 2 ? pages_s[first + lane] : a.sel_pages[(long long)bh * a.max_sel + first + lane];
+      if (my_lp >= 0 && my_lp < P) {
+        const int pp = FUSE == 2 ? pool_s[first + lane] : a.page_table[(long long)b * a.max_pages + my_lp];
+        if (pp >= 0 && pp < a.pool_pages) my_pool = pp;
+      }
+    }
+    int npages = count - first;
+    npages = npages < 0 ? 0 : (npages > ppw ? ppw : npages);
+    tw_quantize_q1(qv, qi_s, qred, qc_s);
+    const int j = lane & 3, g = h / G;
+    int qw[8], qs = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      qw[k] = qi_s[0][8 * j + k];
+      qs = __builtin_amdgcn_sdot4(qw[k], 0x01010101, qs, false);
+    }
+    const float qsf = (float)qs, cc = qc_s[0];
+#pragma unroll 1
+    for (int k0 = 0; k0 < npages; k0 += UF) {
+      // UF pages per round: all their loads first (unconditional: lanes past the wave's last page hold pool -1 and
+      // read pool page 0), then the arithmetic; every lane of a quad stores the token's score (same word), so the
+      // round has no branches and the loads stay together.  Slots past the list's end get -inf (inside the array:
+      // NW * ppw <= NT * EPT / 16 pages).
+      uint4 nib[UF];
+      uint32_t meta[UF];
+      int lpk[UF], plk[UF];
+#pragma unroll
+      for (int kk = 0; kk < UF; ++kk) {
+        lpk[kk] = __builtin_amdgcn_readlane(my_lp, (k0 + kk) & 63);
+        plk[kk] = __builtin_amdgcn_readlane(my_pool, (k0 + kk) & 63);
+        const long long blk = ((long long)(plk[kk] >= 0 ? plk[kk] : 0) * a.Hkv + g) * 64;
+        nib[kk] = a.kq_pool[blk + lane];
+        meta[kk] = a.kq_meta[blk + lane];
+      }
+#pragma unroll
+      for (int kk = 0; kk < UF; ++kk) {
+        int u[8];
+        u[0] = nib[kk].x & 0x0F0F0F0F; u[1] = (nib[kk].x >> 4) & 0x0F0F0F0F;
+        u[2] = nib[kk].y & 0x0F0F0F0F; u[3] = (nib[kk].y >> 4) & 0x0F0F0F0F;
+        u[4] = nib[kk].z & 0x0F0F0F0F; u[5] = (nib[kk].z >> 4) & 0x0F0F0F0F;
+        u[6] = nib[kk].w & 0x0F0F0F0F; u[7] = (nib[kk].w >> 4) & 0x0F0F0F0F;
+        const bool valid = plk[kk] >= 0 && lpk[kk] * TW_PAGE + (lane >> 2) < n;
+        const float T = tw_token_sum(meta[kk], tw_group_dot(qw, u, 0), qsf);
+        sc_s[(first + k0 + kk) * TW_PAGE + (lane >> 2)] = valid ? __fmul_rn(T, cc) : -__builtin_inff();
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < EPT / 4; ++v) {
+      const float4 x = *(const float4*)(sc_s + c0 + 4 * v);
+      s[4 * v] = x.x; s[4 * v + 1] = x.y; s[4 * v + 2] = x.z; s[4 * v + 3] = x.w;
+    }
+    __syncthreads();                               // the bitmap, cleared below, lies in the same words
+  } else
 #pragma unroll
   for (int v = 0; v < EPT / 4; ++v) {              // clamped, unconditional: all loads go out together
     const int cc = c0 + 4 * v < a.cand_stride ? c0 + 4 * v : a.cand_stride - 4;
@@ -559,7 +740,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
 #pragma unroll
     for (int v = 0; v < NPG; ++v) {
       const int pi = (c0 >> 4) + v < a.max_sel ? (c0 >> 4) + v : a.max_sel - 1;
-      pg[v] = a.sel_pages[(long long)bh * a.max_sel + pi];
+      pg[v] = FUSE == 2 ? pages_s[pi] : a.sel_pages[(long long)bh * a.max_sel + pi];
     }
   }
 #pragma unroll
@@ -1031,13 +1212,13 @@ int run_score(const twilight_kv_t* kv, const TwDims& d, const void* q, const int
 }
 
 
-template <int NT, int EPT, bool TOK>
+template <int NT, int EPT, bool TOK, int FUSE>
 void launch_topp_one(const HeadArgs& f, int G, dim3 grid, hipStream_t s) {
   switch (G) {
-    case 1: TW_LAUNCH((topp_head_kernel<NT, EPT, 1, TOK>), grid, dim3(NT), 0, s, f); break;
-    case 2: TW_LAUNCH((topp_head_kernel<NT, EPT, 2, TOK>), grid, dim3(NT), 0, s, f); break;
-    case 4: TW_LAUNCH((topp_head_kernel<NT, EPT, 4, TOK>), grid, dim3(NT), 0, s, f); break;
-    default: TW_LAUNCH((topp_head_kernel<NT, EPT, 8, TOK>), grid, dim3(NT), 0, s, f); break;
+    case 1: TW_LAUNCH((topp_head_kernel<NT, EPT, 1, TOK, FUSE>), grid, dim3(NT), 0, s, f); break;
+    case 2: TW_LAUNCH((topp_head_kernel<NT, EPT, 2, TOK, FUSE>), grid, dim3(NT), 0, s, f); break;
+    case 4: TW_LAUNCH((topp_head_kernel<NT, EPT, 4, TOK, FUSE>), grid, dim3(NT), 0, s, f); break;
+    default: TW_LAUNCH((topp_head_kernel<NT, EPT, 8, TOK, FUSE>), grid, dim3(NT), 0, s, f); break;
   }
 }
 
@@ -1047,22 +1228,24 @@ void launch_topp_one(const HeadArgs& f, int G, dim3 grid, hipStream_t s) {
 //    workgroup has a CU to itself at this register count: 8 x 32 x 4 = 1024 heads took 35.8 us that way, 22.9 us so);
 //  - many heads with a bound above 4096 candidates (ragged batches): heads of at most 4096 candidates go to a
 //    512-thread launch of their own, the longer ones to the 1024-thread launch.
-template <bool TOK>
+// FUSE: the kernels score the candidates themselves (page lists, 4-bit codes).
+template <bool TOK, int FUSE = 0>
 int launch_topp(HeadArgs f, const TwDims& d, int cand_stride, hipStream_t s) {
   const dim3 grid(d.Hq, d.batch);
   const long long heads = (long long)d.batch * d.Hq;
+  f.remap = (FUSE != 0 && ((long long)d.batch * d.Hkv) % 8 == 0) ? 1 : 0;
   f.n_above = -1; f.n_upto = cand_stride;
   if (cand_stride > 4096 && heads > 2ll * tw_num_cus()) {
     f.n_upto = 4096;
-    tw_prof_before(TW_K_TOPP, s);
-    launch_topp_one<512, 8, TOK>(f, d.G, grid, s);
+    tw_prof_before(FUSE == 2 ? TW_K_SELECT_SCORE_TOPP : (FUSE == 1 ? TW_K_SCORE_TOPP : TW_K_TOPP), s);
+    launch_topp_one<512, 8, TOK, FUSE>(f, d.G, grid, s);
     if (int e = tw_prof_after(s)) return e;
     f.n_above = 4096; f.n_upto = cand_stride;
   }
-  tw_prof_before(TW_K_TOPP, s);
-  if (cand_stride <= 4096 && heads > tw_num_cus()) launch_topp_one<512, 8, TOK>(f, d.G, grid, s);
-  else if (cand_stride <= 4096) launch_topp_one<1024, 4, TOK>(f, d.G, grid, s);
-  else launch_topp_one<1024, 8, TOK>(f, d.G, grid, s);
+  tw_prof_before(FUSE == 2 ? TW_K_SELECT_SCORE_TOPP : (FUSE == 1 ? TW_K_SCORE_TOPP : TW_K_TOPP), s);
+  if (cand_stride <= 4096 && heads > tw_num_cus()) launch_topp_one<512, 8, TOK, FUSE>(f, d.G, grid, s);
+  else if (cand_stride <= 4096) launch_topp_one<1024, 4, TOK, FUSE>(f, d.G, grid, s);
+  else launch_topp_one<1024, 8, TOK, FUSE>(f, d.G, grid, s);
   return tw_prof_after(s);
 }
 
@@ -1172,8 +1355,37 @@ extern "C" int twilight_topp_prune(const twilight_kv_t* kv, const void* q, const
     f.union_count = union_count; f.union_idx = union_idx; f.status = status;
     f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_sel; f.cand_stride = cand_stride;
     f.kept_stride = kept_stride; f.words_stride = words_stride; f.union_stride = union_stride; f.p = p;
+    f.q = nullptr; f.page_table = nullptr; f.kq_pool = nullptr; f.kq_meta = nullptr; f.pool_pages = 0;
+    f.bounds = nullptr; f.budget = nullptr; f.sel_pages_w = nullptr; f.sel_count_w = nullptr;
     return launch_topp<false>(f, d, cand_stride, s);
   }
+}
+
+// Pruner over per-head page lists with the scoring done inside the top-p kernel (one launch).  The arrival
+// counters at `ws` + layout.arrive must be zero: a kernel earlier on the stream clears them.
+// bounds != nullptr: the kernel also selects the head's pages from the bounds of all pages ([b][Hq][max_pages],
+// with the budgets) and writes the lists to sel_pages / sel_count; else it reads the lists from there.
+bool tw_prune_fused_ok(const TwDims& d, int max_sel, bool with_select) {
+  if (d.bits != 4 || max_sel <= 0 || !tw_prune_uses_head_kernel(d, false, max_sel)) return false;
+  return !with_select || d.max_pages <= 4096;      // the selection's keys share the kernel's LDS staging array
+}
+int tw_prune_fused(const twilight_kv_t* kv, const TwDims& d, const void* q, const float* bounds, const int32_t* budget,
+                   int32_t* sel_pages, int32_t* sel_count, int32_t max_sel, float p, int32_t* kept_count, int32_t* kept_idx,
+                   int32_t kept_stride, int32_t* union_count, int32_t* union_idx, int32_t union_stride,
+                   uint32_t* status, void* ws, hipStream_t s) {
+  const PruneWs L = tw_prune_layout(d, max_sel, false);
+  HeadArgs f;
+  f.scores = nullptr; f.sel_pages = sel_pages; f.sel_count = sel_count; f.seq_lens = kv->seq_lens;
+  f.kept_count = kept_count; f.kept_idx = kept_idx; f.bitmaps = (uint32_t*)((char*)ws + L.bitmaps);
+  f.arrive = (uint32_t*)((char*)ws + L.arrive);
+  f.union_count = union_count; f.union_idx = union_idx; f.status = status;
+  f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_sel; f.cand_stride = max_sel * TW_PAGE;
+  f.kept_stride = kept_stride; f.words_stride = L.words_stride; f.union_stride = union_stride; f.p = p;
+  f.q = (const uint16_t*)q; f.page_table = kv->page_table; f.kq_pool = (const uint4*)kv->kq_pool;
+  f.kq_meta = (const uint32_t*)kv->kq_meta; f.pool_pages = d.pool_pages;
+  f.bounds = bounds; f.budget = budget; f.sel_pages_w = sel_pages; f.sel_count_w = sel_count;
+  if (bounds) return launch_topp<false, 2>(f, d, max_sel * TW_PAGE, s);
+  return launch_topp<false, 1>(f, d, max_sel * TW_PAGE, s);
 }
 
 // ------------------------------------------------------------------ token-list candidates
@@ -1266,5 +1478,7 @@ extern "C" int twilight_topp_prune_tokens(const twilight_kv_t* kv, const void* q
   f.union_count = union_count; f.union_idx = union_idx; f.status = status;
   f.Hq = d.Hq; f.Hkv = d.Hkv; f.max_pages = d.max_pages; f.max_sel = max_cand; f.cand_stride = max_cand;
   f.kept_stride = kept_stride; f.words_stride = L.words_stride; f.union_stride = union_stride; f.p = p;
+  f.q = nullptr; f.page_table = nullptr; f.kq_pool = nullptr; f.kq_meta = nullptr; f.pool_pages = 0;
+  f.bounds = nullptr; f.budget = nullptr; f.sel_pages_w = nullptr; f.sel_count_w = nullptr;
   return launch_topp<true>(f, d, max_cand, s);
 }

@@ -69,6 +69,10 @@ extern "C" size_t twilight_workspace_bytes(int which, const twilight_kv_t* kv, i
       const int bound = max_sel > 0 ? max_sel : d.max_pages;
       return tw_prune_layout(d, bound, max_sel <= 0).total;
     }
+    case TW_WS_SELECT_PRUNE: {
+      if (max_sel <= 0) return 0;
+      return align256(bh * d.max_pages * 4) + tw_prune_layout(d, max_sel, false).total;
+    }
     case TW_WS_PRUNE_TOKENS:
       if (max_sel <= 0 || (max_sel & 15) || max_sel > 8192) return 0;
       return tw_prune_layout_tokens(d, max_sel).total;
@@ -102,7 +106,7 @@ extern "C" int twilight_abi_version(void) { return TW_ABI_VERSION; }
 
 extern "C" const char* twilight_kernel_name(int id) {
   static const char* names[TW_K_COUNT] = {"kquant_append", "page_score", "page_select", "int4_score",
-                                          "topp", "union", "sparse_decode", "combine"};
+                                          "topp", "union", "sparse_decode", "combine", "score_topp", "select_score_topp"};
   return (id >= 0 && id < TW_K_COUNT) ? names[id] : "?";
 }
 

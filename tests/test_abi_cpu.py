@@ -70,9 +70,17 @@ def test_bad_arguments_are_rejected_on_the_host(T):
     assert L.twilight_append_select(ctypes.byref(kv), None, None, one, one, one, one, one, 4, one, 1 << 20, None) == -1
     assert L.twilight_append_select(ctypes.byref(kv), one, None, None, one, one, one, one, 4, one, 1 << 20, None) == -1
     assert L.twilight_append_select(ctypes.byref(kv), one, None, one, one, one, one, one, 4, one, 16, None) == -2
-    kv.quant_bits = 8
-    assert L.twilight_append_select(ctypes.byref(kv), one, None, one, one, one, one, one, 4, one, 1 << 20, None) == -1
-    kv.quant_bits = 4
+    # selector + pruner in one call: budgets, list outputs, p in (0, 1], its own workspace size
+    f09 = ctypes.c_float(0.9)
+    sp = lambda budget, p, ws_bytes, sel=one: L.twilight_select_prune(ctypes.byref(kv), None, None, None, one, budget, p, sel, one, 4,
+                                                                      one, None, 0, one, one, 64, one, one, ws_bytes, None)
+    assert sp(None, f09, 1 << 20) == -1
+    assert sp(one, f09, 1 << 20, None) == -1
+    assert sp(one, ctypes.c_float(1.5), 1 << 20) == -1
+    assert sp(one, f09, 16) == -2
+    assert T.twilight_workspace_bytes(T.TW_WS_SELECT_PRUNE, kv, 4, 0) == (T.twilight_workspace_bytes(T.TW_WS_SELECT, kv, 4, 0)
+                                                                          + T.twilight_workspace_bytes(T.TW_WS_PRUNE, kv, 4, 0))
+    assert T.twilight_workspace_bytes(T.TW_WS_SELECT_PRUNE, kv, 0, 0) == 0
     # per-head variant: no dense mode, needs counts, checks its own workspace size
     assert L.twilight_sparse_decode_per_head(ctypes.byref(kv), one, one, None, 64, one, None, one, 1 << 20, None) == -1
     assert L.twilight_sparse_decode_per_head(ctypes.byref(kv), one, None, one, 64, one, None, one, 1 << 20, None) == -1
@@ -95,7 +103,6 @@ def test_bad_arguments_are_rejected_on_the_host(T):
     assert L.twilight_topp_prune(ctypes.byref(long_row), one, None, None, 0, ctypes.c_float(0.9), one, None, 0, one, one,
                                  64, one, one, 1 << 40, None) == -1                                # 2^24 candidates
     # token-list candidates: row length a multiple of 16 and at most 8192, sequences of at most 196608 tokens
-    f09 = ctypes.c_float(0.9)
     assert L.twilight_topp_prune_tokens(ctypes.byref(kv), one, one, one, 100, f09, one, None, 0, one, one, 64, one, one, 1 << 30, None) == -1
     assert L.twilight_topp_prune_tokens(ctypes.byref(kv), one, one, one, 8208, f09, one, None, 0, one, one, 64, one, one, 1 << 30, None) == -1
     assert L.twilight_topp_prune_tokens(ctypes.byref(kv), one, None, one, 64, f09, one, None, 0, one, one, 64, one, one, 1 << 30, None) == -1

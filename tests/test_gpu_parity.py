@@ -96,8 +96,9 @@ def run_pipeline(w, cache, with_kept=True):
     q = w.q.to(dev)
     if cache.v_pool is None:                       # pruner-only workload (no V): stages 1-2
         if not st.full:
-            st.select(q, w.budget.to(dev))
-        st.prune(q, w.p)
+            st.select_prune(None, None, None, q, w.budget.to(dev), w.p)
+        else:
+            st.prune(q, w.p)
     else:
         st.run(q, w.budget.to(dev), w.p)
     torch.cuda.synchronize()
@@ -471,6 +472,104 @@ def test_append_select_equals_append_then_select(bits):
     assert torch.equal(c.kq_pool[pg], ref.kq_pool[pg]) and torch.equal(c.page_minmax[pg].view(torch.int16), ref.page_minmax[pg].view(torch.int16))
     # the rest of the step on the fused cache, against the oracle
     pipeline_against_oracle(w, bits, b_)
+
+
+def _lists_equal(a, b, what):
+    """Two DecodeSteps hold the same page lists, kept sets and unions (entries past the counts are not compared)."""
+    for name in ("sel_count", "kept_count", "union_count"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), (what, name)
+    for lst, cnt in (("sel_pages", "sel_count"), ("kept_idx", "kept_count"), ("union_idx", "union_count")):
+        x, y, c = getattr(a, lst), getattr(b, lst), getattr(a, cnt)
+        if x is None:
+            continue
+        live = torch.arange(x.shape[-1], device=x.device) < c.reshape(*x.shape[:-1], 1)
+        assert bool(((x == y) | ~live).all()), (what, lst)
+    assert int(a.status.item()) == int(b.status.item()), what
+
+
+@pytest.mark.parametrize("bits", [4, 2, 8])
+def test_select_prune_equals_the_separate_calls_with_append(bits):
+    """twilight_select_prune with the step's new token: the cache, the page lists, the kept sets and the unions are
+    those of twilight_append_select followed by twilight_topp_prune, bit for bit (4-bit codes: the one-launch
+    selector + pruner; 2 and 8 bits: the call falls back to the separate launches)."""
+    T = _T()
+    lens = [1009, 48, 33, 2049, 513, 700]
+    w = synth.make_workload("selprune", lens, budget=[max(16, n // 4) for n in lens], p=0.9, heavy_frac=0.02,
+                            alpha_range=(0.0, 3.0), shuffle_pool=True, extra_pool_pages=5, seed=43)
+    dev = "cuda"
+    k, v, q, budget = w.k.to(dev), w.v.to(dev), w.q.to(dev), w.budget.to(dev)
+    last = torch.tensor([w.seq_offsets[b + 1] - 1 for b in range(w.batch)], dtype=torch.int64, device=dev)
+    k_last, v_last = k[last].contiguous(), v[last].contiguous()
+    start = torch.zeros(w.batch, dtype=torch.int32, device=dev)
+    offs = torch.tensor(w.seq_offsets[:-1], dtype=torch.int32, device=dev)
+    max_sel = int(max(-(-int(b) // 16) for b in w.budget))
+    pos = (torch.tensor(lens, dtype=torch.int32, device=dev) - 1).contiguous()
+
+    def prefilled():
+        c = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev, quant_bits=bits)
+        c.append(k, v, start, c.seq_lens - 1, offs, max(lens) - 1)
+        return c
+
+    a, b_ = prefilled(), prefilled()
+    sa = T.DecodeStep(a, max_sel=max_sel, with_kept_idx=True)
+    sa.append_select(k_last, v_last, pos, q, budget)
+    sa.prune(q, w.p)
+    sb = T.DecodeStep(b_, max_sel=max_sel, with_kept_idx=True)
+    for rep in range(2):                               # the second call finds the arrival counters as the first left them
+        sb.select_prune(k_last, v_last, pos, q, budget, w.p)
+        torch.cuda.synchronize()
+        for name in ("k_pool", "v_pool", "kq_pool", "kq_meta", "page_minmax"):
+            assert torch.equal(getattr(a, name).view(torch.uint8), getattr(b_, name).view(torch.uint8)), name
+        _lists_equal(sa, sb, "rep %d" % rep)
+    pipeline_against_oracle(w, bits, b_)
+
+
+@pytest.mark.parametrize("shape", ["few_heads", "heads_over_cus", "split_launch", "over_4096_pages", "few_heads_long_lists",
+                                   "mha", "gqa8", "empty_and_full"])
+def test_select_prune_equals_the_separate_calls(shape):
+    """Every launch shape of twilight_select_prune against twilight_select_pages + twilight_topp_prune: one
+    1024-thread workgroup per head; 512-thread workgroups when there are more heads than CUs; the two launches of a
+    ragged batch with lists above 4096 candidates; sequences of more than 4096 pages (page lists made by the
+    selection kernel, scoring inside the top-p kernel); a single long sequence (all launches separate); one and
+    eight query heads per KV head; an empty sequence, a zero budget and budgets that cover whole sequences."""
+    T = _T()
+    kw = dict(p=0.9, heavy_frac=0.01, alpha_range=(0.0, 3.0), shuffle_pool=True)
+    if shape == "few_heads":
+        w = synth.make_workload(shape, [5000, 1234, 16], num_q_heads=8, num_kv_heads=2, budget=[1024, 400, 16], seed=51, **kw)
+    elif shape == "heads_over_cus":
+        w = synth.make_workload(shape, [900 + 211 * i for i in range(10)], budget=512, seed=52, **kw)
+    elif shape == "split_launch":
+        lens = [40_000, 70_000] + [600 + 150 * i for i in range(16)]
+        w = synth.make_workload(shape, lens, budget=[n // 8 for n in lens], seed=53, **kw)
+    elif shape == "over_4096_pages":
+        w = synth.make_workload(shape, [70_000, 3000], num_q_heads=8, num_kv_heads=2, budget=2048, seed=54, **kw)
+    elif shape == "few_heads_long_lists":
+        w = synth.make_workload(shape, [40_000], num_q_heads=8, num_kv_heads=2, budget=8192, seed=55, **kw)
+    elif shape == "mha":
+        w = synth.make_workload(shape, [700, 300, 2000], num_q_heads=4, num_kv_heads=4, budget=256, seed=56, **kw)
+    elif shape == "gqa8":
+        w = synth.make_workload(shape, [1500, 800], num_q_heads=16, num_kv_heads=2, budget=512, seed=57, **kw)
+    else:
+        w = synth.make_workload(shape, [300, 1, 64, 500], budget=[64, 16, 0, 100000], seed=58, **kw)
+    cache = build_cache(w)
+    dev = cache.device
+    if shape == "empty_and_full":
+        cache.seq_lens[1] = 0
+    q, budget = w.q.to(dev), w.budget.to(dev)
+    max_sel = min(int(max(-(-int(b) // 16) for b in w.budget)), cache.max_pages)
+    for p in (w.p, 1.0):
+        sa = T.DecodeStep(cache, max_sel=max_sel, with_kept_idx=True)
+        sb = T.DecodeStep(cache, max_sel=max_sel, with_kept_idx=True)
+        sa.run(q, budget, p, separate=True)
+        sb.run(q, budget, p)
+        torch.cuda.synchronize()
+        _lists_equal(sa, sb, "p=%g" % p)
+        assert torch.equal(sa.out, sb.out)
+        sc = T.DecodeStep(cache, max_sel=max_sel, with_kept_idx=False)      # without the per-head lists
+        sc.run(q, budget, p)
+        torch.cuda.synchronize()
+        assert torch.equal(sc.union_count, sa.union_count) and torch.equal(sc.kept_count, sa.kept_count)
+        assert torch.equal(sc.out, sa.out)
 
 
 def test_p1_full_budget_reproduces_dense_attention():
@@ -1585,6 +1684,17 @@ def test_canaries_pool_pages_workspace_tails_and_list_tails(kind):
             assert bool((kept_idx[bb, h, int(kept_count[bb, h]):] == -7).all())
     for gi in range(b_ * Hkv):
         assert bool((union_idx[gi, int(union_count[gi]):] == -7).all())
+    if not full:                                       # selector and pruner in one call: same lists, same canaries
+        sp4, sc4 = G_.buf((b_, Hq, max_sel), i32, -7), G_.buf((b_, Hq), i32, -7)
+        kc4, ki4 = G_.buf((b_, Hq), i32, -7), G_.buf((b_, Hq, cand), i32, -7)
+        uc4, ui4 = G_.buf((b_ * Hkv,), i32, -7), G_.buf((b_ * Hkv, union_stride), i32, -7)
+        ws_sp = G_.buf((T.twilight_workspace_bytes(T.TW_WS_SELECT_PRUNE, cache.kv, max_sel),), torch.uint8)
+        T.twilight_select_prune(cache.kv, None, None, None, q, budget, w.p, sp4, sc4, max_sel, kc4, ki4, cand, uc4, ui4,
+                                union_stride, status, ws_sp)
+        G_.check("select_prune")
+        assert int(status.item()) == 0
+        assert torch.equal(sp4, sel_pages) and torch.equal(sc4, sel_count) and torch.equal(kc4, kept_count)
+        assert torch.equal(ki4, kept_idx) and torch.equal(uc4, union_count) and torch.equal(ui4, union_idx)
     out = G_.buf((b_, Hq, 128), torch.bfloat16)
     lse = G_.buf((b_, Hq), torch.float32)
     ws_dec = G_.buf((T.twilight_workspace_bytes(T.TW_WS_DECODE, cache.kv, 0, union_stride),), torch.uint8)
