@@ -131,6 +131,11 @@ def algorithmic_bytes(w, cache, st, bits=4):
         ncand = int(st.sel_count.sum().item()) * 16
         out["int4_score"] = ncand * (16 * bits + 16) + ncand * 4
     out["page_select"] = pages * Hq * 4
+    if not st.full:
+        # the one-launch forms of twilight_select_prune: the codes and (scale, zero) of every candidate, the lists;
+        # with the selection inside, the bounds of every page as well; no score rows through memory
+        out["score_topp"] = ncand * (16 * bits + 16) + ncand // 16 * 4
+        out["select_score_topp"] = out["score_topp"] + pages * Hq * 4
     # register-resident top-p reads each score once; the long-row path reads the row twice
     # (one histogram pass, one pass that writes the kept bitmap) - its launches are summed per step
     out["topp"] = ncand * 4 * (2 if st.full or ncand / (w.batch * Hq) > 8192 else 1)
@@ -266,7 +271,8 @@ def other_config(T, idx, steps, warmup, layers, batch=None):
            "dominant_kernel_algorithmic_bytes": nbytes[dom], "dominant_kernel_GBps": ach, "frac": ach / HBM_PEAK_GBS,
            "per_kernel_us": {k: kavg[k] * kcalls[k] * 1e3 for k in kavg},
            "per_kernel_frac_of_peak": {k: nbytes[k] / (kavg[k] * kcalls[k] * 1e-3) / 1e9 / HBM_PEAK_GBS
-                                       for k in ("page_score", "int4_score", "sparse_decode") if k in kavg and nbytes.get(k)},
+                                       for k in ("page_score", "int4_score", "score_topp", "select_score_topp", "sparse_decode")
+                                       if k in kavg and nbytes.get(k)},
            "dense_decode_frac_of_peak": (nbytes["dense_decode"] / (d_us * 1e-6) / 1e9 / HBM_PEAK_GBS) if d_us else None,
            "workload_stats": stats,
            "decode_work_list": decode_balance(T, cache, st.union_count, st.union_stride) if w.v.numel() and not st.full else None,
@@ -292,7 +298,8 @@ def profile_figures(dom):
     summaries do not list a kernel of that stage."""
     from paper_2502_02770_amd.rocprof_summary import read_trace_table, read_traffic_table
     stem = {"page_score": "page_score_kernel", "int4_score": "int4_score", "sparse_decode": "sparse_decode_kernel",
-            "topp": "topp_head_kernel", "page_select": "page_select", "combine": "combine_kernel",
+            "topp": "topp_head_kernel", "score_topp": "topp_head_kernel", "select_score_topp": "topp_head_kernel",
+            "page_select": "page_select", "combine": "combine_kernel",
             "kquant_append": "kquant_append_kernel"}.get(dom, dom)
     tr_file, tf_file = "c2_decode_step_kernel_trace.md", "c2_decode_step_hbm_traffic.md"
     tr = {k: v for k, v in read_trace_table(os.path.join(PROFILES, tr_file)).items() if k.startswith(stem)}
@@ -497,6 +504,8 @@ def main():
                     help="bf16 K/V pools in pinned host memory (the paper's offloading scenario); attention is then bound by the host link")
     ap.add_argument("--separate-append", action="store_true",
                     help="append the step's token with twilight_kquant_append instead of twilight_append_select")
+    ap.add_argument("--separate-prune", action="store_true",
+                    help="twilight_append_select + twilight_topp_prune instead of twilight_select_prune (selection, scoring and top-p as launches of their own)")
     ap.add_argument("--graph", action="store_true", help="also time the steps replayed from HIP graphs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--step-only", action="store_true",
@@ -515,7 +524,8 @@ def main():
     torch.cuda.set_device(0)
     t_start = time.time()
 
-    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits, a.p, a.full_selector, a.offload, a.separate_append, a.kv_heads)
+    w, cache, st, q, step, dense, setup = build_state(a.config, a.scale, a.seed, a.batch, max(1, a.layers), a.bits, a.p, a.full_selector, a.offload, a.separate_append, a.kv_heads,
+                                                      a.separate_prune)
     if a.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
@@ -618,7 +628,7 @@ def main():
 
     ach = nbytes[dom] / (dom_avg * dom_calls * 1e-3) / 1e9
     default_cfg = (a.config == 1 and a.scale == 1.0 and a.batch is None and a.seed == 0 and a.bits == 4 and a.p is None and a.kv_heads is None
-                   and not a.full_selector and not a.offload)
+                   and not a.full_selector and not a.offload and not a.separate_prune and not a.separate_append)
     prof = profile_figures(dom) if default_cfg else {"traffic": None, "traffic_source": None, "rocprofv3_kernel_us": None, "rocprofv3_source": None}
     roofline = {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": ach / HBM_PEAK_GBS,
@@ -664,7 +674,8 @@ def main():
         "config": {"workload": describe(w, a.scale),
                    "config_index": a.config, "seed": a.seed, "layers_rotated": max(1, a.layers),
                    "kv_offloaded_to_host": bool(a.offload),
-                   "append": "separate launch" if (a.separate_append or w.full_selector) else "inside page_score"},
+                   "append": "separate launch" if (a.separate_append or w.full_selector) else "inside page_score",
+                   "selector_and_pruner": "separate calls" if (a.separate_prune or a.separate_append or w.full_selector) else "twilight_select_prune"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "us_per_layer_events_off": ms_plain * 1e3,

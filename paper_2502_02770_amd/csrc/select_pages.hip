@@ -51,7 +51,6 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
   const int b = blockIdx.z, g = blockIdx.x;
   const int tid = threadIdx.x, seg = tid & 15, grp = tid >> 4;   // grp: 0..15 page slot in the WG
   TW_STAMP(0);
-  if (a.arrive && blockIdx.y == 0 && tid == 0) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
   const int n = a.seq_lens[b];
   // last pages first: the workgroup that appends the step's new token (the sequence's last page) has the longest
   // chain of dependent accesses and should not be the one that starts last
@@ -67,7 +66,13 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
   }
   int P = (n + TW_PAGE - 1) / TW_PAGE;
   if (P > a.max_pages) P = a.max_pages;
-  if (base >= P) return;
+  // (the counters of a top-p launch that follows are cleared on the way out, after every load of the kernel: a store
+  //  ahead of them would turn the scalar loads of the prologue into vector loads that wait for one another)
+  const bool clears = a.arrive && blockIdx.y == 0 && tid == 0;
+  if (base >= P) {
+    if (clears) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
+    return;
+  }
 
   // q of the G heads, the 8 dims of this lane; the sign decides which corner
   // of the [min,max] box maximises q_d * k_d.
@@ -191,6 +196,7 @@ __global__ __launch_bounds__(256) void page_score_kernel(ScoreArgs a) {
       }
     }
   }
+  if (clears) a.arrive[(b * a.Hkv + g) * TW_CTR] = 0;
 }
 
 struct SelectArgs {

@@ -664,7 +664,10 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
     __shared__ float qred[4];
     __shared__ float qc_s[1];
     // this wave's share of the list: lane k holds its k-th page (at most EPT * 4 <= 32 of them)
-    constexpr int UF = NT >= 1024 ? 8 : 4;            // pages in flight per wave (register budget)
+#ifndef TW_FUSE_UF
+#define TW_FUSE_UF 8
+#endif
+    constexpr int UF = NT >= 1024 ? TW_FUSE_UF : 4;   // pages in flight per wave (register budget)
     const int ppw = ((count + NW - 1) / NW + UF - 1) & ~(UF - 1);
     const int first = __builtin_amdgcn_readfirstlane(wave) * ppw;   // (scalar: the loop below is wave-uniform)
     int my_lp = -1, my_pool = -1;
