@@ -135,31 +135,52 @@ __global__ __launch_bounds__(256, G == 4 ? 4 : 1) void sparse_decode_kernel(Deco
     const int gi = lo, b = gi / a.LH, l = gi % a.LH, g = l / a.kv_div;   // list l of sequence b, KV head g
     const int ck = item - prefix[gi];
     const int nchunks = prefix[gi + 1] - prefix[gi];
-    int cnt;
-    int nseq = a.seq_lens[b];                    // list entries at or beyond the sequence's end are ignored
-    if (nseq > a.max_pages * TW_PAGE) nseq = a.max_pages * TW_PAGE;
-    if (dense) cnt = nseq;
-    else { cnt = a.union_count[gi]; if (cnt > a.union_stride) cnt = a.union_stride; }
+    // Everything the row staging reads that does not depend on another load goes out together: the sequence's
+    // length, the list's length, this thread's (at most two) list entries - any entry of the list's row may be read,
+    // those at or beyond the count are ignored below - and q.  The page-table entries then depend on the list
+    // entries, the K/V rows on those: three round trips to memory per item instead of five.
     const int t0 = ck * chunk;
-    const int len = cnt - t0 < chunk ? cnt - t0 : chunk;
-
-    // ---- stage the chunk's token rows (pool row ids) in LDS
-    for (int i = tid; i < chunk; i += 256) {
-      int r = -1;
-      if (i < len) {
-        const int tok = dense ? t0 + i : a.union_idx[(long long)gi * a.union_stride + t0 + i];
-        if (tok >= 0 && tok < nseq) {
-          const long long pp = a.page_table[(long long)b * a.max_pages + (tok >> 4)];
-          if (pp >= 0 && pp < a.pool_pages) r = (int)((pp * a.Hkv + g) * TW_PAGE + (tok & 15));
-        }
-      }
-      rows[i] = r;
+    // (dense: the same loads from an address that is always valid, their values unused - no branch between the loads)
+    int nseq = a.seq_lens[b];                    // list entries at or beyond the sequence's end are ignored
+    const int32_t* const cnt_p = dense ? a.seq_lens + b : a.union_count + gi;
+    int cnt = *cnt_p;
+    int tokv[DEC_MAX_CHUNK / 256];
+#pragma unroll
+    for (int j = 0; j < DEC_MAX_CHUNK / 256; ++j) {
+      const int e = t0 + j * 256 + tid;
+      const int32_t* const tp = dense ? a.seq_lens + b
+                                      : a.union_idx + (long long)gi * a.union_stride + (e < a.union_stride ? e : a.union_stride - 1);
+      const int tv = *tp;
+      tokv[j] = dense ? e : tv;
     }
-    if (item == 0) TW_STAMP(2);
     // q of the G heads, this lane's 8 dims, as loaded (bf16 pairs)
     uint4 q[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) q[h] = a.q[((long long)(b * a.Hq + l * G + h)) * 16 + seg];
+    // (keeps the list-entry loads up here: the compiler would otherwise move them down to their first use, behind
+    //  the wait for the two lengths)
+#pragma unroll
+    for (int j = 0; j < DEC_MAX_CHUNK / 256; ++j) asm volatile("" : "+v"(tokv[j]));
+    if (nseq > a.max_pages * TW_PAGE) nseq = a.max_pages * TW_PAGE;
+    if (dense) cnt = nseq;
+    else if (cnt > a.union_stride) cnt = a.union_stride;
+    const int len = cnt - t0 < chunk ? cnt - t0 : chunk;
+
+    // ---- stage the chunk's token rows (pool row ids) in LDS
+#pragma unroll
+    for (int j = 0; j < DEC_MAX_CHUNK / 256; ++j) {
+      const int i = j * 256 + tid;
+      if (i < chunk) {                            // block-uniform per j
+        int r = -1;
+        const int tok = tokv[j];
+        if (i < len && tok >= 0 && tok < nseq) {
+          const long long pp = a.page_table[(long long)b * a.max_pages + (tok >> 4)];
+          if (pp >= 0 && pp < a.pool_pages) r = (int)((pp * a.Hkv + g) * TW_PAGE + (tok & 15));
+        }
+        rows[i] = r;
+      }
+    }
+    if (item == 0) TW_STAMP(2);
     float acc[G][8], M[G], Mmine[R], lacc[R];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
