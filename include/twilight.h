@@ -200,15 +200,20 @@ int twilight_append_select(const twilight_kv_t* kv, const void* k_new, const voi
  * selector's subset handed straight to the pruner; Section 4.2, Algorithm 1):
  * what twilight_append_select (k_new given) or twilight_select_pages (k_new,
  * v_new, new_pos all NULL) followed by twilight_topp_prune over the selected
- * pages computes - the same page lists, kept sets and unions bit for bit - in
+ * pages computes - the same cache update, page lists, kept sets and unions,
+ * bit for bit.  Where a head's list is short enough for one workgroup
+ * (quant_bits = 4, max_sel <= 512 pages, sequences of at most 196608 tokens,
+ * and not just a few heads with more than 4096 candidates each) the call is
  * two launches instead of four: the bounds of all pages, then one workgroup
- * per query head that picks the head's pages, scores their tokens from the
+ * per query head that picks the head's pages (sequences of at most 4096 pages;
+ * longer ones keep the selection launch), scores their tokens from the
  * quantised K copy, runs top-p and, as the last head of its group, lists the
- * union.  For quant_bits = 4 and max_sel <= 512 pages on sequences of at most
- * 196608 tokens (TW_EINVAL otherwise: use the separate calls).
+ * union.  Otherwise it runs the launches of the separate calls.  The
+ * workspace needs no initialising.
  *   sel_pages, sel_count   out, as twilight_select_pages
  *   kept_count ... status  out, as twilight_topp_prune
  *   ws             >= twilight_workspace_bytes(TW_WS_SELECT_PRUNE, kv, max_sel, 0)
+ *                  (the sizes of TW_WS_SELECT and TW_WS_PRUNE added)
  */
 int twilight_select_prune(const twilight_kv_t* kv, const void* k_new, const void* v_new, const int32_t* new_pos,
                           const void* q, const int32_t* budget_tokens, float p,
