@@ -30,13 +30,15 @@ __device__ __forceinline__ void tw_select_sizes(int n, int B, int max_pages, int
 // The Kp (0 < Kp < P) largest of sc[0..P), ties to the lower index, written in ascending index order to out[0..Kp)
 // (global) and, when given, to out_lds.  Called by all NT threads of the workgroup.  LDS of the caller: key_s[P],
 // hist[SEL_NB], ck[SEL_CAP], ci[SEL_CAP].  SB: first phase-stamp slot (timing builds).
-// EMAX > 0 (rows of at most EMAX * NT entries): thread t brings a value for each of the entries
-// [t * E, (t + 1) * E), E = ceil(P / NT), it will list - pay[e] for entry t * E + e - and the values of the
-// selected entries go to pay_lds in list order.
-template <int NT, int SB, int EMAX = 0>
+// EMAX > 0 (rows of at most EMAX * NT entries): thread t brings a value for each of the E entries [t * E, (t + 1) * E)
+// it will list - pay[e] for entry t * E + e - which goes to pay_lds in list order for the selected ones; E =
+// ceil(P / NT).  PRE: the caller asked for everything before it knew the row's length: E = EMAX, and pre[e] holds the
+// score of entry e * NT + t (sc is then not read).
+template <int NT, int SB, int EMAX = 0, bool PRE = false>
 __device__ __forceinline__ void tw_select_row(const float* sc, int P, int Kp, int max_sel, int32_t* out, int32_t* out_lds,
                                               uint32_t* key_s, uint32_t* hist, uint32_t* ck, int32_t* ci,
-                                              const int32_t* pay = nullptr, int32_t* pay_lds = nullptr) {
+                                              const int32_t* pay = nullptr, int32_t* pay_lds = nullptr,
+                                              const float* pre = nullptr) {
   constexpr int NW = NT / 64, BPT = SEL_NB / NT;      // waves; histogram buckets per thread
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   TW_STAMP(SB);
@@ -46,6 +48,18 @@ __device__ __forceinline__ void tw_select_row(const float* sc, int P, int Kp, in
   __shared__ uint32_t sh_bkt, sh_need, sh_pop, sh_n, sh_T, sh_need_eq;
 
   uint32_t lo = 0xFFFFFFFFu, hi = 0u;
+  if (PRE) {
+#pragma unroll
+    for (int j = 0; j < (EMAX > 0 ? EMAX : 1); ++j) {
+      const int i = j * NT + tid;
+      if (i < P) {
+        const uint32_t k = tw_float_key(pre[j]);
+        key_s[i] = k;
+        lo = k < lo ? k : lo;
+        hi = k > hi ? k : hi;
+      }
+    }
+  } else
   for (int base = 0; base < P; base += 8 * NT) {    // 8 clamped loads in flight per thread
     float v[8];
 #pragma unroll
@@ -160,7 +174,7 @@ __device__ __forceinline__ void tw_select_row(const float* sc, int P, int Kp, in
 
   TW_STAMP(SB + 10);
   // ---- ordered emit: thread t owns the contiguous pages [t*E, (t+1)*E)
-  const int E = (P + NT - 1) / NT;
+  const int E = PRE ? EMAX : (P + NT - 1) / NT;
   const int i0 = tid * E, i1 = (i0 + E < P) ? i0 + E : P;
   uint32_t gt = 0, eq = 0;
   for (int i = i0; i < i1; ++i) { const uint32_t k = key_s[i]; gt += k > T ? 1u : 0u; eq += k == T ? 1u : 0u; }

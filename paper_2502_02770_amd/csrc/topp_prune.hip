@@ -572,7 +572,10 @@ struct HeadArgs {
 
 constexpr int HP_CAP = 64;                    // exact resolve handles up to this many scores
 constexpr int HP_BITMAP_WORDS = 6144;         // 196608 tokens
-constexpr int HP_USTAGE = 2048;               // union lists up to this length leave through LDS
+#ifndef TW_HP_USTAGE
+#define TW_HP_USTAGE 4096
+#endif
+constexpr int HP_USTAGE = TW_HP_USTAGE;       // union lists up to this length leave through LDS
 
 // TOK: the candidates are token positions (sel_pages = the token lists, max_sel = their row length,
 // sel_count in tokens) instead of pages of 16 slots.
@@ -595,7 +598,34 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
   }
   const int b = b_, h = h_;
   const int bh = b * a.Hq + h;
+  // FUSE == 2: everything the page selection reads is asked for here, before the sequence's length is known (any
+  // entry of the head's row of bounds and of the sequence's page-table row may be read): the bounds of the pages
+  // j * NT + tid and the page-table entries of the pages tid * SEL_E + e, which this thread will list
+  // (1024-thread workgroups, 4 entries each; the 512-thread form, short of registers, asks when it knows the length)
+  constexpr int SEL_E = 4096 / NT;
+  constexpr bool SEL_EARLY = FUSE == 2 && NT >= 1024;
   const int n = a.seq_lens[b];
+  const int budget_b = FUSE == 2 ? a.budget[b] : 0;
+  float sel_pre[SEL_EARLY ? SEL_E : 1];
+  int32_t sel_pt[FUSE == 2 ? SEL_E : 1];
+  // (when the heads are split over two launches by list length, half the workgroups of each return at once: those
+  //  must not leave with loads in flight, so the loads then follow the test)
+  const bool all_heads = a.n_above < 0 && a.n_upto >= a.cand_stride;
+  auto ask_selection = [&]() {
+#pragma unroll
+    for (int j = 0; j < SEL_E; ++j) {
+      const int i = j * NT + tid, e = tid * SEL_E + j;
+      sel_pre[SEL_EARLY ? j : 0] = a.bounds[(long long)bh * a.max_pages + (i < a.max_pages ? i : a.max_pages - 1)];
+      sel_pt[SEL_EARLY ? j : 0] = a.page_table[(long long)b * a.max_pages + (e < a.max_pages ? e : a.max_pages - 1)];
+    }
+  };
+  // FUSE: this thread's element of the query, asked for early too (no branch around the load: all threads read)
+  uint32_t q_raw = 0u;
+  if (FUSE && all_heads) {
+    if (SEL_EARLY) ask_selection();
+    q_raw = (uint32_t)a.q[(long long)bh * 128 + (tid & 127)];
+    __builtin_amdgcn_sched_barrier(0);               // these loads are issued before anything below waits for the lengths
+  }
   int P = n > 0 ? (n + TW_PAGE - 1) / TW_PAGE : 0;
   if (P > a.max_pages) P = a.max_pages;
   const int ntok = P * TW_PAGE < n ? P * TW_PAGE : n;
@@ -603,7 +633,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
   int count;
   if (FUSE == 2) {
     int P2;
-    tw_select_sizes<TW_PAGE>(n, a.budget[b], a.max_pages, a.max_sel, &P2, &count);
+    tw_select_sizes<TW_PAGE>(n, budget_b, a.max_pages, a.max_sel, &P2, &count);
   } else {
     count = a.sel_count[bh];
     if (count > a.max_sel) count = a.max_sel;
@@ -611,6 +641,10 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
   }
   const int N = TOK ? count : count * TW_PAGE;
   if (N <= a.n_above || N > a.n_upto) return;     // another launch's head (block-uniform)
+  if (FUSE && !all_heads) {
+    if (SEL_EARLY) ask_selection();
+    q_raw = (uint32_t)a.q[(long long)bh * 128 + (tid & 127)];
+  }
   const float* row = a.scores + (long long)bh * a.cand_stride;
   const int c0 = tid * EPT;
   TW_STAMP(0);
@@ -629,8 +663,6 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
 
   __shared__ int32_t pages_s[FUSE == 2 ? 512 : 1];   // FUSE == 2: the head's page list ...
   __shared__ int32_t pool_s[FUSE == 2 ? 512 : 1];    // ... and the pages' places in the pool
-  float qv = 0.f;                                    // FUSE: this thread's element of the query, asked for early
-  if (FUSE && tid < 128) qv = __uint_as_float((uint32_t)a.q[(long long)bh * 128 + tid] << 16);
   if (FUSE == 2) {
     static_assert(4096 + SEL_NB + 2 * SEL_CAP <= HP_BITMAP_WORDS + HP_USTAGE, "the selection's arrays lie in big_s");
     int32_t* const out = a.sel_pages_w + (long long)bh * a.max_sel;
@@ -639,14 +671,18 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
     if (count == P) {                               // the budget covers the sequence (block-uniform)
       for (int i = tid; i < P; i += NT) { out[i] = i; pages_s[i] = i; pool_s[i] = ptab[i]; }
     } else if (count > 0) {
-      // page-table entries of the pages this thread will list, in flight while the threshold is found
-      constexpr int EMAX = 4096 / NT;
-      const int E = (P + NT - 1) / NT;
-      int32_t pt[EMAX];
+      if (SEL_EARLY) {
+        tw_select_row<NT, 30, SEL_E, true>(nullptr, P, count, a.max_sel, out, pages_s, big_s, big_s + 4096, big_s + 4096 + SEL_NB,
+                                           (int32_t*)(big_s + 4096 + SEL_NB + SEL_CAP), sel_pt, pool_s, sel_pre);
+      } else {
+        // page-table entries of the pages this thread will list, in flight while the threshold is found
+        const int E = (P + NT - 1) / NT;
 #pragma unroll
-      for (int e = 0; e < EMAX; ++e) { const int i = tid * E + e; pt[e] = ptab[i < P ? i : P - 1]; }
-      tw_select_row<NT, 30, EMAX>(a.bounds + (long long)bh * a.max_pages, P, count, a.max_sel, out, pages_s, big_s, big_s + 4096,
-                                  big_s + 4096 + SEL_NB, (int32_t*)(big_s + 4096 + SEL_NB + SEL_CAP), pt, pool_s);
+        for (int e = 0; e < SEL_E; ++e) { const int i = tid * E + e; sel_pt[FUSE == 2 ? e : 0] = ptab[i < P ? i : P - 1]; }
+        tw_select_row<NT, 30, SEL_E, false>(a.bounds + (long long)bh * a.max_pages, P, count, a.max_sel, out, pages_s, big_s,
+                                            big_s + 4096, big_s + 4096 + SEL_NB, (int32_t*)(big_s + 4096 + SEL_NB + SEL_CAP),
+                                            sel_pt, pool_s);
+      }
     }
     __syncthreads();                                // list complete; big_s free for the scores
   }
@@ -680,7 +716,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
     }
     int npages = count - first;
     npages = npages < 0 ? 0 : (npages > ppw ? ppw : npages);
-    tw_quantize_q1(qv, qi_s, qred, qc_s);
+    tw_quantize_q1(tid < 128 ? __uint_as_float(q_raw << 16) : 0.f, qi_s, qred, qc_s);
     const int j = lane & 3, g = h / G;
     int qw[8], qs = 0;
 #pragma unroll
