@@ -565,7 +565,9 @@ def main():
     # odd period because every 128th step - some periodic work of the runtime - runs this kernel 6 us slower, and a
     # period that divides 128 would sample those steps far too often)
     T.twilight_prof_select(dom, every=41 if a.steps >= 256 else (19 if a.steps >= 128 else 3))
-    T.twilight_prof_enable(2)
+    # (mode 3: the launch ahead of it carries events too - a timed kernel behind an untimed one reads 1.5 us long,
+    #  its start stamp being taken before the predecessor has drained)
+    T.twilight_prof_enable(3)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(a.steps):

@@ -21,7 +21,12 @@ struct twilight_kv;   /* twilight.h */
  * kernel's own dispatch (hipExtLaunchKernelGGL: start and stop timestamps of
  * the kernel, no extra packets on the stream).  mode 0 = off (default), 1 =
  * every kernel, 2 = only the kernel id given to twilight_prof_select, at
- * every `every`-th of its launches.  Timed launches are not meant to be
+ * every `every`-th of its launches, 3 = as 2, and with each of those launches
+ * the launch just ahead of it on the stream (the library kernel that preceded
+ * the chosen one the last time): a timed kernel's start stamp is taken when
+ * its dispatch is reached, which is before an untimed predecessor has
+ * drained (1.5 us early on MI355X), not when both carry events.  Timed
+ * launches are not meant to be
  * captured into a graph.  While on,
  * each launch adds one record {kernel id, start event, stop event} (at most
  * TW_PROF_MAX_RECORDS between two collects; further launches are not timed).

@@ -125,6 +125,8 @@ int g_created = 0;   // events exist for records [0, g_created)
 int g_only = -1;     // mode 2: the one kernel id that is timed ...
 int g_every = 1;     // ... at every g_every-th of its launches
 long long g_seen = 0;
+int g_last = -1;     // id of the latest launch of any kernel
+int g_pred = -1;     // mode 3: the kernel id that was launched just before g_only's latest launch
 }  // namespace
 
 extern "C" int twilight_prof_select(int kernel_id, int every) {
@@ -132,12 +134,13 @@ extern "C" int twilight_prof_select(int kernel_id, int every) {
   g_only = kernel_id;
   g_every = every > 0 ? every : 1;
   g_seen = 0;
+  g_last = g_pred = -1;
   return TW_OK;
 }
 
 extern "C" int twilight_prof_enable(int mode) {
   std::lock_guard<std::mutex> lk(g_lock);
-  g_mode = mode < 0 || mode > 2 ? 1 : mode;
+  g_mode = mode < 0 || mode > 3 ? 1 : mode;
   g_on.store(g_mode != 0, std::memory_order_release);
   g_n = 0;
   return TW_OK;
@@ -152,7 +155,15 @@ void tw_prof_before(int kernel_id, hipStream_t s) {
   if (!g_on.load(std::memory_order_acquire)) return;
   g_lock.lock();
   bool take = g_mode != 0 && g_n < TW_PROF_MAX_RECORDS;
-  if (take && g_mode == 2 && (kernel_id != g_only || (g_seen++ % g_every) != 0)) take = false;
+  if (g_mode >= 2) {
+    // mode 3 also times the launch that comes just before a timed launch of the chosen kernel (the kernel id seen
+    // there last time), so that the chosen kernel's start stamp does not wait for an untimed predecessor to drain
+    const bool sampled = g_seen % g_every == 0;
+    if (kernel_id == g_only) { g_pred = g_last; ++g_seen; }
+    else if (!(g_mode == 3 && kernel_id == g_pred)) take = false;
+    if (!sampled) take = false;
+    g_last = kernel_id;
+  }
   if (take && g_n >= g_created) {
     if (hipEventCreate(&g_rec[g_n].e0) != hipSuccess) take = false;
     else if (hipEventCreate(&g_rec[g_n].e1) != hipSuccess) { (void)hipEventDestroy(g_rec[g_n].e0); take = false; }
