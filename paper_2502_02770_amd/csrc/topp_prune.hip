@@ -1023,7 +1023,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
   __syncthreads();
 #endif
   if (!sh_last) return;
-  TW_STAMP(14);
+  TW_STAMP_IF(gi == 0, 14);
   if (tid == 0) __hip_atomic_store(a.arrive + gi * TW_CTR, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next call
   // OR of the group's bitmaps into LDS (this block's own bitmap is no longer needed there): coalesced,
   // four words per thread and bitmap in flight
@@ -1052,7 +1052,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
     }
   }
   __syncthreads();
-  TW_STAMP(15);
+  TW_STAMP_IF(gi == 0, 15);
   int32_t* uout = a.union_idx + (long long)gi * a.union_stride;
   uint32_t utotal;
   // (block-uniform choice: long sequences - more than two bitmap words per thread - take the wave-cooperative
@@ -1077,7 +1077,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
     utotal = 0;
   #pragma unroll
     for (int w = 0; w < NW; ++w) { const uint32_t t = ws32[w]; run += w < wave ? t : 0u; utotal += t; }
-    TW_STAMP(16);
+    TW_STAMP_IF(gi == 0, 16);
     // positions staged in LDS and copied out coalesced when they fit (the usual case; block-uniform), else stored directly
     const bool staged = utotal <= (uint32_t)HP_USTAGE;
     auto put = [&](uint32_t pos, int tok) {
@@ -1128,7 +1128,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
     uint32_t ucnt = 0;
     for (int i = w0; i < w1; ++i) ucnt += __popc(bitmap[i]);
     const uint32_t uincl = tw_block_scan_u32(ucnt, ws32, &utotal);
-    TW_STAMP(16);
+    TW_STAMP_IF(gi == 0, 16);
     uint32_t upos = uincl - ucnt;
     if (utotal <= (uint32_t)HP_USTAGE) {               // block-uniform; the usual case
       // positions staged in LDS, then copied out coalesced: a dense word costs its thread 32 scattered
@@ -1160,7 +1160,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
     if (utotal > (uint32_t)a.union_stride) { atomicOr(a.status, TW_STATUS_UNION_TRUNCATED); utotal = a.union_stride; }
     a.union_count[gi] = (int32_t)utotal;
   }
-  TW_STAMP(13);
+  TW_STAMP_IF(gi == 0, 13);
 }
 
 // ------------------------------------------------------------------ launches

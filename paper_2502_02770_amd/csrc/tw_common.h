@@ -130,8 +130,10 @@ __device__ __forceinline__ uint32_t tw_float_key(float f) {
 #ifdef TW_PHASE_TIMING
 static __device__ unsigned long long tw_dbg_stamps[64];
 #define TW_STAMP(k) do { if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) tw_dbg_stamps[k] = wall_clock64(); } while (0)
+#define TW_STAMP_IF(c, k) do { if ((c) && threadIdx.x == 0) tw_dbg_stamps[k] = wall_clock64(); } while (0)
 #else
 #define TW_STAMP(k) do { } while (0)
+#define TW_STAMP_IF(c, k) do { } while (0)
 #endif
 
 // inverse of tw_float_key
