@@ -813,12 +813,33 @@ def check_sampled_groups(w, cache, st, q, groups, pages_to_check=(0,)):
 def test_full_size_bench_config_sampled():
     """Benchmark config C2 at full size (batch 8 x 32768, budget 4096, p 0.9), the launch
     configuration bench.py times; the oracle recomputes sampled (sequence, KV head) groups."""
+    T = _T()
     w = synth.config(1)
-    cache = build_cache(w)
-    st, q = run_pipeline(w, cache, with_kept=True)
+    dev = "cuda"
+    # as bench.py's step: the cache holds all but the last token of every sequence; the step appends it, selects,
+    # prunes (twilight_select_prune: two launches) and attends
+    cache = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev)
+    k, v = w.k.to(dev), w.v.to(dev)
+    start = torch.zeros(w.batch, dtype=torch.int32, device=dev)
+    offs = torch.tensor(w.seq_offsets[:-1], dtype=torch.int32, device=dev)
+    cache.append(k, v, start, cache.seq_lens - 1, offs, int(w.seq_lens.max()) - 1)
+    last = torch.tensor([w.seq_offsets[b + 1] - 1 for b in range(w.batch)], dtype=torch.int64, device=dev)
+    k_last, v_last = k[last].contiguous(), v[last].contiguous()
+    del k, v
+    q, budget = w.q.to(dev), w.budget.to(dev)
+    st = T.DecodeStep(cache, max_sel=int(max(-(-int(b) // 16) for b in w.budget)), with_kept_idx=True)
+    st.select_prune(k_last, v_last, (cache.seq_lens - 1).contiguous(), q, budget, w.p)
+    st.attend(q)
+    torch.cuda.synchronize()
     assert int(st.status.item()) == 0
     every = [(b, g) for b in range(w.batch) for g in range(w.num_kv_heads)]       # all 64 groups: a few seconds of oracle
     check_sampled_groups(w, cache, st, q, every, pages_to_check=(0, 1000, 2047))
+    # and the separate calls on the same cache give the same lists and outputs bit for bit
+    s2 = T.DecodeStep(cache, max_sel=st.max_sel, with_kept_idx=True)
+    s2.run(q, budget, w.p, separate=True)
+    torch.cuda.synchronize()
+    _lists_equal(st, s2, "C2")
+    assert torch.equal(st.out, s2.out)
 
 
 def test_full_size_smallest_config_every_group():
