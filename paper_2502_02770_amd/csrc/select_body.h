@@ -79,6 +79,7 @@ __device__ __forceinline__ void tw_select_row(const float* sc, int P, int Kp, in
   hi = tw_wave_max_u32(hi);
   if (lane == 0) { red_lo[wave] = lo; red_hi[wave] = hi; }
   if (tid == 0) sh_n = 0;
+  for (int i = tid; i < SEL_NB; i += NT) hist[i] = 0;     // for the first pass (cleared again before any later one)
   __syncthreads();
   uint32_t klo = red_lo[0], khi = red_hi[0];
 #pragma unroll
@@ -104,8 +105,10 @@ __device__ __forceinline__ void tw_select_row(const float* sc, int P, int Kp, in
       const int bk = (int)((tw_key_to_float(k) - smn) * scale);
       return bk > SEL_NB - 1 ? SEL_NB - 1 : (bk < 0 ? 0 : bk);
     };
-    for (int i = tid; i < SEL_NB; i += NT) hist[i] = 0;
-    __syncthreads();
+    if (pass > 0) {
+      for (int i = tid; i < SEL_NB; i += NT) hist[i] = 0;
+      __syncthreads();
+    }
     for (int i = tid; i < P; i += NT) {
       const uint32_t k = key_s[i];
       if (k >= klo && k <= khi) atomicAdd(&hist[bucket_of(k)], 1u);
@@ -116,7 +119,7 @@ __device__ __forceinline__ void tw_select_row(const float* sc, int P, int Kp, in
 #pragma unroll
     for (int j = 0; j < BPT; ++j) { c[j] = hist[SEL_NB - 1 - (BPT * tid + j)]; mine += c[j]; }
     uint32_t total;
-    const uint32_t incl = tw_block_scan_u32(mine, wsum, &total);
+    const uint32_t incl = tw_block_scan_u32_open(mine, wsum, &total);   // (wsum is next written behind the barrier below)
     uint32_t above = incl - mine;
     if (above < need && incl >= need) {
 #pragma unroll
@@ -179,7 +182,7 @@ __device__ __forceinline__ void tw_select_row(const float* sc, int P, int Kp, in
   uint32_t gt = 0, eq = 0;
   for (int i = i0; i < i1; ++i) { const uint32_t k = key_s[i]; gt += k > T ? 1u : 0u; eq += k == T ? 1u : 0u; }
   uint32_t total;
-  const uint32_t incl = tw_block_scan_u32(gt | (eq << 16), wsum, &total);
+  const uint32_t incl = tw_block_scan_u32_open(gt | (eq << 16), wsum, &total);   // (last use of wsum)
   uint32_t gt_before = (incl & 0xFFFFu) - gt, eq_before = (incl >> 16) - eq;
   if (EMAX > 0) {
 #pragma unroll

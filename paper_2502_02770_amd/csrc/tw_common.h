@@ -239,4 +239,16 @@ __device__ __forceinline__ uint32_t tw_block_scan_u32(uint32_t v, uint32_t* wsum
   return x + off;
 }
 
+// The same without the closing barrier: the caller passes a block barrier of its own before `wsum` is written again.
+__device__ __forceinline__ uint32_t tw_block_scan_u32_open(uint32_t v, uint32_t* wsum, uint32_t* total) {
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const uint32_t x = tw_wave_scan_u32(v);
+  if ((threadIdx.x & 63) == 63) wsum[wave] = x;
+  __syncthreads();
+  uint32_t off = 0, tot = 0;
+  for (int i = 0; i < nw; ++i) { const uint32_t t = wsum[i]; off += i < wave ? t : 0u; tot += t; }
+  *total = tot;
+  return x + off;
+}
+
 #endif  // __HIPCC__
