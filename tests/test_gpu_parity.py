@@ -417,6 +417,39 @@ def test_step_replays_from_a_hip_graph():
         del scratch
 
 
+def test_per_kernel_timing_modes():
+    """twilight_prof_*: every kernel; one kernel at every n-th of its launches; that kernel together with the launch
+    just ahead of it (the record list then holds the pair, nothing else)."""
+    T = _T()
+    w = list(small_workloads())[1]
+    cache = build_cache(w)
+    st = T.DecodeStep(cache, max_sel=int(max(-(-int(b) // 16) for b in w.budget)))
+    q, budget = w.q.to(cache.device), w.budget.to(cache.device)
+    st.run(q, budget, w.p)
+    torch.cuda.synchronize()
+    step_kernels = ["page_score", "select_score_topp", "sparse_decode", "combine"]
+
+    def names(mode, kernel, every, steps):
+        T.twilight_prof_select(kernel, every=every)
+        T.twilight_prof_enable(mode)
+        for _ in range(steps):
+            st.run(q, budget, w.p)
+        torch.cuda.synchronize()
+        recs = T.twilight_prof_collect()
+        T.twilight_prof_enable(0)
+        assert all(ms > 0 for _, ms in recs)
+        return [n for n, _ in recs]
+
+    assert names(1, "sparse_decode", 1, 3) == step_kernels * 3
+    assert names(2, "sparse_decode", 2, 6) == ["sparse_decode"] * 3
+    got = names(3, "sparse_decode", 2, 6)
+    # the first sampled launch comes before the library has seen what precedes the kernel
+    assert got == ["sparse_decode"] + ["select_score_topp", "sparse_decode"] * 2
+    st.run(q, budget, w.p)
+    torch.cuda.synchronize()
+    assert T.twilight_prof_collect() == []             # off again: nothing recorded
+
+
 @pytest.mark.parametrize("bits", [4, 2, 8])
 def test_append_select_equals_append_then_select(bits):
     """twilight_append_select (one new token per sequence appended on the selector's way) leaves the cache
