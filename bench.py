@@ -560,7 +560,7 @@ def main():
             within = mass_within_candidates(T, w, cache, st, q)
 
     # ---- timed region: K steps; HIP events (on the launch stream) around the dominant kernel only,
-    # so the event pairs do not stretch the step the way bracketing all seven launches does
+    # so the event pairs do not stretch the step the way bracketing every launch does
     # (and only at every 41st of its launches: a launch that carries events delays the stream by some 40 us; an
     # odd period because every 128th step - some periodic work of the runtime - runs this kernel 6 us slower, and a
     # period that divides 128 would sample those steps far too often)
