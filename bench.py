@@ -485,7 +485,7 @@ def mass_within_candidates(T, w, cache, st, q):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--steps", type=int, default=800)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=1, help="benchmark configuration 0..4 = C1..C5 (default 1 = C2)")
     ap.add_argument("--scale", type=float, default=1.0)
@@ -561,10 +561,10 @@ def main():
 
     # ---- timed region: K steps; HIP events (on the launch stream) around the dominant kernel only,
     # so the event pairs do not stretch the step the way bracketing every launch does
-    # (and only at every 41st of its launches: a launch that carries events delays the stream by some 40 us; an
-    # odd period because every 128th step - some periodic work of the runtime - runs this kernel 6 us slower, and a
-    # period that divides 128 would sample those steps far too often)
-    T.twilight_prof_select(dom, every=41 if a.steps >= 256 else (19 if a.steps >= 128 else 3))
+    # (and only at every 101st of its launches in the default 800 steps: a launch that carries events delays the
+    # stream by some 40 us; an odd period because every 128th step - some periodic work of the runtime - runs this
+    # kernel 6 us slower, and a period that divides 128 would sample those steps far too often)
+    T.twilight_prof_select(dom, every=101 if a.steps >= 512 else (41 if a.steps >= 256 else (19 if a.steps >= 128 else 3)))
     # (mode 3: the launch ahead of it carries events too - a timed kernel behind an untimed one reads 1.5 us long,
     #  its start stamp being taken before the predecessor has drained)
     T.twilight_prof_enable(3)

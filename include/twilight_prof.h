@@ -21,7 +21,8 @@ struct twilight_kv;   /* twilight.h */
  * kernel's own dispatch (hipExtLaunchKernelGGL: start and stop timestamps of
  * the kernel, no extra packets on the stream).  mode 0 = off (default), 1 =
  * every kernel, 2 = only the kernel id given to twilight_prof_select, at
- * every `every`-th of its launches, 3 = as 2, and with each of those launches
+ * every `every`-th of its launches (the every-th, 2 * every-th, ... since
+ * twilight_prof_select), 3 = as 2, and with each of those launches
  * the launch just ahead of it on the stream (the library kernel that preceded
  * the chosen one the last time): a timed kernel's start stamp is taken when
  * its dispatch is reached, which is before an untimed predecessor has

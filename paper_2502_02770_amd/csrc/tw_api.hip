@@ -158,7 +158,7 @@ void tw_prof_before(int kernel_id, hipStream_t s) {
   if (g_mode >= 2) {
     // mode 3 also times the launch that comes just before a timed launch of the chosen kernel (the kernel id seen
     // there last time), so that the chosen kernel's start stamp does not wait for an untimed predecessor to drain
-    const bool sampled = g_seen % g_every == 0;
+    const bool sampled = g_seen % g_every == g_every - 1;   // (the last of every g_every launches: never the first after a start)
     if (kernel_id == g_only) { g_pred = g_last; ++g_seen; }
     else if (!(g_mode == 3 && kernel_id == g_pred)) take = false;
     if (!sampled) take = false;
