@@ -1398,6 +1398,43 @@ def test_random_small_workloads_other_entry_points():
                     assert_attention(out[b, h], ref)
 
 
+def test_random_workloads_select_prune_with_append():
+    """60 seeded random workloads through the decode step's one call (twilight_select_prune with the step's new
+    token; sequences without a new token among them) against twilight_append_select + twilight_topp_prune on a second
+    copy of the cache: pools, page lists, kept sets, unions and status bit for bit; every sixth also against the oracle."""
+    T = _T()
+    rng = np.random.default_rng(6061)
+    dev = "cuda"
+    for i in range(60):
+        w, bits = _random_workload(rng, i)
+        k, v, q, budget = w.k.to(dev), w.v.to(dev), w.q.to(dev), w.budget.to(dev)
+        lens = [int(n) for n in w.seq_lens]
+        last = torch.tensor([w.seq_offsets[b + 1] - 1 for b in range(w.batch)], dtype=torch.int64, device=dev)
+        k_last, v_last = k[last].contiguous(), v[last].contiguous()
+        start = torch.zeros(w.batch, dtype=torch.int32, device=dev)
+        offs = torch.tensor(w.seq_offsets[:-1], dtype=torch.int32, device=dev)
+        pos = (torch.tensor(lens, dtype=torch.int32, device=dev) - 1).contiguous()
+        skip = int(rng.integers(w.batch)) if (i % 4 == 3 and w.batch > 1) else -1
+        if skip >= 0:
+            pos[skip] = -1                              # this sequence gets no new token in this step
+        max_sel = min(int(max(-(-int(b) // 16) for b in w.budget)), w.page_table.shape[1])
+        caches, steps = [], []
+        for _ in range(2):
+            c = T.PagedKV(w.num_q_heads, w.num_kv_heads, w.page_table, w.seq_lens, w.num_pool_pages, dev, quant_bits=bits)
+            c.append(k, v, start, c.seq_lens - 1, offs, max(lens) - 1)
+            caches.append(c)
+            steps.append(T.DecodeStep(c, max_sel=max_sel, with_kept_idx=True))
+        steps[0].append_select(k_last, v_last, pos, q, budget)
+        steps[0].prune(q, w.p)
+        steps[1].select_prune(k_last, v_last, pos, q, budget, w.p)
+        torch.cuda.synchronize()
+        for name in ("k_pool", "v_pool", "kq_pool", "kq_meta", "page_minmax"):
+            assert torch.equal(getattr(caches[0], name).view(torch.uint8), getattr(caches[1], name).view(torch.uint8)), (i, name)
+        _lists_equal(steps[0], steps[1], "workload %d" % i)
+        if i % 6 == 0 and skip < 0:
+            pipeline_against_oracle(w, bits, caches[1])
+
+
 def test_two_streams_with_their_own_buffers_do_not_interfere():
     """The library keeps no state between calls: two decode steps on two streams, each with its own cache,
     outputs and workspaces, give the results of the same steps run one after the other."""
