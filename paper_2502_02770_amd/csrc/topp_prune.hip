@@ -572,10 +572,7 @@ struct HeadArgs {
 
 constexpr int HP_CAP = 64;                    // exact resolve handles up to this many scores
 constexpr int HP_BITMAP_WORDS = 6144;         // 196608 tokens
-#ifndef TW_HP_USTAGE
-#define TW_HP_USTAGE 4096
-#endif
-constexpr int HP_USTAGE = TW_HP_USTAGE;       // union lists up to this length leave through LDS
+constexpr int HP_USTAGE = 4096;               // union lists up to this length leave through LDS
 
 // TOK: the candidates are token positions (sel_pages = the token lists, max_sel = their row length,
 // sel_count in tokens) instead of pages of 16 slots.
@@ -700,10 +697,7 @@ __global__ __launch_bounds__(NT, NT == 512 ? 6 : 1) void topp_head_kernel(HeadAr
     __shared__ float qred[4];
     __shared__ float qc_s[1];
     // this wave's share of the list: lane k holds its k-th page (at most EPT * 4 <= 32 of them)
-#ifndef TW_FUSE_UF
-#define TW_FUSE_UF 8
-#endif
-    constexpr int UF = NT >= 1024 ? TW_FUSE_UF : 4;   // pages in flight per wave (register budget)
+    constexpr int UF = NT >= 1024 ? 8 : 4;            // pages in flight per wave (register budget)
     const int ppw = ((count + NW - 1) / NW + UF - 1) & ~(UF - 1);
     const int first = __builtin_amdgcn_readfirstlane(wave) * ppw;   // (scalar: the loop below is wave-uniform)
     int my_lp = -1, my_pool = -1;
